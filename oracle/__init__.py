@@ -1,0 +1,175 @@
+"""ctypes front end of the CPU oracle (oracle/bagua_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's
+cpu_baseline leg.  The GPU package never imports this module.  All arrays are numpy,
+C-contiguous, float32 / uint8 / uint32; in-out residuals and replicas are updated in place.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+_c_sz = ctypes.c_size_t
+_c_p = ctypes.c_void_p
+
+
+def lib():
+    """Load (building if necessary) the oracle shared library."""
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build()
+        _lib = ctypes.CDLL(path)
+        for name in ("oracle_compress_minmax_u8", "oracle_decompress_minmax_u8", "oracle_drr_minmax_u8",
+                     "oracle_ring_avg_fp", "oracle_ring_avg_lp", "oracle_sign_compress_ef",
+                     "oracle_decompress_sign", "oracle_drr_sign", "oracle_bucket_flatten"):
+            getattr(_lib, name).restype = ctypes.c_int
+        _lib.oracle_compress_minmax_u8.argtypes = [_c_p, _c_p, _c_sz, _c_sz, _c_p, _c_p]
+        _lib.oracle_decompress_minmax_u8.argtypes = [_c_p, _c_p, _c_sz, _c_sz, _c_p]
+        _lib.oracle_drr_minmax_u8.argtypes = [_c_p, _c_p, ctypes.c_int, _c_p, _c_sz, _c_sz, _c_p, _c_p, _c_p]
+        _lib.oracle_ring_avg_fp.argtypes = [_c_p, _c_p, ctypes.c_int, _c_sz]
+        _lib.oracle_ring_avg_lp.argtypes = [_c_p, _c_p, _c_p, _c_p, _c_p, ctypes.c_int, _c_sz, _c_sz]
+        _lib.oracle_sign_compress_ef.argtypes = [_c_p, _c_p, _c_sz, _c_sz, _c_p, _c_p]
+        _lib.oracle_decompress_sign.argtypes = [_c_p, _c_p, _c_sz, _c_sz, _c_p]
+        _lib.oracle_drr_sign.argtypes = [_c_p, _c_p, ctypes.c_int, _c_p, _c_sz, _c_sz, _c_p, _c_p, _c_p]
+        _lib.oracle_bucket_flatten.argtypes = [_c_p, _c_p, _c_p, _c_sz, _c_p, _c_sz]
+        _lib.oracle_set_threads.argtypes = [ctypes.c_int]
+        _lib.oracle_get_threads.restype = ctypes.c_int
+        _lib.oracle_max_threads.restype = ctypes.c_int
+    return _lib
+
+
+def set_threads(t):
+    lib().oracle_set_threads(int(t))
+
+
+def get_threads():
+    return lib().oracle_get_threads()
+
+
+def max_threads():
+    return lib().oracle_max_threads()
+
+
+def num_chunks(n, chunk):
+    return (n + chunk - 1) // chunk if chunk > 0 else 0
+
+
+def _chk(a, dtype):
+    assert isinstance(a, np.ndarray) and a.dtype == dtype and a.flags["C_CONTIGUOUS"], (type(a), getattr(a, "dtype", None))
+    return a.ctypes.data
+
+
+def _ptr_array(arrays, dtype):
+    ptrs = (ctypes.c_void_p * len(arrays))()
+    for i, a in enumerate(arrays):
+        ptrs[i] = _chk(a, dtype)
+    return ptrs
+
+
+def _ok(rc, what):
+    if rc != 0:
+        raise ValueError("%s: oracle status %d" % (what, rc))
+
+
+def compress_minmax_u8(x, residual, chunk):
+    """Worker side of C_LP_S with Q = MinMax-u8. Returns (codes, minmax); residual updated in place (or None)."""
+    n = x.size
+    codes = np.empty(n, np.uint8)
+    minmax = np.empty(2 * num_chunks(n, chunk), np.float32)
+    _ok(lib().oracle_compress_minmax_u8(_chk(x, np.float32), None if residual is None else _chk(residual, np.float32),
+                                         n, chunk, _chk(codes, np.uint8), _chk(minmax, np.float32)), "compress_minmax_u8")
+    return codes, minmax
+
+
+def decompress_minmax_u8(codes, minmax, chunk):
+    n = codes.size
+    out = np.empty(n, np.float32)
+    _ok(lib().oracle_decompress_minmax_u8(_chk(codes, np.uint8), _chk(minmax, np.float32), n, chunk,
+                                           _chk(out, np.float32)), "decompress_minmax_u8")
+    return out
+
+
+def drr_minmax_u8(codes_in, minmax_in, server_residual, chunk, want_fp32=True):
+    """Server side of C_LP_S with Q = MinMax-u8. Returns (codes', minmax', out_fp32 or None)."""
+    k = len(codes_in)
+    n = codes_in[0].size
+    codes = np.empty(n, np.uint8)
+    minmax = np.empty(2 * num_chunks(n, chunk), np.float32)
+    out = np.empty(n, np.float32) if want_fp32 else None
+    _ok(lib().oracle_drr_minmax_u8(_ptr_array(codes_in, np.uint8), _ptr_array(minmax_in, np.float32), k,
+                                    None if server_residual is None else _chk(server_residual, np.float32),
+                                    n, chunk, _chk(codes, np.uint8), _chk(minmax, np.float32),
+                                    None if out is None else _chk(out, np.float32)), "drr_minmax_u8")
+    return codes, minmax, out
+
+
+def ring_avg_fp(x_in):
+    """D_FP_S on a ring, averaged. Returns the list of new replicas."""
+    k = len(x_in)
+    n = x_in[0].size
+    outs = [np.empty(n, np.float32) for _ in range(k)]
+    _ok(lib().oracle_ring_avg_fp(_ptr_array(x_in, np.float32), _ptr_array(outs, np.float32), k, n), "ring_avg_fp")
+    return outs
+
+
+def ring_avg_lp(x_in, xhat, chunk):
+    """D_LP_S on a ring, one round. xhat (list) is updated in place. Returns (x_out, codes, minmax) lists."""
+    k = len(x_in)
+    n = x_in[0].size
+    nc = num_chunks(n, chunk)
+    outs = [np.empty(n, np.float32) for _ in range(k)]
+    codes = [np.empty(n, np.uint8) for _ in range(k)]
+    minmax = [np.empty(2 * nc, np.float32) for _ in range(k)]
+    _ok(lib().oracle_ring_avg_lp(_ptr_array(x_in, np.float32), _ptr_array(outs, np.float32),
+                                  _ptr_array(xhat, np.float32), _ptr_array(codes, np.uint8),
+                                  _ptr_array(minmax, np.float32), k, n, chunk), "ring_avg_lp")
+    return outs, codes, minmax
+
+
+def sign_compress_ef(x, residual, chunk):
+    """Worker side of C_LP_S with Q = Sign-1bit. Returns (bits u32[ceil(n/32)], scale f32[nc])."""
+    n = x.size
+    bits = np.empty((n + 31) // 32, np.uint32)
+    scale = np.empty(num_chunks(n, chunk), np.float32)
+    _ok(lib().oracle_sign_compress_ef(_chk(x, np.float32), None if residual is None else _chk(residual, np.float32),
+                                       n, chunk, _chk(bits, np.uint32), _chk(scale, np.float32)), "sign_compress_ef")
+    return bits, scale
+
+
+def decompress_sign(bits, scale, n, chunk):
+    out = np.empty(n, np.float32)
+    _ok(lib().oracle_decompress_sign(_chk(bits, np.uint32), _chk(scale, np.float32), n, chunk,
+                                      _chk(out, np.float32)), "decompress_sign")
+    return out
+
+
+def drr_sign(bits_in, scale_in, server_residual, n, chunk, want_fp32=True):
+    """Server side of C_LP_S with Q = Sign-1bit. Returns (bits', scale', out_fp32 or None)."""
+    k = len(bits_in)
+    bits = np.empty((n + 31) // 32, np.uint32)
+    scale = np.empty(num_chunks(n, chunk), np.float32)
+    out = np.empty(n, np.float32) if want_fp32 else None
+    _ok(lib().oracle_drr_sign(_ptr_array(bits_in, np.uint32), _ptr_array(scale_in, np.float32), k,
+                               None if server_residual is None else _chk(server_residual, np.float32),
+                               n, chunk, _chk(bits, np.uint32), _chk(scale, np.float32),
+                               None if out is None else _chk(out, np.float32)), "drr_sign")
+    return bits, scale, out
+
+
+def bucket_flatten(srcs, dst_offset, bucket_numel):
+    """Flatten: copy every tensor to its element offset in a zero-filled bucket."""
+    T = len(srcs)
+    numel = (ctypes.c_size_t * max(T, 1))(*[s.size for s in srcs])
+    offs = (ctypes.c_size_t * max(T, 1))(*[int(o) for o in dst_offset])
+    bucket = np.empty(bucket_numel, np.float32)
+    ptrs = (ctypes.c_void_p * max(T, 1))()
+    for i, s in enumerate(srcs):
+        ptrs[i] = _chk(s, np.float32) if s.size else None
+    _ok(lib().oracle_bucket_flatten(ptrs, numel, offs, T, _chk(bucket, np.float32), bucket_numel), "bucket_flatten")
+    return bucket
