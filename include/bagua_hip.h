@@ -1,0 +1,156 @@
+/*
+ * bagua_hip.h -- C ABI of the MI355X (gfx950) compression hot path behind the communication
+ * primitives of "BAGUA: Scaling up Distributed Learning with System Relaxations".
+ *
+ * The library implements the on-device compute of the paper's primitives (Section 3.2,
+ * "Communication Primitives"): C_LP_S (centralised, low precision, with the error states
+ * delta and epsilon), D_FP_S / D_LP_S (decentralised, full / low precision) on the ring
+ * peer topology of Section 3.4, and the bucket flattening of Section 3.5.  The k workers
+ * (peers) are k buffers in one GPU's memory; nothing here communicates between GPUs.
+ *
+ * Conventions shared by every entry point
+ *   - Return value: BAGUA_OK or an error code below.  Nothing is enqueued when an error other
+ *     than BAGUA_ERR_LAUNCH is returned.  No exceptions, no aborts, nothing is printed.
+ *   - Pointers named "device" point to GPU memory owned by the caller; "host[k]" arrays are
+ *     host arrays of k device pointers and are only read during the call.  The library
+ *     allocates no device memory and keeps no state between calls.
+ *   - Bucket-level buffers (x, residual, codes, bits, minmax, scale, replicas, bucket) must be
+ *     16-byte aligned (BAGUA_ERR_ALIGNMENT otherwise).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
+ *     work and return without synchronising unless stated otherwise.
+ *   - n = number of fp32 elements of the bucket; chunk = C = elements per statistics chunk,
+ *     a multiple of 256 in [256, 16384]; nc = ceil(n / C); the last chunk may be short.
+ *   - All arithmetic is IEEE binary32, one rounding per operation in a fixed order (no fused
+ *     multiply-add), so results are reproducible bit for bit.  Inputs must be finite.
+ *   - The primitives return averages (the paper states sums): the sum over workers in
+ *     ascending index order is multiplied by fl(1/k), on the ring by fl(1/3).
+ *   - Error compensation follows the C_LP_S equations with the stored error carried in as
+ *     v = x + residual and updated as residual <- v - decode(Q(v)).
+ */
+#ifndef BAGUA_HIP_H
+#define BAGUA_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    BAGUA_OK = 0,
+    BAGUA_ERR_INVALID_ARG = 1, /* NULL where required, n == 0, k outside [1,32], bad chunk, bad enum, aliasing */
+    BAGUA_ERR_ALIGNMENT = 2,   /* a bucket-level pointer is not 16-byte aligned */
+    BAGUA_ERR_LAUNCH = 3,      /* the HIP runtime reported an error for a copy or a launch */
+    BAGUA_ERR_UNSUPPORTED = 4  /* valid request outside what this build implements */
+};
+
+enum { BAGUA_CODEC_MINMAX_U8 = 0, BAGUA_CODEC_SIGN1 = 1 };
+enum { BAGUA_AVG_FP = 0, BAGUA_AVG_LP_MINMAX_U8 = 1 };
+
+#define BAGUA_MAX_WORKERS 32
+
+/* Human-readable name of a status code (static storage). */
+const char* bagua_status_string(int status);
+
+/*
+ * Bucket flatten (Section 3.1 "Flattening"; Section 3.5 "Tensor Bucketing and Memory
+ * Flattening"): copy T layer tensors into one contiguous fp32 bucket, tensor t to elements
+ * [dst_offset[t], dst_offset[t] + numel[t]); every bucket element not covered by a tensor
+ * is set to +0.0f.
+ *   src         host[T] of device pointers to fp32 data, 4-byte aligned (may be NULL if numel[t] == 0)
+ *   numel       host[T]
+ *   dst_offset  host[T], in elements, ascending; tensors must not overlap and must fit
+ *   bucket      device, fp32[bucket_numel], 16-byte aligned
+ *   workspace   device, >= bagua_flatten_workspace_bytes(T, bucket_numel) bytes, 16-byte aligned;
+ *               holds the tensor table the copy kernel reads
+ * bagua_flatten_plan validates the layout and uploads the table into `workspace`; it
+ * SYNCHRONISES `stream` before returning (a set-up call: the layout of a bucket is fixed after
+ * the first iteration).  bagua_bucket_flatten_run only launches the copy using a planned
+ * workspace (T and bucket_numel must be those given to the plan).  bagua_bucket_flatten is
+ * plan followed by run.
+ */
+size_t bagua_flatten_workspace_bytes(size_t T, size_t bucket_numel);
+int bagua_flatten_plan(const void* const* src, const size_t* numel, const size_t* dst_offset, size_t T,
+                       size_t bucket_numel, void* workspace, size_t workspace_bytes, void* stream);
+int bagua_bucket_flatten_run(const void* workspace, size_t T, float* bucket, size_t bucket_numel, void* stream);
+int bagua_bucket_flatten(const void* const* src, const size_t* numel, const size_t* dst_offset, size_t T,
+                         float* bucket, size_t bucket_numel, void* workspace, size_t workspace_bytes,
+                         void* stream);
+
+/*
+ * Worker side of C_LP_S (Section 3.2, terms Q(x_j - delta_j) and delta_j' of the C_LP_S
+ * equations) with Q = per-chunk MinMax uint8:
+ *   v = x + residual (v = x if residual == NULL);  per chunk mn = min v, mx = max v;
+ *   code = clamp(rint((v - mn) * fl(255 / fl(mx - mn))), 0, 255)   (all 0 when mx == mn);
+ *   residual <- v - (mn + code * fl(fl(mx - mn) / 255)).
+ *   x        device fp32[n], read only
+ *   residual device fp32[n], updated in place, or NULL (no error compensation)
+ *   codes    device u8[n], written
+ *   minmax   device fp32[2*nc], written as (min, max) pairs; -0 is stored as +0
+ */
+int bagua_compress_minmax_u8(const float* x, float* residual, size_t n, size_t chunk,
+                             uint8_t* codes, float* minmax, void* stream);
+
+/*
+ * Server side of C_LP_S (Section 3.2, x_i' and epsilon_i' of the C_LP_S equations; steps 3-5 of
+ * ScatterReduce, Section 3.4): decode the k workers' compressed buckets, average them in
+ * ascending worker order, add the server error state, compress again, update the state:
+ *   a = (sum_j decode_j) * fl(1/k);  w = a + server_residual (w = a if NULL);
+ *   (codes_out, meta_out) = Q(w);  server_residual <- w - decode(Q(w));
+ *   out_fp32 (optional) = decode(Q(w)), the tensor every worker ends up with.
+ *   codec      BAGUA_CODEC_MINMAX_U8: codes are u8[n], meta is minmax fp32[2*nc]
+ *              BAGUA_CODEC_SIGN1:     codes are u32[ceil(n/32)] sign words, meta is scale fp32[nc]
+ *   codes_in   host[k] of device pointers;  meta_in host[k] of device pointers
+ *   k          number of workers, 1..BAGUA_MAX_WORKERS
+ *   codes_out, meta_out   device, written (must not alias any input)
+ *   out_fp32   device fp32[n] or NULL
+ */
+int bagua_decompress_reduce_recompress(int codec, const void* const* codes_in, const float* const* meta_in,
+                                       int k, float* server_residual, size_t n, size_t chunk,
+                                       void* codes_out, float* meta_out, float* out_fp32, void* stream);
+
+/*
+ * Decentralised averaging on a ring, one round (D_FP_S and D_LP_S equations, Section 3.2; "ring"
+ * peer allocation, Section 3.4).  Neighbours of peer i are i-1, i, i+1 (mod k) with weight 1/3;
+ * every output is computed from the old inputs.
+ *   BAGUA_AVG_FP:            x_out[i] = ((x_in[i-1] + x_in[i]) + x_in[i+1]) * fl(1/3)
+ *   BAGUA_AVG_LP_MINMAX_U8:  the wire carries Q(x_i - xhat_i) with Q = MinMax uint8, no error state:
+ *        (codes[i], minmax[i]) = Q(x_in[i] - xhat[i]);   xhat[i] <- xhat[i] + decode(codes[i], minmax[i]);
+ *        x_out[i] = ((xhat[i-1] + xhat[i]) + xhat[i+1]) * fl(1/3) + (x_in[i] - xhat[i])   (updated xhat)
+ *   x_in    host[k] of device fp32[n], read only
+ *   x_out   host[k] of device fp32[n], written; must not alias any x_in or xhat (BAGUA_ERR_INVALID_ARG)
+ *   xhat    host[k] of device fp32[n], LP only: public copies of the replicas, updated in place
+ *   codes   host[k] of device u8[n], LP only, written;  minmax host[k] of device fp32[2*nc], LP only, written
+ *   chunk   used by LP only (ignored for FP)
+ */
+int bagua_decentralized_avg(int mode, const float* const* x_in, float* const* x_out, float* const* xhat,
+                            uint8_t* const* codes, float* const* minmax, int k, size_t n, size_t chunk,
+                            void* stream);
+
+/*
+ * Worker side of C_LP_S with Q = 1-bit sign and per-chunk scale (the compression of "1-bit
+ * Adam", Section 4.1 "Bagua Algorithms"):
+ *   v = x + residual (v = x if NULL);  scale_c = mean over the chunk of |v| (fixed summation order);
+ *   bit = (v >= 0);  residual <- v - (bit ? +scale_c : -scale_c).
+ *   bits   device u32[ceil(n/32)], written; bit b of word w is element 32*w + b; unused tail bits are 0
+ *   scale  device fp32[nc], written
+ * Summation order of |v| within a chunk: groups of four consecutive elements reduced as
+ * (|a|+|b|)+(|c|+|d|), group m added to accumulator m mod 64, the 64 accumulators combined by
+ * acc[l] += acc[l xor s] for s = 1,2,4,8,16,32.  scale = sum * fl(1/C) for a full chunk with C a
+ * power of two, else sum / (float)length.
+ */
+int bagua_sign_compress_ef(const float* x, float* residual, size_t n, size_t chunk,
+                           uint32_t* bits, float* scale, void* stream);
+
+/*
+ * Decode a compressed bucket to fp32 (the last step of C_LP_S on every worker):
+ *   MINMAX_U8: out = mn + code * fl(fl(mx - mn) / 255);   SIGN1: out = bit ? +scale : -scale.
+ */
+int bagua_decompress(int codec, const void* codes, const float* meta, size_t n, size_t chunk,
+                     float* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BAGUA_HIP_H */

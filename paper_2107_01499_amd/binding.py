@@ -1,0 +1,173 @@
+"""Thin ctypes binding of libbagua_hip.so (include/bagua_hip.h).
+
+Argument marshalling only: every function takes torch tensors that already live on the GPU,
+passes their device pointers and the current HIP stream to the C entry point of the same name,
+and raises BaguaError on a non-zero status.  PyTorch is used for device memory and streams;
+no arithmetic of the method happens in Python and there is no CPU fallback: if the shared
+library is missing, importing this module fails.
+"""
+import ctypes
+import os
+
+import torch  # noqa: F401  (must be imported before the library so that both share one HIP runtime)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libbagua_hip.so")
+
+CODEC_MINMAX_U8 = 0
+CODEC_SIGN1 = 1
+AVG_FP = 0
+AVG_LP_MINMAX_U8 = 1
+MAX_WORKERS = 32
+
+EXPORTS = (
+    "bagua_status_string", "bagua_flatten_workspace_bytes", "bagua_flatten_plan", "bagua_bucket_flatten_run",
+    "bagua_bucket_flatten", "bagua_compress_minmax_u8", "bagua_decompress_reduce_recompress",
+    "bagua_decentralized_avg", "bagua_sign_compress_ef", "bagua_decompress",
+)
+
+
+class BaguaError(RuntimeError):
+    def __init__(self, fn, status):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (fn, status_string(status), status))
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libbagua_hip.so is not built (%s missing); run __graft_entry__.build() or "
+                          "python paper_2107_01499_amd/build.py" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    sz, vp, i32 = ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int
+    lib.bagua_status_string.restype = ctypes.c_char_p
+    lib.bagua_status_string.argtypes = [i32]
+    lib.bagua_flatten_workspace_bytes.restype = sz
+    lib.bagua_flatten_workspace_bytes.argtypes = [sz, sz]
+    lib.bagua_flatten_plan.argtypes = [vp, vp, vp, sz, sz, vp, sz, vp]
+    lib.bagua_bucket_flatten_run.argtypes = [vp, sz, vp, sz, vp]
+    lib.bagua_bucket_flatten.argtypes = [vp, vp, vp, sz, vp, sz, vp, sz, vp]
+    lib.bagua_compress_minmax_u8.argtypes = [vp, vp, sz, sz, vp, vp, vp]
+    lib.bagua_decompress_reduce_recompress.argtypes = [i32, vp, vp, i32, vp, sz, sz, vp, vp, vp, vp]
+    lib.bagua_decentralized_avg.argtypes = [i32, vp, vp, vp, vp, vp, i32, sz, sz, vp]
+    lib.bagua_sign_compress_ef.argtypes = [vp, vp, sz, sz, vp, vp, vp]
+    lib.bagua_decompress.argtypes = [i32, vp, vp, sz, sz, vp, vp]
+    for name in EXPORTS[2:]:
+        getattr(lib, name).restype = i32
+    return lib
+
+
+_lib = _load()
+
+
+def status_string(status):
+    return _lib.bagua_status_string(int(status)).decode()
+
+
+def _check(fn, rc):
+    if rc != 0:
+        raise BaguaError(fn, rc)
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous GPU tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("expected dtype %s, got %s" % (dtype, t.dtype))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _ptr_array(tensors, dtype=None):
+    arr = (ctypes.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = None if t is None else _ptr(t, dtype).value
+    return arr
+
+
+def num_chunks(n, chunk):
+    return (n + chunk - 1) // chunk
+
+
+def bagua_flatten_workspace_bytes(T, bucket_numel):
+    return int(_lib.bagua_flatten_workspace_bytes(T, bucket_numel))
+
+
+def _flatten_args(srcs, dst_offset):
+    T = len(srcs)
+    ptrs = (ctypes.c_void_p * max(T, 1))()
+    numel = (ctypes.c_size_t * max(T, 1))()
+    offs = (ctypes.c_size_t * max(T, 1))()
+    for i, s in enumerate(srcs):
+        if s.dtype != torch.float32 or not s.is_cuda or not s.is_contiguous():
+            raise ValueError("flatten sources must be contiguous fp32 GPU tensors")
+        ptrs[i] = s.data_ptr() if s.numel() else None
+        numel[i] = s.numel()
+        offs[i] = int(dst_offset[i])
+    return T, ptrs, numel, offs
+
+
+def bagua_flatten_plan(srcs, dst_offset, bucket_numel, workspace, stream=None):
+    """Upload the tensor table of one bucket into `workspace` (uint8 GPU tensor). Synchronises the stream."""
+    T, ptrs, numel, offs = _flatten_args(srcs, dst_offset)
+    _check("bagua_flatten_plan", _lib.bagua_flatten_plan(ptrs, numel, offs, T, bucket_numel, _ptr(workspace),
+                                                         workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def bagua_bucket_flatten_run(workspace, T, bucket, stream=None):
+    _check("bagua_bucket_flatten_run", _lib.bagua_bucket_flatten_run(_ptr(workspace), T, _ptr(bucket, torch.float32),
+                                                                     bucket.numel(), _stream(stream)))
+
+
+def bagua_bucket_flatten(srcs, dst_offset, bucket, workspace, stream=None):
+    T, ptrs, numel, offs = _flatten_args(srcs, dst_offset)
+    _check("bagua_bucket_flatten", _lib.bagua_bucket_flatten(ptrs, numel, offs, T, _ptr(bucket, torch.float32),
+                                                             bucket.numel(), _ptr(workspace),
+                                                             workspace.numel() * workspace.element_size(),
+                                                             _stream(stream)))
+
+
+def bagua_compress_minmax_u8(x, residual, chunk, codes, minmax, stream=None):
+    _check("bagua_compress_minmax_u8", _lib.bagua_compress_minmax_u8(
+        _ptr(x, torch.float32), _ptr(residual, torch.float32), x.numel(), chunk, _ptr(codes, torch.uint8),
+        _ptr(minmax, torch.float32), _stream(stream)))
+
+
+def bagua_decompress_reduce_recompress(codec, codes_in, meta_in, server_residual, n, chunk, codes_out, meta_out,
+                                       out_fp32=None, stream=None):
+    k = len(codes_in)
+    _check("bagua_decompress_reduce_recompress", _lib.bagua_decompress_reduce_recompress(
+        codec, _ptr_array(codes_in), _ptr_array(meta_in, torch.float32), k, _ptr(server_residual, torch.float32),
+        n, chunk, _ptr(codes_out), _ptr(meta_out, torch.float32), _ptr(out_fp32, torch.float32), _stream(stream)))
+
+
+def bagua_decentralized_avg(mode, x_in, x_out, xhat=None, codes=None, minmax=None, chunk=0, stream=None):
+    k = len(x_in)
+    n = x_in[0].numel()
+    _check("bagua_decentralized_avg", _lib.bagua_decentralized_avg(
+        mode, _ptr_array(x_in, torch.float32), _ptr_array(x_out, torch.float32),
+        None if xhat is None else _ptr_array(xhat, torch.float32),
+        None if codes is None else _ptr_array(codes, torch.uint8),
+        None if minmax is None else _ptr_array(minmax, torch.float32), k, n, chunk, _stream(stream)))
+
+
+def bagua_sign_compress_ef(x, residual, chunk, bits, scale, stream=None):
+    _check("bagua_sign_compress_ef", _lib.bagua_sign_compress_ef(
+        _ptr(x, torch.float32), _ptr(residual, torch.float32), x.numel(), chunk, _ptr(bits, torch.int32),
+        _ptr(scale, torch.float32), _stream(stream)))
+
+
+def bagua_decompress(codec, codes, meta, n, chunk, out, stream=None):
+    _check("bagua_decompress", _lib.bagua_decompress(codec, _ptr(codes), _ptr(meta, torch.float32), n, chunk,
+                                                     _ptr(out, torch.float32), _stream(stream)))
+
+
+def raw():
+    """The ctypes library object (tests call entry points with hand-made invalid arguments through it)."""
+    return _lib

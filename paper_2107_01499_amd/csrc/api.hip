@@ -1,0 +1,54 @@
+// C-ABI entry points that dispatch over the codec (see include/bagua_hip.h), and status strings.
+#include "launchers.hpp"
+
+using namespace bagua;
+
+extern "C" const char* bagua_status_string(int status)
+{
+    switch (status) {
+        case BAGUA_OK: return "BAGUA_OK";
+        case BAGUA_ERR_INVALID_ARG: return "BAGUA_ERR_INVALID_ARG";
+        case BAGUA_ERR_ALIGNMENT: return "BAGUA_ERR_ALIGNMENT";
+        case BAGUA_ERR_LAUNCH: return "BAGUA_ERR_LAUNCH";
+        case BAGUA_ERR_UNSUPPORTED: return "BAGUA_ERR_UNSUPPORTED";
+        default: return "BAGUA_ERR_UNKNOWN";
+    }
+}
+
+extern "C" int bagua_decompress_reduce_recompress(int codec, const void* const* codes_in, const float* const* meta_in,
+                                                  int k, float* server_residual, size_t n, size_t chunk,
+                                                  void* codes_out, float* meta_out, float* out_fp32, void* stream)
+{
+    if (codec != BAGUA_CODEC_MINMAX_U8 && codec != BAGUA_CODEC_SIGN1) return BAGUA_ERR_INVALID_ARG;
+    if (!codes_in || !meta_in || k < 1 || k > BAGUA_MAX_WORKERS || !codes_out || !meta_out || n == 0 ||
+        !chunk_ok(chunk))
+        return BAGUA_ERR_INVALID_ARG;
+    for (int j = 0; j < k; ++j) {
+        if (!codes_in[j] || !meta_in[j]) return BAGUA_ERR_INVALID_ARG;
+        if (codes_in[j] == codes_out || meta_in[j] == meta_out) return BAGUA_ERR_INVALID_ARG;
+    }
+    if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    for (int j = 0; j < k; ++j)
+        if (!aligned16(codes_in[j]) || !aligned16(meta_in[j])) return BAGUA_ERR_ALIGNMENT;
+    if (!aligned16(server_residual) || !aligned16(codes_out) || !aligned16(meta_out) || !aligned16(out_fp32))
+        return BAGUA_ERR_ALIGNMENT;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (codec == BAGUA_CODEC_MINMAX_U8)
+        return launch_drr_minmax(codes_in, meta_in, k, server_residual, n, chunk, static_cast<uint8_t*>(codes_out),
+                                 meta_out, out_fp32, s);
+    return launch_drr_sign(codes_in, meta_in, k, server_residual, n, chunk, static_cast<uint32_t*>(codes_out),
+                           meta_out, out_fp32, s);
+}
+
+extern "C" int bagua_decompress(int codec, const void* codes, const float* meta, size_t n, size_t chunk, float* out,
+                                void* stream)
+{
+    if (codec != BAGUA_CODEC_MINMAX_U8 && codec != BAGUA_CODEC_SIGN1) return BAGUA_ERR_INVALID_ARG;
+    if (!codes || !meta || !out || n == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
+    if (((n + kRow - 1) / kRow + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (!aligned16(codes) || !aligned16(meta) || !aligned16(out)) return BAGUA_ERR_ALIGNMENT;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (codec == BAGUA_CODEC_MINMAX_U8)
+        return launch_decompress_minmax(static_cast<const uint8_t*>(codes), meta, n, chunk, out, s);
+    return launch_decompress_sign(static_cast<const uint32_t*>(codes), meta, n, chunk, out, s);
+}

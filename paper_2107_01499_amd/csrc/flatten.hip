@@ -1,0 +1,146 @@
+// Bucket flatten (Section 3.1 "Flattening", Section 3.5 "Tensor Bucketing and Memory Flattening"):
+// gather T layer tensors into one contiguous fp32 bucket, zero-filling what no tensor covers.
+//
+// The copy is driven from the destination side: each lane owns 16-byte aligned groups of four
+// bucket elements and looks up which tensor covers them, so every bucket byte is written exactly
+// once with 128-bit stores (8 bytes of traffic per element).  A host-built table in the
+// caller's workspace gives, for every tile of the bucket, the first tensor that can intersect it.
+#include <vector>
+
+#include "common.hpp"
+
+namespace bagua {
+
+struct TensorDesc {
+    const float* src;
+    size_t numel;
+    size_t dst;  // element offset in the bucket
+};
+
+constexpr int kTile = 4096;  // bucket elements per workgroup (256 lanes x 4 groups of four)
+
+static size_t align16_up(size_t b) { return (b + 15) & ~static_cast<size_t>(15); }
+static size_t num_tiles(size_t bucket_numel) { return (bucket_numel + kTile - 1) / kTile; }
+
+// Value of bucket element e, starting the search at tensor t (the first tensor whose end is > some e' <= e).
+__device__ __forceinline__ float element_at(const TensorDesc* __restrict__ desc, uint32_t& t, uint32_t T, size_t e)
+{
+    while (t < T && desc[t].dst + desc[t].numel <= e) ++t;
+    if (t < T && desc[t].dst <= e) return desc[t].src[e - desc[t].dst];
+    return 0.0f;
+}
+
+__global__ void __launch_bounds__(256)
+k_flatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile_first, uint32_t T,
+          float* __restrict__ bucket, size_t bucket_numel)
+{
+    const size_t tile0 = static_cast<size_t>(blockIdx.x) * kTile;
+    const uint32_t lo0 = tile_first[blockIdx.x], hi0 = tile_first[blockIdx.x + 1];
+#pragma unroll
+    for (int g = 0; g < kTile / 1024; ++g) {
+        const size_t e = tile0 + static_cast<size_t>(g) * 1024 + threadIdx.x * 4;
+        if (e >= bucket_numel) continue;
+        // first tensor whose end lies beyond e, searched in [lo0, hi0]
+        uint32_t lo = lo0, hi = hi0;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (desc[mid].dst + desc[mid].numel <= e) lo = mid + 1;
+            else hi = mid;
+        }
+        uint32_t t = lo;
+        float4 v;
+        bool done = false;
+        if (t < T) {
+            const TensorDesc d = desc[t];
+            if (d.dst <= e && e + 4 <= d.dst + d.numel) {
+                const float* s = d.src + (e - d.dst);
+                if ((reinterpret_cast<uintptr_t>(s) & 15u) == 0) {
+                    v = *reinterpret_cast<const float4*>(s);
+                } else {
+                    v.x = s[0]; v.y = s[1]; v.z = s[2]; v.w = s[3];
+                }
+                done = true;
+            }
+        }
+        if (!done) {
+            v.x = (e + 0 < bucket_numel) ? element_at(desc, t, T, e + 0) : 0.0f;
+            v.y = (e + 1 < bucket_numel) ? element_at(desc, t, T, e + 1) : 0.0f;
+            v.z = (e + 2 < bucket_numel) ? element_at(desc, t, T, e + 2) : 0.0f;
+            v.w = (e + 3 < bucket_numel) ? element_at(desc, t, T, e + 3) : 0.0f;
+        }
+        if (e + 4 <= bucket_numel) {
+            *reinterpret_cast<float4*>(bucket + e) = v;
+        } else {
+            bucket[e] = v.x;
+            if (e + 1 < bucket_numel) bucket[e + 1] = v.y;
+            if (e + 2 < bucket_numel) bucket[e + 2] = v.z;
+        }
+    }
+}
+
+}  // namespace bagua
+
+using namespace bagua;
+
+extern "C" size_t bagua_flatten_workspace_bytes(size_t T, size_t bucket_numel)
+{
+    return align16_up((T ? T : 1) * sizeof(TensorDesc)) + align16_up((num_tiles(bucket_numel) + 1) * sizeof(uint32_t));
+}
+
+extern "C" int bagua_flatten_plan(const void* const* src, const size_t* numel, const size_t* dst_offset, size_t T,
+                                  size_t bucket_numel, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (bucket_numel == 0 || !workspace || (T && (!src || !numel || !dst_offset))) return BAGUA_ERR_INVALID_ARG;
+    if (T > 0xfffffff0u || num_tiles(bucket_numel) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (workspace_bytes < bagua_flatten_workspace_bytes(T, bucket_numel)) return BAGUA_ERR_INVALID_ARG;
+    if (!aligned16(workspace)) return BAGUA_ERR_ALIGNMENT;
+    size_t prev_end = 0;
+    for (size_t t = 0; t < T; ++t) {
+        if (numel[t] && !src[t]) return BAGUA_ERR_INVALID_ARG;
+        if (dst_offset[t] < prev_end) return BAGUA_ERR_INVALID_ARG;                 // ascending, no overlap
+        if (numel[t] > bucket_numel || dst_offset[t] > bucket_numel - numel[t]) return BAGUA_ERR_INVALID_ARG;
+        if (reinterpret_cast<uintptr_t>(src[t]) & 3u) return BAGUA_ERR_ALIGNMENT;
+        prev_end = dst_offset[t] + numel[t];
+    }
+    const size_t desc_bytes = align16_up((T ? T : 1) * sizeof(TensorDesc));
+    const size_t tiles = num_tiles(bucket_numel);
+    std::vector<unsigned char> host(bagua_flatten_workspace_bytes(T, bucket_numel), 0);
+    TensorDesc* d = reinterpret_cast<TensorDesc*>(host.data());
+    uint32_t* first = reinterpret_cast<uint32_t*>(host.data() + desc_bytes);
+    for (size_t t = 0; t < T; ++t) d[t] = TensorDesc{static_cast<const float*>(src[t]), numel[t], dst_offset[t]};
+    // first[i] = first tensor whose end lies beyond the start of tile i (T if none); first[tiles] = same for the end
+    size_t t = 0;
+    for (size_t i = 0; i <= tiles; ++i) {
+        const size_t e = i * static_cast<size_t>(kTile);
+        while (t < T && dst_offset[t] + numel[t] <= e) ++t;
+        first[i] = static_cast<uint32_t>(t);
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(workspace, host.data(), host.size(), hipMemcpyHostToDevice, s) != hipSuccess) return BAGUA_ERR_LAUNCH;
+    if (hipStreamSynchronize(s) != hipSuccess) return BAGUA_ERR_LAUNCH;   // `host` dies at return
+    return BAGUA_OK;
+}
+
+extern "C" int bagua_bucket_flatten_run(const void* workspace, size_t T, float* bucket, size_t bucket_numel, void* stream)
+{
+    if (!workspace || !bucket || bucket_numel == 0) return BAGUA_ERR_INVALID_ARG;
+    if (T > 0xfffffff0u || num_tiles(bucket_numel) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (!aligned16(workspace) || !aligned16(bucket)) return BAGUA_ERR_ALIGNMENT;
+    const size_t desc_bytes = align16_up((T ? T : 1) * sizeof(TensorDesc));
+    const TensorDesc* d = static_cast<const TensorDesc*>(workspace);
+    const uint32_t* first = reinterpret_cast<const uint32_t*>(static_cast<const unsigned char*>(workspace) + desc_bytes);
+    hipLaunchKernelGGL(k_flatten, dim3(static_cast<unsigned>(num_tiles(bucket_numel))), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), d, first, static_cast<uint32_t>(T), bucket, bucket_numel);
+    return launch_status();
+}
+
+extern "C" int bagua_bucket_flatten(const void* const* src, const size_t* numel, const size_t* dst_offset, size_t T,
+                                    float* bucket, size_t bucket_numel, void* workspace, size_t workspace_bytes,
+                                    void* stream)
+{
+    if (!bucket) return BAGUA_ERR_INVALID_ARG;
+    if (!aligned16(bucket)) return BAGUA_ERR_ALIGNMENT;
+    const int rc = bagua_flatten_plan(src, numel, dst_offset, T, bucket_numel, workspace, workspace_bytes, stream);
+    if (rc != BAGUA_OK) return rc;
+    return bagua_bucket_flatten_run(workspace, T, bucket, bucket_numel, stream);
+}

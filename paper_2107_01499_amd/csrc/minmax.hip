@@ -1,0 +1,220 @@
+// MinMax-u8 codec kernels: worker-side compress with error feedback, server-side
+// decompress-average-recompress, and plain decompress (C_LP_S, Section 3.2 of the paper).
+//
+// All three are single-pass streaming kernels bound by HBM bandwidth: a chunk lives in
+// registers between the statistics phase and the quantisation phase.
+#include "launchers.hpp"
+#include "minmax_device.hpp"
+
+#pragma clang fp contract(off)
+
+namespace bagua {
+
+// ------------------------------------------------------------------------------------------
+// Worker side: v = x (+ residual); codes = Q(v); residual <- v - decode.
+// grid = one workgroup per chunk, block = 64 * ceil(rows / RPW).
+template <int RPW, bool EF>
+__global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
+k_compress_minmax(const float* __restrict__ x, float* __restrict__ residual, size_t n, uint32_t chunk,
+                  uint8_t* __restrict__ codes, float* __restrict__ minmax)
+{
+    __shared__ float s_red[2 * kMaxWaves];
+    const size_t c = blockIdx.x;
+    const size_t base = c * static_cast<size_t>(chunk);
+    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+
+    float4 v[RPW];
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        const long off = static_cast<long>(wave * RPW + i) * kRow;
+        const long remain = len - off;
+        v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (remain > 0) v[i] = load_row(x + base + off, lane, remain, 0.0f);
+    }
+    if (EF) {
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const long off = static_cast<long>(wave * RPW + i) * kRow;
+            const long remain = len - off;
+            if (remain > 0) {
+                const float4 d = load_row(residual + base + off, lane, remain, 0.0f);
+                v[i].x = v[i].x + d.x;
+                v[i].y = v[i].y + d.y;
+                v[i].z = v[i].z + d.z;
+                v[i].w = v[i].w + d.w;
+            }
+        }
+    }
+    minmax_encode_chunk<RPW, EF, false>(v, len, wave, lane, nwaves, EF ? residual + base : nullptr,
+                                        codes + base, minmax + 2 * c, nullptr, s_red);
+}
+
+// ------------------------------------------------------------------------------------------
+// Server side: a = (sum_j decode_j) * inv_k in ascending j; w = a (+ epsilon); then as above.
+template <int RPW, bool EF, bool OUT>
+__global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
+k_drr_minmax(PtrTable codes_in, PtrTable meta_in, int k, float inv_k, float* __restrict__ eps, size_t n,
+             uint32_t chunk, uint8_t* __restrict__ codes_out, float* __restrict__ minmax_out,
+             float* __restrict__ out)
+{
+    __shared__ float s_red[2 * kMaxWaves];
+    __shared__ float s_mn[BAGUA_MAX_WORKERS], s_step[BAGUA_MAX_WORKERS];
+    const size_t c = blockIdx.x;
+    const size_t base = c * static_cast<size_t>(chunk);
+    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+
+    // per-worker (min, step) of this chunk: one lane per worker, so the k divisions run side by side
+    if (static_cast<int>(threadIdx.x) < k) {
+        const float* m = static_cast<const float*>(meta_in.p[threadIdx.x]);
+        const float mn = m[2 * c], mx = m[2 * c + 1];
+        s_mn[threadIdx.x] = mn;
+        s_step[threadIdx.x] = minmax_step(mn, mx);
+    }
+    __syncthreads();
+
+    float4 v[RPW];
+    for (int j = 0; j < k; ++j) {
+        const uint8_t* cj = static_cast<const uint8_t*>(codes_in.p[j]) + base;
+        const float mn = s_mn[j], step = s_step[j];
+        uint32_t w[RPW];
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const long off = static_cast<long>(wave * RPW + i) * kRow;
+            const long remain = len - off;
+            w[i] = 0;
+            if (remain > 0) w[i] = load_codes_row(cj + off, lane, remain);
+        }
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            float4 d;
+            d.x = mn + byte_to_float(w[i], 0) * step;
+            d.y = mn + byte_to_float(w[i], 1) * step;
+            d.z = mn + byte_to_float(w[i], 2) * step;
+            d.w = mn + byte_to_float(w[i], 3) * step;
+            if (j == 0) {
+                v[i] = d;
+            } else {
+                v[i].x = v[i].x + d.x;
+                v[i].y = v[i].y + d.y;
+                v[i].z = v[i].z + d.z;
+                v[i].w = v[i].w + d.w;
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        v[i].x = v[i].x * inv_k;
+        v[i].y = v[i].y * inv_k;
+        v[i].z = v[i].z * inv_k;
+        v[i].w = v[i].w * inv_k;
+    }
+    if (EF) {
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const long off = static_cast<long>(wave * RPW + i) * kRow;
+            const long remain = len - off;
+            if (remain > 0) {
+                const float4 d = load_row(eps + base + off, lane, remain, 0.0f);
+                v[i].x = v[i].x + d.x;
+                v[i].y = v[i].y + d.y;
+                v[i].z = v[i].z + d.z;
+                v[i].w = v[i].w + d.w;
+            }
+        }
+    }
+    minmax_encode_chunk<RPW, EF, OUT>(v, len, wave, lane, nwaves, EF ? eps + base : nullptr,
+                                      codes_out + base, minmax_out + 2 * c, OUT ? out + base : nullptr, s_red);
+}
+
+// ------------------------------------------------------------------------------------------
+// Decode: out = mn + code * step.  One wave per row, 4 rows per workgroup.
+__global__ void __launch_bounds__(256)
+k_decompress_minmax(const uint8_t* __restrict__ codes, const float* __restrict__ minmax, size_t n,
+                    uint32_t chunk, float* __restrict__ out)
+{
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const size_t e0 = row * kRow;
+    if (e0 >= n) return;
+    const size_t c = e0 / chunk;
+    const float mn = minmax[2 * c], step = minmax_step(mn, minmax[2 * c + 1]);
+    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const uint32_t w = load_codes_row(codes + e0, lane, remain);
+    float4 d;
+    d.x = mn + byte_to_float(w, 0) * step;
+    d.y = mn + byte_to_float(w, 1) * step;
+    d.z = mn + byte_to_float(w, 2) * step;
+    d.w = mn + byte_to_float(w, 3) * step;
+    store_row(out + e0, lane, remain, d);
+}
+
+// ------------------------------------------------------------------------------------------ host
+// Eight rows (2048 elements, 32 value registers per lane) per wave: chunk 4096 -> 2 waves per
+// workgroup, 8192 -> 4 waves, 16384 -> 8 waves.
+int launch_compress_minmax(const float* x, float* residual, size_t n, size_t chunk, uint8_t* codes,
+                           float* minmax, hipStream_t stream)
+{
+    const size_t nc = num_chunks(n, chunk);
+    const int rows = static_cast<int>(chunk / kRow);
+    constexpr int RPW = 8;
+    const int waves = (rows + RPW - 1) / RPW;
+    dim3 grid(static_cast<unsigned>(nc)), block(64 * waves);
+    if (residual)
+        hipLaunchKernelGGL((k_compress_minmax<RPW, true>), grid, block, 0, stream, x, residual, n,
+                           static_cast<uint32_t>(chunk), codes, minmax);
+    else
+        hipLaunchKernelGGL((k_compress_minmax<RPW, false>), grid, block, 0, stream, x, residual, n,
+                           static_cast<uint32_t>(chunk), codes, minmax);
+    return launch_status();
+}
+
+int launch_drr_minmax(const void* const* codes_in, const float* const* meta_in, int k, float* eps, size_t n,
+                      size_t chunk, uint8_t* codes_out, float* minmax_out, float* out, hipStream_t stream)
+{
+    PtrTable ct{}, mt{};
+    for (int j = 0; j < k; ++j) {
+        ct.p[j] = codes_in[j];
+        mt.p[j] = meta_in[j];
+    }
+    const size_t nc = num_chunks(n, chunk);
+    const int rows = static_cast<int>(chunk / kRow);
+    constexpr int RPW = 8;
+    const int waves = (rows + RPW - 1) / RPW;
+    dim3 grid(static_cast<unsigned>(nc)), block(64 * waves);
+    const float inv_k = 1.0f / static_cast<float>(k);
+    const uint32_t ch = static_cast<uint32_t>(chunk);
+#define BAGUA_DRR(EFv, OUTv)                                                                              \
+    hipLaunchKernelGGL((k_drr_minmax<RPW, EFv, OUTv>), grid, block, 0, stream, ct, mt, k, inv_k, eps, n, ch, \
+                       codes_out, minmax_out, out)
+    if (eps && out) BAGUA_DRR(true, true);
+    else if (eps) BAGUA_DRR(true, false);
+    else if (out) BAGUA_DRR(false, true);
+    else BAGUA_DRR(false, false);
+#undef BAGUA_DRR
+    return launch_status();
+}
+
+int launch_decompress_minmax(const uint8_t* codes, const float* minmax, size_t n, size_t chunk, float* out,
+                             hipStream_t stream)
+{
+    const size_t rows = (n + kRow - 1) / kRow;
+    dim3 grid(static_cast<unsigned>((rows + 3) / 4)), block(256);
+    hipLaunchKernelGGL(k_decompress_minmax, grid, block, 0, stream, codes, minmax, n,
+                       static_cast<uint32_t>(chunk), out);
+    return launch_status();
+}
+
+}  // namespace bagua
+
+using namespace bagua;
+
+extern "C" int bagua_compress_minmax_u8(const float* x, float* residual, size_t n, size_t chunk,
+                                        uint8_t* codes, float* minmax, void* stream)
+{
+    if (!x || !codes || !minmax || n == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
+    if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(residual) || !aligned16(codes) || !aligned16(minmax)) return BAGUA_ERR_ALIGNMENT;
+    return launch_compress_minmax(x, residual, n, chunk, codes, minmax, static_cast<hipStream_t>(stream));
+}

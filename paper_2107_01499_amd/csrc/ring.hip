@@ -1,0 +1,292 @@
+// Decentralised averaging on a ring (D_FP_S / D_LP_S, Section 3.2; ring peers, Section 3.4).
+//
+// Full precision: one thread owns the same four elements of all k replicas, so every replica is
+// read once and written once (8 bytes per element per peer) although each output has three inputs.
+// Low precision: one workgroup owns one chunk of all k peers.  The per-peer difference is
+// quantised, the public copies xhat are advanced and the three-neighbour mix is formed while x and
+// the new xhat of every peer are still in registers: 17 bytes per element per peer, one pass.
+#include "launchers.hpp"
+#include "minmax_device.hpp"
+
+#pragma clang fp contract(off)
+
+namespace bagua {
+
+__device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+__device__ __forceinline__ float4 sub4(float4 a, float4 b) { return make_float4(a.x - b.x, a.y - b.y, a.z - b.z, a.w - b.w); }
+__device__ __forceinline__ float4 mul4(float4 a, float s) { return make_float4(a.x * s, a.y * s, a.z * s, a.w * s); }
+
+// ------------------------------------------------------------------------------------------ FP
+// One wave per 256-element row; K replicas held in registers.
+template <int K>
+__global__ void __launch_bounds__(256)
+k_ring_avg_fp(PtrTable xin, MutPtrTable xout, size_t n, float third)
+{
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const size_t e0 = row * kRow;
+    if (e0 >= n) return;
+    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    float4 x[K];
+#pragma unroll
+    for (int i = 0; i < K; ++i) x[i] = load_row(static_cast<const float*>(xin.p[i]) + e0, lane, remain, 0.0f);
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+        const float4 s = add4(add4(x[(i + K - 1) % K], x[i]), x[(i + 1) % K]);
+        store_row(static_cast<float*>(xout.p[i]) + e0, lane, remain, mul4(s, third));
+    }
+}
+
+// Any k: rolling window over the peers (fewer loads in flight; used above the templated range).
+__global__ void __launch_bounds__(256)
+k_ring_avg_fp_any(PtrTable xin, MutPtrTable xout, int k, size_t n, float third)
+{
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const size_t e0 = row * kRow;
+    if (e0 >= n) return;
+    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const float4 first = load_row(static_cast<const float*>(xin.p[0]) + e0, lane, remain, 0.0f);
+    float4 prev = load_row(static_cast<const float*>(xin.p[k - 1]) + e0, lane, remain, 0.0f);
+    float4 cur = first;
+    for (int i = 0; i < k; ++i) {
+        const float4 next = (i + 1 < k) ? load_row(static_cast<const float*>(xin.p[i + 1]) + e0, lane, remain, 0.0f) : first;
+        const float4 s = add4(add4(prev, cur), next);
+        store_row(static_cast<float*>(xout.p[i]) + e0, lane, remain, mul4(s, third));
+        prev = cur;
+        cur = next;
+    }
+}
+
+// ------------------------------------------------------------------------------------------ LP, fused
+// Workgroup = one chunk of all K peers; wave w holds rows [w*RPW, (w+1)*RPW) of every peer.
+template <int K, int RPW>
+__global__ void __launch_bounds__(512)
+k_ring_avg_lp(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, MutPtrTable codes, MutPtrTable minmax, size_t n,
+              uint32_t chunk, float third)
+{
+    __shared__ float s_red[K][2 * kMaxWaves];
+    const size_t c = blockIdx.x;
+    const size_t base = c * static_cast<size_t>(chunk);
+    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+
+    float4 x[K][RPW], h[K][RPW];
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+            const long off = static_cast<long>(wave * RPW + r) * kRow;
+            const long remain = len - off;
+            x[i][r] = make_float4(0.f, 0.f, 0.f, 0.f);
+            h[i][r] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (remain > 0) {
+                x[i][r] = load_row(static_cast<const float*>(xin.p[i]) + base + off, lane, remain, 0.0f);
+                h[i][r] = load_row(static_cast<const float*>(xhat.p[i]) + base + off, lane, remain, 0.0f);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+        float4 d[RPW];
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) d[r] = sub4(x[i][r], h[i][r]);
+        // d <- decode(Q(d)); codes and (min,max) of peer i are written on the way
+        minmax_encode_chunk<RPW, false, false, true>(d, len, wave, lane, nwaves, nullptr,
+                                                     static_cast<uint8_t*>(codes.p[i]) + base,
+                                                     static_cast<float*>(minmax.p[i]) + 2 * c, nullptr, s_red[i]);
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+            const long off = static_cast<long>(wave * RPW + r) * kRow;
+            const long remain = len - off;
+            h[i][r] = add4(h[i][r], d[r]);
+            if (remain > 0) store_row(static_cast<float*>(xhat.p[i]) + base + off, lane, remain, h[i][r]);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+            const long off = static_cast<long>(wave * RPW + r) * kRow;
+            const long remain = len - off;
+            const float4 s = add4(add4(h[(i + K - 1) % K][r], h[i][r]), h[(i + 1) % K][r]);
+            const float4 o = add4(mul4(s, third), sub4(x[i][r], h[i][r]));
+            if (remain > 0) store_row(static_cast<float*>(xout.p[i]) + base + off, lane, remain, o);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------ LP, two-pass fallback
+// Pass 1 (per peer): d = x - xhat; codes, minmax = Q(d); xhat <- xhat + decode.
+template <int RPW>
+__global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
+k_lp_encode(const float* __restrict__ x, float* __restrict__ xhat, size_t n, uint32_t chunk,
+            uint8_t* __restrict__ codes, float* __restrict__ minmax)
+{
+    __shared__ float s_red[2 * kMaxWaves];
+    const size_t c = blockIdx.x;
+    const size_t base = c * static_cast<size_t>(chunk);
+    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    float4 h[RPW], d[RPW];
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) {
+        const long off = static_cast<long>(wave * RPW + r) * kRow;
+        const long remain = len - off;
+        h[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+        d[r] = h[r];
+        if (remain > 0) {
+            h[r] = load_row(xhat + base + off, lane, remain, 0.0f);
+            d[r] = sub4(load_row(x + base + off, lane, remain, 0.0f), h[r]);
+        }
+    }
+    minmax_encode_chunk<RPW, false, false, true>(d, len, wave, lane, nwaves, nullptr, codes + base,
+                                                 minmax + 2 * c, nullptr, s_red);
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) {
+        const long off = static_cast<long>(wave * RPW + r) * kRow;
+        const long remain = len - off;
+        if (remain > 0) store_row(xhat + base + off, lane, remain, add4(h[r], d[r]));
+    }
+}
+
+// Pass 2: x_out[i] = ((xhat[i-1] + xhat[i]) + xhat[i+1]) * third + (x[i] - xhat[i]), rolling over peers.
+__global__ void __launch_bounds__(256)
+k_lp_mix(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, int k, size_t n, float third)
+{
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const size_t e0 = row * kRow;
+    if (e0 >= n) return;
+    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const float4 first = load_row(static_cast<const float*>(xhat.p[0]) + e0, lane, remain, 0.0f);
+    float4 prev = load_row(static_cast<const float*>(xhat.p[k - 1]) + e0, lane, remain, 0.0f);
+    float4 cur = first;
+    for (int i = 0; i < k; ++i) {
+        const float4 next = (i + 1 < k) ? load_row(static_cast<const float*>(xhat.p[i + 1]) + e0, lane, remain, 0.0f) : first;
+        const float4 xi = load_row(static_cast<const float*>(xin.p[i]) + e0, lane, remain, 0.0f);
+        const float4 s = add4(add4(prev, cur), next);
+        store_row(static_cast<float*>(xout.p[i]) + e0, lane, remain, add4(mul4(s, third), sub4(xi, cur)));
+        prev = cur;
+        cur = next;
+    }
+}
+
+// ------------------------------------------------------------------------------------------ host
+template <int K>
+static void launch_fp_k(const PtrTable& in, const MutPtrTable& out, size_t n, float third, dim3 grid, hipStream_t s)
+{
+    hipLaunchKernelGGL((k_ring_avg_fp<K>), grid, dim3(256), 0, s, in, out, n, third);
+}
+
+static int launch_ring_fp(const float* const* x_in, float* const* x_out, int k, size_t n, hipStream_t stream)
+{
+    PtrTable in{};
+    MutPtrTable out{};
+    for (int i = 0; i < k; ++i) {
+        in.p[i] = x_in[i];
+        out.p[i] = x_out[i];
+    }
+    const size_t rows = (n + kRow - 1) / kRow;
+    dim3 grid(static_cast<unsigned>((rows + 3) / 4));
+    const float third = 1.0f / 3.0f;
+    switch (k) {
+#define BAGUA_FP_CASE(K) case K: launch_fp_k<K>(in, out, n, third, grid, stream); break;
+        BAGUA_FP_CASE(1) BAGUA_FP_CASE(2) BAGUA_FP_CASE(3) BAGUA_FP_CASE(4) BAGUA_FP_CASE(5) BAGUA_FP_CASE(6)
+        BAGUA_FP_CASE(7) BAGUA_FP_CASE(8) BAGUA_FP_CASE(9) BAGUA_FP_CASE(10) BAGUA_FP_CASE(11) BAGUA_FP_CASE(12)
+        BAGUA_FP_CASE(13) BAGUA_FP_CASE(14) BAGUA_FP_CASE(15) BAGUA_FP_CASE(16)
+#undef BAGUA_FP_CASE
+        default:
+            hipLaunchKernelGGL(k_ring_avg_fp_any, grid, dim3(256), 0, stream, in, out, k, n, third);
+    }
+    return launch_status();
+}
+
+template <int K>
+static void launch_lp_k(const PtrTable& in, const MutPtrTable& out, const MutPtrTable& hat, const MutPtrTable& cd,
+                        const MutPtrTable& mm, size_t n, uint32_t chunk, float third, dim3 grid, dim3 block,
+                        hipStream_t s)
+{
+    hipLaunchKernelGGL((k_ring_avg_lp<K, 2>), grid, block, 0, s, in, out, hat, cd, mm, n, chunk, third);
+}
+
+static int launch_ring_lp(const float* const* x_in, float* const* x_out, float* const* xhat, uint8_t* const* codes,
+                          float* const* minmax, int k, size_t n, size_t chunk, hipStream_t stream)
+{
+    PtrTable in{};
+    MutPtrTable out{}, hat{}, cd{}, mm{};
+    for (int i = 0; i < k; ++i) {
+        in.p[i] = x_in[i];
+        out.p[i] = x_out[i];
+        hat.p[i] = xhat[i];
+        cd.p[i] = codes[i];
+        mm.p[i] = minmax[i];
+    }
+    const float third = 1.0f / 3.0f;
+    const size_t nc = num_chunks(n, chunk);
+    const int rows = static_cast<int>(chunk / kRow);
+    if (k <= 8 && rows <= 16) {
+        dim3 grid(static_cast<unsigned>(nc)), block(64 * ((rows + 1) / 2));
+        const uint32_t ch = static_cast<uint32_t>(chunk);
+        switch (k) {
+#define BAGUA_LP_CASE(K) case K: launch_lp_k<K>(in, out, hat, cd, mm, n, ch, third, grid, block, stream); break;
+            BAGUA_LP_CASE(1) BAGUA_LP_CASE(2) BAGUA_LP_CASE(3) BAGUA_LP_CASE(4) BAGUA_LP_CASE(5) BAGUA_LP_CASE(6)
+            BAGUA_LP_CASE(7) BAGUA_LP_CASE(8)
+#undef BAGUA_LP_CASE
+        }
+        return launch_status();
+    }
+    // larger k or chunk: the chunk of all peers does not fit one workgroup's registers
+    constexpr int RPW = 8;
+    dim3 grid(static_cast<unsigned>(nc)), block(64 * ((rows + RPW - 1) / RPW));
+    for (int i = 0; i < k; ++i)
+        hipLaunchKernelGGL((k_lp_encode<RPW>), grid, block, 0, stream, x_in[i], xhat[i], n,
+                           static_cast<uint32_t>(chunk), codes[i], minmax[i]);
+    const size_t nrows = (n + kRow - 1) / kRow;
+    hipLaunchKernelGGL(k_lp_mix, dim3(static_cast<unsigned>((nrows + 3) / 4)), dim3(256), 0, stream, in, out, hat, k, n,
+                       third);
+    return launch_status();
+}
+
+}  // namespace bagua
+
+using namespace bagua;
+
+static bool overlaps(const void* a, const void* b, size_t bytes)
+{
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y + bytes && y < x + bytes;
+}
+
+extern "C" int bagua_decentralized_avg(int mode, const float* const* x_in, float* const* x_out, float* const* xhat,
+                                       uint8_t* const* codes, float* const* minmax, int k, size_t n, size_t chunk,
+                                       void* stream)
+{
+    if (mode != BAGUA_AVG_FP && mode != BAGUA_AVG_LP_MINMAX_U8) return BAGUA_ERR_INVALID_ARG;
+    if (!x_in || !x_out || k < 1 || k > BAGUA_MAX_WORKERS || n == 0) return BAGUA_ERR_INVALID_ARG;
+    const bool lp = mode == BAGUA_AVG_LP_MINMAX_U8;
+    if (lp && (!xhat || !codes || !minmax || !chunk_ok(chunk))) return BAGUA_ERR_INVALID_ARG;
+    for (int i = 0; i < k; ++i) {
+        if (!x_in[i] || !x_out[i]) return BAGUA_ERR_INVALID_ARG;
+        if (lp && (!xhat[i] || !codes[i] || !minmax[i])) return BAGUA_ERR_INVALID_ARG;
+    }
+    const size_t bytes = n * sizeof(float);
+    for (int i = 0; i < k; ++i) {
+        for (int j = 0; j < k; ++j) {
+            if (overlaps(x_out[i], x_in[j], bytes)) return BAGUA_ERR_INVALID_ARG;
+            if (j != i && overlaps(x_out[i], x_out[j], bytes)) return BAGUA_ERR_INVALID_ARG;
+            if (lp && overlaps(x_out[i], xhat[j], bytes)) return BAGUA_ERR_INVALID_ARG;
+            if (lp && overlaps(xhat[i], x_in[j], bytes)) return BAGUA_ERR_INVALID_ARG;
+            if (lp && j != i && overlaps(xhat[i], xhat[j], bytes)) return BAGUA_ERR_INVALID_ARG;
+        }
+    }
+    for (int i = 0; i < k; ++i) {
+        if (!aligned16(x_in[i]) || !aligned16(x_out[i])) return BAGUA_ERR_ALIGNMENT;
+        if (lp && (!aligned16(xhat[i]) || !aligned16(codes[i]) || !aligned16(minmax[i]))) return BAGUA_ERR_ALIGNMENT;
+    }
+    const size_t rows = (n + kRow - 1) / kRow;
+    if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!lp) return launch_ring_fp(x_in, x_out, k, n, s);
+    return launch_ring_lp(x_in, x_out, xhat, codes, minmax, k, n, chunk, s);
+}

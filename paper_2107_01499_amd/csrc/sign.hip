@@ -1,0 +1,308 @@
+// 1-bit sign codec kernels: worker-side compress with error feedback, server-side
+// decompress-average-recompress, and decompress (C_LP_S with the compression of "1-bit Adam",
+// Sections 3.2 and 4.1 of the paper).
+//
+// Lane l of a wave owns elements 4l..4l+3 of every 256-element row, so the group of four that the
+// fixed |v| summation order is defined on is exactly one lane's 128-bit load, accumulator m mod 64
+// is lane m mod 64, and the final xor butterfly is a wave-level shuffle reduction.
+#include "launchers.hpp"
+
+#pragma clang fp contract(off)
+
+namespace bagua {
+
+// Sum of |v| over the chunk in the fixed order (see bagua_sign_compress_ef in the header).
+// s_q: LDS, rows*64 floats, used only when the chunk is spread over several waves.
+template <int RPW>
+__device__ __forceinline__ float chunk_abs_sum(const float4 (&v)[RPW], int rows, int wave, int lane, int nwaves,
+                                               float* s_q)
+{
+    float acc = 0.0f;
+    if (nwaves == 1) {
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            if (i < rows) {
+                const float p = fabsf(v[i].x) + fabsf(v[i].y);
+                const float q = fabsf(v[i].z) + fabsf(v[i].w);
+                acc = acc + (p + q);
+            }
+        }
+    } else {
+        // rows are accumulated in row order, which crosses waves: park the per-row group sums in LDS
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const int row = wave * RPW + i;
+            if (row < rows) {
+                const float p = fabsf(v[i].x) + fabsf(v[i].y);
+                const float q = fabsf(v[i].z) + fabsf(v[i].w);
+                s_q[row * kWave + lane] = p + q;
+            }
+        }
+        __syncthreads();
+        for (int row = 0; row < rows; ++row) acc = acc + s_q[row * kWave + lane];
+    }
+    return wave_butterfly_sum(acc);
+}
+
+// OR of the 4-bit nibbles of the 8 lanes that share one 32-bit sign word.
+__device__ __forceinline__ uint32_t gather_word(uint32_t nib, int lane)
+{
+    uint32_t w = nib << (4 * (lane & 7));
+    w |= __shfl_xor(w, 1, kWave);
+    w |= __shfl_xor(w, 2, kWave);
+    w |= __shfl_xor(w, 4, kWave);
+    return w;
+}
+
+// Encode the chunk held in v (absent elements must be +0.0f).  `bits` points at the word of the
+// chunk's first element; residual/out point at the chunk's first element.
+template <int RPW, bool EF, bool OUT>
+__device__ __forceinline__ void sign_encode_chunk(float4 (&v)[RPW], long len, uint32_t chunk, int wave, int lane,
+                                                  int nwaves, float* __restrict__ residual,
+                                                  uint32_t* __restrict__ bits, float* __restrict__ scale_c,
+                                                  float* __restrict__ out, float* s_q)
+{
+    const int rows = static_cast<int>((len + kRow - 1) / kRow);
+    const float sum = chunk_abs_sum<RPW>(v, rows, wave, lane, nwaves, s_q);
+    const bool pow2 = (chunk & (chunk - 1)) == 0;
+    float scale;
+    if (len == static_cast<long>(chunk) && pow2) scale = sum * (1.0f / static_cast<float>(chunk));
+    else scale = sum / static_cast<float>(len);
+    if (threadIdx.x == 0) *scale_c = scale;
+    const float neg = -scale;
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        const long off = static_cast<long>(wave * RPW + i) * kRow;
+        const long remain = len - off;
+        if (remain <= 0) continue;
+        const int e = lane * 4;
+        const bool b0 = (v[i].x >= 0.0f) && (e + 0 < remain);
+        const bool b1 = (v[i].y >= 0.0f) && (e + 1 < remain);
+        const bool b2 = (v[i].z >= 0.0f) && (e + 2 < remain);
+        const bool b3 = (v[i].w >= 0.0f) && (e + 3 < remain);
+        const uint32_t nib = (b0 ? 1u : 0u) | (b1 ? 2u : 0u) | (b2 ? 4u : 0u) | (b3 ? 8u : 0u);
+        const uint32_t w = gather_word(nib, lane);
+        if ((lane & 7) == 0 && static_cast<long>(lane >> 3) * 32 < remain) bits[(off >> 5) + (lane >> 3)] = w;
+        if (EF || OUT) {
+            float4 deq;
+            deq.x = b0 ? scale : neg;
+            deq.y = b1 ? scale : neg;
+            deq.z = b2 ? scale : neg;
+            deq.w = b3 ? scale : neg;
+            if (EF) {
+                float4 r;
+                r.x = v[i].x - deq.x;
+                r.y = v[i].y - deq.y;
+                r.z = v[i].z - deq.z;
+                r.w = v[i].w - deq.w;
+                store_row(residual + off, lane, remain, r);
+            }
+            if (OUT) store_row(out + off, lane, remain, deq);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+template <int RPW, bool EF>
+__global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
+k_sign_compress(const float* __restrict__ x, float* __restrict__ residual, size_t n, uint32_t chunk,
+                uint32_t* __restrict__ bits, float* __restrict__ scale)
+{
+    extern __shared__ float s_q[];
+    const size_t c = blockIdx.x;
+    const size_t base = c * static_cast<size_t>(chunk);
+    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+
+    float4 v[RPW];
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        const long off = static_cast<long>(wave * RPW + i) * kRow;
+        const long remain = len - off;
+        v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (remain > 0) v[i] = load_row(x + base + off, lane, remain, 0.0f);
+    }
+    if (EF) {
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const long off = static_cast<long>(wave * RPW + i) * kRow;
+            const long remain = len - off;
+            if (remain > 0) {
+                const float4 d = load_row(residual + base + off, lane, remain, 0.0f);
+                v[i].x = v[i].x + d.x;
+                v[i].y = v[i].y + d.y;
+                v[i].z = v[i].z + d.z;
+                v[i].w = v[i].w + d.w;
+            }
+        }
+    }
+    sign_encode_chunk<RPW, EF, false>(v, len, chunk, wave, lane, nwaves, EF ? residual + base : nullptr,
+                                      bits + (base >> 5), scale + c, nullptr, s_q);
+}
+
+// Server side with the sign codec: a = (sum_j +-scale_j) * inv_k in ascending j; w = a (+ eps).
+template <int RPW, bool EF, bool OUT>
+__global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
+k_drr_sign(PtrTable bits_in, PtrTable scale_in, int k, float inv_k, float* __restrict__ eps, size_t n,
+           uint32_t chunk, uint32_t* __restrict__ bits_out, float* __restrict__ scale_out,
+           float* __restrict__ out)
+{
+    extern __shared__ float s_q[];
+    const size_t c = blockIdx.x;
+    const size_t base = c * static_cast<size_t>(chunk);
+    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int sh = 4 * (lane & 7);
+
+    float4 v[RPW];
+    for (int j = 0; j < k; ++j) {
+        const uint32_t* bj = static_cast<const uint32_t*>(bits_in.p[j]) + (base >> 5);
+        const float sc = static_cast<const float*>(scale_in.p[j])[c];
+        const float neg = -sc;
+        uint32_t w[RPW];
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const long off = static_cast<long>(wave * RPW + i) * kRow;
+            const long remain = len - off;
+            w[i] = 0;
+            if (static_cast<long>(lane >> 3) * 32 < remain) w[i] = bj[(off >> 5) + (lane >> 3)];
+        }
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const uint32_t nib = w[i] >> sh;
+            float4 d;
+            d.x = (nib & 1u) ? sc : neg;
+            d.y = (nib & 2u) ? sc : neg;
+            d.z = (nib & 4u) ? sc : neg;
+            d.w = (nib & 8u) ? sc : neg;
+            if (j == 0) {
+                v[i] = d;
+            } else {
+                v[i].x = v[i].x + d.x;
+                v[i].y = v[i].y + d.y;
+                v[i].z = v[i].z + d.z;
+                v[i].w = v[i].w + d.w;
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        const long off = static_cast<long>(wave * RPW + i) * kRow;
+        const long remain = len - off;
+        const int e = lane * 4;
+        // elements beyond the chunk must enter the |v| sum as +0.0f
+        v[i].x = (e + 0 < remain) ? v[i].x * inv_k : 0.0f;
+        v[i].y = (e + 1 < remain) ? v[i].y * inv_k : 0.0f;
+        v[i].z = (e + 2 < remain) ? v[i].z * inv_k : 0.0f;
+        v[i].w = (e + 3 < remain) ? v[i].w * inv_k : 0.0f;
+    }
+    if (EF) {
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const long off = static_cast<long>(wave * RPW + i) * kRow;
+            const long remain = len - off;
+            if (remain > 0) {
+                const float4 d = load_row(eps + base + off, lane, remain, 0.0f);
+                v[i].x = v[i].x + d.x;
+                v[i].y = v[i].y + d.y;
+                v[i].z = v[i].z + d.z;
+                v[i].w = v[i].w + d.w;
+            }
+        }
+    }
+    sign_encode_chunk<RPW, EF, OUT>(v, len, chunk, wave, lane, nwaves, EF ? eps + base : nullptr,
+                                    bits_out + (base >> 5), scale_out + c, OUT ? out + base : nullptr, s_q);
+}
+
+__global__ void __launch_bounds__(256)
+k_decompress_sign(const uint32_t* __restrict__ bits, const float* __restrict__ scale, size_t n, uint32_t chunk,
+                  float* __restrict__ out)
+{
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const size_t e0 = row * kRow;
+    if (e0 >= n) return;
+    const float sc = scale[e0 / chunk];
+    const float neg = -sc;
+    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    uint32_t w = 0;
+    if (static_cast<long>(lane >> 3) * 32 < remain) w = bits[(e0 >> 5) + (lane >> 3)];
+    const uint32_t nib = w >> (4 * (lane & 7));
+    float4 d;
+    d.x = (nib & 1u) ? sc : neg;
+    d.y = (nib & 2u) ? sc : neg;
+    d.z = (nib & 4u) ? sc : neg;
+    d.w = (nib & 8u) ? sc : neg;
+    store_row(out + e0, lane, remain, d);
+}
+
+// ------------------------------------------------------------------------------------------ host
+static void sign_geometry(size_t n, size_t chunk, dim3& grid, dim3& block, size_t& lds)
+{
+    constexpr int RPW = 8;
+    const int rows = static_cast<int>(chunk / kRow);
+    const int waves = (rows + RPW - 1) / RPW;
+    grid = dim3(static_cast<unsigned>(num_chunks(n, chunk)));
+    block = dim3(64 * waves);
+    lds = waves > 1 ? static_cast<size_t>(rows) * kWave * sizeof(float) : 0;
+}
+
+int launch_sign_compress(const float* x, float* residual, size_t n, size_t chunk, uint32_t* bits, float* scale,
+                         hipStream_t stream)
+{
+    dim3 grid, block;
+    size_t lds;
+    sign_geometry(n, chunk, grid, block, lds);
+    const uint32_t ch = static_cast<uint32_t>(chunk);
+    if (residual)
+        hipLaunchKernelGGL((k_sign_compress<8, true>), grid, block, lds, stream, x, residual, n, ch, bits, scale);
+    else
+        hipLaunchKernelGGL((k_sign_compress<8, false>), grid, block, lds, stream, x, residual, n, ch, bits, scale);
+    return launch_status();
+}
+
+int launch_drr_sign(const void* const* bits_in, const float* const* scale_in, int k, float* eps, size_t n,
+                    size_t chunk, uint32_t* bits_out, float* scale_out, float* out, hipStream_t stream)
+{
+    PtrTable bt{}, st{};
+    for (int j = 0; j < k; ++j) {
+        bt.p[j] = bits_in[j];
+        st.p[j] = scale_in[j];
+    }
+    dim3 grid, block;
+    size_t lds;
+    sign_geometry(n, chunk, grid, block, lds);
+    const float inv_k = 1.0f / static_cast<float>(k);
+    const uint32_t ch = static_cast<uint32_t>(chunk);
+#define BAGUA_DRR(EFv, OUTv)                                                                                \
+    hipLaunchKernelGGL((k_drr_sign<8, EFv, OUTv>), grid, block, lds, stream, bt, st, k, inv_k, eps, n, ch, \
+                       bits_out, scale_out, out)
+    if (eps && out) BAGUA_DRR(true, true);
+    else if (eps) BAGUA_DRR(true, false);
+    else if (out) BAGUA_DRR(false, true);
+    else BAGUA_DRR(false, false);
+#undef BAGUA_DRR
+    return launch_status();
+}
+
+int launch_decompress_sign(const uint32_t* bits, const float* scale, size_t n, size_t chunk, float* out,
+                           hipStream_t stream)
+{
+    const size_t rows = (n + kRow - 1) / kRow;
+    dim3 grid(static_cast<unsigned>((rows + 3) / 4)), block(256);
+    hipLaunchKernelGGL(k_decompress_sign, grid, block, 0, stream, bits, scale, n, static_cast<uint32_t>(chunk), out);
+    return launch_status();
+}
+
+}  // namespace bagua
+
+using namespace bagua;
+
+extern "C" int bagua_sign_compress_ef(const float* x, float* residual, size_t n, size_t chunk, uint32_t* bits,
+                                      float* scale, void* stream)
+{
+    if (!x || !bits || !scale || n == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
+    if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(residual) || !aligned16(bits) || !aligned16(scale)) return BAGUA_ERR_ALIGNMENT;
+    return launch_sign_compress(x, residual, n, chunk, bits, scale, static_cast<hipStream_t>(stream));
+}

@@ -1,0 +1,83 @@
+"""The C-ABI library: loads, exports every symbol the header declares, and rejects invalid arguments
+before touching the GPU (these calls return from host-side validation; no kernel is launched)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def bg():
+    import paper_2107_01499_amd as b
+    return b
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "bagua_hip.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bagua_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(bg):
+    names = declared_functions()
+    assert len(names) >= 10
+    lib = ctypes.CDLL(bg.binding.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(bg.binding.EXPORTS)
+
+
+def test_status_strings(bg):
+    assert bg.status_string(0) == "BAGUA_OK"
+    assert bg.status_string(1) == "BAGUA_ERR_INVALID_ARG"
+    assert bg.status_string(2) == "BAGUA_ERR_ALIGNMENT"
+    assert bg.status_string(3) == "BAGUA_ERR_LAUNCH"
+    assert bg.status_string(4) == "BAGUA_ERR_UNSUPPORTED"
+    assert bg.status_string(77) == "BAGUA_ERR_UNKNOWN"
+
+
+def test_validation_errors_without_gpu(bg):
+    lib = bg.binding.raw()
+    A = 0x1000  # a fake, 16-byte aligned "device pointer"; validation fails before it is ever used
+    INVALID, ALIGN = 1, 2
+    # compress: NULL, n == 0, bad chunk sizes, misalignment
+    assert lib.bagua_compress_minmax_u8(None, None, 10, 256, A, A, None) == INVALID
+    assert lib.bagua_compress_minmax_u8(A, None, 0, 256, A, A, None) == INVALID
+    for chunk in (0, 100, 255, 300, 16384 + 256):
+        assert lib.bagua_compress_minmax_u8(A, None, 10, chunk, A, A, None) == INVALID
+    assert lib.bagua_compress_minmax_u8(A + 4, None, 10, 256, A, A, None) == ALIGN
+    assert lib.bagua_compress_minmax_u8(A, A + 8, 10, 256, A, A, None) == ALIGN
+    assert lib.bagua_sign_compress_ef(A, None, 10, 128, A, A, None) == INVALID
+    assert lib.bagua_sign_compress_ef(A, None, 10, 256, A + 1, A, None) == ALIGN
+    # d-r-r: k range, codec enum, NULL entries
+    arr = (ctypes.c_void_p * 33)(*([A] * 33))
+    assert lib.bagua_decompress_reduce_recompress(0, arr, arr, 0, None, 10, 256, A + 16, A + 32, None, None) == INVALID
+    assert lib.bagua_decompress_reduce_recompress(0, arr, arr, 33, None, 10, 256, A + 16, A + 32, None, None) == INVALID
+    assert lib.bagua_decompress_reduce_recompress(2, arr, arr, 2, None, 10, 256, A + 16, A + 32, None, None) == INVALID
+    assert lib.bagua_decompress_reduce_recompress(0, arr, arr, 2, None, 10, 256, A, A + 32, None, None) == INVALID  # out aliases in
+    arr2 = (ctypes.c_void_p * 2)(A, None)
+    assert lib.bagua_decompress_reduce_recompress(0, arr2, arr, 2, None, 10, 256, A + 16, A + 32, None, None) == INVALID
+    # decentralised: aliasing and mode
+    xin = (ctypes.c_void_p * 2)(0x10000, 0x20000)
+    xout = (ctypes.c_void_p * 2)(0x30000, 0x40000)
+    assert lib.bagua_decentralized_avg(5, xin, xout, None, None, None, 2, 16, 0, None) == INVALID
+    assert lib.bagua_decentralized_avg(0, xin, xin, None, None, None, 2, 16, 0, None) == INVALID
+    assert lib.bagua_decentralized_avg(1, xin, xout, None, None, None, 2, 16, 256, None) == INVALID  # LP needs xhat
+    assert lib.bagua_decentralized_avg(0, xin, xout, None, None, None, 0, 16, 0, None) == INVALID
+    # flatten: overlap, overflow, workspace too small
+    src = (ctypes.c_void_p * 2)(A, A)
+    numel = (ctypes.c_size_t * 2)(10, 10)
+    assert lib.bagua_flatten_plan(src, numel, (ctypes.c_size_t * 2)(0, 5), 2, 100, A, 1 << 20, None) == INVALID
+    assert lib.bagua_flatten_plan(src, numel, (ctypes.c_size_t * 2)(0, 95), 2, 100, A, 1 << 20, None) == INVALID
+    assert lib.bagua_flatten_plan(src, numel, (ctypes.c_size_t * 2)(0, 10), 2, 100, A, 8, None) == INVALID
+    assert lib.bagua_decompress(0, None, A, 10, 256, A, None) == INVALID
+    assert bg.bagua_flatten_workspace_bytes(3, 10000) >= 3 * 24 + 4 * 4
+
+
+def test_missing_library_fails_loudly(bg, monkeypatch):
+    monkeypatch.setattr(bg.binding, "LIB_PATH", "/nonexistent/libbagua_hip.so")
+    with pytest.raises(ImportError):
+        bg.binding._load()

@@ -1,0 +1,331 @@
+"""GPU parity: every entry point of libbagua_hip.so against the CPU oracle on the same seeded inputs.
+
+Bar: bit-exact codes, sign words, (min,max), scales; fp32 outputs (residuals, averages, replicas) within
+1e-6 relative / 1e-7 absolute -- and the count of fp32 words that are not bit-identical is asserted to be 0,
+since both sides are specified with one rounding per operation in a fixed order.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+SIZES = [1, 3, 255, 256, 257, 4095, 4096, 4097, 2 * 4096 + 7, 70001]
+
+
+@pytest.fixture(scope="module")
+def bg():
+    import paper_2107_01499_amd as b
+    assert torch.cuda.is_available()
+    return b
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def vals(n, seed, dist="normal"):
+    r = np.random.default_rng(seed)
+    if dist == "normal":
+        return (r.standard_normal(n) * 1e-3).astype(np.float32)
+    if dist == "t3":
+        return (r.standard_t(3, n) * 1e-3).astype(np.float32)
+    if dist == "laplace":
+        return r.laplace(0, 1e-3, n).astype(np.float32)
+    raise ValueError(dist)
+
+
+def assert_fp32_close_and_exact(got, want, what):
+    got, want = np.asarray(got), np.asarray(want)
+    assert got.shape == want.shape, what
+    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    assert np.all(err <= 1e-6 * np.abs(want.astype(np.float64)) + 1e-7), what
+    nbad = int(np.count_nonzero(got.view(np.uint32) != want.view(np.uint32)))
+    assert nbad == 0, "%s: %d fp32 words not bit-identical" % (what, nbad)
+
+
+# ----------------------------------------------------------------------------- MinMax-u8 worker side
+def gpu_compress(bg, x, res, C):
+    n = x.size
+    xg = dev(x)
+    rg = None if res is None else dev(res)
+    codes = torch.full((n,), 0xAB, dtype=torch.uint8, device="cuda")
+    mm = torch.full((2 * bg.num_chunks(n, C),), float("nan"), device="cuda")
+    bg.bagua_compress_minmax_u8(xg, rg, C, codes, mm)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(xg), x)            # input untouched
+    return host(codes), host(mm), None if rg is None else host(rg)
+
+
+@pytest.mark.parametrize("n", SIZES)
+@pytest.mark.parametrize("C", [256, 768, 2048, 4096, 8192, 16384])
+@pytest.mark.parametrize("ef", [False, True])
+def test_compress_minmax(bg, oracle, n, C, ef):
+    print("compress_minmax n=%d C=%d ef=%s" % (n, C, ef), flush=True)
+    x = vals(n, n + C, "t3" if (n % 2) else "normal")
+    res = vals(n, n + C + 1) * np.float32(0.1) if ef else None
+    res_o = None if res is None else res.copy()
+    co, mo = oracle.compress_minmax_u8(x, res_o, C)
+    cg, mg, rg = gpu_compress(bg, x, res, C)
+    assert np.array_equal(cg, co)
+    assert np.array_equal(mg.view(np.uint32), mo.view(np.uint32))
+    if ef:
+        assert_fp32_close_and_exact(rg, res_o, "residual")
+
+
+def test_compress_edge_cases(bg, oracle):
+    C = 256
+    x = np.zeros(6 * C, np.float32)
+    x[0:C] = 0.375                                  # flat chunk
+    x[C:2 * C] = np.float32(-0.0); x[C + 3] = 0.0   # signed zeros
+    x[2 * C + 5] = np.float32(1e-40)                # denormal range: 255/range overflows
+    x[3 * C:4 * C] = np.linspace(-1e38, 1e38, C).astype(np.float32)   # huge range
+    x[4 * C:5 * C] = np.arange(C, dtype=np.float32); x[4 * C + 2:4 * C + 12] = np.arange(10, dtype=np.float32) + 0.5
+    x[4 * C + 1] = 255.0                            # ties -> even
+    x[5 * C:] = np.float32(1e-42) * np.arange(C, dtype=np.float32)   # all denormal
+    for ef in (False, True):
+        res = np.zeros_like(x) if ef else None
+        res_o = None if res is None else res.copy()
+        co, mo = oracle.compress_minmax_u8(x, res_o, C)
+        cg, mg, rg = gpu_compress(bg, x, res, C)
+        assert np.array_equal(cg, co)
+        assert np.array_equal(mg.view(np.uint32), mo.view(np.uint32))
+        if ef:
+            assert_fp32_close_and_exact(rg, res_o, "residual")
+
+
+def test_decompress_both_codecs(bg, oracle):
+    for n, C in [(1, 256), (257, 256), (3 * 4096 + 5, 4096), (70001, 2048)]:
+        x = vals(n, n, "t3")
+        co, mo = oracle.compress_minmax_u8(x, None, C)
+        out = torch.empty(n, device="cuda")
+        bg.bagua_decompress(bg.CODEC_MINMAX_U8, dev(co), dev(mo), n, C, out)
+        assert_fp32_close_and_exact(host(out), oracle.decompress_minmax_u8(co, mo, C), "decompress minmax")
+        bo, so = oracle.sign_compress_ef(x, None, C)
+        bg.bagua_decompress(bg.CODEC_SIGN1, dev(bo.view(np.int32)), dev(so), n, C, out)
+        assert_fp32_close_and_exact(host(out), oracle.decompress_sign(bo, so, n, C), "decompress sign")
+
+
+# ----------------------------------------------------------------------------- MinMax-u8 server side
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 8, 16, 32])
+@pytest.mark.parametrize("n,C", [(1, 256), (257, 256), (3 * 4096 + 77, 4096), (5 * 8192 + 1, 8192), (40000, 16384), (9000, 768)])
+@pytest.mark.parametrize("ef,want_out", [(True, True), (False, False), (True, False), (False, True)])
+def test_drr_minmax(bg, oracle, k, n, C, ef, want_out):
+    print("drr_minmax k=%d n=%d C=%d ef=%s out=%s" % (k, n, C, ef, want_out), flush=True)
+    codes_in, mm_in = [], []
+    for j in range(k):
+        c, m = oracle.compress_minmax_u8(vals(n, 1000 * k + j, "t3" if j % 2 else "normal"), None, C)
+        codes_in.append(c); mm_in.append(m)
+    eps = vals(n, 5) * np.float32(0.05) if ef else None
+    eps_o = None if eps is None else eps.copy()
+    co, mo, oo = oracle.drr_minmax_u8(codes_in, mm_in, eps_o, C, want_fp32=want_out)
+    eg = None if eps is None else dev(eps)
+    cg = torch.full((n,), 0xAB, dtype=torch.uint8, device="cuda")
+    mg = torch.full((2 * bg.num_chunks(n, C),), float("nan"), device="cuda")
+    og = torch.full((n,), float("nan"), device="cuda") if want_out else None
+    bg.bagua_decompress_reduce_recompress(bg.CODEC_MINMAX_U8, [dev(c) for c in codes_in], [dev(m) for m in mm_in],
+                                          eg, n, C, cg, mg, og)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(cg), co)
+    assert np.array_equal(host(mg).view(np.uint32), mo.view(np.uint32))
+    if ef:
+        assert_fp32_close_and_exact(host(eg), eps_o, "server residual")
+    if want_out:
+        assert_fp32_close_and_exact(host(og), oo, "out_fp32")
+
+
+def test_c_lp_s_three_iterations_state_carried(bg, oracle):
+    """Configuration-1-like loop: k workers compress with delta, the server averages with epsilon, three
+    iterations with fresh gradients; all state lives on the GPU between iterations."""
+    n, C, k = 5 * 4096 + 300, 4096, 4
+    nc = bg.num_chunks(n, C)
+    d_o = [np.zeros(n, np.float32) for _ in range(k)]
+    e_o = np.zeros(n, np.float32)
+    d_g = [torch.zeros(n, device="cuda") for _ in range(k)]
+    e_g = torch.zeros(n, device="cuda")
+    for it in range(3):
+        cs_o, ms_o, cs_g, ms_g = [], [], [], []
+        for j in range(k):
+            x = vals(n, 100 * it + j)
+            c, m = oracle.compress_minmax_u8(x, d_o[j], C)
+            cs_o.append(c); ms_o.append(m)
+            cg = torch.empty(n, dtype=torch.uint8, device="cuda"); mg = torch.empty(2 * nc, device="cuda")
+            bg.bagua_compress_minmax_u8(dev(x), d_g[j], C, cg, mg)
+            cs_g.append(cg); ms_g.append(mg)
+        co, mo, oo = oracle.drr_minmax_u8(cs_o, ms_o, e_o, C)
+        cg = torch.empty(n, dtype=torch.uint8, device="cuda"); mg = torch.empty(2 * nc, device="cuda")
+        og = torch.empty(n, device="cuda")
+        bg.bagua_decompress_reduce_recompress(bg.CODEC_MINMAX_U8, cs_g, ms_g, e_g, n, C, cg, mg, og)
+        assert np.array_equal(host(cg), co) and np.array_equal(host(mg).view(np.uint32), mo.view(np.uint32))
+        assert_fp32_close_and_exact(host(og), oo, "out iteration %d" % it)
+        assert_fp32_close_and_exact(host(e_g), e_o, "epsilon iteration %d" % it)
+        for j in range(k):
+            assert_fp32_close_and_exact(host(d_g[j]), d_o[j], "delta iteration %d" % it)
+
+
+# ----------------------------------------------------------------------------- sign codec
+@pytest.mark.parametrize("n", SIZES)
+@pytest.mark.parametrize("C", [256, 768, 2048, 4096, 16384])
+@pytest.mark.parametrize("ef", [False, True])
+def test_sign_compress(bg, oracle, n, C, ef):
+    print("sign_compress n=%d C=%d ef=%s" % (n, C, ef), flush=True)
+    x = vals(n, 3 * n + C, "laplace")
+    x[::97] = 0.0
+    x[1::97] = -0.0
+    res = vals(n, n + 1, "laplace") * np.float32(0.1) if ef else None
+    res_o = None if res is None else res.copy()
+    bo, so = oracle.sign_compress_ef(x, res_o, C)
+    rg = None if res is None else dev(res)
+    bits = torch.full(((n + 31) // 32,), -1, dtype=torch.int32, device="cuda")
+    scale = torch.full((bg.num_chunks(n, C),), float("nan"), device="cuda")
+    bg.bagua_sign_compress_ef(dev(x), rg, C, bits, scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(bits).view(np.uint32), bo)
+    assert np.array_equal(host(scale).view(np.uint32), so.view(np.uint32))
+    if ef:
+        assert_fp32_close_and_exact(host(rg), res_o, "sign residual")
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 8, 32])
+@pytest.mark.parametrize("n,C", [(1, 256), (257, 256), (5 * 2048 + 77, 2048), (3 * 4096 + 31, 4096), (40000, 16384), (9000, 768)])
+@pytest.mark.parametrize("ef,want_out", [(True, True), (False, False)])
+def test_drr_sign(bg, oracle, k, n, C, ef, want_out):
+    print("drr_sign k=%d n=%d C=%d ef=%s" % (k, n, C, ef), flush=True)
+    bits_in, scale_in = [], []
+    for j in range(k):
+        b, s = oracle.sign_compress_ef(vals(n, 77 * k + j, "laplace"), None, C)
+        bits_in.append(b); scale_in.append(s)
+    eps = vals(n, 6, "laplace") * np.float32(0.05) if ef else None
+    eps_o = None if eps is None else eps.copy()
+    bo, so, oo = oracle.drr_sign(bits_in, scale_in, eps_o, n, C, want_fp32=want_out)
+    eg = None if eps is None else dev(eps)
+    bg_ = torch.full(((n + 31) // 32,), -1, dtype=torch.int32, device="cuda")
+    sg = torch.full((bg.num_chunks(n, C),), float("nan"), device="cuda")
+    og = torch.full((n,), float("nan"), device="cuda") if want_out else None
+    bg.bagua_decompress_reduce_recompress(bg.CODEC_SIGN1, [dev(b.view(np.int32)) for b in bits_in],
+                                          [dev(s) for s in scale_in], eg, n, C, bg_, sg, og)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(bg_).view(np.uint32), bo)
+    assert np.array_equal(host(sg).view(np.uint32), so.view(np.uint32))
+    if ef:
+        assert_fp32_close_and_exact(host(eg), eps_o, "sign server residual")
+    if want_out:
+        assert_fp32_close_and_exact(host(og), oo, "sign out_fp32")
+
+
+# ----------------------------------------------------------------------------- decentralised averaging
+def make_replicas(k, n, seed):
+    r = np.random.default_rng(seed)
+    base = (r.standard_normal(n) * 0.02).astype(np.float32)
+    return base, [(base + (r.standard_normal(n) * 1e-3).astype(np.float32)).astype(np.float32) for _ in range(k)]
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 8, 16, 17, 32])
+@pytest.mark.parametrize("n", [1, 255, 1027, 70001])
+def test_ring_avg_fp(bg, oracle, k, n):
+    print("ring_fp k=%d n=%d" % (k, n), flush=True)
+    _, xs = make_replicas(k, n, k * 7 + n)
+    cur_o = xs
+    cur_g = [dev(x) for x in xs]
+    for rnd in range(3):
+        cur_o = oracle.ring_avg_fp(cur_o)
+        nxt = [torch.full((n,), float("nan"), device="cuda") for _ in range(k)]
+        bg.bagua_decentralized_avg(bg.AVG_FP, cur_g, nxt)
+        cur_g = nxt
+        for i in range(k):
+            assert_fp32_close_and_exact(host(cur_g[i]), cur_o[i], "ring fp round %d peer %d" % (rnd, i))
+
+
+@pytest.mark.parametrize("k,C", [(1, 256), (2, 4096), (3, 768), (8, 4096), (8, 256), (5, 2048), (9, 4096), (4, 8192), (16, 16384)])
+@pytest.mark.parametrize("n", [1, 257, 3 * 4096 + 77, 70001])
+def test_ring_avg_lp(bg, oracle, k, C, n):
+    print("ring_lp k=%d C=%d n=%d" % (k, C, n), flush=True)
+    base, xs = make_replicas(k, n, k * 13 + n + C)
+    nc = bg.num_chunks(n, C)
+    hat_o = [base.copy() for _ in range(k)]
+    hat_g = [dev(base) for _ in range(k)]
+    cur_o = xs
+    cur_g = [dev(x) for x in xs]
+    for rnd in range(3):
+        cur_o, codes_o, mm_o = oracle.ring_avg_lp(cur_o, hat_o, C)
+        nxt = [torch.full((n,), float("nan"), device="cuda") for _ in range(k)]
+        codes = [torch.full((n,), 0xAB, dtype=torch.uint8, device="cuda") for _ in range(k)]
+        mm = [torch.full((2 * nc,), float("nan"), device="cuda") for _ in range(k)]
+        bg.bagua_decentralized_avg(bg.AVG_LP_MINMAX_U8, cur_g, nxt, hat_g, codes, mm, C)
+        cur_g = nxt
+        for i in range(k):
+            assert np.array_equal(host(codes[i]), codes_o[i]), "codes round %d peer %d" % (rnd, i)
+            assert np.array_equal(host(mm[i]).view(np.uint32), mm_o[i].view(np.uint32))
+            assert_fp32_close_and_exact(host(hat_g[i]), hat_o[i], "xhat round %d peer %d" % (rnd, i))
+            assert_fp32_close_and_exact(host(cur_g[i]), cur_o[i], "x round %d peer %d" % (rnd, i))
+
+
+# ----------------------------------------------------------------------------- flatten
+def test_flatten_gaps_misaligned_and_tiny(bg, oracle):
+    r = np.random.default_rng(0)
+    sizes = [1, 7, 64, 1000, 3, 4096, 0, 129, 30522, 5, 5, 5, 8191, 2]
+    srcs = [r.standard_normal(s).astype(np.float32) for s in sizes]
+    offs, pos = [], 0
+    for i, s in enumerate(sizes):
+        pos += (i % 3)
+        offs.append(pos)
+        pos += s
+    total = pos + 50
+    want = oracle.bucket_flatten(srcs, offs, total)
+    # sources at deliberately odd (4-byte aligned only) device addresses
+    arena = torch.zeros(sum(sizes) + 4 * len(sizes) + 8, device="cuda")
+    gs, p = [], 1
+    for s in srcs:
+        t = arena[p:p + s.size]
+        t.copy_(torch.from_numpy(s))
+        gs.append(t)
+        p += s.size + 1
+    bucket = torch.full((total,), float("nan"), device="cuda")
+    ws = torch.empty(bg.bagua_flatten_workspace_bytes(len(srcs), total), dtype=torch.uint8, device="cuda")
+    bg.bagua_bucket_flatten(gs, offs, bucket, ws)
+    torch.cuda.synchronize()
+    assert host(bucket).tobytes() == want.tobytes()
+    # planned run again into a fresh bucket
+    bucket2 = torch.full((total,), float("nan"), device="cuda")
+    bg.bagua_bucket_flatten_run(ws, len(srcs), bucket2)
+    assert host(bucket2).tobytes() == want.tobytes()
+
+
+def test_flatten_empty_table_zero_fills(bg):
+    bucket = torch.full((5000,), float("nan"), device="cuda")
+    ws = torch.empty(bg.bagua_flatten_workspace_bytes(0, 5000), dtype=torch.uint8, device="cuda")
+    bg.bagua_bucket_flatten([], [], bucket, ws)
+    assert not host(bucket).view(np.uint32).any()
+
+
+def test_flatten_resnet50_bucket(bg, oracle):
+    from bagua_workloads import resnet50_shapes, pack_buckets
+    from bagua_workloads.shapes import numel
+    shapes = resnet50_shapes()
+    b = pack_buckets(shapes, 8, 4096)[0]
+    r = np.random.default_rng(2)
+    srcs = [r.standard_normal(numel(shapes[t][1])).astype(np.float32) for t in b.tensors]
+    want = oracle.bucket_flatten(srcs, b.offsets, b.n_pad)
+    gs = [dev(s) for s in srcs]
+    bucket = torch.full((b.n_pad,), float("nan"), device="cuda")
+    ws = torch.empty(bg.bagua_flatten_workspace_bytes(len(gs), b.n_pad), dtype=torch.uint8, device="cuda")
+    bg.bagua_bucket_flatten(gs, b.offsets, bucket, ws)
+    assert host(bucket).tobytes() == want.tobytes()
+
+
+def test_non_default_stream(bg, oracle):
+    n, C = 3 * 4096 + 1, 4096
+    x = vals(n, 1)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        xg = dev(x)
+        codes = torch.empty(n, dtype=torch.uint8, device="cuda")
+        mm = torch.empty(2 * bg.num_chunks(n, C), device="cuda")
+        bg.bagua_compress_minmax_u8(xg, None, C, codes, mm)
+    s.synchronize()
+    co, mo = oracle.compress_minmax_u8(x, None, C)
+    assert np.array_equal(host(codes), co) and np.array_equal(host(mm), mo)
