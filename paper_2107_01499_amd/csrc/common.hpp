@@ -18,6 +18,49 @@
 
 namespace bagua {
 
+// 128-bit lane payload as a native clang vector (the nontemporal builtins need one).
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+// Streaming accesses: every bucket byte is touched once per kernel, so loads and stores carry the
+// nontemporal hint and do not displace each other in L2 / Infinity Cache.
+#ifndef BAGUA_NT
+#define BAGUA_NT 1
+#endif
+template <typename T>
+__device__ __forceinline__ T ld_stream(const T* p)
+{
+#if BAGUA_NT
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+template <typename T>
+__device__ __forceinline__ void st_stream(T* p, T v)
+{
+#if BAGUA_NT
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
+
+// Preferred rows (of 256 elements) per wave for each chunked kernel.  Measured on MI355X: two rows
+// per wave (512 elements, 8 waves for a 4096-element chunk) stream fastest; the sign-codec server
+// kernel prefers four.  Larger values are used only when a chunk would need more than 16 waves.
+#ifndef BAGUA_RPW_COMPRESS
+#define BAGUA_RPW_COMPRESS 2
+#endif
+#ifndef BAGUA_RPW_DRR
+#define BAGUA_RPW_DRR 2
+#endif
+#ifndef BAGUA_RPW_SIGN
+#define BAGUA_RPW_SIGN 2
+#endif
+#ifndef BAGUA_RPW_DRR_SIGN
+#define BAGUA_RPW_DRR_SIGN 4
+#endif
+
 constexpr int kWave = 64;
 constexpr int kRow = 256;      // elements per wave-wide 128-bit access
 constexpr int kMaxWaves = 16;  // waves per workgroup (1024 threads)
@@ -53,11 +96,11 @@ __device__ __forceinline__ float wave_butterfly_sum(float v)
 // ---------------------------------------------------------------- row accessors with ragged tails
 // `remain` = number of valid elements counted from the start of the row (wave-uniform, may be <= 0
 // for an absent row or >= 256 for a full one).  Absent elements read as `fill`.
-__device__ __forceinline__ float4 load_row(const float* __restrict__ row, int lane, long remain, float fill)
+__device__ __forceinline__ f4 load_row(const float* __restrict__ row, int lane, long remain, float fill)
 {
-    float4 r;
+    f4 r;
     if (remain >= kRow) {
-        r = reinterpret_cast<const float4*>(row)[lane];
+        r = ld_stream(reinterpret_cast<const f4*>(row) + lane);
     } else {
         const int e = lane * 4;
         r.x = (e + 0 < remain) ? row[e + 0] : fill;
@@ -67,10 +110,10 @@ __device__ __forceinline__ float4 load_row(const float* __restrict__ row, int la
     }
     return r;
 }
-__device__ __forceinline__ void store_row(float* __restrict__ row, int lane, long remain, float4 v)
+__device__ __forceinline__ void store_row(float* __restrict__ row, int lane, long remain, f4 v)
 {
     if (remain >= kRow) {
-        reinterpret_cast<float4*>(row)[lane] = v;
+        st_stream(reinterpret_cast<f4*>(row) + lane, v);
     } else {
         const int e = lane * 4;
         if (e + 0 < remain) row[e + 0] = v.x;
@@ -82,7 +125,7 @@ __device__ __forceinline__ void store_row(float* __restrict__ row, int lane, lon
 // Four u8 codes per lane, little-endian in one dword.
 __device__ __forceinline__ uint32_t load_codes_row(const uint8_t* __restrict__ row, int lane, long remain)
 {
-    if (remain >= kRow) return reinterpret_cast<const uint32_t*>(row)[lane];
+    if (remain >= kRow) return ld_stream(reinterpret_cast<const uint32_t*>(row) + lane);
     uint32_t w = 0;
     const int e = lane * 4;
 #pragma unroll
@@ -93,7 +136,7 @@ __device__ __forceinline__ uint32_t load_codes_row(const uint8_t* __restrict__ r
 __device__ __forceinline__ void store_codes_row(uint8_t* __restrict__ row, int lane, long remain, uint32_t w)
 {
     if (remain >= kRow) {
-        reinterpret_cast<uint32_t*>(row)[lane] = w;
+        st_stream(reinterpret_cast<uint32_t*>(row) + lane, w);
     } else {
         const int e = lane * 4;
 #pragma unroll
@@ -116,6 +159,22 @@ inline bool chunk_ok(size_t chunk) { return chunk >= 256 && chunk <= 16384 && ch
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t num_chunks(size_t n, size_t chunk) { return (n + chunk - 1) / chunk; }
 constexpr size_t kMaxGrid = 0x7fffffffu;
+
+// Rows per wave actually used: the preferred value, doubled until the chunk fits kMaxWaves waves.
+inline int pick_rpw(int rows, int preferred)
+{
+    int rpw = preferred;
+    while (rpw < 8 && (rows + rpw - 1) / rpw > kMaxWaves) rpw *= 2;
+    return rpw;
+}
+
+// Expands `stmt` with a constexpr RPW equal to the runtime value rpw (2, 4 or 8).
+#define BAGUA_DISPATCH_RPW(rpw, stmt)                    \
+    switch (rpw) {                                        \
+        case 2: { constexpr int RPW = 2; stmt; } break;  \
+        case 4: { constexpr int RPW = 4; stmt; } break;  \
+        default: { constexpr int RPW = 8; stmt; } break; \
+    }
 
 inline int launch_status()
 {

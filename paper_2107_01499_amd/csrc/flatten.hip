@@ -48,14 +48,14 @@ k_flatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile
             else hi = mid;
         }
         uint32_t t = lo;
-        float4 v;
+        f4 v;
         bool done = false;
         if (t < T) {
             const TensorDesc d = desc[t];
             if (d.dst <= e && e + 4 <= d.dst + d.numel) {
                 const float* s = d.src + (e - d.dst);
                 if ((reinterpret_cast<uintptr_t>(s) & 15u) == 0) {
-                    v = *reinterpret_cast<const float4*>(s);
+                    v = *reinterpret_cast<const f4*>(s);
                 } else {
                     v.x = s[0]; v.y = s[1]; v.z = s[2]; v.w = s[3];
                 }
@@ -69,7 +69,7 @@ k_flatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile
             v.w = (e + 3 < bucket_numel) ? element_at(desc, t, T, e + 3) : 0.0f;
         }
         if (e + 4 <= bucket_numel) {
-            *reinterpret_cast<float4*>(bucket + e) = v;
+            *reinterpret_cast<f4*>(bucket + e) = v;
         } else {
             bucket[e] = v.x;
             if (e + 1 < bucket_numel) bucket[e + 1] = v.y;

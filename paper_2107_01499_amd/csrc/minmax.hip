@@ -24,12 +24,12 @@ k_compress_minmax(const float* __restrict__ x, float* __restrict__ residual, siz
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
-    float4 v[RPW];
+    f4 v[RPW];
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
         const long off = static_cast<long>(wave * RPW + i) * kRow;
         const long remain = len - off;
-        v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        v[i] = f4{0.f, 0.f, 0.f, 0.f};
         if (remain > 0) v[i] = load_row(x + base + off, lane, remain, 0.0f);
     }
     if (EF) {
@@ -38,7 +38,7 @@ k_compress_minmax(const float* __restrict__ x, float* __restrict__ residual, siz
             const long off = static_cast<long>(wave * RPW + i) * kRow;
             const long remain = len - off;
             if (remain > 0) {
-                const float4 d = load_row(residual + base + off, lane, remain, 0.0f);
+                const f4 d = load_row(residual + base + off, lane, remain, 0.0f);
                 v[i].x = v[i].x + d.x;
                 v[i].y = v[i].y + d.y;
                 v[i].z = v[i].z + d.z;
@@ -74,7 +74,7 @@ k_drr_minmax(PtrTable codes_in, PtrTable meta_in, int k, float inv_k, float* __r
     }
     __syncthreads();
 
-    float4 v[RPW];
+    f4 v[RPW];
     for (int j = 0; j < k; ++j) {
         const uint8_t* cj = static_cast<const uint8_t*>(codes_in.p[j]) + base;
         const float mn = s_mn[j], step = s_step[j];
@@ -88,7 +88,7 @@ k_drr_minmax(PtrTable codes_in, PtrTable meta_in, int k, float inv_k, float* __r
         }
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
-            float4 d;
+            f4 d;
             d.x = mn + byte_to_float(w[i], 0) * step;
             d.y = mn + byte_to_float(w[i], 1) * step;
             d.z = mn + byte_to_float(w[i], 2) * step;
@@ -116,7 +116,7 @@ k_drr_minmax(PtrTable codes_in, PtrTable meta_in, int k, float inv_k, float* __r
             const long off = static_cast<long>(wave * RPW + i) * kRow;
             const long remain = len - off;
             if (remain > 0) {
-                const float4 d = load_row(eps + base + off, lane, remain, 0.0f);
+                const f4 d = load_row(eps + base + off, lane, remain, 0.0f);
                 v[i].x = v[i].x + d.x;
                 v[i].y = v[i].y + d.y;
                 v[i].z = v[i].z + d.z;
@@ -142,7 +142,7 @@ k_decompress_minmax(const uint8_t* __restrict__ codes, const float* __restrict__
     const float mn = minmax[2 * c], step = minmax_step(mn, minmax[2 * c + 1]);
     const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
     const uint32_t w = load_codes_row(codes + e0, lane, remain);
-    float4 d;
+    f4 d;
     d.x = mn + byte_to_float(w, 0) * step;
     d.y = mn + byte_to_float(w, 1) * step;
     d.z = mn + byte_to_float(w, 2) * step;
@@ -151,22 +151,20 @@ k_decompress_minmax(const uint8_t* __restrict__ codes, const float* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------ host
-// Eight rows (2048 elements, 32 value registers per lane) per wave: chunk 4096 -> 2 waves per
-// workgroup, 8192 -> 4 waves, 16384 -> 8 waves.
 int launch_compress_minmax(const float* x, float* residual, size_t n, size_t chunk, uint8_t* codes,
                            float* minmax, hipStream_t stream)
 {
-    const size_t nc = num_chunks(n, chunk);
     const int rows = static_cast<int>(chunk / kRow);
-    constexpr int RPW = 8;
-    const int waves = (rows + RPW - 1) / RPW;
-    dim3 grid(static_cast<unsigned>(nc)), block(64 * waves);
-    if (residual)
-        hipLaunchKernelGGL((k_compress_minmax<RPW, true>), grid, block, 0, stream, x, residual, n,
-                           static_cast<uint32_t>(chunk), codes, minmax);
-    else
-        hipLaunchKernelGGL((k_compress_minmax<RPW, false>), grid, block, 0, stream, x, residual, n,
-                           static_cast<uint32_t>(chunk), codes, minmax);
+    const int rpw = pick_rpw(rows, BAGUA_RPW_COMPRESS);
+    dim3 grid(static_cast<unsigned>(num_chunks(n, chunk))), block(64 * ((rows + rpw - 1) / rpw));
+    const uint32_t ch = static_cast<uint32_t>(chunk);
+    if (residual) {
+        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_compress_minmax<RPW, true>), grid, block, 0, stream, x,
+                                                   residual, n, ch, codes, minmax))
+    } else {
+        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_compress_minmax<RPW, false>), grid, block, 0, stream, x,
+                                                   residual, n, ch, codes, minmax))
+    }
     return launch_status();
 }
 
@@ -178,20 +176,18 @@ int launch_drr_minmax(const void* const* codes_in, const float* const* meta_in, 
         ct.p[j] = codes_in[j];
         mt.p[j] = meta_in[j];
     }
-    const size_t nc = num_chunks(n, chunk);
     const int rows = static_cast<int>(chunk / kRow);
-    constexpr int RPW = 8;
-    const int waves = (rows + RPW - 1) / RPW;
-    dim3 grid(static_cast<unsigned>(nc)), block(64 * waves);
+    const int rpw = pick_rpw(rows, BAGUA_RPW_DRR);
+    dim3 grid(static_cast<unsigned>(num_chunks(n, chunk))), block(64 * ((rows + rpw - 1) / rpw));
     const float inv_k = 1.0f / static_cast<float>(k);
     const uint32_t ch = static_cast<uint32_t>(chunk);
-#define BAGUA_DRR(EFv, OUTv)                                                                              \
-    hipLaunchKernelGGL((k_drr_minmax<RPW, EFv, OUTv>), grid, block, 0, stream, ct, mt, k, inv_k, eps, n, ch, \
-                       codes_out, minmax_out, out)
-    if (eps && out) BAGUA_DRR(true, true);
-    else if (eps) BAGUA_DRR(true, false);
-    else if (out) BAGUA_DRR(false, true);
-    else BAGUA_DRR(false, false);
+#define BAGUA_DRR(EFv, OUTv)                                                                                   \
+    BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_drr_minmax<RPW, EFv, OUTv>), grid, block, 0, stream, ct, mt, \
+                                               k, inv_k, eps, n, ch, codes_out, minmax_out, out))
+    if (eps && out) { BAGUA_DRR(true, true) }
+    else if (eps) { BAGUA_DRR(true, false) }
+    else if (out) { BAGUA_DRR(false, true) }
+    else { BAGUA_DRR(false, false) }
 #undef BAGUA_DRR
     return launch_status();
 }

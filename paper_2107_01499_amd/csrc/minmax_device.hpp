@@ -10,7 +10,7 @@ namespace bagua {
 // of the chunk; rows beyond it are ignored.  Result is canonicalised (-0 -> +0).
 // s_red: LDS scratch of 2*kMaxWaves floats, not otherwise in use until the next barrier.
 template <int RPW>
-__device__ __forceinline__ void chunk_minmax(const float4 (&v)[RPW], long len, int wave, int lane, int nwaves,
+__device__ __forceinline__ void chunk_minmax(const f4 (&v)[RPW], long len, int wave, int lane, int nwaves,
                                              float* s_red, float& mn_out, float& mx_out)
 {
     float mn = INFINITY, mx = -INFINITY;
@@ -71,7 +71,7 @@ __device__ __forceinline__ uint32_t pack_codes(float q0, float q1, float q2, flo
 // (v - decode) and the decoded values.  Pointers are already offset to the start of the chunk.
 // If DEQ_BACK, v is overwritten with the decoded values (used by the decentralised LP kernel).
 template <int RPW, bool EF, bool OUT, bool DEQ_BACK = false>
-__device__ __forceinline__ void minmax_encode_chunk(float4 (&v)[RPW], long len, int wave, int lane, int nwaves,
+__device__ __forceinline__ void minmax_encode_chunk(f4 (&v)[RPW], long len, int wave, int lane, int nwaves,
                                                     float* __restrict__ residual, uint8_t* __restrict__ codes,
                                                     float* __restrict__ minmax_c, float* __restrict__ out,
                                                     float* s_red)
@@ -94,13 +94,13 @@ __device__ __forceinline__ void minmax_encode_chunk(float4 (&v)[RPW], long len, 
         const float q2 = quantise(v[i].z, mn, inv), q3 = quantise(v[i].w, mn, inv);
         store_codes_row(codes + off, lane, remain, pack_codes(q0, q1, q2, q3));
         if (EF || OUT || DEQ_BACK) {
-            float4 deq;
+            f4 deq;
             deq.x = mn + q0 * step;
             deq.y = mn + q1 * step;
             deq.z = mn + q2 * step;
             deq.w = mn + q3 * step;
             if (EF) {
-                float4 e;
+                f4 e;
                 e.x = v[i].x - deq.x;
                 e.y = v[i].y - deq.y;
                 e.z = v[i].z - deq.z;

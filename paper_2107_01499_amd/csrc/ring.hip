@@ -12,9 +12,9 @@
 
 namespace bagua {
 
-__device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
-__device__ __forceinline__ float4 sub4(float4 a, float4 b) { return make_float4(a.x - b.x, a.y - b.y, a.z - b.z, a.w - b.w); }
-__device__ __forceinline__ float4 mul4(float4 a, float s) { return make_float4(a.x * s, a.y * s, a.z * s, a.w * s); }
+__device__ __forceinline__ f4 add4(f4 a, f4 b) { return f4{a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w}; }
+__device__ __forceinline__ f4 sub4(f4 a, f4 b) { return f4{a.x - b.x, a.y - b.y, a.z - b.z, a.w - b.w}; }
+__device__ __forceinline__ f4 mul4(f4 a, float s) { return f4{a.x * s, a.y * s, a.z * s, a.w * s}; }
 
 // ------------------------------------------------------------------------------------------ FP
 // One wave per 256-element row; K replicas held in registers.
@@ -27,12 +27,12 @@ k_ring_avg_fp(PtrTable xin, MutPtrTable xout, size_t n, float third)
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
     const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
-    float4 x[K];
+    f4 x[K];
 #pragma unroll
     for (int i = 0; i < K; ++i) x[i] = load_row(static_cast<const float*>(xin.p[i]) + e0, lane, remain, 0.0f);
 #pragma unroll
     for (int i = 0; i < K; ++i) {
-        const float4 s = add4(add4(x[(i + K - 1) % K], x[i]), x[(i + 1) % K]);
+        const f4 s = add4(add4(x[(i + K - 1) % K], x[i]), x[(i + 1) % K]);
         store_row(static_cast<float*>(xout.p[i]) + e0, lane, remain, mul4(s, third));
     }
 }
@@ -46,12 +46,12 @@ k_ring_avg_fp_any(PtrTable xin, MutPtrTable xout, int k, size_t n, float third)
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
     const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
-    const float4 first = load_row(static_cast<const float*>(xin.p[0]) + e0, lane, remain, 0.0f);
-    float4 prev = load_row(static_cast<const float*>(xin.p[k - 1]) + e0, lane, remain, 0.0f);
-    float4 cur = first;
+    const f4 first = load_row(static_cast<const float*>(xin.p[0]) + e0, lane, remain, 0.0f);
+    f4 prev = load_row(static_cast<const float*>(xin.p[k - 1]) + e0, lane, remain, 0.0f);
+    f4 cur = first;
     for (int i = 0; i < k; ++i) {
-        const float4 next = (i + 1 < k) ? load_row(static_cast<const float*>(xin.p[i + 1]) + e0, lane, remain, 0.0f) : first;
-        const float4 s = add4(add4(prev, cur), next);
+        const f4 next = (i + 1 < k) ? load_row(static_cast<const float*>(xin.p[i + 1]) + e0, lane, remain, 0.0f) : first;
+        const f4 s = add4(add4(prev, cur), next);
         store_row(static_cast<float*>(xout.p[i]) + e0, lane, remain, mul4(s, third));
         prev = cur;
         cur = next;
@@ -71,15 +71,15 @@ k_ring_avg_lp(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, MutPtrTable code
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
-    float4 x[K][RPW], h[K][RPW];
+    f4 x[K][RPW], h[K][RPW];
 #pragma unroll
     for (int i = 0; i < K; ++i) {
 #pragma unroll
         for (int r = 0; r < RPW; ++r) {
             const long off = static_cast<long>(wave * RPW + r) * kRow;
             const long remain = len - off;
-            x[i][r] = make_float4(0.f, 0.f, 0.f, 0.f);
-            h[i][r] = make_float4(0.f, 0.f, 0.f, 0.f);
+            x[i][r] = f4{0.f, 0.f, 0.f, 0.f};
+            h[i][r] = f4{0.f, 0.f, 0.f, 0.f};
             if (remain > 0) {
                 x[i][r] = load_row(static_cast<const float*>(xin.p[i]) + base + off, lane, remain, 0.0f);
                 h[i][r] = load_row(static_cast<const float*>(xhat.p[i]) + base + off, lane, remain, 0.0f);
@@ -88,7 +88,7 @@ k_ring_avg_lp(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, MutPtrTable code
     }
 #pragma unroll
     for (int i = 0; i < K; ++i) {
-        float4 d[RPW];
+        f4 d[RPW];
 #pragma unroll
         for (int r = 0; r < RPW; ++r) d[r] = sub4(x[i][r], h[i][r]);
         // d <- decode(Q(d)); codes and (min,max) of peer i are written on the way
@@ -109,8 +109,8 @@ k_ring_avg_lp(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, MutPtrTable code
         for (int r = 0; r < RPW; ++r) {
             const long off = static_cast<long>(wave * RPW + r) * kRow;
             const long remain = len - off;
-            const float4 s = add4(add4(h[(i + K - 1) % K][r], h[i][r]), h[(i + 1) % K][r]);
-            const float4 o = add4(mul4(s, third), sub4(x[i][r], h[i][r]));
+            const f4 s = add4(add4(h[(i + K - 1) % K][r], h[i][r]), h[(i + 1) % K][r]);
+            const f4 o = add4(mul4(s, third), sub4(x[i][r], h[i][r]));
             if (remain > 0) store_row(static_cast<float*>(xout.p[i]) + base + off, lane, remain, o);
         }
     }
@@ -128,12 +128,12 @@ k_lp_encode(const float* __restrict__ x, float* __restrict__ xhat, size_t n, uin
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
-    float4 h[RPW], d[RPW];
+    f4 h[RPW], d[RPW];
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
         const long off = static_cast<long>(wave * RPW + r) * kRow;
         const long remain = len - off;
-        h[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+        h[r] = f4{0.f, 0.f, 0.f, 0.f};
         d[r] = h[r];
         if (remain > 0) {
             h[r] = load_row(xhat + base + off, lane, remain, 0.0f);
@@ -159,13 +159,13 @@ k_lp_mix(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, int k, size_t n, floa
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
     const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
-    const float4 first = load_row(static_cast<const float*>(xhat.p[0]) + e0, lane, remain, 0.0f);
-    float4 prev = load_row(static_cast<const float*>(xhat.p[k - 1]) + e0, lane, remain, 0.0f);
-    float4 cur = first;
+    const f4 first = load_row(static_cast<const float*>(xhat.p[0]) + e0, lane, remain, 0.0f);
+    f4 prev = load_row(static_cast<const float*>(xhat.p[k - 1]) + e0, lane, remain, 0.0f);
+    f4 cur = first;
     for (int i = 0; i < k; ++i) {
-        const float4 next = (i + 1 < k) ? load_row(static_cast<const float*>(xhat.p[i + 1]) + e0, lane, remain, 0.0f) : first;
-        const float4 xi = load_row(static_cast<const float*>(xin.p[i]) + e0, lane, remain, 0.0f);
-        const float4 s = add4(add4(prev, cur), next);
+        const f4 next = (i + 1 < k) ? load_row(static_cast<const float*>(xhat.p[i + 1]) + e0, lane, remain, 0.0f) : first;
+        const f4 xi = load_row(static_cast<const float*>(xin.p[i]) + e0, lane, remain, 0.0f);
+        const f4 s = add4(add4(prev, cur), next);
         store_row(static_cast<float*>(xout.p[i]) + e0, lane, remain, add4(mul4(s, third), sub4(xi, cur)));
         prev = cur;
         cur = next;
@@ -237,11 +237,12 @@ static int launch_ring_lp(const float* const* x_in, float* const* x_out, float* 
         return launch_status();
     }
     // larger k or chunk: the chunk of all peers does not fit one workgroup's registers
-    constexpr int RPW = 8;
-    dim3 grid(static_cast<unsigned>(nc)), block(64 * ((rows + RPW - 1) / RPW));
-    for (int i = 0; i < k; ++i)
-        hipLaunchKernelGGL((k_lp_encode<RPW>), grid, block, 0, stream, x_in[i], xhat[i], n,
-                           static_cast<uint32_t>(chunk), codes[i], minmax[i]);
+    const int rpw = pick_rpw(rows, BAGUA_RPW_COMPRESS);
+    dim3 grid(static_cast<unsigned>(nc)), block(64 * ((rows + rpw - 1) / rpw));
+    for (int i = 0; i < k; ++i) {
+        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_lp_encode<RPW>), grid, block, 0, stream, x_in[i], xhat[i], n,
+                                                   static_cast<uint32_t>(chunk), codes[i], minmax[i]))
+    }
     const size_t nrows = (n + kRow - 1) / kRow;
     hipLaunchKernelGGL(k_lp_mix, dim3(static_cast<unsigned>((nrows + 3) / 4)), dim3(256), 0, stream, in, out, hat, k, n,
                        third);

@@ -14,7 +14,7 @@ namespace bagua {
 // Sum of |v| over the chunk in the fixed order (see bagua_sign_compress_ef in the header).
 // s_q: LDS, rows*64 floats, used only when the chunk is spread over several waves.
 template <int RPW>
-__device__ __forceinline__ float chunk_abs_sum(const float4 (&v)[RPW], int rows, int wave, int lane, int nwaves,
+__device__ __forceinline__ float chunk_abs_sum(const f4 (&v)[RPW], int rows, int wave, int lane, int nwaves,
                                                float* s_q)
 {
     float acc = 0.0f;
@@ -57,7 +57,7 @@ __device__ __forceinline__ uint32_t gather_word(uint32_t nib, int lane)
 // Encode the chunk held in v (absent elements must be +0.0f).  `bits` points at the word of the
 // chunk's first element; residual/out point at the chunk's first element.
 template <int RPW, bool EF, bool OUT>
-__device__ __forceinline__ void sign_encode_chunk(float4 (&v)[RPW], long len, uint32_t chunk, int wave, int lane,
+__device__ __forceinline__ void sign_encode_chunk(f4 (&v)[RPW], long len, uint32_t chunk, int wave, int lane,
                                                   int nwaves, float* __restrict__ residual,
                                                   uint32_t* __restrict__ bits, float* __restrict__ scale_c,
                                                   float* __restrict__ out, float* s_q)
@@ -84,13 +84,13 @@ __device__ __forceinline__ void sign_encode_chunk(float4 (&v)[RPW], long len, ui
         const uint32_t w = gather_word(nib, lane);
         if ((lane & 7) == 0 && static_cast<long>(lane >> 3) * 32 < remain) bits[(off >> 5) + (lane >> 3)] = w;
         if (EF || OUT) {
-            float4 deq;
+            f4 deq;
             deq.x = b0 ? scale : neg;
             deq.y = b1 ? scale : neg;
             deq.z = b2 ? scale : neg;
             deq.w = b3 ? scale : neg;
             if (EF) {
-                float4 r;
+                f4 r;
                 r.x = v[i].x - deq.x;
                 r.y = v[i].y - deq.y;
                 r.z = v[i].z - deq.z;
@@ -114,12 +114,12 @@ k_sign_compress(const float* __restrict__ x, float* __restrict__ residual, size_
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
-    float4 v[RPW];
+    f4 v[RPW];
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
         const long off = static_cast<long>(wave * RPW + i) * kRow;
         const long remain = len - off;
-        v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        v[i] = f4{0.f, 0.f, 0.f, 0.f};
         if (remain > 0) v[i] = load_row(x + base + off, lane, remain, 0.0f);
     }
     if (EF) {
@@ -128,7 +128,7 @@ k_sign_compress(const float* __restrict__ x, float* __restrict__ residual, size_
             const long off = static_cast<long>(wave * RPW + i) * kRow;
             const long remain = len - off;
             if (remain > 0) {
-                const float4 d = load_row(residual + base + off, lane, remain, 0.0f);
+                const f4 d = load_row(residual + base + off, lane, remain, 0.0f);
                 v[i].x = v[i].x + d.x;
                 v[i].y = v[i].y + d.y;
                 v[i].z = v[i].z + d.z;
@@ -154,7 +154,7 @@ k_drr_sign(PtrTable bits_in, PtrTable scale_in, int k, float inv_k, float* __res
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
     const int sh = 4 * (lane & 7);
 
-    float4 v[RPW];
+    f4 v[RPW];
     for (int j = 0; j < k; ++j) {
         const uint32_t* bj = static_cast<const uint32_t*>(bits_in.p[j]) + (base >> 5);
         const float sc = static_cast<const float*>(scale_in.p[j])[c];
@@ -170,7 +170,7 @@ k_drr_sign(PtrTable bits_in, PtrTable scale_in, int k, float inv_k, float* __res
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
             const uint32_t nib = w[i] >> sh;
-            float4 d;
+            f4 d;
             d.x = (nib & 1u) ? sc : neg;
             d.y = (nib & 2u) ? sc : neg;
             d.z = (nib & 4u) ? sc : neg;
@@ -202,7 +202,7 @@ k_drr_sign(PtrTable bits_in, PtrTable scale_in, int k, float inv_k, float* __res
             const long off = static_cast<long>(wave * RPW + i) * kRow;
             const long remain = len - off;
             if (remain > 0) {
-                const float4 d = load_row(eps + base + off, lane, remain, 0.0f);
+                const f4 d = load_row(eps + base + off, lane, remain, 0.0f);
                 v[i].x = v[i].x + d.x;
                 v[i].y = v[i].y + d.y;
                 v[i].z = v[i].z + d.z;
@@ -228,7 +228,7 @@ k_decompress_sign(const uint32_t* __restrict__ bits, const float* __restrict__ s
     uint32_t w = 0;
     if (static_cast<long>(lane >> 3) * 32 < remain) w = bits[(e0 >> 5) + (lane >> 3)];
     const uint32_t nib = w >> (4 * (lane & 7));
-    float4 d;
+    f4 d;
     d.x = (nib & 1u) ? sc : neg;
     d.y = (nib & 2u) ? sc : neg;
     d.z = (nib & 4u) ? sc : neg;
@@ -237,27 +237,35 @@ k_decompress_sign(const uint32_t* __restrict__ bits, const float* __restrict__ s
 }
 
 // ------------------------------------------------------------------------------------------ host
-static void sign_geometry(size_t n, size_t chunk, dim3& grid, dim3& block, size_t& lds)
+struct SignGeometry {
+    dim3 grid, block;
+    size_t lds;
+    int rpw;
+};
+static SignGeometry sign_geometry(size_t n, size_t chunk, int preferred)
 {
-    constexpr int RPW = 8;
+    SignGeometry g;
     const int rows = static_cast<int>(chunk / kRow);
-    const int waves = (rows + RPW - 1) / RPW;
-    grid = dim3(static_cast<unsigned>(num_chunks(n, chunk)));
-    block = dim3(64 * waves);
-    lds = waves > 1 ? static_cast<size_t>(rows) * kWave * sizeof(float) : 0;
+    g.rpw = pick_rpw(rows, preferred);
+    const int waves = (rows + g.rpw - 1) / g.rpw;
+    g.grid = dim3(static_cast<unsigned>(num_chunks(n, chunk)));
+    g.block = dim3(64 * waves);
+    g.lds = waves > 1 ? static_cast<size_t>(rows) * kWave * sizeof(float) : 0;
+    return g;
 }
 
 int launch_sign_compress(const float* x, float* residual, size_t n, size_t chunk, uint32_t* bits, float* scale,
                          hipStream_t stream)
 {
-    dim3 grid, block;
-    size_t lds;
-    sign_geometry(n, chunk, grid, block, lds);
+    const SignGeometry g = sign_geometry(n, chunk, BAGUA_RPW_SIGN);
     const uint32_t ch = static_cast<uint32_t>(chunk);
-    if (residual)
-        hipLaunchKernelGGL((k_sign_compress<8, true>), grid, block, lds, stream, x, residual, n, ch, bits, scale);
-    else
-        hipLaunchKernelGGL((k_sign_compress<8, false>), grid, block, lds, stream, x, residual, n, ch, bits, scale);
+    if (residual) {
+        BAGUA_DISPATCH_RPW(g.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, true>), g.grid, g.block, g.lds, stream, x,
+                                                     residual, n, ch, bits, scale))
+    } else {
+        BAGUA_DISPATCH_RPW(g.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, false>), g.grid, g.block, g.lds, stream, x,
+                                                     residual, n, ch, bits, scale))
+    }
     return launch_status();
 }
 
@@ -269,18 +277,16 @@ int launch_drr_sign(const void* const* bits_in, const float* const* scale_in, in
         bt.p[j] = bits_in[j];
         st.p[j] = scale_in[j];
     }
-    dim3 grid, block;
-    size_t lds;
-    sign_geometry(n, chunk, grid, block, lds);
+    const SignGeometry g = sign_geometry(n, chunk, BAGUA_RPW_DRR_SIGN);
     const float inv_k = 1.0f / static_cast<float>(k);
     const uint32_t ch = static_cast<uint32_t>(chunk);
-#define BAGUA_DRR(EFv, OUTv)                                                                                \
-    hipLaunchKernelGGL((k_drr_sign<8, EFv, OUTv>), grid, block, lds, stream, bt, st, k, inv_k, eps, n, ch, \
-                       bits_out, scale_out, out)
-    if (eps && out) BAGUA_DRR(true, true);
-    else if (eps) BAGUA_DRR(true, false);
-    else if (out) BAGUA_DRR(false, true);
-    else BAGUA_DRR(false, false);
+#define BAGUA_DRR(EFv, OUTv)                                                                                      \
+    BAGUA_DISPATCH_RPW(g.rpw, hipLaunchKernelGGL((k_drr_sign<RPW, EFv, OUTv>), g.grid, g.block, g.lds, stream, bt, \
+                                                 st, k, inv_k, eps, n, ch, bits_out, scale_out, out))
+    if (eps && out) { BAGUA_DRR(true, true) }
+    else if (eps) { BAGUA_DRR(true, false) }
+    else if (out) { BAGUA_DRR(false, true) }
+    else { BAGUA_DRR(false, false) }
 #undef BAGUA_DRR
     return launch_status();
 }
