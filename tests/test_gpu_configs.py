@@ -1,0 +1,252 @@
+"""GPU parity at the five benchmark configurations' full sizes, in the launch configuration bench.py times
+(one launch per worker covering all its buckets).
+
+Inputs are drawn on the GPU by the seeded generators of bagua_workloads and the identical bits are copied to
+the host for the oracle.  Configurations 1 and 2 are compared element by element; configurations 3-5 run at
+full size on the GPU and are compared on sampled chunk-aligned ranges (first, last/ragged and seeded random
+ones): chunks are independent of each other in every primitive, so the oracle run on a range of whole chunks
+is exactly the oracle's result for those elements.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+
+
+@pytest.fixture(scope="module")
+def bg():
+    import paper_2107_01499_amd as b
+    assert torch.cuda.is_available()
+    return b
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def exact(got, want, what):
+    got, want = np.ascontiguousarray(got), np.ascontiguousarray(want)
+    assert got.shape == want.shape, what
+    if got.dtype == np.float32:
+        err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+        assert np.all(err <= 1e-6 * np.abs(want.astype(np.float64)) + 1e-7), what
+        nbad = int(np.count_nonzero(got.view(np.uint32) != want.view(np.uint32)))
+        assert nbad == 0, "%s: %d fp32 words not bit-identical" % (what, nbad)
+    else:
+        assert np.array_equal(got, want), what
+
+
+def ranges(n, C, count, span_chunks, seed):
+    """Chunk-aligned sample ranges: the first chunks, the last ones (ragged tail included) and random ones."""
+    nc = (n + C - 1) // C
+    span = min(span_chunks, nc)
+    r = np.random.default_rng(seed)
+    starts = {0, nc - span}
+    while len(starts) < min(count, nc // span):
+        starts.add(int(r.integers(0, nc - span + 1)))
+    return [(s * C, min(n, (s + span) * C)) for s in sorted(starts)]
+
+
+# ------------------------------------------------------------------------------------------------- config 1
+def test_config1_single_bucket(bg, oracle):
+    from bagua_workloads import draw, seed_for
+    n, k, C = 1048576, 4, 4096
+    nc = n // C
+    xs = [draw("normal", n, seed_for(0, 0, j), DEV, 1e-3) for j in range(k)]
+    delta = [torch.zeros(n, device=DEV) for _ in range(k)]
+    codes = [torch.empty(n, dtype=torch.uint8, device=DEV) for _ in range(k)]
+    mm = [torch.empty(2 * nc, device=DEV) for _ in range(k)]
+    for j in range(k):
+        bg.bagua_compress_minmax_u8(xs[j], delta[j], C, codes[j], mm[j])
+    eps = torch.zeros(n, device=DEV)
+    c2 = torch.empty(n, dtype=torch.uint8, device=DEV); m2 = torch.empty(2 * nc, device=DEV); out = torch.empty(n, device=DEV)
+    bg.bagua_decompress_reduce_recompress(bg.CODEC_MINMAX_U8, codes, mm, eps, n, C, c2, m2, out)
+    co, mo = [], []
+    for j in range(k):
+        d = np.zeros(n, np.float32)
+        c, m = oracle.compress_minmax_u8(host(xs[j]), d, C)
+        exact(host(codes[j]), c, "codes %d" % j); exact(host(mm[j]), m, "minmax %d" % j); exact(host(delta[j]), d, "delta %d" % j)
+        co.append(c); mo.append(m)
+    e = np.zeros(n, np.float32)
+    c, m, o = oracle.drr_minmax_u8(co, mo, e, C)
+    exact(host(c2), c, "server codes"); exact(host(m2), m, "server minmax"); exact(host(out), o, "out"); exact(host(eps), e, "epsilon")
+
+
+# ------------------------------------------------------------------------------------------------- config 2
+def test_config2_resnet50_three_iterations(bg, oracle):
+    """The C_LP_S chain of configuration 2: flatten, compress with delta, server step with
+    epsilon, three iterations with fresh gradients, one launch per worker over its five buckets; every element
+    compared.  The per-bucket launch of the same work must give the same bits."""
+    from bagua_workloads import resnet50_shapes, pack_buckets, draw, seed_for, layer_sigmas
+    from bagua_workloads.shapes import numel
+    from bagua_workloads.generators import SHARED
+    k, C = 8, 4096
+    shapes = resnet50_shapes()
+    sizes = [numel(s) for _, s in shapes]
+    starts = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+    buckets = pack_buckets(shapes, k, C)
+    bases = np.concatenate([[0], np.cumsum([b.n_pad for b in buckets])]).tolist()
+    n = bases[-1]
+    nc = n // C
+    sig = layer_sigmas(len(shapes), seed_for(1, 0, SHARED))
+    ids, offs = [], []
+    for b, bk in enumerate(buckets):
+        ids += list(bk.tensors)
+        offs += [bases[b] + o for o in bk.offsets]
+    delta_g = [torch.zeros(n, device=DEV) for _ in range(k)]
+    eps_g = torch.zeros(n, device=DEV)
+    delta_o = [np.zeros(n, np.float32) for _ in range(k)]
+    eps_o = np.zeros(n, np.float32)
+    ws = torch.empty(bg.bagua_flatten_workspace_bytes(len(ids), n), dtype=torch.uint8, device=DEV)
+    for it in range(3):
+        print("config 2 iteration", it, flush=True)
+        codes_g, mm_g, codes_o, mm_o = [], [], [], []
+        for j in range(k):
+            arena = draw("normal", starts[-1], seed_for(1, it, j), DEV, 1.0)
+            layers = []
+            for t in range(len(sizes)):
+                v = arena[starts[t]:starts[t + 1]]
+                v.mul_(sig[t])
+                layers.append(v)
+            flat = torch.full((n,), float("nan"), device=DEV)
+            bg.bagua_bucket_flatten([layers[t] for t in ids], offs, flat, ws)
+            lay_h = [host(l) for l in layers]
+            flat_o = np.concatenate([oracle.bucket_flatten([lay_h[t] for t in bk.tensors], bk.offsets, bk.n_pad) for bk in buckets])
+            assert host(flat).tobytes() == flat_o.tobytes(), "flatten worker %d" % j
+            cg = torch.empty(n, dtype=torch.uint8, device=DEV); mg = torch.empty(2 * nc, device=DEV)
+            if it == 1 and j == 0:
+                # per-bucket launches into the same buffers: must equal the single launch bit for bit
+                d2 = delta_g[j].clone(); c2 = torch.empty_like(cg); m2 = torch.empty_like(mg)
+                for b, bk in enumerate(buckets):
+                    lo, hi = bases[b], bases[b + 1]
+                    bg.bagua_compress_minmax_u8(flat[lo:hi], d2[lo:hi], C, c2[lo:hi], m2[2 * lo // C:2 * hi // C])
+            bg.bagua_compress_minmax_u8(flat, delta_g[j], C, cg, mg)
+            if it == 1 and j == 0:
+                assert torch.equal(c2, cg) and torch.equal(m2, mg) and torch.equal(d2.view(torch.int32), delta_g[j].view(torch.int32))
+            c, m = oracle.compress_minmax_u8(flat_o, delta_o[j], C)
+            exact(host(cg), c, "codes it %d worker %d" % (it, j)); exact(host(mg), m, "minmax")
+            exact(host(delta_g[j]), delta_o[j], "delta it %d worker %d" % (it, j))
+            codes_g.append(cg); mm_g.append(mg); codes_o.append(c); mm_o.append(m)
+        c2 = torch.empty(n, dtype=torch.uint8, device=DEV); m2 = torch.empty(2 * nc, device=DEV); out = torch.empty(n, device=DEV)
+        bg.bagua_decompress_reduce_recompress(bg.CODEC_MINMAX_U8, codes_g, mm_g, eps_g, n, C, c2, m2, out)
+        c, m, o = oracle.drr_minmax_u8(codes_o, mm_o, eps_o, C)
+        exact(host(c2), c, "server codes it %d" % it); exact(host(m2), m, "server minmax")
+        exact(host(out), o, "out it %d" % it); exact(host(eps_g), eps_o, "epsilon it %d" % it)
+
+
+# ------------------------------------------------------------------------------------------------- config 3
+def test_config3_bert_large_sampled(bg, oracle):
+    """335M heavy-tailed elements per worker, 16 workers, C = 8192, zero-initialised delta/epsilon present."""
+    from bagua_workloads import bert_shapes, pack_buckets, draw, seed_for
+    k, C = 16, 8192
+    buckets = pack_buckets(bert_shapes(24, 1024, 4096), k, C)
+    n = sum(b.n_pad for b in buckets)
+    nc = n // C
+    # ranges: the oversize embedding bucket's start, the end of the buffer, random ones
+    rs = ranges(n, C, 5, 256, 3)
+    codes_g, mm_g, codes_o, mm_o = [], [], [[] for _ in rs], [[] for _ in rs]
+    for j in range(k):
+        print("config 3 worker", j, flush=True)
+        x = draw("student_t3", n, seed_for(2, 0, j), DEV, 1e-3)
+        delta = torch.zeros(n, device=DEV)
+        cg = torch.empty(n, dtype=torch.uint8, device=DEV); mg = torch.empty(2 * nc, device=DEV)
+        bg.bagua_compress_minmax_u8(x, delta, C, cg, mg)
+        for r, (lo, hi) in enumerate(rs):
+            d = np.zeros(hi - lo, np.float32)
+            c, m = oracle.compress_minmax_u8(host(x[lo:hi]), d, C)
+            exact(host(cg[lo:hi]), c, "codes"); exact(host(mg[2 * lo // C:2 * ((hi + C - 1) // C)]), m, "minmax")
+            exact(host(delta[lo:hi]), d, "delta")
+            codes_o[r].append(c); mm_o[r].append(m)
+        codes_g.append(cg); mm_g.append(mg)
+        del x, delta
+    eps = torch.zeros(n, device=DEV)
+    c2 = torch.empty(n, dtype=torch.uint8, device=DEV); m2 = torch.empty(2 * nc, device=DEV); out = torch.empty(n, device=DEV)
+    bg.bagua_decompress_reduce_recompress(bg.CODEC_MINMAX_U8, codes_g, mm_g, eps, n, C, c2, m2, out)
+    for r, (lo, hi) in enumerate(rs):
+        e = np.zeros(hi - lo, np.float32)
+        c, m, o = oracle.drr_minmax_u8(codes_o[r], mm_o[r], e, C)
+        exact(host(c2[lo:hi]), c, "server codes"); exact(host(m2[2 * lo // C:2 * ((hi + C - 1) // C)]), m, "server minmax")
+        exact(host(out[lo:hi]), o, "out"); exact(host(eps[lo:hi]), e, "epsilon")
+
+
+# ------------------------------------------------------------------------------------------------- config 4
+def test_config4_decentralised_five_rounds_sampled(bg, oracle):
+    """8 peers x 109.5M (BERT-base shapes), base + drift, 5 rounds of FP and of LP averaging (C = 4096)."""
+    from bagua_workloads import bert_shapes, draw, seed_for
+    from bagua_workloads.shapes import numel
+    from bagua_workloads.generators import SHARED
+    k, C = 8, 4096
+    n = sum(numel(s) for _, s in bert_shapes(12, 768, 3072))     # 109,482,240 = 26729 * 4096 + 256: ragged last chunk
+    nc = (n + C - 1) // C
+    base = draw("normal", n, seed_for(3, 0, SHARED), DEV, 0.02)
+    x0 = [base + draw("normal", n, seed_for(3, 0, i), DEV, 1e-3) for i in range(k)]
+    rs = ranges(n, C, 4, 128, 4)
+    # full precision
+    cur = [x.clone() for x in x0]
+    nxt = [torch.empty(n, device=DEV) for _ in range(k)]
+    for _ in range(5):
+        bg.bagua_decentralized_avg(bg.AVG_FP, cur, nxt)
+        cur, nxt = nxt, cur
+    for lo, hi in rs:
+        ref = [host(x[lo:hi]) for x in x0]
+        for _ in range(5):
+            ref = oracle.ring_avg_fp(ref)
+        for i in range(k):
+            exact(host(cur[i][lo:hi]), ref[i], "FP peer %d" % i)
+    # low precision
+    cur = [x.clone() for x in x0]
+    hat = [base.clone() for _ in range(k)]
+    codes = [torch.empty(n, dtype=torch.uint8, device=DEV) for _ in range(k)]
+    mm = [torch.empty(2 * nc, device=DEV) for _ in range(k)]
+    for _ in range(5):
+        bg.bagua_decentralized_avg(bg.AVG_LP_MINMAX_U8, cur, nxt, hat, codes, mm, C)
+        cur, nxt = nxt, cur
+    for lo, hi in rs:
+        ref = [host(x[lo:hi]) for x in x0]
+        rhat = [host(base[lo:hi]).copy() for _ in range(k)]
+        for _ in range(5):
+            ref, rc, rm = oracle.ring_avg_lp(ref, rhat, C)
+        for i in range(k):
+            exact(host(cur[i][lo:hi]), ref[i], "LP x peer %d" % i)
+            exact(host(hat[i][lo:hi]), rhat[i], "LP xhat peer %d" % i)
+            exact(host(codes[i][lo:hi]), rc[i], "LP codes peer %d" % i)
+            exact(host(mm[i][2 * lo // C:2 * ((hi + C - 1) // C)]), rm[i], "LP minmax peer %d" % i)
+
+
+# ------------------------------------------------------------------------------------------------- config 5
+def test_config5_one_bit_sampled(bg, oracle):
+    """1.5e9 Laplace elements per worker (6 GB buffers: 64-bit indexing), 8 workers, C = 2048, ragged last chunk."""
+    from bagua_workloads import draw, seed_for
+    k, C, n = 8, 2048, 1500000000
+    nc = (n + C - 1) // C
+    assert n % C == 1792
+    rs = ranges(n, C, 5, 512, 5)
+    bits_g, scale_g, bits_o, scale_o = [], [], [[] for _ in rs], [[] for _ in rs]
+    x = torch.empty(n, device=DEV)
+    delta = torch.empty(n, device=DEV)
+    for j in range(k):
+        print("config 5 worker", j, flush=True)
+        draw("laplace", n, seed_for(4, 0, j), DEV, 1e-3, out=x)
+        delta.zero_()
+        bgt = torch.empty((n + 31) // 32, dtype=torch.int32, device=DEV); sg = torch.empty(nc, device=DEV)
+        bg.bagua_sign_compress_ef(x, delta, C, bgt, sg)
+        for r, (lo, hi) in enumerate(rs):
+            d = np.zeros(hi - lo, np.float32)
+            b, s = oracle.sign_compress_ef(host(x[lo:hi]), d, C)
+            exact(host(bgt[lo // 32:(hi + 31) // 32]).view(np.uint32), b, "bits"); exact(host(sg[lo // C:(hi + C - 1) // C]), s, "scale")
+            exact(host(delta[lo:hi]), d, "delta")
+            bits_o[r].append(b); scale_o[r].append(s)
+        bits_g.append(bgt); scale_g.append(sg)
+    del x
+    eps = delta
+    eps.zero_()
+    b2 = torch.empty((n + 31) // 32, dtype=torch.int32, device=DEV); s2 = torch.empty(nc, device=DEV); out = torch.empty(n, device=DEV)
+    bg.bagua_decompress_reduce_recompress(bg.CODEC_SIGN1, bits_g, scale_g, eps, n, C, b2, s2, out)
+    for r, (lo, hi) in enumerate(rs):
+        e = np.zeros(hi - lo, np.float32)
+        b, s, o = oracle.drr_sign(bits_o[r], scale_o[r], e, hi - lo, C)
+        exact(host(b2[lo // 32:(hi + 31) // 32]).view(np.uint32), b, "server bits"); exact(host(s2[lo // C:(hi + C - 1) // C]), s, "server scale")
+        exact(host(out[lo:hi]), o, "out"); exact(host(eps[lo:hi]), e, "epsilon")
