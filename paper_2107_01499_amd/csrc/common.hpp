@@ -52,13 +52,23 @@ __device__ __forceinline__ void st_stream(T* p, T v)
 #define BAGUA_RPW_COMPRESS 2
 #endif
 #ifndef BAGUA_RPW_DRR
-#define BAGUA_RPW_DRR 2
+#define BAGUA_RPW_DRR 4
 #endif
 #ifndef BAGUA_RPW_SIGN
 #define BAGUA_RPW_SIGN 2
 #endif
 #ifndef BAGUA_RPW_DRR_SIGN
 #define BAGUA_RPW_DRR_SIGN 4
+#endif
+#ifndef BAGUA_RPW_LP
+#define BAGUA_RPW_LP 2
+#endif
+// Workers whose code loads are issued together in the server-side kernels.
+#ifndef BAGUA_DRR_NJ
+#define BAGUA_DRR_NJ 1
+#endif
+#ifndef BAGUA_DRR_SIGN_NJ
+#define BAGUA_DRR_SIGN_NJ 4
 #endif
 
 constexpr int kWave = 64;

@@ -17,7 +17,11 @@ struct TensorDesc {
     size_t dst;  // element offset in the bucket
 };
 
-constexpr int kTile = 4096;  // bucket elements per workgroup (256 lanes x 4 groups of four)
+#ifndef BAGUA_FLATTEN_TILE
+#define BAGUA_FLATTEN_TILE 2048
+#endif
+constexpr int kTile = BAGUA_FLATTEN_TILE;  // bucket elements per workgroup (256 lanes x kTile/1024 groups of four)
+static_assert(kTile % 1024 == 0, "a tile is a whole number of 256-lane groups of four elements");
 
 static size_t align16_up(size_t b) { return (b + 15) & ~static_cast<size_t>(15); }
 static size_t num_tiles(size_t bucket_numel) { return (bucket_numel + kTile - 1) / kTile; }
@@ -36,6 +40,26 @@ k_flatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile
 {
     const size_t tile0 = static_cast<size_t>(blockIdx.x) * kTile;
     const uint32_t lo0 = tile_first[blockIdx.x], hi0 = tile_first[blockIdx.x + 1];
+
+    // Fast path (almost every tile of a large tensor): the whole tile lies inside one tensor whose
+    // source is 16-byte congruent with the bucket -> a plain streaming copy with a uniform base pointer.
+    if (lo0 < T && tile0 + kTile <= bucket_numel) {
+        const TensorDesc d = desc[lo0];   // uniform: scalar loads
+        if (d.dst <= tile0 && tile0 + kTile <= d.dst + d.numel) {
+            const float* s = d.src + (tile0 - d.dst);
+            if ((reinterpret_cast<uintptr_t>(s) & 15u) == 0) {
+                const f4* s4 = reinterpret_cast<const f4*>(s);
+                f4* b4 = reinterpret_cast<f4*>(bucket + tile0);
+                f4 v[kTile / 1024];
+#pragma unroll
+                for (int g = 0; g < kTile / 1024; ++g) v[g] = ld_stream(s4 + g * 256 + threadIdx.x);
+#pragma unroll
+                for (int g = 0; g < kTile / 1024; ++g) st_stream(b4 + g * 256 + threadIdx.x, v[g]);
+                return;
+            }
+        }
+    }
+
 #pragma unroll
     for (int g = 0; g < kTile / 1024; ++g) {
         const size_t e = tile0 + static_cast<size_t>(g) * 1024 + threadIdx.x * 4;
@@ -55,7 +79,7 @@ k_flatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile
             if (d.dst <= e && e + 4 <= d.dst + d.numel) {
                 const float* s = d.src + (e - d.dst);
                 if ((reinterpret_cast<uintptr_t>(s) & 15u) == 0) {
-                    v = *reinterpret_cast<const f4*>(s);
+                    v = ld_stream(reinterpret_cast<const f4*>(s));
                 } else {
                     v.x = s[0]; v.y = s[1]; v.z = s[2]; v.w = s[3];
                 }
@@ -69,7 +93,7 @@ k_flatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile
             v.w = (e + 3 < bucket_numel) ? element_at(desc, t, T, e + 3) : 0.0f;
         }
         if (e + 4 <= bucket_numel) {
-            *reinterpret_cast<f4*>(bucket + e) = v;
+            st_stream(reinterpret_cast<f4*>(bucket + e), v);
         } else {
             bucket[e] = v.x;
             if (e + 1 < bucket_numel) bucket[e + 1] = v.y;

@@ -75,17 +75,11 @@ k_drr_minmax(PtrTable codes_in, PtrTable meta_in, int k, float inv_k, float* __r
     __syncthreads();
 
     f4 v[RPW];
-    for (int j = 0; j < k; ++j) {
-        const uint8_t* cj = static_cast<const uint8_t*>(codes_in.p[j]) + base;
+    // Workers are summed in ascending order; the code loads of NJ workers are issued together so
+    // that NJ*RPW dword loads are in flight per wave before the first is consumed.
+    constexpr int NJ = BAGUA_DRR_NJ;
+    auto accumulate = [&](int j, uint32_t (&w)[RPW]) {
         const float mn = s_mn[j], step = s_step[j];
-        uint32_t w[RPW];
-#pragma unroll
-        for (int i = 0; i < RPW; ++i) {
-            const long off = static_cast<long>(wave * RPW + i) * kRow;
-            const long remain = len - off;
-            w[i] = 0;
-            if (remain > 0) w[i] = load_codes_row(cj + off, lane, remain);
-        }
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
             f4 d;
@@ -102,6 +96,29 @@ k_drr_minmax(PtrTable codes_in, PtrTable meta_in, int k, float inv_k, float* __r
                 v[i].w = v[i].w + d.w;
             }
         }
+    };
+    auto fetch = [&](int j, uint32_t (&w)[RPW]) {
+        const uint8_t* cj = static_cast<const uint8_t*>(codes_in.p[j]) + base;
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const long off = static_cast<long>(wave * RPW + i) * kRow;
+            const long remain = len - off;
+            w[i] = 0;
+            if (remain > 0) w[i] = load_codes_row(cj + off, lane, remain);
+        }
+    };
+    int j = 0;
+    for (; j + NJ <= k; j += NJ) {
+        uint32_t w[NJ][RPW];
+#pragma unroll
+        for (int u = 0; u < NJ; ++u) fetch(j + u, w[u]);
+#pragma unroll
+        for (int u = 0; u < NJ; ++u) accumulate(j + u, w[u]);
+    }
+    for (; j < k; ++j) {
+        uint32_t w[RPW];
+        fetch(j, w);
+        accumulate(j, w);
     }
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {

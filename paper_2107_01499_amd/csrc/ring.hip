@@ -60,8 +60,10 @@ k_ring_avg_fp_any(PtrTable xin, MutPtrTable xout, int k, size_t n, float third)
 
 // ------------------------------------------------------------------------------------------ LP, fused
 // Workgroup = one chunk of all K peers; wave w holds rows [w*RPW, (w+1)*RPW) of every peer.
+// Peers are processed in order; peer p's output is formed as soon as the new public copies of
+// p-1, p, p+1 exist, so only a short window of peers is live in registers at any time.
 template <int K, int RPW>
-__global__ void __launch_bounds__(512)
+__global__ void __launch_bounds__(64 * ((16 + RPW - 1) / RPW))
 k_ring_avg_lp(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, MutPtrTable codes, MutPtrTable minmax, size_t n,
               uint32_t chunk, float third)
 {
@@ -71,26 +73,33 @@ k_ring_avg_lp(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, MutPtrTable code
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
-    f4 x[K][RPW], h[K][RPW];
-#pragma unroll
-    for (int i = 0; i < K; ++i) {
+    f4 h[K][RPW];    // new public copy xhat' of every peer
+    f4 own[K][RPW];  // x - xhat' of every peer
+    auto finalize = [&](int p) {
 #pragma unroll
         for (int r = 0; r < RPW; ++r) {
             const long off = static_cast<long>(wave * RPW + r) * kRow;
             const long remain = len - off;
-            x[i][r] = f4{0.f, 0.f, 0.f, 0.f};
-            h[i][r] = f4{0.f, 0.f, 0.f, 0.f};
-            if (remain > 0) {
-                x[i][r] = load_row(static_cast<const float*>(xin.p[i]) + base + off, lane, remain, 0.0f);
-                h[i][r] = load_row(static_cast<const float*>(xhat.p[i]) + base + off, lane, remain, 0.0f);
-            }
+            const f4 s = add4(add4(h[(p + K - 1) % K][r], h[p][r]), h[(p + 1) % K][r]);
+            const f4 o = add4(mul4(s, third), own[p][r]);
+            if (remain > 0) store_row(static_cast<float*>(xout.p[p]) + base + off, lane, remain, o);
         }
-    }
+    };
 #pragma unroll
     for (int i = 0; i < K; ++i) {
-        f4 d[RPW];
+        f4 x[RPW], d[RPW];
 #pragma unroll
-        for (int r = 0; r < RPW; ++r) d[r] = sub4(x[i][r], h[i][r]);
+        for (int r = 0; r < RPW; ++r) {
+            const long off = static_cast<long>(wave * RPW + r) * kRow;
+            const long remain = len - off;
+            x[r] = f4{0.f, 0.f, 0.f, 0.f};
+            h[i][r] = f4{0.f, 0.f, 0.f, 0.f};
+            if (remain > 0) {
+                x[r] = load_row(static_cast<const float*>(xin.p[i]) + base + off, lane, remain, 0.0f);
+                h[i][r] = load_row(static_cast<const float*>(xhat.p[i]) + base + off, lane, remain, 0.0f);
+            }
+            d[r] = sub4(x[r], h[i][r]);
+        }
         // d <- decode(Q(d)); codes and (min,max) of peer i are written on the way
         minmax_encode_chunk<RPW, false, false, true>(d, len, wave, lane, nwaves, nullptr,
                                                      static_cast<uint8_t*>(codes.p[i]) + base,
@@ -100,20 +109,13 @@ k_ring_avg_lp(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, MutPtrTable code
             const long off = static_cast<long>(wave * RPW + r) * kRow;
             const long remain = len - off;
             h[i][r] = add4(h[i][r], d[r]);
+            own[i][r] = sub4(x[r], h[i][r]);
             if (remain > 0) store_row(static_cast<float*>(xhat.p[i]) + base + off, lane, remain, h[i][r]);
         }
+        if (i >= 2) finalize(i - 1);
     }
-#pragma unroll
-    for (int i = 0; i < K; ++i) {
-#pragma unroll
-        for (int r = 0; r < RPW; ++r) {
-            const long off = static_cast<long>(wave * RPW + r) * kRow;
-            const long remain = len - off;
-            const f4 s = add4(add4(h[(i + K - 1) % K][r], h[i][r]), h[(i + 1) % K][r]);
-            const f4 o = add4(mul4(s, third), sub4(x[i][r], h[i][r]));
-            if (remain > 0) store_row(static_cast<float*>(xout.p[i]) + base + off, lane, remain, o);
-        }
-    }
+    finalize(K - 1);
+    if (K > 1) finalize(0);
 }
 
 // ------------------------------------------------------------------------------------------ LP, two-pass fallback
@@ -207,7 +209,7 @@ static void launch_lp_k(const PtrTable& in, const MutPtrTable& out, const MutPtr
                         const MutPtrTable& mm, size_t n, uint32_t chunk, float third, dim3 grid, dim3 block,
                         hipStream_t s)
 {
-    hipLaunchKernelGGL((k_ring_avg_lp<K, 2>), grid, block, 0, s, in, out, hat, cd, mm, n, chunk, third);
+    hipLaunchKernelGGL((k_ring_avg_lp<K, BAGUA_RPW_LP>), grid, block, 0, s, in, out, hat, cd, mm, n, chunk, third);
 }
 
 static int launch_ring_lp(const float* const* x_in, float* const* x_out, float* const* xhat, uint8_t* const* codes,
@@ -226,7 +228,7 @@ static int launch_ring_lp(const float* const* x_in, float* const* x_out, float* 
     const size_t nc = num_chunks(n, chunk);
     const int rows = static_cast<int>(chunk / kRow);
     if (k <= 8 && rows <= 16) {
-        dim3 grid(static_cast<unsigned>(nc)), block(64 * ((rows + 1) / 2));
+        dim3 grid(static_cast<unsigned>(nc)), block(64 * ((rows + BAGUA_RPW_LP - 1) / BAGUA_RPW_LP));
         const uint32_t ch = static_cast<uint32_t>(chunk);
         switch (k) {
 #define BAGUA_LP_CASE(K) case K: launch_lp_k<K>(in, out, hat, cd, mm, n, ch, third, grid, block, stream); break;

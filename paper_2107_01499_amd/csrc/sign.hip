@@ -155,18 +155,11 @@ k_drr_sign(PtrTable bits_in, PtrTable scale_in, int k, float inv_k, float* __res
     const int sh = 4 * (lane & 7);
 
     f4 v[RPW];
-    for (int j = 0; j < k; ++j) {
-        const uint32_t* bj = static_cast<const uint32_t*>(bits_in.p[j]) + (base >> 5);
+    // Workers are summed in ascending order; the sign words of NJ workers are fetched together.
+    constexpr int NJ = BAGUA_DRR_SIGN_NJ;
+    auto accumulate = [&](int j, uint32_t (&w)[RPW]) {
         const float sc = static_cast<const float*>(scale_in.p[j])[c];
         const float neg = -sc;
-        uint32_t w[RPW];
-#pragma unroll
-        for (int i = 0; i < RPW; ++i) {
-            const long off = static_cast<long>(wave * RPW + i) * kRow;
-            const long remain = len - off;
-            w[i] = 0;
-            if (static_cast<long>(lane >> 3) * 32 < remain) w[i] = bj[(off >> 5) + (lane >> 3)];
-        }
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
             const uint32_t nib = w[i] >> sh;
@@ -184,6 +177,29 @@ k_drr_sign(PtrTable bits_in, PtrTable scale_in, int k, float inv_k, float* __res
                 v[i].w = v[i].w + d.w;
             }
         }
+    };
+    auto fetch = [&](int j, uint32_t (&w)[RPW]) {
+        const uint32_t* bj = static_cast<const uint32_t*>(bits_in.p[j]) + (base >> 5);
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const long off = static_cast<long>(wave * RPW + i) * kRow;
+            const long remain = len - off;
+            w[i] = 0;
+            if (static_cast<long>(lane >> 3) * 32 < remain) w[i] = bj[(off >> 5) + (lane >> 3)];
+        }
+    };
+    int j = 0;
+    for (; j + NJ <= k; j += NJ) {
+        uint32_t w[NJ][RPW];
+#pragma unroll
+        for (int u = 0; u < NJ; ++u) fetch(j + u, w[u]);
+#pragma unroll
+        for (int u = 0; u < NJ; ++u) accumulate(j + u, w[u]);
+    }
+    for (; j < k; ++j) {
+        uint32_t w[RPW];
+        fetch(j, w);
+        accumulate(j, w);
     }
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
