@@ -56,6 +56,8 @@ def parse_args():
     ap.add_argument("--workload", default="resnet50", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--only", default="", help="comma list of primitives to run in the step (profiling aid)")
+    ap.add_argument("--fused-flatten", action="store_true",
+                    help="replace flatten + compress_minmax by the fused bagua_flatten_compress_minmax_u8")
     ap.add_argument("--per-bucket-launch", action="store_true",
                     help="one launch per 25 MiB bucket instead of one per worker covering all its buckets")
     return ap.parse_args()
@@ -64,7 +66,7 @@ def parse_args():
 class Workload:
     """Synthetic gradients / replicas of one benchmark configuration, all state resident on the GPU."""
 
-    def __init__(self, torch, bg, name, per_bucket=False, only=None):
+    def __init__(self, torch, bg, name, per_bucket=False, only=None, fused=False):
         from bagua_workloads import resnet50_shapes, bert_shapes, pack_buckets, draw, seed_for, layer_sigmas
         from bagua_workloads.shapes import numel
         from bagua_workloads.generators import SHARED
@@ -73,6 +75,8 @@ class Workload:
         self.w = w
         self.k, self.C, self.SC = w["k"], w["chunk"], w["sign_chunk"]
         self.prims = [p for p in w["prims"] if (only is None or p in only)]
+        if fused and "flatten" in self.prims and "compress_minmax" in self.prims:
+            self.prims = ["flatten_compress" if p == "flatten" else p for p in self.prims if p != "compress_minmax"]
         k, C, SC, cfg = self.k, self.C, self.SC, w["cfg"]
         dev = torch.device("cuda:0")
         f32 = dict(dtype=torch.float32, device=dev)
@@ -118,7 +122,7 @@ class Workload:
         scale = 1e-3
         self.layers, self.plans = [], []
         self.bucket = None
-        if has("flatten"):
+        if has("flatten", "flatten_compress"):
             sig = layer_sigmas(len(shapes), seed_for(cfg, 0, SHARED)) if w["dist"] == "normal_layer" else None
             starts = [0]
             for sz in self.sizes:
@@ -149,12 +153,12 @@ class Workload:
         elif has("compress_minmax", "sign_compress"):
             dist = "normal" if w["dist"] == "normal_layer" else w["dist"]
             self.bucket = [views(draw(dist, n, seed_for(cfg, 0, j), dev, scale)) for j in range(k)]
-        if has("compress_minmax", "drr_minmax"):
+        if has("compress_minmax", "drr_minmax", "flatten_compress"):
             self.delta = [views(z(n, **f32)) for _ in range(k)]
             self.codes = [views(z(n, **u8)) for _ in range(k)]
             self.minmax = [views(z(2 * nc, **f32), C, 2) for _ in range(k)]
         if has("drr_minmax"):
-            if not has("compress_minmax"):
+            if not has("compress_minmax", "flatten_compress"):
                 for j in range(k):
                     for u in range(U):
                         bg.bagua_compress_minmax_u8(self.bucket[j][u], None, C, self.codes[j][u], self.minmax[j][u])
@@ -199,7 +203,8 @@ class Workload:
     # ---- accounting --------------------------------------------------------------------------------
     def bytes_per_element(self):
         k, C, SC = self.k, self.C, self.SC
-        return {"flatten": 8.0, "compress_minmax": 13.0 + 8.0 / C, "drr_minmax": k + 13.0 + 8.0 * (k + 1) / C,
+        wb = 4.0 if "sign_compress" in self.prims else 0.0   # the fused call also writes the bucket if it is needed later
+        return {"flatten": 8.0, "flatten_compress": 13.0 + wb + 8.0 / C, "compress_minmax": 13.0 + 8.0 / C, "drr_minmax": k + 13.0 + 8.0 * (k + 1) / C,
                 "ring_fp": 8.0, "ring_lp": 17.0 + 8.0 / C, "sign_compress": 12.125 + 4.0 / SC,
                 "drr_sign": k / 8.0 + 12.125 + 4.0 * (k + 1) / SC}
 
@@ -209,19 +214,20 @@ class Workload:
 
     def algo_bytes(self):
         n, k = self.n_elems, self.k
-        units = {"flatten": n * k, "compress_minmax": n * k, "drr_minmax": n, "ring_fp": n * k, "ring_lp": n * k,
+        units = {"flatten": n * k, "flatten_compress": n * k, "compress_minmax": n * k, "drr_minmax": n, "ring_fp": n * k, "ring_lp": n * k,
                  "sign_compress": n * k, "drr_sign": n}
         bpe = self.bytes_per_element()
         return {p: bpe[p] * units[p] for p in self.prims}
 
     def launches(self):
         U, k = len(self.units), self.k
-        per = {"flatten": U * k, "compress_minmax": U * k, "drr_minmax": U, "ring_fp": U, "ring_lp": U,
+        per = {"flatten": U * k, "flatten_compress": U * k, "compress_minmax": U * k, "drr_minmax": U, "ring_fp": U, "ring_lp": U,
                "sign_compress": U * k, "drr_sign": U}
         return {p: per[p] for p in self.prims}
 
     def kernel_name(self, p):
-        return {"flatten": "k_flatten", "compress_minmax": "k_compress_minmax<2,true>",
+        return {"flatten": "k_flatten", "flatten_compress": "k_flatten_compress_minmax<2,true,%s>" %
+                ("true" if "sign_compress" in self.prims else "false"), "compress_minmax": "k_compress_minmax<2,true>",
                 "drr_minmax": "k_drr_minmax<4,true,true>", "ring_fp": "k_ring_avg_fp<%d>" % self.k,
                 "ring_lp": "k_ring_avg_lp<%d,2>" % self.k, "sign_compress": "k_sign_compress<2,true>",
                 "drr_sign": "k_drr_sign<4,true,true>"}[p]
@@ -246,6 +252,13 @@ class Workload:
                 for j in range(k):
                     for u in range(U):
                         bg.bagua_bucket_flatten_run(self.plans[it][j][u], len(self.units[u][2]), self.bucket[j][u])
+            elif p == "flatten_compress":
+                keep = "sign_compress" in self.prims
+                for j in range(k):
+                    for u in range(U):
+                        bg.bagua_flatten_compress_minmax_u8(self.plans[it][j][u], len(self.units[u][2]), self.delta[j][u],
+                                                            self.units[u][1], C, self.codes[j][u], self.minmax[j][u],
+                                                            self.bucket[j][u] if keep else None)
             elif p == "compress_minmax":
                 for j in range(k):
                     for u in range(U):
@@ -336,7 +349,7 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     only = set(p for p in args.only.split(",") if p) or None
-    wl = Workload(torch, bg, args.workload, per_bucket=args.per_bucket_launch, only=only)
+    wl = Workload(torch, bg, args.workload, per_bucket=args.per_bucket_launch, only=only, fused=args.fused_flatten)
     prims = wl.prims
 
     for _ in range(args.warmup):
@@ -368,7 +381,7 @@ def main():
         t = prim_ms[p] * 1e-3
         per_prim[p] = {"ms": round(prim_ms[p], 4), "launches": nl[p], "gradient_GBps": round(gb[p] / t / 1e9, 1),
                        "hbm_GBps": round(ab[p] / t / 1e9, 1), "frac_of_peak": round(ab[p] / t / 1e9 / HBM_PEAK_GBS, 4)}
-    dom = "compress_minmax" if "compress_minmax" in prims else max(prims, key=lambda p: prim_ms[p])
+    dom = next((p for p in ("compress_minmax", "flatten_compress") if p in prims), None) or max(prims, key=lambda p: prim_ms[p])
     dom_t = prim_ms[dom] * 1e-3 / nl[dom]
     achieved = ab[dom] / nl[dom] / dom_t / 1e9
     traffic = read_traffic() if (dom == "compress_minmax" and args.workload == "resnet50" and not args.per_bucket_launch) else None
@@ -390,7 +403,7 @@ def main():
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "avg_launch_us": round(dom_t * 1e6, 3), "algorithmic_bytes_per_launch": ab[dom] / nl[dom]},
     }
-    if not args.no_cpu_baseline and args.workload == "resnet50" and only is None:
+    if not args.no_cpu_baseline and args.workload == "resnet50" and only is None and not args.fused_flatten:
         result["cpu_baseline"] = cpu_baseline(wl, torch)
     print(json.dumps(result))
 

@@ -93,6 +93,21 @@ int bagua_compress_minmax_u8(const float* x, float* residual, size_t n, size_t c
                              uint8_t* codes, float* minmax, void* stream);
 
 /*
+ * Flatten fused into the worker-side compression (the step right before the path: Section 3.5 has the
+ * compression work on the flattened view of a bucket; here that view is never materialised).  The result is exactly
+ * bagua_bucket_flatten followed by bagua_compress_minmax_u8 on the bucket, but the rows of each chunk are
+ * gathered straight from the layer tensors through a planned workspace (bagua_flatten_plan with the same T and
+ * bucket_numel), so the bucket is not written to and read back from memory.
+ *   workspace   device, planned;  T, bucket_numel as given to the plan
+ *   residual    device fp32[bucket_numel], in-out, or NULL
+ *   codes       device u8[bucket_numel];  minmax device fp32[2*nc]
+ *   bucket_out  device fp32[bucket_numel] or NULL: if given, the flattened bucket is also written (for callers
+ *               that need the flat view as well); 16-byte aligned
+ */
+int bagua_flatten_compress_minmax_u8(const void* workspace, size_t T, float* residual, size_t bucket_numel,
+                                     size_t chunk, uint8_t* codes, float* minmax, float* bucket_out, void* stream);
+
+/*
  * Server side of C_LP_S (Section 3.2, x_i' and epsilon_i' of the C_LP_S equations; steps 3-5 of
  * ScatterReduce, Section 3.4): decode the k workers' compressed buckets, average them in
  * ascending worker order, add the server error state, compress again, update the state:

@@ -23,7 +23,7 @@ MAX_WORKERS = 32
 EXPORTS = (
     "bagua_status_string", "bagua_flatten_workspace_bytes", "bagua_flatten_plan", "bagua_bucket_flatten_run",
     "bagua_bucket_flatten", "bagua_compress_minmax_u8", "bagua_decompress_reduce_recompress",
-    "bagua_decentralized_avg", "bagua_sign_compress_ef", "bagua_decompress",
+    "bagua_decentralized_avg", "bagua_sign_compress_ef", "bagua_decompress", "bagua_flatten_compress_minmax_u8",
 )
 
 
@@ -51,6 +51,7 @@ def _load():
     lib.bagua_decentralized_avg.argtypes = [i32, vp, vp, vp, vp, vp, i32, sz, sz, vp]
     lib.bagua_sign_compress_ef.argtypes = [vp, vp, sz, sz, vp, vp, vp]
     lib.bagua_decompress.argtypes = [i32, vp, vp, sz, sz, vp, vp]
+    lib.bagua_flatten_compress_minmax_u8.argtypes = [vp, sz, vp, sz, sz, vp, vp, vp, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = i32
     return lib
@@ -137,6 +138,12 @@ def bagua_compress_minmax_u8(x, residual, chunk, codes, minmax, stream=None):
     _check("bagua_compress_minmax_u8", _lib.bagua_compress_minmax_u8(
         _ptr(x, torch.float32), _ptr(residual, torch.float32), x.numel(), chunk, _ptr(codes, torch.uint8),
         _ptr(minmax, torch.float32), _stream(stream)))
+
+
+def bagua_flatten_compress_minmax_u8(workspace, T, residual, n, chunk, codes, minmax, bucket_out=None, stream=None):
+    _check("bagua_flatten_compress_minmax_u8", _lib.bagua_flatten_compress_minmax_u8(
+        _ptr(workspace), T, _ptr(residual, torch.float32), n, chunk, _ptr(codes, torch.uint8),
+        _ptr(minmax, torch.float32), _ptr(bucket_out, torch.float32), _stream(stream)))
 
 
 def bagua_decompress_reduce_recompress(codec, codes_in, meta_in, server_residual, n, chunk, codes_out, meta_out,

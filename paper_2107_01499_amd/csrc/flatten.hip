@@ -7,32 +7,9 @@
 // caller's workspace gives, for every tile of the bucket, the first tensor that can intersect it.
 #include <vector>
 
-#include "common.hpp"
+#include "flatten_device.hpp"
 
 namespace bagua {
-
-struct TensorDesc {
-    const float* src;
-    size_t numel;
-    size_t dst;  // element offset in the bucket
-};
-
-#ifndef BAGUA_FLATTEN_TILE
-#define BAGUA_FLATTEN_TILE 2048
-#endif
-constexpr int kTile = BAGUA_FLATTEN_TILE;  // bucket elements per workgroup (256 lanes x kTile/1024 groups of four)
-static_assert(kTile % 1024 == 0, "a tile is a whole number of 256-lane groups of four elements");
-
-static size_t align16_up(size_t b) { return (b + 15) & ~static_cast<size_t>(15); }
-static size_t num_tiles(size_t bucket_numel) { return (bucket_numel + kTile - 1) / kTile; }
-
-// Value of bucket element e, starting the search at tensor t (the first tensor whose end is > some e' <= e).
-__device__ __forceinline__ float element_at(const TensorDesc* __restrict__ desc, uint32_t& t, uint32_t T, size_t e)
-{
-    while (t < T && desc[t].dst + desc[t].numel <= e) ++t;
-    if (t < T && desc[t].dst <= e) return desc[t].src[e - desc[t].dst];
-    return 0.0f;
-}
 
 __global__ void __launch_bounds__(256)
 k_flatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile_first, uint32_t T,
@@ -150,11 +127,9 @@ extern "C" int bagua_bucket_flatten_run(const void* workspace, size_t T, float* 
     if (!workspace || !bucket || bucket_numel == 0) return BAGUA_ERR_INVALID_ARG;
     if (T > 0xfffffff0u || num_tiles(bucket_numel) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(workspace) || !aligned16(bucket)) return BAGUA_ERR_ALIGNMENT;
-    const size_t desc_bytes = align16_up((T ? T : 1) * sizeof(TensorDesc));
-    const TensorDesc* d = static_cast<const TensorDesc*>(workspace);
-    const uint32_t* first = reinterpret_cast<const uint32_t*>(static_cast<const unsigned char*>(workspace) + desc_bytes);
+    const FlattenPlanView pv = plan_view(workspace, T);
     hipLaunchKernelGGL(k_flatten, dim3(static_cast<unsigned>(num_tiles(bucket_numel))), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), d, first, static_cast<uint32_t>(T), bucket, bucket_numel);
+                       static_cast<hipStream_t>(stream), pv.desc, pv.tile_first, static_cast<uint32_t>(T), bucket, bucket_numel);
     return launch_status();
 }
 

@@ -1,0 +1,72 @@
+// Tensor table of a planned bucket (see bagua_flatten_plan) and the device-side lookups on it.
+#pragma once
+#include "common.hpp"
+
+namespace bagua {
+
+struct TensorDesc {
+    const float* src;
+    size_t numel;
+    size_t dst;  // element offset in the bucket
+};
+
+#ifndef BAGUA_FLATTEN_TILE
+#define BAGUA_FLATTEN_TILE 2048
+#endif
+constexpr int kTile = BAGUA_FLATTEN_TILE;  // bucket elements per workgroup (256 lanes x kTile/1024 groups of four)
+static_assert(kTile % 1024 == 0, "a tile is a whole number of 256-lane groups of four elements");
+
+inline size_t align16_up(size_t b) { return (b + 15) & ~static_cast<size_t>(15); }
+inline size_t num_tiles(size_t bucket_numel) { return (bucket_numel + kTile - 1) / kTile; }
+
+// Value of bucket element e, starting the search at tensor t (the first tensor whose end is > some e' <= e).
+__device__ __forceinline__ float element_at(const TensorDesc* __restrict__ desc, uint32_t& t, uint32_t T, size_t e)
+{
+    while (t < T && desc[t].dst + desc[t].numel <= e) ++t;
+    if (t < T && desc[t].dst <= e) return desc[t].src[e - desc[t].dst];
+    return 0.0f;
+}
+
+
+// The planned workspace: T descriptors, then (tiles + 1) "first tensor" indices.
+struct FlattenPlanView {
+    const TensorDesc* desc;
+    const uint32_t* tile_first;
+};
+inline FlattenPlanView plan_view(const void* workspace, size_t T)
+{
+    const size_t desc_bytes = align16_up((T ? T : 1) * sizeof(TensorDesc));
+    return FlattenPlanView{static_cast<const TensorDesc*>(workspace),
+                           reinterpret_cast<const uint32_t*>(static_cast<const unsigned char*>(workspace) + desc_bytes)};
+}
+
+// One 256-element row of the (virtual) bucket starting at element e0 (a multiple of 256), gathered
+// straight from the layer tensors: lane l receives elements e0+4l .. e0+4l+3; elements beyond
+// `remain` or not covered by a tensor read as +0.0f.
+__device__ __forceinline__ f4 gather_row(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile_first,
+                                         uint32_t T, size_t e0, int lane, long remain)
+{
+    const size_t tile = e0 / kTile;
+    uint32_t lo = tile_first[tile];
+    const uint32_t hi = tile_first[tile + 1];
+    // first tensor whose end lies beyond e0 (wave-uniform search)
+    while (lo < hi && desc[lo].dst + desc[lo].numel <= e0) ++lo;
+    if (lo < T && remain >= kRow) {
+        const TensorDesc d = desc[lo];
+        if (d.dst <= e0 && e0 + kRow <= d.dst + d.numel) {
+            const float* s = d.src + (e0 - d.dst);
+            if ((reinterpret_cast<uintptr_t>(s) & 15u) == 0) return ld_stream(reinterpret_cast<const f4*>(s) + lane);
+        }
+    }
+    uint32_t t = lo;
+    const size_t e = e0 + lane * 4;
+    const int l4 = lane * 4;
+    f4 v;
+    v.x = (l4 + 0 < remain) ? element_at(desc, t, T, e + 0) : 0.0f;
+    v.y = (l4 + 1 < remain) ? element_at(desc, t, T, e + 1) : 0.0f;
+    v.z = (l4 + 2 < remain) ? element_at(desc, t, T, e + 2) : 0.0f;
+    v.w = (l4 + 3 < remain) ? element_at(desc, t, T, e + 3) : 0.0f;
+    return v;
+}
+
+}  // namespace bagua

@@ -1,0 +1,89 @@
+// Flatten fused into the worker-side MinMax-u8 compression: the rows of a chunk are gathered
+// straight from the layer tensors (through the planned tensor table), so the flattened bucket is
+// never written to and re-read from HBM.  Result = bagua_bucket_flatten followed by
+// bagua_compress_minmax_u8, bit for bit; traffic = that of the compression alone.
+#include "flatten_device.hpp"
+#include "launchers.hpp"
+#include "minmax_device.hpp"
+
+#pragma clang fp contract(off)
+
+namespace bagua {
+
+template <int RPW, bool EF, bool WB>
+__global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
+k_flatten_compress_minmax(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile_first, uint32_t T,
+                          float* __restrict__ residual, size_t n, uint32_t chunk, uint8_t* __restrict__ codes,
+                          float* __restrict__ minmax, float* __restrict__ bucket_out)
+{
+    __shared__ float s_red[2 * kMaxWaves];
+    const size_t c = blockIdx.x;
+    const size_t base = c * static_cast<size_t>(chunk);
+    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+
+    // the error state does not depend on the table lookups: get its loads going first
+    f4 d[RPW];
+    if (EF) {
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const long off = static_cast<long>(wave * RPW + i) * kRow;
+            const long remain = len - off;
+            d[i] = f4{0.f, 0.f, 0.f, 0.f};
+            if (remain > 0) d[i] = load_row(residual + base + off, lane, remain, 0.0f);
+        }
+    }
+    f4 v[RPW];
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        const long off = static_cast<long>(wave * RPW + i) * kRow;
+        const long remain = len - off;
+        v[i] = f4{0.f, 0.f, 0.f, 0.f};
+        if (remain > 0) {
+            v[i] = gather_row(desc, tile_first, T, base + off, lane, remain);
+            if (WB) store_row(bucket_out + base + off, lane, remain, v[i]);
+        }
+    }
+    if (EF) {
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            v[i].x = v[i].x + d[i].x;
+            v[i].y = v[i].y + d[i].y;
+            v[i].z = v[i].z + d[i].z;
+            v[i].w = v[i].w + d[i].w;
+        }
+    }
+    minmax_encode_chunk<RPW, EF, false>(v, len, wave, lane, nwaves, EF ? residual + base : nullptr,
+                                        codes + base, minmax + 2 * c, nullptr, s_red);
+}
+
+}  // namespace bagua
+
+using namespace bagua;
+
+extern "C" int bagua_flatten_compress_minmax_u8(const void* workspace, size_t T, float* residual, size_t bucket_numel,
+                                                size_t chunk, uint8_t* codes, float* minmax, float* bucket_out,
+                                                void* stream)
+{
+    if (!workspace || !codes || !minmax || bucket_numel == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
+    if (T > 0xfffffff0u || num_chunks(bucket_numel, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (!aligned16(workspace) || !aligned16(residual) || !aligned16(codes) || !aligned16(minmax) ||
+        !aligned16(bucket_out))
+        return BAGUA_ERR_ALIGNMENT;
+    const FlattenPlanView pv = plan_view(workspace, T);
+    const int rows = static_cast<int>(chunk / kRow);
+    const int rpw = pick_rpw(rows, BAGUA_RPW_COMPRESS);
+    dim3 grid(static_cast<unsigned>(num_chunks(bucket_numel, chunk))), block(64 * ((rows + rpw - 1) / rpw));
+    const uint32_t ch = static_cast<uint32_t>(chunk), t32 = static_cast<uint32_t>(T);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define BAGUA_FC(EFv, WBv)                                                                                       \
+    BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_flatten_compress_minmax<RPW, EFv, WBv>), grid, block, 0, s,    \
+                                               pv.desc, pv.tile_first, t32, residual, bucket_numel, ch, codes,  \
+                                               minmax, bucket_out))
+    if (residual && bucket_out) { BAGUA_FC(true, true) }
+    else if (residual) { BAGUA_FC(true, false) }
+    else if (bucket_out) { BAGUA_FC(false, true) }
+    else { BAGUA_FC(false, false) }
+#undef BAGUA_FC
+    return launch_status();
+}

@@ -329,3 +329,70 @@ def test_non_default_stream(bg, oracle):
     s.synchronize()
     co, mo = oracle.compress_minmax_u8(x, None, C)
     assert np.array_equal(host(codes), co) and np.array_equal(host(mm), mo)
+
+
+# ----------------------------------------------------------------------------- flatten fused into compress
+@pytest.mark.parametrize("ef", [False, True])
+@pytest.mark.parametrize("C", [256, 4096, 16384])
+@pytest.mark.parametrize("want_bucket", [False, True])
+def test_flatten_compress_fused(bg, oracle, ef, C, want_bucket):
+    """bagua_flatten_compress_minmax_u8 == flatten then compress (oracle composition): gaps, tiny and empty
+    tensors, sources at odd 4-byte addresses, a ragged last chunk."""
+    print("flatten_compress C=%d ef=%s bucket=%s" % (C, ef, want_bucket), flush=True)
+    r = np.random.default_rng(C + ef)
+    sizes = [1, 7, 64, 1000, 3, 4096, 0, 129, 30522, 5, 5, 5, 8191, 2, 70000, 256, 1024]
+    srcs = [(r.standard_normal(s) * 1e-3).astype(np.float32) for s in sizes]
+    offs, pos = [], 0
+    for i, s in enumerate(sizes):
+        pos += (i % 3)
+        offs.append(pos)
+        pos += s
+    total = pos + 50
+    flat = oracle.bucket_flatten(srcs, offs, total)
+    res = (r.standard_normal(total) * 1e-4).astype(np.float32) if ef else None
+    res_o = None if res is None else res.copy()
+    co, mo = oracle.compress_minmax_u8(flat, res_o, C)
+    for aligned in (False, True):
+        arena = torch.zeros(sum(sizes) + 8 * len(sizes) + 8, device="cuda")
+        gs, p = [], (0 if aligned else 1)
+        for s in srcs:
+            t = arena[p:p + s.size]
+            t.copy_(torch.from_numpy(s))
+            gs.append(t)
+            p += s.size + (((-s.size) % 4) if aligned else 1)
+        ws = torch.empty(bg.bagua_flatten_workspace_bytes(len(gs), total), dtype=torch.uint8, device="cuda")
+        bg.bagua_flatten_plan(gs, offs, total, ws)
+        rg = None if res is None else dev(res)
+        codes = torch.full((total,), 0xAB, dtype=torch.uint8, device="cuda")
+        mm = torch.full((2 * bg.num_chunks(total, C),), float("nan"), device="cuda")
+        bucket = torch.full((total,), float("nan"), device="cuda") if want_bucket else None
+        bg.bagua_flatten_compress_minmax_u8(ws, len(gs), rg, total, C, codes, mm, bucket)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(codes), co)
+        assert np.array_equal(host(mm).view(np.uint32), mo.view(np.uint32))
+        if ef:
+            assert_fp32_close_and_exact(host(rg), res_o, "fused residual")
+        if want_bucket:
+            assert host(bucket).tobytes() == flat.tobytes()
+
+
+def test_flatten_compress_fused_resnet50(bg, oracle):
+    from bagua_workloads import resnet50_shapes, pack_buckets
+    from bagua_workloads.shapes import numel
+    shapes = resnet50_shapes()
+    C = 4096
+    b = pack_buckets(shapes, 8, C)[0]
+    r = np.random.default_rng(2)
+    srcs = [(r.standard_normal(numel(shapes[t][1])) * 1e-3).astype(np.float32) for t in b.tensors]
+    flat = oracle.bucket_flatten(srcs, b.offsets, b.n_pad)
+    res_o = np.zeros(b.n_pad, np.float32)
+    co, mo = oracle.compress_minmax_u8(flat, res_o, C)
+    gs = [dev(s) for s in srcs]
+    ws = torch.empty(bg.bagua_flatten_workspace_bytes(len(gs), b.n_pad), dtype=torch.uint8, device="cuda")
+    bg.bagua_flatten_plan(gs, b.offsets, b.n_pad, ws)
+    rg = torch.zeros(b.n_pad, device="cuda")
+    codes = torch.empty(b.n_pad, dtype=torch.uint8, device="cuda")
+    mm = torch.empty(2 * b.n_pad // C, device="cuda")
+    bg.bagua_flatten_compress_minmax_u8(ws, len(gs), rg, b.n_pad, C, codes, mm)
+    assert np.array_equal(host(codes), co) and np.array_equal(host(mm).view(np.uint32), mo.view(np.uint32))
+    assert_fp32_close_and_exact(host(rg), res_o, "fused residual resnet50")
