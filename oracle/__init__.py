@@ -173,3 +173,13 @@ def bucket_flatten(srcs, dst_offset, bucket_numel):
         ptrs[i] = _chk(s, np.float32) if s.size else None
     _ok(lib().oracle_bucket_flatten(ptrs, numel, offs, T, _chk(bucket, np.float32), bucket_numel), "bucket_flatten")
     return bucket
+
+
+def decompress_sgd_step(codec, codes, meta, n, chunk, param, momentum_buf, lr, momentum=0.0, weight_decay=0.0):
+    """Decode a compressed bucket and apply SGD (optional weight decay and momentum) in place on param / momentum_buf."""
+    f = lib().oracle_decompress_sgd_step
+    f.restype = ctypes.c_int
+    f.argtypes = [ctypes.c_int, _c_p, _c_p, _c_sz, _c_sz, _c_p, _c_p, ctypes.c_float, ctypes.c_float, ctypes.c_float]
+    cp = _chk(codes, np.uint8) if codec == 0 else _chk(codes, np.uint32)
+    _ok(f(codec, cp, _chk(meta, np.float32), n, chunk, _chk(param, np.float32),
+          None if momentum_buf is None else _chk(momentum_buf, np.float32), lr, momentum, weight_decay), "decompress_sgd_step")

@@ -457,3 +457,46 @@ int oracle_bucket_flatten(const float* const* src, const size_t* numel, const si
         for (size_t e = 0; e < numel[t]; ++e) bucket[dst_offset[t] + e] = src[t][e];
     return 0;
 }
+
+/* ------------------------------------------------------- decode fused into the optimizer step */
+
+/*
+ * Last step of C_LP_S on every worker followed by the bucket-level model update (Section 3.5:
+ * the stochastic-gradient optimizer also runs on the flattened bucket; Appendix listing: the
+ * primitive is followed by optimizer.step()).  The optimizer is left open by the paper; reading
+ * R16: plain SGD with optional weight decay and momentum (no dampening, no Nesterov), one
+ * rounding per operation in this order:
+ *     g = decode(codes, meta)                         (MinMax-u8 or Sign-1bit, as above)
+ *     if weight_decay != 0:  g = g + weight_decay * p
+ *     if momentum buffer:    m = momentum * m + g ;  u = m     else u = g
+ *     p = p - lr * u
+ * A zero-initialised momentum buffer reproduces the usual "first step: m = g".
+ */
+int oracle_decompress_sgd_step(int codec, const void* codes, const float* meta, size_t n, size_t chunk,
+                               float* param, float* momentum_buf, float lr, float momentum, float weight_decay)
+{
+    if ((codec != 0 && codec != 1) || !codes || !meta || !param || n == 0 || !chunk_ok(chunk)) return 1;
+    float* g = (float*)malloc(n * sizeof(float));
+    if (!g) return 1;
+    int rc = codec == 0 ? oracle_decompress_minmax_u8((const uint8_t*)codes, meta, n, chunk, g)
+                        : oracle_decompress_sign((const uint32_t*)codes, meta, n, chunk, g);
+    if (rc) { free(g); return rc; }
+    for (size_t i = 0; i < n; ++i) {
+        float gi = g[i];
+        if (weight_decay != 0.0f) {
+            float w = weight_decay * param[i];
+            gi = gi + w;
+        }
+        float u = gi;
+        if (momentum_buf) {
+            float t = momentum * momentum_buf[i];
+            float m = t + gi;
+            momentum_buf[i] = m;
+            u = m;
+        }
+        float s = lr * u;
+        param[i] = param[i] - s;
+    }
+    free(g);
+    return 0;
+}
