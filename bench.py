@@ -56,6 +56,8 @@ def parse_args():
     ap.add_argument("--workload", default="resnet50", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--only", default="", help="comma list of primitives to run in the step (profiling aid)")
+    ap.add_argument("--extras", default="", help="comma list of additional primitives appended to the step: sgd_step "
+                    "(decode of the server's codes fused into an SGD-momentum update of every worker's replica)")
     ap.add_argument("--fused-flatten", action="store_true",
                     help="replace flatten + compress_minmax by the fused bagua_flatten_compress_minmax_u8")
     ap.add_argument("--per-bucket-launch", action="store_true",
@@ -66,7 +68,7 @@ def parse_args():
 class Workload:
     """Synthetic gradients / replicas of one benchmark configuration, all state resident on the GPU."""
 
-    def __init__(self, torch, bg, name, per_bucket=False, only=None, fused=False):
+    def __init__(self, torch, bg, name, per_bucket=False, only=None, fused=False, extras=()):
         from bagua_workloads import resnet50_shapes, bert_shapes, pack_buckets, draw, seed_for, layer_sigmas
         from bagua_workloads.shapes import numel
         from bagua_workloads.generators import SHARED
@@ -77,6 +79,8 @@ class Workload:
         self.prims = [p for p in w["prims"] if (only is None or p in only)]
         if fused and "flatten" in self.prims and "compress_minmax" in self.prims:
             self.prims = ["flatten_compress" if p == "flatten" else p for p in self.prims if p != "compress_minmax"]
+        if "sgd_step" in extras and "drr_minmax" in self.prims:
+            self.prims = self.prims + ["sgd_step"]
         k, C, SC, cfg = self.k, self.C, self.SC, w["cfg"]
         dev = torch.device("cuda:0")
         f32 = dict(dtype=torch.float32, device=dev)
@@ -166,6 +170,9 @@ class Workload:
             self.codes_out = views(z(n, **u8))
             self.minmax_out = views(z(2 * nc, **f32), C, 2)
             self.out = views(z(n, **f32))
+        if has("sgd_step"):
+            self.param = [views(draw("normal", n, seed_for(cfg, 50, j), dev, 0.02)) for j in range(k)]
+            self.mbuf = [views(z(n, **f32)) for _ in range(k)]
         if has("sign_compress", "drr_sign"):
             self.sdelta = [views(z(n, **f32)) for _ in range(k)]
             self.bits = [views(z((n + 31) // 32, **i32), 32) for _ in range(k)]
@@ -205,7 +212,7 @@ class Workload:
         k, C, SC = self.k, self.C, self.SC
         wb = 4.0 if "sign_compress" in self.prims else 0.0   # the fused call also writes the bucket if it is needed later
         return {"flatten": 8.0, "flatten_compress": 13.0 + wb + 8.0 / C, "compress_minmax": 13.0 + 8.0 / C, "drr_minmax": k + 13.0 + 8.0 * (k + 1) / C,
-                "ring_fp": 8.0, "ring_lp": 17.0 + 8.0 / C, "sign_compress": 12.125 + 4.0 / SC,
+                "sgd_step": 17.0 + 8.0 / C, "ring_fp": 8.0, "ring_lp": 17.0 + 8.0 / C, "sign_compress": 12.125 + 4.0 / SC,
                 "drr_sign": k / 8.0 + 12.125 + 4.0 * (k + 1) / SC}
 
     def grad_bytes(self):
@@ -215,14 +222,14 @@ class Workload:
     def algo_bytes(self):
         n, k = self.n_elems, self.k
         units = {"flatten": n * k, "flatten_compress": n * k, "compress_minmax": n * k, "drr_minmax": n, "ring_fp": n * k, "ring_lp": n * k,
-                 "sign_compress": n * k, "drr_sign": n}
+                 "sign_compress": n * k, "drr_sign": n, "sgd_step": n * k}
         bpe = self.bytes_per_element()
         return {p: bpe[p] * units[p] for p in self.prims}
 
     def launches(self):
         U, k = len(self.units), self.k
         per = {"flatten": U * k, "flatten_compress": U * k, "compress_minmax": U * k, "drr_minmax": U, "ring_fp": U, "ring_lp": U,
-               "sign_compress": U * k, "drr_sign": U}
+               "sign_compress": U * k, "drr_sign": U, "sgd_step": U * k}
         return {p: per[p] for p in self.prims}
 
     def kernel_name(self, p):
@@ -230,7 +237,7 @@ class Workload:
                 ("true" if "sign_compress" in self.prims else "false"), "compress_minmax": "k_compress_minmax<2,true>",
                 "drr_minmax": "k_drr_minmax<4,true,true>", "ring_fp": "k_ring_avg_fp<%d>" % self.k,
                 "ring_lp": "k_ring_avg_lp<%d,2>" % self.k, "sign_compress": "k_sign_compress<2,true>",
-                "drr_sign": "k_drr_sign<4,true,true>"}[p]
+                "drr_sign": "k_drr_sign<4,true,true>", "sgd_step": "k_decompress_sgd<0,true,false>"}[p]
 
     # ---- one pass of the hot path ------------------------------------------------------------------
     def step(self, marks=None):
@@ -269,6 +276,11 @@ class Workload:
                                                           [self.minmax[j][u] for j in range(k)], self.eps[u],
                                                           self.units[u][1], C, self.codes_out[u], self.minmax_out[u],
                                                           self.out[u])
+            elif p == "sgd_step":
+                for j in range(k):
+                    for u in range(U):
+                        bg.bagua_decompress_sgd_step(bg.CODEC_MINMAX_U8, self.codes_out[u], self.minmax_out[u],
+                                                     self.units[u][1], C, self.param[j][u], self.mbuf[j][u], 0.01, 0.9, 0.0)
             elif p == "ring_fp":
                 for u in range(U):
                     bg.bagua_decentralized_avg(bg.AVG_FP, [self.rep_fp[src][i][u] for i in range(k)],
@@ -349,7 +361,8 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     only = set(p for p in args.only.split(",") if p) or None
-    wl = Workload(torch, bg, args.workload, per_bucket=args.per_bucket_launch, only=only, fused=args.fused_flatten)
+    wl = Workload(torch, bg, args.workload, per_bucket=args.per_bucket_launch, only=only, fused=args.fused_flatten,
+                  extras=tuple(e for e in args.extras.split(",") if e))
     prims = wl.prims
 
     for _ in range(args.warmup):
@@ -403,7 +416,7 @@ def main():
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "avg_launch_us": round(dom_t * 1e6, 3), "algorithmic_bytes_per_launch": ab[dom] / nl[dom]},
     }
-    if not args.no_cpu_baseline and args.workload == "resnet50" and only is None and not args.fused_flatten:
+    if not args.no_cpu_baseline and args.workload == "resnet50" and only is None and not args.fused_flatten and not args.extras:
         result["cpu_baseline"] = cpu_baseline(wl, torch)
     print(json.dumps(result))
 

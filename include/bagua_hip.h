@@ -165,6 +165,22 @@ int bagua_sign_compress_ef(const float* x, float* residual, size_t n, size_t chu
 int bagua_decompress(int codec, const void* codes, const float* meta, size_t n, size_t chunk,
                      float* out, void* stream);
 
+/*
+ * Decode fused into the bucket-level optimizer step (Section 3.5: the stochastic-gradient optimizer also works
+ * on the flattened bucket; in the appendix listing the primitive is followed by the optimizer step).  The
+ * optimizer itself is not fixed by the paper; this entry point implements SGD with optional weight decay and
+ * momentum (no dampening, no Nesterov), one rounding per operation in this order:
+ *   g = decode(codes, meta);  if weight_decay != 0: g = g + weight_decay * p;
+ *   if momentum_buf: m = momentum * m + g, u = m;  else u = g;      p = p - lr * u.
+ * A zero-initialised momentum buffer gives the usual first step m = g.  The decoded gradient is not stored.
+ *   codec, codes, meta   a compressed bucket as produced by bagua_decompress_reduce_recompress
+ *   param                device fp32[n], updated in place
+ *   momentum_buf         device fp32[n], updated in place, or NULL (no momentum; `momentum` is ignored)
+ */
+int bagua_decompress_sgd_step(int codec, const void* codes, const float* meta, size_t n, size_t chunk,
+                              float* param, float* momentum_buf, float lr, float momentum, float weight_decay,
+                              void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,6 +24,7 @@ EXPORTS = (
     "bagua_status_string", "bagua_flatten_workspace_bytes", "bagua_flatten_plan", "bagua_bucket_flatten_run",
     "bagua_bucket_flatten", "bagua_compress_minmax_u8", "bagua_decompress_reduce_recompress",
     "bagua_decentralized_avg", "bagua_sign_compress_ef", "bagua_decompress", "bagua_flatten_compress_minmax_u8",
+    "bagua_decompress_sgd_step",
 )
 
 
@@ -52,6 +53,8 @@ def _load():
     lib.bagua_sign_compress_ef.argtypes = [vp, vp, sz, sz, vp, vp, vp]
     lib.bagua_decompress.argtypes = [i32, vp, vp, sz, sz, vp, vp]
     lib.bagua_flatten_compress_minmax_u8.argtypes = [vp, sz, vp, sz, sz, vp, vp, vp, vp]
+    lib.bagua_decompress_sgd_step.argtypes = [i32, vp, vp, sz, sz, vp, vp, ctypes.c_float, ctypes.c_float,
+                                              ctypes.c_float, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = i32
     return lib
@@ -173,6 +176,13 @@ def bagua_sign_compress_ef(x, residual, chunk, bits, scale, stream=None):
 def bagua_decompress(codec, codes, meta, n, chunk, out, stream=None):
     _check("bagua_decompress", _lib.bagua_decompress(codec, _ptr(codes), _ptr(meta, torch.float32), n, chunk,
                                                      _ptr(out, torch.float32), _stream(stream)))
+
+
+def bagua_decompress_sgd_step(codec, codes, meta, n, chunk, param, momentum_buf, lr, momentum=0.0, weight_decay=0.0,
+                              stream=None):
+    _check("bagua_decompress_sgd_step", _lib.bagua_decompress_sgd_step(
+        codec, _ptr(codes), _ptr(meta, torch.float32), n, chunk, _ptr(param, torch.float32),
+        _ptr(momentum_buf, torch.float32), lr, momentum, weight_decay, _stream(stream)))
 
 
 def raw():

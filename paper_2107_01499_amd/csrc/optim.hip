@@ -1,0 +1,100 @@
+// Decode fused into the bucket-level optimizer step: the last step of C_LP_S on every worker
+// (decode the tensor the server sent back) and the stochastic-gradient update of the flattened
+// bucket (Section 3.5 of the paper) in one pass.  The decoded gradient is never written to memory:
+// 1 (or 1/8) + 8 (+ 8 with momentum) bytes per element instead of 4 + 4 more.
+#include "launchers.hpp"
+
+#pragma clang fp contract(off)
+
+namespace bagua {
+
+// One wave per 256-element row, four rows per workgroup.
+template <int CODEC, bool MOM, bool WD>
+__global__ void __launch_bounds__(256)
+k_decompress_sgd(const void* __restrict__ codes, const float* __restrict__ meta, size_t n, uint32_t chunk,
+                 float* __restrict__ param, float* __restrict__ mbuf, float lr, float mu, float wd)
+{
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const size_t e0 = row * kRow;
+    if (e0 >= n) return;
+    const size_t c = e0 / chunk;
+    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+
+    f4 p = load_row(param + e0, lane, remain, 0.0f);
+    f4 m = f4{0.f, 0.f, 0.f, 0.f};
+    if (MOM) m = load_row(mbuf + e0, lane, remain, 0.0f);
+
+    f4 g;
+    if (CODEC == BAGUA_CODEC_MINMAX_U8) {
+        const float mn = meta[2 * c], step = minmax_step(mn, meta[2 * c + 1]);
+        const uint32_t w = load_codes_row(static_cast<const uint8_t*>(codes) + e0, lane, remain);
+        g.x = mn + byte_to_float(w, 0) * step;
+        g.y = mn + byte_to_float(w, 1) * step;
+        g.z = mn + byte_to_float(w, 2) * step;
+        g.w = mn + byte_to_float(w, 3) * step;
+    } else {
+        const float sc = meta[c];
+        const float neg = -sc;
+        uint32_t w = 0;
+        if (static_cast<long>(lane >> 3) * 32 < remain) w = static_cast<const uint32_t*>(codes)[(e0 >> 5) + (lane >> 3)];
+        const uint32_t nib = w >> (4 * (lane & 7));
+        g.x = (nib & 1u) ? sc : neg;
+        g.y = (nib & 2u) ? sc : neg;
+        g.z = (nib & 4u) ? sc : neg;
+        g.w = (nib & 8u) ? sc : neg;
+    }
+    if (WD) {
+        g.x = g.x + wd * p.x;
+        g.y = g.y + wd * p.y;
+        g.z = g.z + wd * p.z;
+        g.w = g.w + wd * p.w;
+    }
+    f4 u = g;
+    if (MOM) {
+        m.x = mu * m.x + g.x;
+        m.y = mu * m.y + g.y;
+        m.z = mu * m.z + g.z;
+        m.w = mu * m.w + g.w;
+        store_row(mbuf + e0, lane, remain, m);
+        u = m;
+    }
+    p.x = p.x - lr * u.x;
+    p.y = p.y - lr * u.y;
+    p.z = p.z - lr * u.z;
+    p.w = p.w - lr * u.w;
+    store_row(param + e0, lane, remain, p);
+}
+
+}  // namespace bagua
+
+using namespace bagua;
+
+extern "C" int bagua_decompress_sgd_step(int codec, const void* codes, const float* meta, size_t n, size_t chunk,
+                                         float* param, float* momentum_buf, float lr, float momentum,
+                                         float weight_decay, void* stream)
+{
+    if (codec != BAGUA_CODEC_MINMAX_U8 && codec != BAGUA_CODEC_SIGN1) return BAGUA_ERR_INVALID_ARG;
+    if (!codes || !meta || !param || n == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
+    if (param == momentum_buf) return BAGUA_ERR_INVALID_ARG;
+    const size_t rows = (n + kRow - 1) / kRow;
+    if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (!aligned16(codes) || !aligned16(meta) || !aligned16(param) || !aligned16(momentum_buf)) return BAGUA_ERR_ALIGNMENT;
+    dim3 grid(static_cast<unsigned>((rows + 3) / 4)), block(256);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint32_t ch = static_cast<uint32_t>(chunk);
+    const bool mom = momentum_buf != nullptr, wd = weight_decay != 0.0f;
+#define BAGUA_SGD(CODEC, MOMv, WDv)                                                                          \
+    hipLaunchKernelGGL((k_decompress_sgd<CODEC, MOMv, WDv>), grid, block, 0, s, codes, meta, n, ch, param, \
+                       momentum_buf, lr, momentum, weight_decay)
+#define BAGUA_SGD_CODEC(CODEC)                       \
+    if (mom && wd) BAGUA_SGD(CODEC, true, true);     \
+    else if (mom) BAGUA_SGD(CODEC, true, false);     \
+    else if (wd) BAGUA_SGD(CODEC, false, true);      \
+    else BAGUA_SGD(CODEC, false, false);
+    if (codec == BAGUA_CODEC_MINMAX_U8) { BAGUA_SGD_CODEC(BAGUA_CODEC_MINMAX_U8) }
+    else { BAGUA_SGD_CODEC(BAGUA_CODEC_SIGN1) }
+#undef BAGUA_SGD_CODEC
+#undef BAGUA_SGD
+    return launch_status();
+}
