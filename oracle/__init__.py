@@ -183,3 +183,16 @@ def decompress_sgd_step(codec, codes, meta, n, chunk, param, momentum_buf, lr, m
     cp = _chk(codes, np.uint8) if codec == 0 else _chk(codes, np.uint32)
     _ok(f(codec, cp, _chk(meta, np.float32), n, chunk, _chk(param, np.float32),
           None if momentum_buf is None else _chk(momentum_buf, np.float32), lr, momentum, weight_decay), "decompress_sgd_step")
+
+
+def peer_avg_fp(x_in, peer):
+    """D_FP_S with one chosen peer per worker: x_i' = (x_i + x_peer[i]) / 2. Returns the list of new replicas."""
+    k = len(x_in)
+    n = x_in[0].size
+    outs = [np.empty(n, np.float32) for _ in range(k)]
+    f = lib().oracle_peer_avg_fp
+    f.restype = ctypes.c_int
+    f.argtypes = [_c_p, _c_p, _c_p, ctypes.c_int, _c_sz]
+    pa = (ctypes.c_int * k)(*[int(p) for p in peer])
+    _ok(f(_ptr_array(x_in, np.float32), _ptr_array(outs, np.float32), pa, k, n), "peer_avg_fp")
+    return outs

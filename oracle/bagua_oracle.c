@@ -500,3 +500,29 @@ int oracle_decompress_sgd_step(int codec, const void* codes, const float* meta, 
     free(g);
     return 0;
 }
+
+/* ------------------------------------------------ decentralised averaging, "random" peer strategy */
+
+/*
+ * D_FP_S with the random peer allocation of Section 3.4 (each worker exchanges with one peer
+ * chosen for the round; "Decen-32bits" of Section 4.1 uses it).  peer[i] is the worker that
+ * worker i exchanges with in this round; reading R17: N(i) = {i, peer[i]} with weight 1/2,
+ *     x_i' = (x_i + x_peer[i]) * 0.5f        from the old values (outputs must not alias inputs).
+ * peer[i] == i leaves the replica unchanged.  For a matching (peer[peer[i]] == i) both partners
+ * receive the same bits and the replica mean is preserved.
+ */
+int oracle_peer_avg_fp(const float* const* x_in, float* const* x_out, const int* peer, int k, size_t n)
+{
+    if (!x_in || !x_out || !peer || k < 1 || k > 32 || n == 0) return 1;
+    for (int i = 0; i < k; ++i)
+        if (!x_in[i] || !x_out[i] || peer[i] < 0 || peer[i] >= k) return 1;
+    for (int i = 0; i < k; ++i) {
+        const float* a = x_in[i];
+        const float* b = x_in[peer[i]];
+        for (size_t e = 0; e < n; ++e) {
+            float s = a[e] + b[e];
+            x_out[i][e] = s * 0.5f;
+        }
+    }
+    return 0;
+}
