@@ -144,6 +144,17 @@ int bagua_decentralized_avg(int mode, const float* const* x_in, float* const* x_
                             void* stream);
 
 /*
+ * Decentralised full-precision averaging with the "random" peer strategy of Section 3.4 (each worker exchanges
+ * with one peer chosen for the round; the D_FP_S equation of Section 3.2 with N(i) = {i, peer[i]}, weight 1/2):
+ *   x_out[i] = (x_in[i] + x_in[peer[i]]) * 0.5f        from the old values.
+ *   peer    host[k], peer[i] in [0,k); chosen by the caller (e.g. a random perfect matching).  peer[i] == i
+ *           leaves replica i unchanged.  Matched pairs (peer[peer[i]] == i) are read once and receive equal bits.
+ *   x_in, x_out as in bagua_decentralized_avg (no aliasing).
+ */
+int bagua_decentralized_avg_peers(const float* const* x_in, float* const* x_out, const int* peer, int k, size_t n,
+                                  void* stream);
+
+/*
  * Worker side of C_LP_S with Q = 1-bit sign and per-chunk scale (the compression of "1-bit
  * Adam", Section 4.1 "Bagua Algorithms"):
  *   v = x + residual (v = x if NULL);  scale_c = mean over the chunk of |v| (fixed summation order);

@@ -24,7 +24,7 @@ EXPORTS = (
     "bagua_status_string", "bagua_flatten_workspace_bytes", "bagua_flatten_plan", "bagua_bucket_flatten_run",
     "bagua_bucket_flatten", "bagua_compress_minmax_u8", "bagua_decompress_reduce_recompress",
     "bagua_decentralized_avg", "bagua_sign_compress_ef", "bagua_decompress", "bagua_flatten_compress_minmax_u8",
-    "bagua_decompress_sgd_step",
+    "bagua_decompress_sgd_step", "bagua_decentralized_avg_peers",
 )
 
 
@@ -53,6 +53,7 @@ def _load():
     lib.bagua_sign_compress_ef.argtypes = [vp, vp, sz, sz, vp, vp, vp]
     lib.bagua_decompress.argtypes = [i32, vp, vp, sz, sz, vp, vp]
     lib.bagua_flatten_compress_minmax_u8.argtypes = [vp, sz, vp, sz, sz, vp, vp, vp, vp]
+    lib.bagua_decentralized_avg_peers.argtypes = [vp, vp, vp, i32, sz, vp]
     lib.bagua_decompress_sgd_step.argtypes = [i32, vp, vp, sz, sz, vp, vp, ctypes.c_float, ctypes.c_float,
                                               ctypes.c_float, vp]
     for name in EXPORTS[2:]:
@@ -165,6 +166,13 @@ def bagua_decentralized_avg(mode, x_in, x_out, xhat=None, codes=None, minmax=Non
         None if xhat is None else _ptr_array(xhat, torch.float32),
         None if codes is None else _ptr_array(codes, torch.uint8),
         None if minmax is None else _ptr_array(minmax, torch.float32), k, n, chunk, _stream(stream)))
+
+
+def bagua_decentralized_avg_peers(x_in, x_out, peer, stream=None):
+    k = len(x_in)
+    pa = (ctypes.c_int * k)(*[int(p) for p in peer])
+    _check("bagua_decentralized_avg_peers", _lib.bagua_decentralized_avg_peers(
+        _ptr_array(x_in, torch.float32), _ptr_array(x_out, torch.float32), pa, k, x_in[0].numel(), _stream(stream)))
 
 
 def bagua_sign_compress_ef(x, residual, chunk, bits, scale, stream=None):

@@ -293,3 +293,67 @@ extern "C" int bagua_decentralized_avg(int mode, const float* const* x_in, float
     if (!lp) return launch_ring_fp(x_in, x_out, k, n, s);
     return launch_ring_lp(x_in, x_out, xhat, codes, minmax, k, n, chunk, s);
 }
+
+// ------------------------------------------------------------------------------------------ chosen peers
+// x_out[i] = (x_in[i] + x_in[peer[i]]) * 0.5.  The host turns the peer map into "jobs": a matched
+// pair (a, b) is one job that reads both replicas once and writes the same bits to both outputs
+// (8 bytes per element per peer); any other worker is a job of its own that reads its two inputs.
+namespace bagua {
+
+struct PeerJobs {
+    const float* a[BAGUA_MAX_WORKERS];
+    const float* b[BAGUA_MAX_WORKERS];
+    float* out_a[BAGUA_MAX_WORKERS];
+    float* out_b[BAGUA_MAX_WORKERS];  // nullptr for a single-output job
+};
+
+__global__ void __launch_bounds__(256)
+k_peer_avg_fp(PeerJobs jobs, size_t n)
+{
+    const int job = blockIdx.y;
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const size_t e0 = row * kRow;
+    if (e0 >= n) return;
+    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const f4 xa = load_row(jobs.a[job] + e0, lane, remain, 0.0f);
+    const f4 xb = load_row(jobs.b[job] + e0, lane, remain, 0.0f);
+    const f4 o = mul4(add4(xa, xb), 0.5f);
+    store_row(jobs.out_a[job] + e0, lane, remain, o);
+    if (jobs.out_b[job]) store_row(jobs.out_b[job] + e0, lane, remain, o);
+}
+
+}  // namespace bagua
+
+extern "C" int bagua_decentralized_avg_peers(const float* const* x_in, float* const* x_out, const int* peer, int k,
+                                             size_t n, void* stream)
+{
+    if (!x_in || !x_out || !peer || k < 1 || k > BAGUA_MAX_WORKERS || n == 0) return BAGUA_ERR_INVALID_ARG;
+    for (int i = 0; i < k; ++i)
+        if (!x_in[i] || !x_out[i] || peer[i] < 0 || peer[i] >= k) return BAGUA_ERR_INVALID_ARG;
+    const size_t bytes = n * sizeof(float);
+    for (int i = 0; i < k; ++i)
+        for (int j = 0; j < k; ++j) {
+            if (overlaps(x_out[i], x_in[j], bytes)) return BAGUA_ERR_INVALID_ARG;
+            if (j != i && overlaps(x_out[i], x_out[j], bytes)) return BAGUA_ERR_INVALID_ARG;
+        }
+    for (int i = 0; i < k; ++i)
+        if (!aligned16(x_in[i]) || !aligned16(x_out[i])) return BAGUA_ERR_ALIGNMENT;
+    const size_t rows = (n + kRow - 1) / kRow;
+    if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    PeerJobs jobs{};
+    int nj = 0;
+    for (int i = 0; i < k; ++i) {
+        const int p = peer[i];
+        const bool matched = p != i && peer[p] == i;
+        if (matched && p < i) continue;  // written by the partner's job
+        jobs.a[nj] = x_in[i];
+        jobs.b[nj] = x_in[p];
+        jobs.out_a[nj] = x_out[i];
+        jobs.out_b[nj] = matched ? x_out[p] : nullptr;
+        ++nj;
+    }
+    hipLaunchKernelGGL(k_peer_avg_fp, dim3(static_cast<unsigned>((rows + 3) / 4), nj), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), jobs, n);
+    return launch_status();
+}

@@ -81,3 +81,15 @@ def test_missing_library_fails_loudly(bg, monkeypatch):
     monkeypatch.setattr(bg.binding, "LIB_PATH", "/nonexistent/libbagua_hip.so")
     with pytest.raises(ImportError):
         bg.binding._load()
+
+
+def test_peer_validation_without_gpu(bg):
+    lib = bg.binding.raw()
+    xin = (ctypes.c_void_p * 2)(0x10000, 0x20000)
+    xout = (ctypes.c_void_p * 2)(0x30000, 0x40000)
+    assert lib.bagua_decentralized_avg_peers(xin, xout, (ctypes.c_int * 2)(1, 2), 2, 16, None) == 1    # peer out of range
+    assert lib.bagua_decentralized_avg_peers(xin, xin, (ctypes.c_int * 2)(1, 0), 2, 16, None) == 1     # aliasing
+    assert lib.bagua_decentralized_avg_peers(xin, xout, None, 2, 16, None) == 1
+    assert lib.bagua_decompress_sgd_step(0, 0x1000, 0x1000, 16, 256, 0x2000, 0x2000, 0.1, 0.9, 0.0, None) == 1  # param aliases momentum
+    assert lib.bagua_decompress_sgd_step(3, 0x1000, 0x1000, 16, 256, 0x2000, None, 0.1, 0.9, 0.0, None) == 1
+    assert lib.bagua_flatten_compress_minmax_u8(None, 1, None, 16, 256, 0x1000, 0x1000, None, None) == 1
