@@ -196,3 +196,16 @@ def peer_avg_fp(x_in, peer):
     pa = (ctypes.c_int * k)(*[int(p) for p in peer])
     _ok(f(_ptr_array(x_in, np.float32), _ptr_array(outs, np.float32), pa, k, n), "peer_avg_fp")
     return outs
+
+
+def reduce_compress_minmax_u8(xs, residual, chunk):
+    """Intra-node stage of hierarchical C_LP_S: average k_local uncompressed buckets, then the leader compresses."""
+    k, n = len(xs), xs[0].size
+    codes = np.empty(n, np.uint8)
+    minmax = np.empty(2 * num_chunks(n, chunk), np.float32)
+    f = lib().oracle_reduce_compress_minmax_u8
+    f.restype = ctypes.c_int
+    f.argtypes = [_c_p, ctypes.c_int, _c_p, _c_sz, _c_sz, _c_p, _c_p]
+    _ok(f(_ptr_array(xs, np.float32), k, None if residual is None else _chk(residual, np.float32), n, chunk,
+          _chk(codes, np.uint8), _chk(minmax, np.float32)), "reduce_compress_minmax_u8")
+    return codes, minmax

@@ -526,3 +526,35 @@ int oracle_peer_avg_fp(const float* const* x_in, float* const* x_out, const int*
     }
     return 0;
 }
+
+/* ------------------------------------------------------ hierarchical C_LP_S: intra-node step */
+
+/*
+ * First stage of the hierarchical variant of C_LP_S (Section 3.5 "Hierarchical Communications"):
+ * the tensors of the k_local workers of one node are aggregated WITHOUT compression, and only the
+ * node leader compresses the aggregate for the inter-node exchange (which is the ordinary server
+ * step among leaders, oracle_drr_minmax_u8, followed by a broadcast and a local decode).
+ * Reading R18 (consistent with R2): the aggregate is the average, a = (x_0 + x_1 + ...) * fl(1/k_local)
+ * summed in ascending worker order; the leader's error state enters as in R1:
+ *     codes = Q(a + delta),  delta <- (a + delta) - decode(codes).
+ * With k_local == 1 this is not the plain worker-side compression bit for bit only because of the
+ * multiplication by 1.0f, which is exact: the results are identical.
+ */
+int oracle_reduce_compress_minmax_u8(const float* const* x, int k_local, float* residual, size_t n,
+                                     size_t chunk, uint8_t* codes, float* minmax)
+{
+    if (!x || k_local < 1 || k_local > 32 || !codes || !minmax || n == 0 || !chunk_ok(chunk)) return 1;
+    for (int j = 0; j < k_local; ++j)
+        if (!x[j]) return 1;
+    float* a = (float*)malloc(n * sizeof(float));
+    if (!a) return 1;
+    float inv = 1.0f / (float)k_local;
+    for (size_t i = 0; i < n; ++i) {
+        float s = x[0][i];
+        for (int j = 1; j < k_local; ++j) s = s + x[j][i];
+        a[i] = s * inv;
+    }
+    int rc = oracle_compress_minmax_u8(a, residual, n, chunk, codes, minmax);
+    free(a);
+    return rc;
+}
