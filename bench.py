@@ -58,7 +58,8 @@ def parse_args():
     ap.add_argument("--only", default="", help="comma list of primitives to run in the step (profiling aid)")
     ap.add_argument("--extras", default="", help="comma list of additional primitives appended to the step: sgd_step "
                     "(decode of the server's codes fused into an SGD-momentum update of every worker's replica), "
-                    "peer_fp (full-precision averaging with one chosen peer per worker)")
+                    "peer_fp (full-precision averaging with one chosen peer per worker), reduce_compress (intra-node "
+                    "stage of hierarchical C_LP_S: 4 local workers averaged uncompressed, leader compresses)")
     ap.add_argument("--fused-flatten", action="store_true",
                     help="replace flatten + compress_minmax by the fused bagua_flatten_compress_minmax_u8")
     ap.add_argument("--per-bucket-launch", action="store_true",
@@ -82,6 +83,8 @@ class Workload:
             self.prims = ["flatten_compress" if p == "flatten" else p for p in self.prims if p != "compress_minmax"]
         if "sgd_step" in extras and "drr_minmax" in self.prims:
             self.prims = self.prims + ["sgd_step"]
+        if "reduce_compress" in extras and ("flatten" in self.prims or "flatten_compress" in self.prims):
+            self.prims = self.prims + ["reduce_compress"]
         if "peer_fp" in extras and "ring_fp" in self.prims:
             self.prims = self.prims + ["peer_fp"]
         k, C, SC, cfg = self.k, self.C, self.SC, w["cfg"]
@@ -173,6 +176,11 @@ class Workload:
             self.codes_out = views(z(n, **u8))
             self.minmax_out = views(z(2 * nc, **f32), C, 2)
             self.out = views(z(n, **f32))
+        if has("reduce_compress"):      # hierarchical C_LP_S: nodes of 4 local workers, one leader each
+            self.kl = 4
+            self.hdelta = [views(z(n, **f32)) for _ in range(k // self.kl)]
+            self.hcodes = [views(z(n, **u8)) for _ in range(k // self.kl)]
+            self.hminmax = [views(z(2 * nc, **f32), C, 2) for _ in range(k // self.kl)]
         if has("sgd_step"):
             self.param = [views(draw("normal", n, seed_for(cfg, 50, j), dev, 0.02)) for j in range(k)]
             self.mbuf = [views(z(n, **f32)) for _ in range(k)]
@@ -215,7 +223,7 @@ class Workload:
         k, C, SC = self.k, self.C, self.SC
         wb = 4.0 if "sign_compress" in self.prims else 0.0   # the fused call also writes the bucket if it is needed later
         return {"flatten": 8.0, "flatten_compress": 13.0 + wb + 8.0 / C, "compress_minmax": 13.0 + 8.0 / C, "drr_minmax": k + 13.0 + 8.0 * (k + 1) / C,
-                "sgd_step": 17.0 + 8.0 / C, "peer_fp": 8.0, "ring_fp": 8.0, "ring_lp": 17.0 + 8.0 / C, "sign_compress": 12.125 + 4.0 / SC,
+                "sgd_step": 17.0 + 8.0 / C, "reduce_compress": 4.0 * 4 + 9.0 + 8.0 / C, "peer_fp": 8.0, "ring_fp": 8.0, "ring_lp": 17.0 + 8.0 / C, "sign_compress": 12.125 + 4.0 / SC,
                 "drr_sign": k / 8.0 + 12.125 + 4.0 * (k + 1) / SC}
 
     def grad_bytes(self):
@@ -225,14 +233,14 @@ class Workload:
     def algo_bytes(self):
         n, k = self.n_elems, self.k
         units = {"flatten": n * k, "flatten_compress": n * k, "compress_minmax": n * k, "drr_minmax": n, "ring_fp": n * k, "ring_lp": n * k,
-                 "sign_compress": n * k, "drr_sign": n, "sgd_step": n * k, "peer_fp": n * k}
+                 "sign_compress": n * k, "drr_sign": n, "sgd_step": n * k, "peer_fp": n * k, "reduce_compress": n * (k // 4)}
         bpe = self.bytes_per_element()
         return {p: bpe[p] * units[p] for p in self.prims}
 
     def launches(self):
         U, k = len(self.units), self.k
         per = {"flatten": U * k, "flatten_compress": U * k, "compress_minmax": U * k, "drr_minmax": U, "ring_fp": U, "ring_lp": U,
-               "sign_compress": U * k, "drr_sign": U, "sgd_step": U * k, "peer_fp": U}
+               "sign_compress": U * k, "drr_sign": U, "sgd_step": U * k, "peer_fp": U, "reduce_compress": U * (k // 4)}
         return {p: per[p] for p in self.prims}
 
     def kernel_name(self, p):
@@ -241,7 +249,7 @@ class Workload:
                 "drr_minmax": "k_drr_minmax<4,true,true>", "ring_fp": "k_ring_avg_fp<%d>" % self.k,
                 "ring_lp": "k_ring_avg_lp<%d,2>" % self.k, "sign_compress": "k_sign_compress<2,true>",
                 "drr_sign": "k_drr_sign<4,true,true>", "sgd_step": "k_decompress_sgd<0,true,false>",
-                "peer_fp": "k_peer_avg_fp"}[p]
+                "peer_fp": "k_peer_avg_fp", "reduce_compress": "k_reduce_compress_minmax<2,true>"}[p]
 
     # ---- one pass of the hot path ------------------------------------------------------------------
     def step(self, marks=None):
@@ -285,6 +293,11 @@ class Workload:
                     for u in range(U):
                         bg.bagua_decompress_sgd_step(bg.CODEC_MINMAX_U8, self.codes_out[u], self.minmax_out[u],
                                                      self.units[u][1], C, self.param[j][u], self.mbuf[j][u], 0.01, 0.9, 0.0)
+            elif p == "reduce_compress":
+                for a in range(k // self.kl):
+                    for u in range(U):
+                        bg.bagua_reduce_compress_minmax_u8([self.bucket[a * self.kl + b][u] for b in range(self.kl)],
+                                                           self.hdelta[a][u], C, self.hcodes[a][u], self.hminmax[a][u])
             elif p == "peer_fp":
                 for u in range(U):     # a fixed perfect matching (0,1)(2,3)...; reads what ring_fp just wrote
                     bg.bagua_decentralized_avg_peers([self.rep_fp[dst][i][u] for i in range(k)],

@@ -144,6 +144,18 @@ int bagua_decentralized_avg(int mode, const float* const* x_in, float* const* x_
                             void* stream);
 
 /*
+ * Intra-node stage of the hierarchical variant of C_LP_S (Section 3.5 "Hierarchical Communications": the workers
+ * of one node are aggregated without compression, only the node leaders exchange compressed tensors): average the
+ * k_local workers' uncompressed buckets in ascending order, then compress as bagua_compress_minmax_u8 does, with
+ * the leader's error state:
+ *   a = (x[0] + x[1] + ...) * fl(1/k_local);  v = a + residual;  codes = Q(v);  residual <- v - decode(codes).
+ * The inter-node stage is bagua_decompress_reduce_recompress over the leaders' codes.
+ *   x   host[k_local] of device fp32[n], read only;  residual device fp32[n] in-out or NULL; codes, minmax written
+ */
+int bagua_reduce_compress_minmax_u8(const float* const* x, int k_local, float* residual, size_t n, size_t chunk,
+                                    uint8_t* codes, float* minmax, void* stream);
+
+/*
  * Decentralised full-precision averaging with the "random" peer strategy of Section 3.4 (each worker exchanges
  * with one peer chosen for the round; the D_FP_S equation of Section 3.2 with N(i) = {i, peer[i]}, weight 1/2):
  *   x_out[i] = (x_in[i] + x_in[peer[i]]) * 0.5f        from the old values.

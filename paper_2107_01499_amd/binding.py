@@ -24,7 +24,7 @@ EXPORTS = (
     "bagua_status_string", "bagua_flatten_workspace_bytes", "bagua_flatten_plan", "bagua_bucket_flatten_run",
     "bagua_bucket_flatten", "bagua_compress_minmax_u8", "bagua_decompress_reduce_recompress",
     "bagua_decentralized_avg", "bagua_sign_compress_ef", "bagua_decompress", "bagua_flatten_compress_minmax_u8",
-    "bagua_decompress_sgd_step", "bagua_decentralized_avg_peers",
+    "bagua_decompress_sgd_step", "bagua_decentralized_avg_peers", "bagua_reduce_compress_minmax_u8",
 )
 
 
@@ -53,6 +53,7 @@ def _load():
     lib.bagua_sign_compress_ef.argtypes = [vp, vp, sz, sz, vp, vp, vp]
     lib.bagua_decompress.argtypes = [i32, vp, vp, sz, sz, vp, vp]
     lib.bagua_flatten_compress_minmax_u8.argtypes = [vp, sz, vp, sz, sz, vp, vp, vp, vp]
+    lib.bagua_reduce_compress_minmax_u8.argtypes = [vp, i32, vp, sz, sz, vp, vp, vp]
     lib.bagua_decentralized_avg_peers.argtypes = [vp, vp, vp, i32, sz, vp]
     lib.bagua_decompress_sgd_step.argtypes = [i32, vp, vp, sz, sz, vp, vp, ctypes.c_float, ctypes.c_float,
                                               ctypes.c_float, vp]
@@ -166,6 +167,12 @@ def bagua_decentralized_avg(mode, x_in, x_out, xhat=None, codes=None, minmax=Non
         None if xhat is None else _ptr_array(xhat, torch.float32),
         None if codes is None else _ptr_array(codes, torch.uint8),
         None if minmax is None else _ptr_array(minmax, torch.float32), k, n, chunk, _stream(stream)))
+
+
+def bagua_reduce_compress_minmax_u8(xs, residual, chunk, codes, minmax, stream=None):
+    _check("bagua_reduce_compress_minmax_u8", _lib.bagua_reduce_compress_minmax_u8(
+        _ptr_array(xs, torch.float32), len(xs), _ptr(residual, torch.float32), xs[0].numel(), chunk,
+        _ptr(codes, torch.uint8), _ptr(minmax, torch.float32), _stream(stream)))
 
 
 def bagua_decentralized_avg_peers(x_in, x_out, peer, stream=None):

@@ -57,6 +57,64 @@ k_flatten_compress_minmax(const TensorDesc* __restrict__ desc, const uint32_t* _
                                         codes + base, minmax + 2 * c, nullptr, s_red);
 }
 
+// Intra-node stage of hierarchical C_LP_S (Section 3.5): the k_local workers' uncompressed buckets are
+// averaged (ascending order, one multiply by inv_k) and the leader compresses the average with its
+// error state.  4*k_local + 9 bytes per element, one pass.
+template <int RPW, bool EF>
+__global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
+k_reduce_compress_minmax(PtrTable xs, int k_local, float inv_k, float* __restrict__ residual, size_t n, uint32_t chunk,
+                         uint8_t* __restrict__ codes, float* __restrict__ minmax)
+{
+    __shared__ float s_red[2 * kMaxWaves];
+    const size_t c = blockIdx.x;
+    const size_t base = c * static_cast<size_t>(chunk);
+    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+
+    f4 v[RPW];
+    for (int j = 0; j < k_local; ++j) {
+        const float* xj = static_cast<const float*>(xs.p[j]) + base;
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const long off = static_cast<long>(wave * RPW + i) * kRow;
+            const long remain = len - off;
+            f4 d = f4{0.f, 0.f, 0.f, 0.f};
+            if (remain > 0) d = load_row(xj + off, lane, remain, 0.0f);
+            if (j == 0) {
+                v[i] = d;
+            } else {
+                v[i].x = v[i].x + d.x;
+                v[i].y = v[i].y + d.y;
+                v[i].z = v[i].z + d.z;
+                v[i].w = v[i].w + d.w;
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        v[i].x = v[i].x * inv_k;
+        v[i].y = v[i].y * inv_k;
+        v[i].z = v[i].z * inv_k;
+        v[i].w = v[i].w * inv_k;
+    }
+    if (EF) {
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const long off = static_cast<long>(wave * RPW + i) * kRow;
+            const long remain = len - off;
+            if (remain > 0) {
+                const f4 d = load_row(residual + base + off, lane, remain, 0.0f);
+                v[i].x = v[i].x + d.x;
+                v[i].y = v[i].y + d.y;
+                v[i].z = v[i].z + d.z;
+                v[i].w = v[i].w + d.w;
+            }
+        }
+    }
+    minmax_encode_chunk<RPW, EF, false>(v, len, wave, lane, nwaves, EF ? residual + base : nullptr,
+                                        codes + base, minmax + 2 * c, nullptr, s_red);
+}
+
 }  // namespace bagua
 
 using namespace bagua;
@@ -85,5 +143,34 @@ extern "C" int bagua_flatten_compress_minmax_u8(const void* workspace, size_t T,
     else if (bucket_out) { BAGUA_FC(false, true) }
     else { BAGUA_FC(false, false) }
 #undef BAGUA_FC
+    return launch_status();
+}
+
+extern "C" int bagua_reduce_compress_minmax_u8(const float* const* x, int k_local, float* residual, size_t n,
+                                               size_t chunk, uint8_t* codes, float* minmax, void* stream)
+{
+    if (!x || k_local < 1 || k_local > BAGUA_MAX_WORKERS || !codes || !minmax || n == 0 || !chunk_ok(chunk))
+        return BAGUA_ERR_INVALID_ARG;
+    for (int j = 0; j < k_local; ++j)
+        if (!x[j] || x[j] == residual) return BAGUA_ERR_INVALID_ARG;
+    if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    for (int j = 0; j < k_local; ++j)
+        if (!aligned16(x[j])) return BAGUA_ERR_ALIGNMENT;
+    if (!aligned16(residual) || !aligned16(codes) || !aligned16(minmax)) return BAGUA_ERR_ALIGNMENT;
+    PtrTable xt{};
+    for (int j = 0; j < k_local; ++j) xt.p[j] = x[j];
+    const int rows = static_cast<int>(chunk / kRow);
+    const int rpw = pick_rpw(rows, BAGUA_RPW_COMPRESS);
+    dim3 grid(static_cast<unsigned>(num_chunks(n, chunk))), block(64 * ((rows + rpw - 1) / rpw));
+    const float inv_k = 1.0f / static_cast<float>(k_local);
+    const uint32_t ch = static_cast<uint32_t>(chunk);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (residual) {
+        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_reduce_compress_minmax<RPW, true>), grid, block, 0, s, xt, k_local,
+                                                   inv_k, residual, n, ch, codes, minmax))
+    } else {
+        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_reduce_compress_minmax<RPW, false>), grid, block, 0, s, xt, k_local,
+                                                   inv_k, residual, n, ch, codes, minmax))
+    }
     return launch_status();
 }
