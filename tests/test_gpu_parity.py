@@ -396,3 +396,89 @@ def test_flatten_compress_fused_resnet50(bg, oracle):
     bg.bagua_flatten_compress_minmax_u8(ws, len(gs), rg, b.n_pad, C, codes, mm)
     assert np.array_equal(host(codes), co) and np.array_equal(host(mm).view(np.uint32), mo.view(np.uint32))
     assert_fp32_close_and_exact(host(rg), res_o, "fused residual resnet50")
+
+
+# ----------------------------------------------------------------------------- state round trip, graph replay
+def test_error_state_checkpoint_round_trip(bg):
+    """The only persistent state of the path are the caller-owned residual buffers: three iterations straight
+    equal two iterations + copying the residuals out and back in (as a checkpoint would) + one iteration."""
+    n, C, k = 6 * 4096 + 100, 4096, 3
+    nc = bg.num_chunks(n, C)
+    xs = [[dev(vals(n, 10 * it + j)) for j in range(k)] for it in range(3)]
+
+    def run(iters, delta, eps):
+        out = None
+        for it in iters:
+            codes = [torch.empty(n, dtype=torch.uint8, device="cuda") for _ in range(k)]
+            mm = [torch.empty(2 * nc, device="cuda") for _ in range(k)]
+            for j in range(k):
+                bg.bagua_compress_minmax_u8(xs[it][j], delta[j], C, codes[j], mm[j])
+            c2 = torch.empty(n, dtype=torch.uint8, device="cuda"); m2 = torch.empty(2 * nc, device="cuda")
+            out = torch.empty(n, device="cuda")
+            bg.bagua_decompress_reduce_recompress(bg.CODEC_MINMAX_U8, codes, mm, eps, n, C, c2, m2, out)
+        return out
+
+    d1 = [torch.zeros(n, device="cuda") for _ in range(k)]; e1 = torch.zeros(n, device="cuda")
+    straight = run(range(3), d1, e1)
+    d2 = [torch.zeros(n, device="cuda") for _ in range(k)]; e2 = torch.zeros(n, device="cuda")
+    run(range(2), d2, e2)
+    saved = [host(d).copy() for d in d2], host(e2).copy()
+    d3 = [dev(s) for s in saved[0]]; e3 = dev(saved[1])
+    resumed = run([2], d3, e3)
+    assert torch.equal(straight.view(torch.int32), resumed.view(torch.int32))
+    assert torch.equal(e1.view(torch.int32), e3.view(torch.int32))
+    for a, b in zip(d1, d3):
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+
+
+def test_hip_graph_replay_matches_eager(bg, oracle):
+    """The entry points allocate nothing and only enqueue kernels, so a step can be captured into a HIP graph.
+    Replayed several times with eager work and synchronisation in between, every replay must equal the oracle."""
+    n, C, k = 5 * 4096 + 300, 4096, 4
+    nc = bg.num_chunks(n, C)
+    x = [torch.zeros(n, device="cuda") for _ in range(k)]
+    delta = [torch.zeros(n, device="cuda") for _ in range(k)]
+    eps = torch.zeros(n, device="cuda")
+    codes = [torch.empty(n, dtype=torch.uint8, device="cuda") for _ in range(k)]
+    mm = [torch.empty(2 * nc, device="cuda") for _ in range(k)]
+    c2 = torch.empty(n, dtype=torch.uint8, device="cuda"); m2 = torch.empty(2 * nc, device="cuda"); out = torch.empty(n, device="cuda")
+    bits = torch.empty((n + 31) // 32, dtype=torch.int32, device="cuda"); scale = torch.empty(bg.num_chunks(n, 2048), device="cuda")
+
+    def step():
+        for j in range(k):
+            bg.bagua_compress_minmax_u8(x[j], delta[j], C, codes[j], mm[j])
+        bg.bagua_decompress_reduce_recompress(bg.CODEC_MINMAX_U8, codes, mm, eps, n, C, c2, m2, out)
+        bg.bagua_sign_compress_ef(out, None, 2048, bits, scale)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                  # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    for d in delta:
+        d.zero_()
+    eps.zero_()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for d in delta:
+        d.zero_()
+    eps.zero_()
+    d_o = [np.zeros(n, np.float32) for _ in range(k)]
+    e_o = np.zeros(n, np.float32)
+    for it in range(3):
+        xs = [vals(n, 500 + 10 * it + j) for j in range(k)]
+        for j in range(k):
+            x[j].copy_(torch.from_numpy(xs[j]))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        enc = [oracle.compress_minmax_u8(xs[j], d_o[j], C) for j in range(k)]
+        co, mo, oo = oracle.drr_minmax_u8([e[0] for e in enc], [e[1] for e in enc], e_o, C)
+        bo, so = oracle.sign_compress_ef(oo, None, 2048)
+        assert np.array_equal(host(c2), co), "replay %d" % it
+        assert np.array_equal(host(out).view(np.uint32), oo.view(np.uint32)), "replay %d" % it
+        assert np.array_equal(host(eps).view(np.uint32), e_o.view(np.uint32)), "replay %d" % it
+        assert np.array_equal(host(bits).view(np.uint32), bo) and np.array_equal(host(scale).view(np.uint32), so.view(np.uint32))
+        for j in range(k):
+            assert np.array_equal(host(delta[j]).view(np.uint32), d_o[j].view(np.uint32))
