@@ -352,9 +352,46 @@ def cpu_baseline(wl, torch):
         oracle.drr_sign([e[0] for e in senc], [e[1] for e in senc], np.zeros(n, np.float32), n, SC)
         dt += time.perf_counter() - t0
     grad_bytes = 4.0 * wl.n_elems * k * len(ALL_PRIMS)
+    # the same on one core, on the last (smallest) bucket only
+    oracle.set_threads(1)
+    bk = wl.buckets[-1]
+    n1, lo = bk.n_pad, wl.bases[len(wl.buckets) - 1]
+    flats = [torch.cat(wl.bucket[j])[lo:lo + n1].cpu().numpy() for j in range(k)]
+    t0 = time.perf_counter()
+    enc = [oracle.compress_minmax_u8(flats[j], np.zeros(n1, np.float32), C) for j in range(k)]
+    oracle.drr_minmax_u8([e[0] for e in enc], [e[1] for e in enc], np.zeros(n1, np.float32), C)
+    senc = [oracle.sign_compress_ef(flats[j], np.zeros(n1, np.float32), SC) for j in range(k)]
+    oracle.drr_sign([e[0] for e in senc], [e[1] for e in senc], np.zeros(n1, np.float32), n1, SC)
+    dt1 = time.perf_counter() - t0
+    oracle.set_threads(threads)
     return {"value": round(grad_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": "one full step of the same workload (%d elements x %d workers, all seven primitives), "
-                      "%.1f s wall on %d threads" % (wl.n_elems, k, dt, threads)}
+                      "%.1f s wall on %d threads" % (wl.n_elems, k, dt, threads),
+            "one_core_value": round(4.0 * n1 * k * 4 / dt1 / 1e9, 3),
+            "one_core_sample": "compress_minmax, drr_minmax, sign_compress, drr_sign on the last bucket "
+                               "(%d elements x %d workers), %.1f s on 1 thread" % (n1, k, dt1)}
+
+
+def copy_ceiling(torch, bg):
+    """Throughput of a plain 128-bit copy on this GPU, for context next to the roofline: bagua_bucket_flatten_run with
+    a single tensor covering the whole bucket is exactly that (read 4 B, write 4 B per element).  GB/s."""
+    n = 128 * 1024 * 1024
+    bufs = [(torch.zeros(n, device="cuda"), torch.empty(n, device="cuda")) for _ in range(2)]   # 2 GiB rotated
+    plans = []
+    for src, dst in bufs:
+        ws = torch.empty(bg.bagua_flatten_workspace_bytes(1, n), dtype=torch.uint8, device="cuda")
+        bg.bagua_flatten_plan([src], [0], n, ws)
+        plans.append(ws)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for i in range(4):
+        bg.bagua_bucket_flatten_run(plans[i % 2], 1, bufs[i % 2][1])
+    ev[0].record()
+    reps = 20
+    for i in range(reps):
+        bg.bagua_bucket_flatten_run(plans[i % 2], 1, bufs[i % 2][1])
+    ev[1].record()
+    torch.cuda.synchronize()
+    return 8.0 * n * reps / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
 
 
 def read_traffic():
@@ -382,6 +419,7 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     only = set(p for p in args.only.split(",") if p) or None
+    ceiling = copy_ceiling(torch, bg)
     wl = Workload(torch, bg, args.workload, per_bucket=args.per_bucket_launch, only=only, fused=args.fused_flatten,
                   extras=tuple(e for e in args.extras.split(",") if e))
     prims = wl.prims
@@ -414,7 +452,8 @@ def main():
     for p in prims:
         t = prim_ms[p] * 1e-3
         per_prim[p] = {"ms": round(prim_ms[p], 4), "launches": nl[p], "gradient_GBps": round(gb[p] / t / 1e9, 1),
-                       "hbm_GBps": round(ab[p] / t / 1e9, 1), "frac_of_peak": round(ab[p] / t / 1e9 / HBM_PEAK_GBS, 4)}
+                       "hbm_GBps": round(ab[p] / t / 1e9, 1), "frac_of_peak": round(ab[p] / t / 1e9 / HBM_PEAK_GBS, 4),
+                       "frac_of_copy_kernel": round(ab[p] / t / 1e9 / ceiling, 4)}
     dom = next((p for p in ("compress_minmax", "flatten_compress") if p in prims), None) or max(prims, key=lambda p: prim_ms[p])
     dom_t = prim_ms[dom] * 1e-3 / nl[dom]
     achieved = ab[dom] / nl[dom] / dom_t / 1e9
@@ -432,6 +471,7 @@ def main():
                    "launch": "per bucket" if args.per_bucket_launch else "per worker (all buckets of a worker in one launch)",
                    "elements_per_worker": wl.n_elems},
         "gpu_ms_per_step": round(gpu_ms / args.steps, 4),
+        "copy_kernel_GBps": round(ceiling, 1),
         "per_primitive": per_prim,
         "roofline": {"bound": "hbm", "kernel": wl.kernel_name(dom), "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,

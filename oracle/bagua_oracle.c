@@ -44,6 +44,24 @@
  *  R9  Bit order of the sign codec: bit b of 32-bit word w is element 32w+b of the bucket.
  *  R10 Flatten (Section 3.5): tensors are copied to caller-given element offsets of one
  *      contiguous bucket, everything not covered by a tensor is +0.0f.
+ *  R11 Bucket size and bucketing heuristic are not given (Section 3.1 "Bucketing"): the
+ *      benchmark workloads use greedy 25 MiB buckets in definition order, padded to a multiple
+ *      of k*C (that rule lives with the workload generators, not here).
+ *  R12 Chunks are counted over the whole padded bucket, so each of the k ScatterReduce
+ *      partitions (Section 3.4) is a whole number of chunks and one pass over n elements
+ *      equals k servers each doing n/k; the server error state epsilon is one fp32[n] buffer,
+ *      the concatenation of the k servers' partitions.
+ *  R13 Chunk sizes come from the benchmark configurations (4096, 8192, 2048); any multiple of
+ *      256 in [256, 16384] is accepted.
+ *  R14 Scale of the sign codec: sum * fl(1/C) for a full chunk with C a power of two (an exact
+ *      scaling), otherwise sum / (float)length.
+ *  R15 A chunk whose range is so small that 255/range overflows follows the same formula
+ *      (inf clamps to 255, NaN to 0).
+ *  R16 The optimizer that follows the primitive on the flattened bucket is not fixed by the
+ *      paper: SGD with optional weight decay and momentum (oracle_decompress_sgd_step).
+ *  R17 Random peer strategy: N(i) = {i, peer[i]}, weight 1/2 (oracle_peer_avg_fp).
+ *  R18 Hierarchical C_LP_S, intra-node stage: uncompressed average of the local workers, then
+ *      the leader's Q with its error state (oracle_reduce_compress_minmax_u8).
  *
  * Status codes: 0 ok, 1 invalid argument.
  */

@@ -278,3 +278,31 @@ def test_invalid_arguments(oracle):
             oracle.compress_minmax_u8(x, None, C)
     with pytest.raises(ValueError):
         oracle.compress_minmax_u8(np.zeros(0, np.float32), None, 256)
+
+
+@pytest.mark.parametrize("n", SIZES + [4096 - 1, 4096 + 1])
+@pytest.mark.parametrize("C", [256, 4096])
+@pytest.mark.parametrize("ef", [False, True])
+def test_independent_numpy_fp32_emulation(oracle, n, C, ef):
+    """P8: a second implementation in NumPy float32 (every operation rounds once, written from the definition of
+    the codec, not from the oracle's source) agrees bit for bit on codes, statistics and residuals."""
+    f = np.float32
+    x = rand(n, 4000 + n + C, "t3")
+    d0 = (rand(n, 4001 + n) * f(0.1)) if ef else None
+    d = None if d0 is None else d0.copy()
+    codes, mm = oracle.compress_minmax_u8(x, d, C)
+    for c, (lo, hi) in enumerate(chunks(n, C)):
+        v = (x[lo:hi] + d0[lo:hi]).astype(f) if ef else x[lo:hi]
+        mn, mx = f(v.min() + f(0)), f(v.max() + f(0))
+        r = f(mx - mn)
+        if r == 0:
+            want_codes = np.zeros(hi - lo, np.uint8); step = f(0)
+        else:
+            inv, step = f(f(255) / r), f(r / f(255))
+            t = ((v - mn).astype(f) * inv).astype(f)
+            want_codes = np.clip(np.rint(t), 0, 255).astype(np.uint8)
+        assert np.array_equal(codes[lo:hi], want_codes)
+        assert mm[2 * c].tobytes() == mn.tobytes() and mm[2 * c + 1].tobytes() == mx.tobytes()
+        if ef:
+            deq = (mn + (want_codes.astype(f) * step).astype(f)).astype(f)
+            assert np.array_equal(d[lo:hi], (v - deq).astype(f))
