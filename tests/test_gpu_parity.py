@@ -482,3 +482,40 @@ def test_hip_graph_replay_matches_eager(bg, oracle):
         assert np.array_equal(host(bits).view(np.uint32), bo) and np.array_equal(host(scale).view(np.uint32), so.view(np.uint32))
         for j in range(k):
             assert np.array_equal(host(delta[j]).view(np.uint32), d_o[j].view(np.uint32))
+
+
+def test_flatten_thousands_of_tiny_tensors(bg, oracle):
+    """Many tensors of 0-5 elements with random gaps: every tile holds hundreds of tensors, so the per-lane
+    binary search and the element-wise walk of both the flatten kernel and the fused gather are exercised."""
+    r = np.random.default_rng(11)
+    sizes = r.integers(0, 6, 3000).tolist() + [5000] + r.integers(0, 6, 500).tolist()
+    srcs = [r.standard_normal(s).astype(np.float32) for s in sizes]
+    offs, pos = [], 0
+    for s in sizes:
+        pos += int(r.integers(0, 3))
+        offs.append(pos)
+        pos += s
+    total = pos + 7
+    flat = oracle.bucket_flatten(srcs, offs, total)
+    arena = torch.zeros(sum(sizes) + len(sizes) + 8, device="cuda")
+    gs, p = [], 3
+    for s in srcs:
+        t = arena[p:p + s.size]
+        if s.size:
+            t.copy_(torch.from_numpy(s))
+        gs.append(t)
+        p += s.size
+    ws = torch.empty(bg.bagua_flatten_workspace_bytes(len(gs), total), dtype=torch.uint8, device="cuda")
+    bucket = torch.full((total,), float("nan"), device="cuda")
+    bg.bagua_bucket_flatten(gs, offs, bucket, ws)
+    assert host(bucket).tobytes() == flat.tobytes()
+    C = 256
+    res_o = (r.standard_normal(total) * 0.1).astype(np.float32)
+    rg = dev(res_o)
+    co, mo = oracle.compress_minmax_u8(flat, res_o, C)
+    codes = torch.empty(total, dtype=torch.uint8, device="cuda"); mm = torch.empty(2 * bg.num_chunks(total, C), device="cuda")
+    b2 = torch.full((total,), float("nan"), device="cuda")
+    bg.bagua_flatten_compress_minmax_u8(ws, len(gs), rg, total, C, codes, mm, b2)
+    assert np.array_equal(host(codes), co) and np.array_equal(host(mm).view(np.uint32), mo.view(np.uint32))
+    assert_fp32_close_and_exact(host(rg), res_o, "residual")
+    assert host(b2).tobytes() == flat.tobytes()
