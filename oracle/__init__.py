@@ -209,3 +209,17 @@ def reduce_compress_minmax_u8(xs, residual, chunk):
     _ok(f(_ptr_array(xs, np.float32), k, None if residual is None else _chk(residual, np.float32), n, chunk,
           _chk(codes, np.uint8), _chk(minmax, np.float32)), "reduce_compress_minmax_u8")
     return codes, minmax
+
+
+def bucket_unflatten(bucket, dsts, src_offset):
+    """Inverse of bucket_flatten: writes every tensor's range of the bucket into the given arrays (in place)."""
+    T = len(dsts)
+    numel = (ctypes.c_size_t * max(T, 1))(*[d.size for d in dsts])
+    offs = (ctypes.c_size_t * max(T, 1))(*[int(o) for o in src_offset])
+    ptrs = (ctypes.c_void_p * max(T, 1))()
+    for i, d in enumerate(dsts):
+        ptrs[i] = _chk(d, np.float32) if d.size else None
+    f = lib().oracle_bucket_unflatten
+    f.restype = ctypes.c_int
+    f.argtypes = [_c_p, _c_sz, _c_p, _c_p, _c_p, _c_sz]
+    _ok(f(_chk(bucket, np.float32), bucket.size, ptrs, numel, offs, T), "bucket_unflatten")

@@ -576,3 +576,24 @@ int oracle_reduce_compress_minmax_u8(const float* const* x, int k_local, float* 
     free(a);
     return rc;
 }
+
+/*
+ * Inverse of the flatten (Section 3.5): copy every tensor's range of the bucket back to the
+ * tensor; bucket elements not covered by a tensor are ignored.  Same layout rules as
+ * oracle_bucket_flatten.
+ */
+int oracle_bucket_unflatten(const float* bucket, size_t bucket_numel, float* const* dst, const size_t* numel,
+                            const size_t* src_offset, size_t T)
+{
+    if (!bucket || bucket_numel == 0 || (T && (!dst || !numel || !src_offset))) return 1;
+    size_t prev_end = 0;
+    for (size_t t = 0; t < T; ++t) {
+        if (numel[t] && !dst[t]) return 1;
+        if (src_offset[t] < prev_end) return 1;
+        if (src_offset[t] + numel[t] > bucket_numel) return 1;
+        prev_end = src_offset[t] + numel[t];
+    }
+    for (size_t t = 0; t < T; ++t)
+        for (size_t e = 0; e < numel[t]; ++e) dst[t][e] = bucket[src_offset[t] + e];
+    return 0;
+}

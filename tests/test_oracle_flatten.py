@@ -38,3 +38,23 @@ def test_flatten_rejects_overlap_and_overflow(oracle):
         oracle.bucket_flatten([a, a], [0, 5], 100)
     with pytest.raises(ValueError):
         oracle.bucket_flatten([a], [95], 100)
+
+
+def test_unflatten_inverts_flatten(oracle):
+    """Round trip: unflatten(flatten(tensors)) returns the tensors; gap elements of the bucket are ignored."""
+    r = np.random.default_rng(4)
+    sizes = [1, 7, 64, 0, 1000, 3, 4096, 129]
+    srcs = [r.standard_normal(s).astype(np.float32) for s in sizes]
+    offs, pos = [], 0
+    for i, s in enumerate(sizes):
+        pos += (i % 3)
+        offs.append(pos)
+        pos += s
+    bucket = oracle.bucket_flatten(srcs, offs, pos + 9)
+    bucket[[o - 1 for o, i in zip(offs, range(len(offs))) if i % 3]] = 123.0      # poison the gaps
+    outs = [np.full(s, np.nan, np.float32) for s in sizes]
+    oracle.bucket_unflatten(bucket, outs, offs)
+    for a, b in zip(outs, srcs):
+        assert a.tobytes() == b.tobytes()
+    with pytest.raises(ValueError):
+        oracle.bucket_unflatten(bucket, outs, [0] * len(offs))
