@@ -79,6 +79,15 @@ int bagua_bucket_flatten(const void* const* src, const size_t* numel, const size
                          void* stream);
 
 /*
+ * Inverse of the flatten: copy each tensor's range [dst_offset[t], dst_offset[t] + numel[t]) of the bucket back
+ * into tensor t (for callers whose layer tensors are not views of the bucket).  Uses a workspace planned by
+ * bagua_flatten_plan; the tensor pointers given to the plan are written through, so they must be writable.
+ * Bucket elements no tensor covers are ignored.
+ */
+int bagua_bucket_unflatten_run(const void* workspace, size_t T, const float* bucket, size_t bucket_numel,
+                               void* stream);
+
+/*
  * Worker side of C_LP_S (Section 3.2, terms Q(x_j - delta_j) and delta_j' of the C_LP_S
  * equations) with Q = per-chunk MinMax uint8:
  *   v = x + residual (v = x if residual == NULL);  per chunk mn = min v, mx = max v;

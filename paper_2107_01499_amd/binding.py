@@ -25,6 +25,7 @@ EXPORTS = (
     "bagua_bucket_flatten", "bagua_compress_minmax_u8", "bagua_decompress_reduce_recompress",
     "bagua_decentralized_avg", "bagua_sign_compress_ef", "bagua_decompress", "bagua_flatten_compress_minmax_u8",
     "bagua_decompress_sgd_step", "bagua_decentralized_avg_peers", "bagua_reduce_compress_minmax_u8",
+    "bagua_bucket_unflatten_run",
 )
 
 
@@ -46,6 +47,7 @@ def _load():
     lib.bagua_flatten_workspace_bytes.argtypes = [sz, sz]
     lib.bagua_flatten_plan.argtypes = [vp, vp, vp, sz, sz, vp, sz, vp]
     lib.bagua_bucket_flatten_run.argtypes = [vp, sz, vp, sz, vp]
+    lib.bagua_bucket_unflatten_run.argtypes = [vp, sz, vp, sz, vp]
     lib.bagua_bucket_flatten.argtypes = [vp, vp, vp, sz, vp, sz, vp, sz, vp]
     lib.bagua_compress_minmax_u8.argtypes = [vp, vp, sz, sz, vp, vp, vp]
     lib.bagua_decompress_reduce_recompress.argtypes = [i32, vp, vp, i32, vp, sz, sz, vp, vp, vp, vp]
@@ -129,6 +131,12 @@ def bagua_flatten_plan(srcs, dst_offset, bucket_numel, workspace, stream=None):
 def bagua_bucket_flatten_run(workspace, T, bucket, stream=None):
     _check("bagua_bucket_flatten_run", _lib.bagua_bucket_flatten_run(_ptr(workspace), T, _ptr(bucket, torch.float32),
                                                                      bucket.numel(), _stream(stream)))
+
+
+def bagua_bucket_unflatten_run(workspace, T, bucket, stream=None):
+    """Inverse of the flatten: scatter the bucket back into the tensors the workspace was planned with."""
+    _check("bagua_bucket_unflatten_run", _lib.bagua_bucket_unflatten_run(_ptr(workspace), T, _ptr(bucket, torch.float32),
+                                                                         bucket.numel(), _stream(stream)))
 
 
 def bagua_bucket_flatten(srcs, dst_offset, bucket, workspace, stream=None):

@@ -79,6 +79,64 @@ k_flatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile
     }
 }
 
+// Inverse scatter: copy every tensor's range of the bucket back into the tensor (same table as the
+// flatten; bucket elements no tensor covers are skipped).  The tensors' pointers in the table are
+// written through, so the table must have been planned with writable tensors.
+__global__ void __launch_bounds__(256)
+k_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile_first, uint32_t T,
+            const float* __restrict__ bucket, size_t bucket_numel)
+{
+    const size_t tile0 = static_cast<size_t>(blockIdx.x) * kTile;
+    const uint32_t lo0 = tile_first[blockIdx.x], hi0 = tile_first[blockIdx.x + 1];
+    if (lo0 < T && tile0 + kTile <= bucket_numel) {
+        const TensorDesc d = desc[lo0];
+        if (d.dst <= tile0 && tile0 + kTile <= d.dst + d.numel) {
+            float* s = const_cast<float*>(d.src) + (tile0 - d.dst);
+            if ((reinterpret_cast<uintptr_t>(s) & 15u) == 0) {
+                f4* s4 = reinterpret_cast<f4*>(s);
+                const f4* b4 = reinterpret_cast<const f4*>(bucket + tile0);
+                f4 v[kTile / 1024];
+#pragma unroll
+                for (int g = 0; g < kTile / 1024; ++g) v[g] = ld_stream(b4 + g * 256 + threadIdx.x);
+#pragma unroll
+                for (int g = 0; g < kTile / 1024; ++g) st_stream(s4 + g * 256 + threadIdx.x, v[g]);
+                return;
+            }
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < kTile / 1024; ++g) {
+        const size_t e = tile0 + static_cast<size_t>(g) * 1024 + threadIdx.x * 4;
+        if (e >= bucket_numel) continue;
+        uint32_t lo = lo0, hi = hi0;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (desc[mid].dst + desc[mid].numel <= e) lo = mid + 1;
+            else hi = mid;
+        }
+        uint32_t t = lo;
+        if (t < T && e + 4 <= bucket_numel) {
+            const TensorDesc d = desc[t];
+            if (d.dst <= e && e + 4 <= d.dst + d.numel) {
+                float* s = const_cast<float*>(d.src) + (e - d.dst);
+                const f4 v = ld_stream(reinterpret_cast<const f4*>(bucket + e));
+                if ((reinterpret_cast<uintptr_t>(s) & 15u) == 0) {
+                    st_stream(reinterpret_cast<f4*>(s), v);
+                } else {
+                    s[0] = v.x; s[1] = v.y; s[2] = v.z; s[3] = v.w;
+                }
+                continue;
+            }
+        }
+        for (int q = 0; q < 4; ++q) {
+            const size_t eq = e + q;
+            if (eq >= bucket_numel) break;
+            while (t < T && desc[t].dst + desc[t].numel <= eq) ++t;
+            if (t < T && desc[t].dst <= eq) const_cast<float*>(desc[t].src)[eq - desc[t].dst] = bucket[eq];
+        }
+    }
+}
+
 }  // namespace bagua
 
 using namespace bagua;
@@ -142,4 +200,16 @@ extern "C" int bagua_bucket_flatten(const void* const* src, const size_t* numel,
     const int rc = bagua_flatten_plan(src, numel, dst_offset, T, bucket_numel, workspace, workspace_bytes, stream);
     if (rc != BAGUA_OK) return rc;
     return bagua_bucket_flatten_run(workspace, T, bucket, bucket_numel, stream);
+}
+
+extern "C" int bagua_bucket_unflatten_run(const void* workspace, size_t T, const float* bucket, size_t bucket_numel,
+                                          void* stream)
+{
+    if (!workspace || !bucket || bucket_numel == 0) return BAGUA_ERR_INVALID_ARG;
+    if (T > 0xfffffff0u || num_tiles(bucket_numel) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (!aligned16(workspace) || !aligned16(bucket)) return BAGUA_ERR_ALIGNMENT;
+    const FlattenPlanView pv = plan_view(workspace, T);
+    hipLaunchKernelGGL(k_unflatten, dim3(static_cast<unsigned>(num_tiles(bucket_numel))), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), pv.desc, pv.tile_first, static_cast<uint32_t>(T), bucket, bucket_numel);
+    return launch_status();
 }

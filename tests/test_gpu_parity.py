@@ -519,3 +519,35 @@ def test_flatten_thousands_of_tiny_tensors(bg, oracle):
     assert np.array_equal(host(codes), co) and np.array_equal(host(mm).view(np.uint32), mo.view(np.uint32))
     assert_fp32_close_and_exact(host(rg), res_o, "residual")
     assert host(b2).tobytes() == flat.tobytes()
+
+
+@pytest.mark.parametrize("aligned", [False, True])
+def test_unflatten_inverts_flatten(bg, oracle, aligned):
+    """bagua_bucket_unflatten_run scatters the bucket back into the planned tensors: equal to the oracle's inverse,
+    gaps of the bucket ignored, memory outside the tensors untouched."""
+    r = np.random.default_rng(21 + aligned)
+    sizes = [1, 7, 64, 1000, 3, 4096, 0, 129, 30522, 5, 5, 5, 8191, 2, 70000] + r.integers(0, 6, 400).tolist()
+    offs, pos = [], 0
+    for i, s in enumerate(sizes):
+        pos += (i % 3)
+        offs.append(pos)
+        pos += s
+    total = pos + 50
+    bucket = r.standard_normal(total).astype(np.float32)
+    want = [np.empty(s, np.float32) for s in sizes]
+    oracle.bucket_unflatten(bucket, want, offs)
+    arena = torch.full((sum(sizes) + 8 * len(sizes) + 8,), 777.0, device="cuda")
+    gs, p = [], (0 if aligned else 1)
+    for s in sizes:
+        gs.append(arena[p:p + s])
+        p += s + (((-s) % 4) if aligned else 1)
+    ws = torch.empty(bg.bagua_flatten_workspace_bytes(len(gs), total), dtype=torch.uint8, device="cuda")
+    bg.bagua_flatten_plan(gs, offs, total, ws)
+    bg.bagua_bucket_unflatten_run(ws, len(gs), dev(bucket))
+    torch.cuda.synchronize()
+    covered = 0
+    for t, w in zip(gs, want):
+        assert host(t).tobytes() == w.tobytes()
+        covered += w.size
+    assert int((arena != 777.0).sum().item()) <= covered          # nothing outside the tensors was written
+    assert int((arena == 777.0).sum().item()) >= arena.numel() - covered
