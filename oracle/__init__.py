@@ -223,3 +223,42 @@ def bucket_unflatten(bucket, dsts, src_offset):
     f.restype = ctypes.c_int
     f.argtypes = [_c_p, _c_sz, _c_p, _c_p, _c_p, _c_sz]
     _ok(f(_chk(bucket, np.float32), bucket.size, ptrs, numel, offs, T), "bucket_unflatten")
+
+
+def compress_topk(x, residual, chunk, keep):
+    """Worker side of C_LP_S with Q = per-chunk top-K. Returns (idx u16[nc*keep], val f32[nc*keep])."""
+    n = x.size
+    nc = num_chunks(n, chunk)
+    idx = np.empty(nc * keep, np.uint16)
+    val = np.empty(nc * keep, np.float32)
+    f = lib().oracle_compress_topk
+    f.restype = ctypes.c_int
+    f.argtypes = [_c_p, _c_p, _c_sz, _c_sz, _c_sz, _c_p, _c_p]
+    _ok(f(_chk(x, np.float32), None if residual is None else _chk(residual, np.float32), n, chunk, keep,
+          _chk(idx, np.uint16), _chk(val, np.float32)), "compress_topk")
+    return idx, val
+
+
+def decompress_topk(idx, val, n, chunk, keep):
+    out = np.empty(n, np.float32)
+    f = lib().oracle_decompress_topk
+    f.restype = ctypes.c_int
+    f.argtypes = [_c_p, _c_p, _c_sz, _c_sz, _c_sz, _c_p]
+    _ok(f(_chk(idx, np.uint16), _chk(val, np.float32), n, chunk, keep, _chk(out, np.float32)), "decompress_topk")
+    return out
+
+
+def drr_topk(idx_in, val_in, server_residual, n, chunk, keep, want_fp32=True):
+    """Server side of C_LP_S with Q = top-K. Returns (idx', val', out_fp32 or None)."""
+    k = len(idx_in)
+    nc = num_chunks(n, chunk)
+    idx = np.empty(nc * keep, np.uint16)
+    val = np.empty(nc * keep, np.float32)
+    out = np.empty(n, np.float32) if want_fp32 else None
+    f = lib().oracle_drr_topk
+    f.restype = ctypes.c_int
+    f.argtypes = [_c_p, _c_p, ctypes.c_int, _c_p, _c_sz, _c_sz, _c_sz, _c_p, _c_p, _c_p]
+    _ok(f(_ptr_array(idx_in, np.uint16), _ptr_array(val_in, np.float32), k,
+          None if server_residual is None else _chk(server_residual, np.float32), n, chunk, keep,
+          _chk(idx, np.uint16), _chk(val, np.float32), None if out is None else _chk(out, np.float32)), "drr_topk")
+    return idx, val, out

@@ -597,3 +597,119 @@ int oracle_bucket_unflatten(const float* bucket, size_t bucket_numel, float* con
         for (size_t e = 0; e < numel[t]; ++e) dst[t][e] = bucket[src_offset[t] + e];
     return 0;
 }
+
+/* --------------------------------------------------------------------------- Top-K codec */
+
+/*
+ * A third compression function Q: per-chunk top-K sparsification, the example of an aggressive
+ * compression for which the paper says error compensation matters most (Section 3.2, last
+ * sentences on C_LP_S).  Reading R19: per chunk of C elements keep the `keep` entries of largest
+ * |v| (ties: the lower index wins; |v| is compared through its IEEE bit pattern, so -0 == +0);
+ * a chunk is encoded as `keep` (index, value) pairs in ascending index order, index = position
+ * inside the chunk as u16, value = fl(v + 0.0f) (v itself, with -0 stored as +0, so that summing the
+ * kept entries of several workers sparsely or densely gives the same bits); a last chunk shorter than `keep` keeps everything and
+ * pads the remaining slots with index 0xFFFF, value +0.0f.  decode = 0 everywhere except the kept
+ * positions.  The error update of C_LP_S is then exact: delta' = v at dropped positions, +0 at kept.
+ */
+typedef struct { uint32_t key; uint32_t pos; } topk_item;
+
+static int topk_cmp(const void* a, const void* b)
+{
+    const topk_item* x = (const topk_item*)a;
+    const topk_item* y = (const topk_item*)b;
+    if (x->key != y->key) return x->key > y->key ? -1 : 1;   /* larger magnitude first */
+    return x->pos < y->pos ? -1 : (x->pos > y->pos ? 1 : 0); /* then lower index */
+}
+
+static void topk_compress_chunk(const float* v, size_t len, size_t keep, uint16_t* idx, float* val, float* residual)
+{
+    topk_item* items = (topk_item*)malloc(len * sizeof(topk_item));
+    uint8_t* sel = (uint8_t*)calloc(len, 1);
+    for (size_t i = 0; i < len; ++i) {
+        uint32_t bits;
+        memcpy(&bits, &v[i], 4);
+        items[i].key = bits & 0x7fffffffu;
+        items[i].pos = (uint32_t)i;
+    }
+    qsort(items, len, sizeof(topk_item), topk_cmp);
+    size_t kk = keep < len ? keep : len;
+    for (size_t s = 0; s < kk; ++s) sel[items[s].pos] = 1;
+    size_t o = 0;
+    for (size_t i = 0; i < len; ++i) {
+        if (sel[i]) {
+            idx[o] = (uint16_t)i;
+            val[o] = v[i] + 0.0f; /* -0 is stored as +0, as for the MinMax statistics (R5) */
+            ++o;
+        }
+        if (residual) residual[i] = sel[i] ? 0.0f : v[i];
+    }
+    for (; o < keep; ++o) {
+        idx[o] = 0xFFFFu;
+        val[o] = 0.0f;
+    }
+    free(items);
+    free(sel);
+}
+
+/* Worker side of C_LP_S with Q = top-K: idx u16[nc*keep], val fp32[nc*keep]. */
+int oracle_compress_topk(const float* x, float* residual, size_t n, size_t chunk, size_t keep,
+                         uint16_t* idx, float* val)
+{
+    if (!x || !idx || !val || n == 0 || !chunk_ok(chunk) || keep < 1 || keep > chunk) return 1;
+    ptrdiff_t nc = (ptrdiff_t)num_chunks(n, chunk);
+    ptrdiff_t c;
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (c = 0; c < nc; ++c) {
+        size_t lo = (size_t)c * chunk;
+        size_t len = (lo + chunk <= n) ? chunk : n - lo;
+        float* v = (float*)malloc(len * sizeof(float));
+        for (size_t i = 0; i < len; ++i) v[i] = residual ? x[lo + i] + residual[lo + i] : x[lo + i];
+        topk_compress_chunk(v, len, keep, idx + (size_t)c * keep, val + (size_t)c * keep,
+                            residual ? residual + lo : NULL);
+        free(v);
+    }
+    return 0;
+}
+
+int oracle_decompress_topk(const uint16_t* idx, const float* val, size_t n, size_t chunk, size_t keep, float* out)
+{
+    if (!idx || !val || !out || n == 0 || !chunk_ok(chunk) || keep < 1 || keep > chunk) return 1;
+    size_t nc = num_chunks(n, chunk);
+    for (size_t i = 0; i < n; ++i) out[i] = 0.0f;
+    for (size_t c = 0; c < nc; ++c) {
+        size_t lo = c * chunk;
+        size_t len = (lo + chunk <= n) ? chunk : n - lo;
+        for (size_t s = 0; s < keep; ++s) {
+            uint16_t p = idx[c * keep + s];
+            if (p == 0xFFFFu) continue;
+            if (p >= len) return 1;
+            out[lo + p] = val[c * keep + s];
+        }
+    }
+    return 0;
+}
+
+/* Server side of C_LP_S with Q = top-K: dense average of the k decoded buckets (ascending j), + epsilon, Q again. */
+int oracle_drr_topk(const uint16_t* const* idx_in, const float* const* val_in, int k, float* server_residual,
+                    size_t n, size_t chunk, size_t keep, uint16_t* idx_out, float* val_out, float* out_fp32)
+{
+    if (!idx_in || !val_in || k < 1 || k > 32 || !idx_out || !val_out || n == 0 || !chunk_ok(chunk) || keep < 1 ||
+        keep > chunk)
+        return 1;
+    float* a = (float*)malloc(n * sizeof(float));
+    float* d = (float*)malloc(n * sizeof(float));
+    if (!a || !d) { free(a); free(d); return 1; }
+    float inv_k = 1.0f / (float)k;
+    for (int j = 0; j < k; ++j) {
+        if (!idx_in[j] || !val_in[j] || oracle_decompress_topk(idx_in[j], val_in[j], n, chunk, keep, d)) {
+            free(a); free(d); return 1;
+        }
+        for (size_t i = 0; i < n; ++i) a[i] = (j == 0) ? d[i] : a[i] + d[i];
+    }
+    for (size_t i = 0; i < n; ++i) a[i] = a[i] * inv_k;
+    int rc = oracle_compress_topk(a, server_residual, n, chunk, keep, idx_out, val_out);
+    if (!rc && out_fp32) rc = oracle_decompress_topk(idx_out, val_out, n, chunk, keep, out_fp32);
+    free(a);
+    free(d);
+    return rc;
+}
