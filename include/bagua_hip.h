@@ -198,6 +198,28 @@ int bagua_decompress(int codec, const void* codes, const float* meta, size_t n, 
                      float* out, void* stream);
 
 /*
+ * C_LP_S with a third compression function: per-chunk top-K sparsification (the aggressive compression the paper
+ * names when it motivates error compensation, Section 3.2).  Per chunk of C elements the `keep` entries of largest
+ * |v| are kept (ties: the lower index wins; -0 and +0 compare equal).  A chunk is encoded as `keep` pairs in
+ * ascending index order: idx = position inside the chunk (u16), val = v with -0 stored as +0; a last chunk shorter
+ * than `keep` keeps everything and pads with idx 0xFFFF, val 0.  decode = 0 except at the kept positions, so the
+ * error update is exact: residual <- v at dropped positions, +0 at kept ones.
+ *   keep   1..chunk;   idx device u16[nc*keep];   val device fp32[nc*keep]   (chunk c owns slots [c*keep, (c+1)*keep))
+ * bagua_compress_topk_ef:                   worker side, v = x + residual (residual NULL = no error compensation)
+ * bagua_decompress_reduce_recompress_topk:  server side, a = (sum_j decode_j) * fl(1/k) in ascending j,
+ *                                           w = a + server_residual, Q(w), server_residual <- w - decode(Q(w)),
+ *                                           out_fp32 (optional) = decode(Q(w))
+ * bagua_decompress_topk:                    out = decode(idx, val)
+ */
+int bagua_compress_topk_ef(const float* x, float* residual, size_t n, size_t chunk, size_t keep, uint16_t* idx,
+                           float* val, void* stream);
+int bagua_decompress_reduce_recompress_topk(const uint16_t* const* idx_in, const float* const* val_in, int k,
+                                            size_t keep, float* server_residual, size_t n, size_t chunk,
+                                            uint16_t* idx_out, float* val_out, float* out_fp32, void* stream);
+int bagua_decompress_topk(const uint16_t* idx, const float* val, size_t n, size_t chunk, size_t keep, float* out,
+                          void* stream);
+
+/*
  * Decode fused into the bucket-level optimizer step (Section 3.5: the stochastic-gradient optimizer also works
  * on the flattened bucket; in the appendix listing the primitive is followed by the optimizer step).  The
  * optimizer itself is not fixed by the paper; this entry point implements SGD with optional weight decay and

@@ -25,7 +25,8 @@ EXPORTS = (
     "bagua_bucket_flatten", "bagua_compress_minmax_u8", "bagua_decompress_reduce_recompress",
     "bagua_decentralized_avg", "bagua_sign_compress_ef", "bagua_decompress", "bagua_flatten_compress_minmax_u8",
     "bagua_decompress_sgd_step", "bagua_decentralized_avg_peers", "bagua_reduce_compress_minmax_u8",
-    "bagua_bucket_unflatten_run",
+    "bagua_bucket_unflatten_run", "bagua_compress_topk_ef", "bagua_decompress_reduce_recompress_topk",
+    "bagua_decompress_topk",
 )
 
 
@@ -47,6 +48,9 @@ def _load():
     lib.bagua_flatten_workspace_bytes.argtypes = [sz, sz]
     lib.bagua_flatten_plan.argtypes = [vp, vp, vp, sz, sz, vp, sz, vp]
     lib.bagua_bucket_flatten_run.argtypes = [vp, sz, vp, sz, vp]
+    lib.bagua_compress_topk_ef.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp]
+    lib.bagua_decompress_reduce_recompress_topk.argtypes = [vp, vp, i32, sz, vp, sz, sz, vp, vp, vp, vp]
+    lib.bagua_decompress_topk.argtypes = [vp, vp, sz, sz, sz, vp, vp]
     lib.bagua_bucket_unflatten_run.argtypes = [vp, sz, vp, sz, vp]
     lib.bagua_bucket_flatten.argtypes = [vp, vp, vp, sz, vp, sz, vp, sz, vp]
     lib.bagua_compress_minmax_u8.argtypes = [vp, vp, sz, sz, vp, vp, vp]
@@ -206,6 +210,25 @@ def bagua_decompress_sgd_step(codec, codes, meta, n, chunk, param, momentum_buf,
     _check("bagua_decompress_sgd_step", _lib.bagua_decompress_sgd_step(
         codec, _ptr(codes), _ptr(meta, torch.float32), n, chunk, _ptr(param, torch.float32),
         _ptr(momentum_buf, torch.float32), lr, momentum, weight_decay, _stream(stream)))
+
+
+def bagua_compress_topk_ef(x, residual, chunk, keep, idx, val, stream=None):
+    _check("bagua_compress_topk_ef", _lib.bagua_compress_topk_ef(
+        _ptr(x, torch.float32), _ptr(residual, torch.float32), x.numel(), chunk, keep, _ptr(idx, torch.int16),
+        _ptr(val, torch.float32), _stream(stream)))
+
+
+def bagua_decompress_reduce_recompress_topk(idx_in, val_in, keep, server_residual, n, chunk, idx_out, val_out,
+                                            out_fp32=None, stream=None):
+    _check("bagua_decompress_reduce_recompress_topk", _lib.bagua_decompress_reduce_recompress_topk(
+        _ptr_array(idx_in, torch.int16), _ptr_array(val_in, torch.float32), len(idx_in), keep,
+        _ptr(server_residual, torch.float32), n, chunk, _ptr(idx_out, torch.int16), _ptr(val_out, torch.float32),
+        _ptr(out_fp32, torch.float32), _stream(stream)))
+
+
+def bagua_decompress_topk(idx, val, n, chunk, keep, out, stream=None):
+    _check("bagua_decompress_topk", _lib.bagua_decompress_topk(_ptr(idx, torch.int16), _ptr(val, torch.float32), n, chunk,
+                                                               keep, _ptr(out, torch.float32), _stream(stream)))
 
 
 def raw():
