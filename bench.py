@@ -59,7 +59,8 @@ def parse_args():
     ap.add_argument("--extras", default="", help="comma list of additional primitives appended to the step: sgd_step "
                     "(decode of the server's codes fused into an SGD-momentum update of every worker's replica), "
                     "peer_fp (full-precision averaging with one chosen peer per worker), reduce_compress (intra-node "
-                    "stage of hierarchical C_LP_S: 4 local workers averaged uncompressed, leader compresses)")
+                    "stage of hierarchical C_LP_S: 4 local workers averaged uncompressed, leader compresses), topk (C_LP_S with "
+                    "the per-chunk top-K codec, keep = chunk/32: worker side and server side)")
     ap.add_argument("--fused-flatten", action="store_true",
                     help="replace flatten + compress_minmax by the fused bagua_flatten_compress_minmax_u8")
     ap.add_argument("--per-bucket-launch", action="store_true",
@@ -85,6 +86,8 @@ class Workload:
             self.prims = self.prims + ["sgd_step"]
         if "reduce_compress" in extras and ("flatten" in self.prims or "flatten_compress" in self.prims):
             self.prims = self.prims + ["reduce_compress"]
+        if "topk" in extras and ("flatten" in self.prims or "flatten_compress" in self.prims):
+            self.prims = self.prims + ["compress_topk", "drr_topk"]
         if "peer_fp" in extras and "ring_fp" in self.prims:
             self.prims = self.prims + ["peer_fp"]
         k, C, SC, cfg = self.k, self.C, self.SC, w["cfg"]
@@ -181,6 +184,15 @@ class Workload:
             self.hdelta = [views(z(n, **f32)) for _ in range(k // self.kl)]
             self.hcodes = [views(z(n, **u8)) for _ in range(k // self.kl)]
             self.hminmax = [views(z(2 * nc, **f32), C, 2) for _ in range(k // self.kl)]
+        if has("compress_topk"):        # top-K codec: keep chunk/32 entries per chunk
+            self.keep = C // 32
+            self.tdelta = [views(z(n, **f32)) for _ in range(k)]
+            self.tidx = [views(z(nc * self.keep, dtype=torch.int16, device=dev), C, self.keep) for _ in range(k)]
+            self.tval = [views(z(nc * self.keep, **f32), C, self.keep) for _ in range(k)]
+            self.teps = views(z(n, **f32))
+            self.tidx_out = views(z(nc * self.keep, dtype=torch.int16, device=dev), C, self.keep)
+            self.tval_out = views(z(nc * self.keep, **f32), C, self.keep)
+            self.tout = views(z(n, **f32))
         if has("sgd_step"):
             self.param = [views(draw("normal", n, seed_for(cfg, 50, j), dev, 0.02)) for j in range(k)]
             self.mbuf = [views(z(n, **f32)) for _ in range(k)]
@@ -221,8 +233,10 @@ class Workload:
     # ---- accounting --------------------------------------------------------------------------------
     def bytes_per_element(self):
         k, C, SC = self.k, self.C, self.SC
+        keep = getattr(self, "keep", 0)
         wb = 4.0 if "sign_compress" in self.prims else 0.0   # the fused call also writes the bucket if it is needed later
         return {"flatten": 8.0, "flatten_compress": 13.0 + wb + 8.0 / C, "compress_minmax": 13.0 + 8.0 / C, "drr_minmax": k + 13.0 + 8.0 * (k + 1) / C,
+                "compress_topk": 12.0 + 6.0 * keep / C, "drr_topk": 12.0 + 6.0 * (k + 1) * keep / C,
                 "sgd_step": 17.0 + 8.0 / C, "reduce_compress": 4.0 * 4 + 9.0 + 8.0 / C, "peer_fp": 8.0, "ring_fp": 8.0, "ring_lp": 17.0 + 8.0 / C, "sign_compress": 12.125 + 4.0 / SC,
                 "drr_sign": k / 8.0 + 12.125 + 4.0 * (k + 1) / SC}
 
@@ -233,14 +247,16 @@ class Workload:
     def algo_bytes(self):
         n, k = self.n_elems, self.k
         units = {"flatten": n * k, "flatten_compress": n * k, "compress_minmax": n * k, "drr_minmax": n, "ring_fp": n * k, "ring_lp": n * k,
-                 "sign_compress": n * k, "drr_sign": n, "sgd_step": n * k, "peer_fp": n * k, "reduce_compress": n * (k // 4)}
+                 "sign_compress": n * k, "drr_sign": n, "sgd_step": n * k, "peer_fp": n * k, "reduce_compress": n * (k // 4),
+                 "compress_topk": n * k, "drr_topk": n}
         bpe = self.bytes_per_element()
         return {p: bpe[p] * units[p] for p in self.prims}
 
     def launches(self):
         U, k = len(self.units), self.k
         per = {"flatten": U * k, "flatten_compress": U * k, "compress_minmax": U * k, "drr_minmax": U, "ring_fp": U, "ring_lp": U,
-               "sign_compress": U * k, "drr_sign": U, "sgd_step": U * k, "peer_fp": U, "reduce_compress": U * (k // 4)}
+               "sign_compress": U * k, "drr_sign": U, "sgd_step": U * k, "peer_fp": U, "reduce_compress": U * (k // 4),
+               "compress_topk": U * k, "drr_topk": U}
         return {p: per[p] for p in self.prims}
 
     def kernel_name(self, p):
@@ -249,7 +265,8 @@ class Workload:
                 "drr_minmax": "k_drr_minmax<4,true,true>", "ring_fp": "k_ring_avg_fp<%d>" % self.k,
                 "ring_lp": "k_ring_avg_lp<%d,2>" % self.k, "sign_compress": "k_sign_compress<2,true>",
                 "drr_sign": "k_drr_sign<4,true,true>", "sgd_step": "k_decompress_sgd<0,true,false>",
-                "peer_fp": "k_peer_avg_fp", "reduce_compress": "k_reduce_compress_minmax<2,true>"}[p]
+                "peer_fp": "k_peer_avg_fp", "reduce_compress": "k_reduce_compress_minmax<2,true>",
+                "compress_topk": "k_compress_topk<2,true>", "drr_topk": "k_drr_topk<2,true,true>"}[p]
 
     # ---- one pass of the hot path ------------------------------------------------------------------
     def step(self, marks=None):
@@ -293,6 +310,17 @@ class Workload:
                     for u in range(U):
                         bg.bagua_decompress_sgd_step(bg.CODEC_MINMAX_U8, self.codes_out[u], self.minmax_out[u],
                                                      self.units[u][1], C, self.param[j][u], self.mbuf[j][u], 0.01, 0.9, 0.0)
+            elif p == "compress_topk":
+                for j in range(k):
+                    for u in range(U):
+                        bg.bagua_compress_topk_ef(self.bucket[j][u], self.tdelta[j][u], C, self.keep, self.tidx[j][u],
+                                                  self.tval[j][u])
+            elif p == "drr_topk":
+                for u in range(U):
+                    bg.bagua_decompress_reduce_recompress_topk([self.tidx[j][u] for j in range(k)],
+                                                               [self.tval[j][u] for j in range(k)], self.keep, self.teps[u],
+                                                               self.units[u][1], C, self.tidx_out[u], self.tval_out[u],
+                                                               self.tout[u])
             elif p == "reduce_compress":
                 for a in range(k // self.kl):
                     for u in range(U):

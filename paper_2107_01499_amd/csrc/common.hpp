@@ -60,6 +60,12 @@ __device__ __forceinline__ void st_stream(T* p, T v)
 #ifndef BAGUA_RPW_DRR_SIGN
 #define BAGUA_RPW_DRR_SIGN 4
 #endif
+#ifndef BAGUA_RPW_TOPK
+#define BAGUA_RPW_TOPK 4
+#endif
+#ifndef BAGUA_RPW_DRR_TOPK
+#define BAGUA_RPW_DRR_TOPK 4
+#endif
 #ifndef BAGUA_RPW_LP
 #define BAGUA_RPW_LP 2
 #endif

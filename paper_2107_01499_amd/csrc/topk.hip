@@ -6,33 +6,54 @@
 // registers; a 4-pass radix select over the IEEE bit pattern of |v| (256-bin histograms in LDS,
 // integer atomics only, so the result does not depend on execution order) finds the K-th largest
 // magnitude T and how many elements equal to T are still needed; one packed prefix count in index
-// order (wave shuffles + one LDS exchange) then gives every kept element its output slot.
+// order (DPP scans on the vector ALU + one LDS exchange between waves) then gives every kept element
+// its output slot.  The first digit is the sign-stripped exponent, which takes only a handful of
+// values inside a chunk: its counters are replicated 16 times, interleaved over the LDS banks, so that
+// equal digits from the lanes of one wave do not serialise on one address.
 #include "launchers.hpp"
 
 #pragma clang fp contract(off)
 
 namespace bagua {
 
-constexpr int kTopkLdsWords = 4 * 256 + kMaxWaves;  // four histograms + per-wave totals
+#ifndef BAGUA_TOPK_COPIES
+#define BAGUA_TOPK_COPIES 16
+#endif
+constexpr int kCopies = BAGUA_TOPK_COPIES;  // interleaved copies of the first-pass histogram (spreads equal digits over banks)
+constexpr int kTopkLdsWords = 256 * kCopies + 4 * 256 + kMaxWaves;
 
 __device__ __forceinline__ uint32_t mag_key(float v) { return __float_as_uint(v) & 0x7fffffffu; }
+
+// Inclusive prefix sum over the 64 lanes on the vector ALU only: DPP row shifts inside each row of
+// 16 lanes, then the totals of the lower rows are added from lanes 15, 31 and 47.
+__device__ __forceinline__ uint32_t wave_prefix_incl(uint32_t x, int lane)
+{
+    x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0x111, 0xf, 0xf, true));  // row_shr:1
+    x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0x112, 0xf, 0xf, true));  // row_shr:2
+    x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0x114, 0xf, 0xf, true));  // row_shr:4
+    x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0x118, 0xf, 0xf, true));  // row_shr:8
+    const uint32_t t0 = __builtin_amdgcn_readlane(static_cast<int>(x), 15);
+    const uint32_t t1 = __builtin_amdgcn_readlane(static_cast<int>(x), 31);
+    const uint32_t t2 = __builtin_amdgcn_readlane(static_cast<int>(x), 47);
+    const int row = lane >> 4;
+    return x + (row >= 1 ? t0 : 0u) + (row >= 2 ? t1 : 0u) + (row >= 3 ? t2 : 0u);
+}
 
 // All lanes of a wave: D = largest digit whose suffix count sum_{d >= D} h[d] reaches `need`,
 // above = sum_{d > D} h[d].  Requires 1 <= need <= sum of all bins.
 __device__ __forceinline__ void find_digit(const uint32_t* h, int lane, uint32_t need, uint32_t& D, uint32_t& above)
 {
-    const uint32_t h0 = h[4 * lane], h1 = h[4 * lane + 1], h2 = h[4 * lane + 2], h3 = h[4 * lane + 3];
-    const uint32_t c = h0 + h1 + h2 + h3;
-    uint32_t s = c;  // inclusive suffix sum over lanes
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const uint32_t t = __shfl_down(s, d, kWave);
-        if (lane + d < kWave) s += t;
-    }
-    const unsigned long long ok = __ballot(s >= need);  // lanes 0..L (suffix sums do not increase with the lane)
+    const uint4 hb = *reinterpret_cast<const uint4*>(h + 4 * lane);
+    const uint32_t c = hb.x + hb.y + hb.z + hb.w;
+    const uint32_t pre = wave_prefix_incl(c, lane);
+    const uint32_t total = __builtin_amdgcn_readlane(static_cast<int>(pre), 63);
+    const uint32_t suffix = total - pre + c;             // sum over lanes >= this one
+    const unsigned long long ok = __ballot(suffix >= need);  // lanes 0..L (suffix sums do not increase with the lane)
     const int L = 63 - __builtin_clzll(ok);
-    uint32_t t = __shfl(s, L, kWave) - __shfl(c, L, kWave);  // everything above lane L's four bins
-    const uint32_t b3 = __shfl(h3, L, kWave), b2 = __shfl(h2, L, kWave), b1 = __shfl(h1, L, kWave);
+    uint32_t t = __builtin_amdgcn_readlane(static_cast<int>(suffix - c), L);  // everything above lane L's four bins
+    const uint32_t b3 = __builtin_amdgcn_readlane(static_cast<int>(hb.w), L);
+    const uint32_t b2 = __builtin_amdgcn_readlane(static_cast<int>(hb.z), L);
+    const uint32_t b1 = __builtin_amdgcn_readlane(static_cast<int>(hb.y), L);
     if (t + b3 >= need) {
         D = 4 * L + 3;
     } else {
@@ -61,27 +82,71 @@ __device__ __forceinline__ void topk_encode_chunk(const f4 (&v)[RPW], long len, 
                                                   uint16_t* __restrict__ idx_c, float* __restrict__ val_c,
                                                   float* __restrict__ out, uint32_t* smem)
 {
-    uint32_t* hist = smem;
-    uint32_t* tot = smem + 4 * 256;
+    uint32_t* copies = smem;                  // [256][kCopies], first pass only
+    uint32_t* hist = smem + 256 * kCopies;    // [4][256]
+    uint32_t* tot = hist + 4 * 256;
     const uint32_t keff = (static_cast<long>(keep) < len) ? keep : static_cast<uint32_t>(len);
-    for (int t = threadIdx.x; t < 4 * 256; t += blockDim.x) hist[t] = 0;
+    for (int t = threadIdx.x; t < 256 * kCopies + 4 * 256; t += blockDim.x) smem[t] = 0;
     __syncthreads();
 
-    // ---- radix select: threshold key T and the number R of elements equal to T that are kept
+    uint32_t key[RPW][4];
+    bool valid[RPW][4];
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        const long e0 = static_cast<long>(wave * RPW + i) * kRow + lane * 4;
+        const float el[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            key[i][e] = mag_key(el[e]);
+            valid[i][e] = e0 + e < len;
+        }
+    }
+
+    // ---- radix select: threshold key T and the number R of elements equal to T that are kept.
+    // First digit (sign-stripped exponent): values of one chunk share a handful of exponents, so equal
+    // digits are spread over kCopies interleaved counters to keep the LDS atomics from serialising.
     uint32_t prefix = 0, need = keff;
 #pragma unroll
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
-        const uint32_t himask = (pass == 0) ? 0u : (0xffffffffu << (shift + 8));
+    for (int i = 0; i < RPW; ++i)
 #pragma unroll
-        for (int i = 0; i < RPW; ++i) {
-            const long e0 = static_cast<long>(wave * RPW + i) * kRow + lane * 4;
-            const float el[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+        for (int e = 0; e < 4; ++e)
+            if (valid[i][e]) atomicAdd(&copies[(key[i][e] >> 24) * kCopies + (lane & (kCopies - 1))], 1u);
+    __syncthreads();
+    for (int b = threadIdx.x; b < 256; b += blockDim.x) {
+        uint32_t sum = 0;
+#pragma unroll
+        for (int q = 0; q < kCopies; q += 4) {
+            const uint4 part = *reinterpret_cast<const uint4*>(copies + b * kCopies + q);
+            sum += part.x + part.y + part.z + part.w;
+        }
+        hist[b] = sum;
+    }
+    __syncthreads();
+    {
+        uint32_t D, above;
+        find_digit(hist, lane, need, D, above);
+        need -= above;
+        prefix = D << 24;
+    }
+#pragma unroll
+    for (int pass = 1; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        const uint32_t himask = 0xffffffffu << (shift + 8);
+        bool cand[RPW][4];
+        bool any = false;
+#pragma unroll
+        for (int i = 0; i < RPW; ++i)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const uint32_t key = mag_key(el[e]);
-                if (e0 + e < len && (key & himask) == prefix) atomicAdd(&hist[pass * 256 + ((key >> shift) & 255u)], 1u);
+                cand[i][e] = valid[i][e] && (key[i][e] & himask) == prefix;
+                any = any || cand[i][e];
             }
+        if (__ballot(any) != 0) {  // after the first pass most waves hold no candidate at all
+#pragma unroll
+            for (int i = 0; i < RPW; ++i)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (cand[i][e]) atomicAdd(&hist[pass * 256 + ((key[i][e] >> shift) & 255u)], 1u);
         }
         __syncthreads();
         uint32_t D, above;
@@ -92,27 +157,17 @@ __device__ __forceinline__ void topk_encode_chunk(const f4 (&v)[RPW], long len, 
     const uint32_t T = prefix, R = need;
 
     // ---- packed prefix counts in index order: low half = elements > T, high half = elements == T
-    uint32_t cnt[RPW], lane_excl[RPW];
+    uint32_t lane_excl[RPW];
     uint32_t run = 0;
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
-        const long e0 = static_cast<long>(wave * RPW + i) * kRow + lane * 4;
-        const float el[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
         uint32_t c = 0;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const uint32_t key = mag_key(el[e]);
-            if (e0 + e < len) c += (key > T ? 1u : 0u) + (key == T ? 0x10000u : 0u);
-        }
-        cnt[i] = c;
-        uint32_t inc = c;  // inclusive prefix over lanes
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const uint32_t t = __shfl_up(inc, d, kWave);
-            if (lane >= d) inc += t;
-        }
+        for (int e = 0; e < 4; ++e)
+            if (valid[i][e]) c += (key[i][e] > T ? 1u : 0u) + (key[i][e] == T ? 0x10000u : 0u);
+        const uint32_t inc = wave_prefix_incl(c, lane);
         lane_excl[i] = run + inc - c;
-        run += __shfl(inc, kWave - 1, kWave);
+        run += __builtin_amdgcn_readlane(static_cast<int>(inc), 63);
     }
     if (lane == 0) tot[wave] = run;
     __syncthreads();
@@ -131,10 +186,8 @@ __device__ __forceinline__ void topk_encode_chunk(const f4 (&v)[RPW], long len, 
         uint32_t before = before_wave + lane_excl[i];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const uint32_t key = mag_key(el[e]);
-            const bool valid = e0 + e < len;
             const uint32_t bgt = before & 0xffffu, beq = before >> 16;
-            const bool gt = valid && key > T, eq = valid && key == T;
+            const bool gt = valid[i][e] && key[i][e] > T, eq = valid[i][e] && key[i][e] == T;
             const bool sel = gt || (eq && beq < R);
             const float stored = el[e] + 0.0f;  // -0 is stored as +0
             if (sel) {
@@ -276,7 +329,7 @@ extern "C" int bagua_compress_topk_ef(const float* x, float* residual, size_t n,
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(residual) || !aligned16(idx) || !aligned16(val)) return BAGUA_ERR_ALIGNMENT;
     const int rows = static_cast<int>(chunk / kRow);
-    const int rpw = pick_rpw(rows, BAGUA_RPW_COMPRESS);
+    const int rpw = pick_rpw(rows, BAGUA_RPW_TOPK);
     dim3 grid(static_cast<unsigned>(num_chunks(n, chunk))), block(64 * ((rows + rpw - 1) / rpw));
     const size_t lds = kTopkLdsWords * sizeof(uint32_t);
     const uint32_t ch = static_cast<uint32_t>(chunk), kp = static_cast<uint32_t>(keep);
@@ -311,7 +364,7 @@ extern "C" int bagua_decompress_reduce_recompress_topk(const uint16_t* const* id
         vt.p[j] = val_in[j];
     }
     const int rows = static_cast<int>(chunk / kRow);
-    const int rpw = pick_rpw(rows, BAGUA_RPW_COMPRESS);
+    const int rpw = pick_rpw(rows, BAGUA_RPW_DRR_TOPK);
     dim3 grid(static_cast<unsigned>(num_chunks(n, chunk))), block(64 * ((rows + rpw - 1) / rpw));
     size_t lds = chunk * sizeof(float);
     if (lds < kTopkLdsWords * sizeof(uint32_t)) lds = kTopkLdsWords * sizeof(uint32_t);
