@@ -23,9 +23,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 
-def build(verbose=False, extra=(), out=LIB):
-    os.makedirs(os.path.dirname(out), exist_ok=True)
-    cmd = [HIPCC] + FLAGS + list(extra) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", out]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd))
     res = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
@@ -36,6 +34,24 @@ def build(verbose=False, extra=(), out=LIB):
         sys.stderr.write(err + "\n")
     if res.returncode != 0:
         raise subprocess.CalledProcessError(res.returncode, cmd)
+
+
+def build(verbose=False, extra=(), out=LIB):
+    """Compile every source to an object (in parallel), then link the shared library."""
+    from concurrent.futures import ThreadPoolExecutor
+    os.makedirs(os.path.dirname(out), exist_ok=True)
+    objdir = out + ".obj"
+    os.makedirs(objdir, exist_ok=True)
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+
+    def compile_one(src):
+        obj = os.path.join(objdir, src.replace(".hip", ".o"))
+        _run([HIPCC] + compile_flags + list(extra) + ["-c", os.path.join(CSRC, src), "-o", obj], verbose)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
+    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", out], verbose)
     return out
 
 

@@ -45,9 +45,10 @@ __device__ __forceinline__ void st_stream(T* p, T v)
 #endif
 }
 
-// Preferred rows (of 256 elements) per wave for each chunked kernel.  Measured on MI355X: two rows
-// per wave (512 elements, 8 waves for a 4096-element chunk) stream fastest; the sign-codec server
-// kernel prefers four.  Larger values are used only when a chunk would need more than 16 waves.
+// Preferred rows (of 256 elements) per wave for each chunked kernel (compile-time tuning knobs).
+// Measured on MI355X: two rows per wave (512 elements, 8 waves for a 4096-element chunk) stream
+// fastest in the worker-side kernels and the fused ring kernel; the server-side kernels and the
+// top-K kernels prefer four.  Larger values are used only when a chunk would need more than 16 waves.
 #ifndef BAGUA_RPW_COMPRESS
 #define BAGUA_RPW_COMPRESS 2
 #endif
