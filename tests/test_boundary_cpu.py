@@ -93,3 +93,15 @@ def test_peer_validation_without_gpu(bg):
     assert lib.bagua_decompress_sgd_step(0, 0x1000, 0x1000, 16, 256, 0x2000, 0x2000, 0.1, 0.9, 0.0, None) == 1  # param aliases momentum
     assert lib.bagua_decompress_sgd_step(3, 0x1000, 0x1000, 16, 256, 0x2000, None, 0.1, 0.9, 0.0, None) == 1
     assert lib.bagua_flatten_compress_minmax_u8(None, 1, None, 16, 256, 0x1000, 0x1000, None, None) == 1
+
+
+def test_header_is_valid_c_and_cpp(tmp_path):
+    """include/bagua_hip.h is a plain C header: it must compile as C99 and as C++ without any HIP or torch include."""
+    import subprocess
+    src_c = tmp_path / "use_header.c"
+    src_c.write_text('#include "bagua_hip.h"\nint main(void) { return BAGUA_MAX_WORKERS != 32; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-I", inc, str(src_c)], check=True)
+    src_cpp = tmp_path / "use_header.cpp"
+    src_cpp.write_text('#include "bagua_hip.h"\nint main() { return BAGUA_OK; }\n')
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(src_cpp)], check=True)
