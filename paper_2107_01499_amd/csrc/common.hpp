@@ -70,6 +70,10 @@ __device__ __forceinline__ void st_stream(T* p, T v)
 #ifndef BAGUA_RPW_LP
 #define BAGUA_RPW_LP 2
 #endif
+// Peers whose statistics share one barrier in the fused ring kernel.
+#ifndef BAGUA_LP_GROUP
+#define BAGUA_LP_GROUP 1
+#endif
 // Workers whose code loads are issued together in the server-side kernels.
 #ifndef BAGUA_DRR_NJ
 #define BAGUA_DRR_NJ 1

@@ -6,12 +6,13 @@
 
 namespace bagua {
 
-// Chunk-wide (min, max) of the values held by the waves of one workgroup.  `len` = valid elements
-// of the chunk; rows beyond it are ignored.  Result is canonicalised (-0 -> +0).
-// s_red: LDS scratch of 2*kMaxWaves floats, not otherwise in use until the next barrier.
+// Chunk-wide (min, max) of the values held by the waves of one workgroup, in two phases so that a
+// caller can put the statistics of several chunks behind one barrier.
+// Phase 1: this wave's (min, max) over its valid elements (`len` = valid elements of the chunk; rows
+// beyond it are ignored); with several waves the pair is also parked in s_red (2*kMaxWaves floats).
 template <int RPW>
-__device__ __forceinline__ void chunk_minmax(const f4 (&v)[RPW], long len, int wave, int lane, int nwaves,
-                                             float* s_red, float& mn_out, float& mx_out)
+__device__ __forceinline__ void chunk_minmax_partial(const f4 (&v)[RPW], long len, int wave, int lane, int nwaves,
+                                                     float* s_red, float& mn_out, float& mx_out)
 {
     float mn = INFINITY, mx = -INFINITY;
 #pragma unroll
@@ -30,19 +31,32 @@ __device__ __forceinline__ void chunk_minmax(const f4 (&v)[RPW], long len, int w
     }
     mn = wave_min(mn);
     mx = wave_max(mx);
+    if (nwaves > 1 && lane == 0) {
+        s_red[wave] = mn;
+        s_red[kMaxWaves + wave] = mx;
+    }
+    mn_out = mn;
+    mx_out = mx;
+}
+// Phase 2 (after a barrier when nwaves > 1): combine the waves' pairs; result canonicalised (-0 -> +0).
+__device__ __forceinline__ void chunk_minmax_finish(int nwaves, const float* s_red, float& mn, float& mx)
+{
     if (nwaves > 1) {
-        if (lane == 0) {
-            s_red[wave] = mn;
-            s_red[kMaxWaves + wave] = mx;
-        }
-        __syncthreads();
         for (int w = 0; w < nwaves; ++w) {
             mn = fminf(mn, s_red[w]);
             mx = fmaxf(mx, s_red[kMaxWaves + w]);
         }
     }
-    mn_out = mn + 0.0f;
-    mx_out = mx + 0.0f;
+    mn = mn + 0.0f;
+    mx = mx + 0.0f;
+}
+template <int RPW>
+__device__ __forceinline__ void chunk_minmax(const f4 (&v)[RPW], long len, int wave, int lane, int nwaves,
+                                             float* s_red, float& mn_out, float& mx_out)
+{
+    chunk_minmax_partial<RPW>(v, len, wave, lane, nwaves, s_red, mn_out, mx_out);
+    if (nwaves > 1) __syncthreads();
+    chunk_minmax_finish(nwaves, s_red, mn_out, mx_out);
 }
 
 // One quantised element: q = clamp(rint((v - mn) * inv), 0, 255) as a float, deq = mn + q * step.
@@ -67,6 +81,11 @@ __device__ __forceinline__ uint32_t pack_codes(float q0, float q1, float q2, flo
     return w;
 }
 
+template <int RPW, bool EF, bool OUT, bool DEQ_BACK>
+__device__ __forceinline__ void minmax_quantise_chunk(f4 (&v)[RPW], float mn, float mx, long len, int wave, int lane,
+                                                      float* __restrict__ residual, uint8_t* __restrict__ codes,
+                                                      float* __restrict__ minmax_c, float* __restrict__ out);
+
 // Encode the chunk held in v: writes codes, (min,max), and optionally the updated residual
 // (v - decode) and the decoded values.  Pointers are already offset to the start of the chunk.
 // If DEQ_BACK, v is overwritten with the decoded values (used by the decentralised LP kernel).
@@ -78,6 +97,16 @@ __device__ __forceinline__ void minmax_encode_chunk(f4 (&v)[RPW], long len, int 
 {
     float mn, mx;
     chunk_minmax<RPW>(v, len, wave, lane, nwaves, s_red, mn, mx);
+    minmax_quantise_chunk<RPW, EF, OUT, DEQ_BACK>(v, mn, mx, len, wave, lane, residual, codes, minmax_c, out);
+}
+
+// Quantise the chunk held in v given its canonical (min, max): writes codes, (min,max), and optionally the
+// updated residual (v - decode) and the decoded values; if DEQ_BACK, v is overwritten with the decoded values.
+template <int RPW, bool EF, bool OUT, bool DEQ_BACK>
+__device__ __forceinline__ void minmax_quantise_chunk(f4 (&v)[RPW], float mn, float mx, long len, int wave, int lane,
+                                                      float* __restrict__ residual, uint8_t* __restrict__ codes,
+                                                      float* __restrict__ minmax_c, float* __restrict__ out)
+{
     const float r = mx - mn;
     const float step = (r == 0.0f) ? 0.0f : r / 255.0f;
     const float inv = (r == 0.0f) ? 0.0f : 255.0f / r;  // flat chunk: (v - mn) * 0 = 0 -> code 0

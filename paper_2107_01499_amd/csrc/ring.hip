@@ -85,34 +85,50 @@ k_ring_avg_lp(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, MutPtrTable code
             if (remain > 0) store_row(static_cast<float*>(xout.p[p]) + base + off, lane, remain, o);
         }
     };
+    // Peers are taken in groups of G: the statistics of a whole group sit behind one barrier.
+    constexpr int G = BAGUA_LP_GROUP;
 #pragma unroll
-    for (int i = 0; i < K; ++i) {
-        f4 x[RPW], d[RPW];
+    for (int g0 = 0; g0 < K; g0 += G) {
+        f4 x[G][RPW], d[G][RPW];
+        float mn[G], mx[G];
 #pragma unroll
-        for (int r = 0; r < RPW; ++r) {
-            const long off = static_cast<long>(wave * RPW + r) * kRow;
-            const long remain = len - off;
-            x[r] = f4{0.f, 0.f, 0.f, 0.f};
-            h[i][r] = f4{0.f, 0.f, 0.f, 0.f};
-            if (remain > 0) {
-                x[r] = load_row(static_cast<const float*>(xin.p[i]) + base + off, lane, remain, 0.0f);
-                h[i][r] = load_row(static_cast<const float*>(xhat.p[i]) + base + off, lane, remain, 0.0f);
+        for (int gi = 0; gi < G; ++gi) {
+            const int i = g0 + gi;
+            if (i >= K) continue;
+#pragma unroll
+            for (int r = 0; r < RPW; ++r) {
+                const long off = static_cast<long>(wave * RPW + r) * kRow;
+                const long remain = len - off;
+                x[gi][r] = f4{0.f, 0.f, 0.f, 0.f};
+                h[i][r] = f4{0.f, 0.f, 0.f, 0.f};
+                if (remain > 0) {
+                    x[gi][r] = load_row(static_cast<const float*>(xin.p[i]) + base + off, lane, remain, 0.0f);
+                    h[i][r] = load_row(static_cast<const float*>(xhat.p[i]) + base + off, lane, remain, 0.0f);
+                }
+                d[gi][r] = sub4(x[gi][r], h[i][r]);
             }
-            d[r] = sub4(x[r], h[i][r]);
+            chunk_minmax_partial<RPW>(d[gi], len, wave, lane, nwaves, s_red[i], mn[gi], mx[gi]);
         }
-        // d <- decode(Q(d)); codes and (min,max) of peer i are written on the way
-        minmax_encode_chunk<RPW, false, false, true>(d, len, wave, lane, nwaves, nullptr,
-                                                     static_cast<uint8_t*>(codes.p[i]) + base,
-                                                     static_cast<float*>(minmax.p[i]) + 2 * c, nullptr, s_red[i]);
+        if (nwaves > 1) __syncthreads();
 #pragma unroll
-        for (int r = 0; r < RPW; ++r) {
-            const long off = static_cast<long>(wave * RPW + r) * kRow;
-            const long remain = len - off;
-            h[i][r] = add4(h[i][r], d[r]);
-            own[i][r] = sub4(x[r], h[i][r]);
-            if (remain > 0) store_row(static_cast<float*>(xhat.p[i]) + base + off, lane, remain, h[i][r]);
+        for (int gi = 0; gi < G; ++gi) {
+            const int i = g0 + gi;
+            if (i >= K) continue;
+            chunk_minmax_finish(nwaves, s_red[i], mn[gi], mx[gi]);
+            // d <- decode(Q(d)); codes and (min,max) of peer i are written on the way
+            minmax_quantise_chunk<RPW, false, false, true>(d[gi], mn[gi], mx[gi], len, wave, lane, nullptr,
+                                                           static_cast<uint8_t*>(codes.p[i]) + base,
+                                                           static_cast<float*>(minmax.p[i]) + 2 * c, nullptr);
+#pragma unroll
+            for (int r = 0; r < RPW; ++r) {
+                const long off = static_cast<long>(wave * RPW + r) * kRow;
+                const long remain = len - off;
+                h[i][r] = add4(h[i][r], d[gi][r]);
+                own[i][r] = sub4(x[gi][r], h[i][r]);
+                if (remain > 0) store_row(static_cast<float*>(xhat.p[i]) + base + off, lane, remain, h[i][r]);
+            }
+            if (i >= 2) finalize(i - 1);
         }
-        if (i >= 2) finalize(i - 1);
     }
     finalize(K - 1);
     if (K > 1) finalize(0);
