@@ -250,3 +250,43 @@ def test_config5_one_bit_sampled(bg, oracle):
         b, s, o = oracle.drr_sign(bits_o[r], scale_o[r], e, hi - lo, C)
         exact(host(b2[lo // 32:(hi + 31) // 32]).view(np.uint32), b, "server bits"); exact(host(s2[lo // C:(hi + C - 1) // C]), s, "server scale")
         exact(host(out[lo:hi]), o, "out"); exact(host(eps[lo:hi]), e, "epsilon")
+
+
+# ------------------------------------------------------------------------------------------------- beyond 2^32
+def test_more_than_2_to_32_elements(bg, oracle):
+    """A single bucket of 2^32 + 12,365 elements (17 GB per fp32 buffer): element indices need 64 bits.  MinMax-u8 with
+    error state, sign codec, decode and the fused SGD step, compared on ranges at the start, across the 2^32
+    boundary and at the ragged end."""
+    from bagua_workloads import draw, seed_for
+    C = 4096
+    n = (1 << 32) + 3 * C + 77
+    nc = (n + C - 1) // C
+    x = draw("normal", n, seed_for(9, 0, 0), DEV, 1e-3)
+    delta = torch.zeros(n, device=DEV)
+    delta[::3] = 1e-4
+    rs = [(0, 64 * C), ((1 << 32) - 32 * C, (1 << 32) + 2 * C), (n - 77 - 16 * C, n)]
+    keep = {(lo, hi): (x[lo:hi].cpu().numpy(), delta[lo:hi].cpu().numpy().copy()) for lo, hi in rs}
+    codes = torch.empty(n, dtype=torch.uint8, device=DEV); mm = torch.empty(2 * nc, device=DEV)
+    bg.bagua_compress_minmax_u8(x, delta, C, codes, mm)
+    for (lo, hi), (xh, dh) in keep.items():
+        c, m = oracle.compress_minmax_u8(xh, dh, C)
+        exact(host(codes[lo:hi]), c, "codes"); exact(host(mm[2 * lo // C:2 * ((hi + C - 1) // C)]), m, "minmax")
+        exact(host(delta[lo:hi]), dh, "delta")
+    out = delta                                    # reuse the 17 GB buffer
+    bg.bagua_decompress(bg.CODEC_MINMAX_U8, codes, mm, n, C, out)
+    for lo, hi in rs:
+        exact(host(out[lo:hi]), oracle.decompress_minmax_u8(host(codes[lo:hi]), host(mm[2 * lo // C:2 * ((hi + C - 1) // C)]), C), "decode")
+    # fused decode + SGD on the same codes
+    param = out
+    param.fill_(1.0)
+    bg.bagua_decompress_sgd_step(bg.CODEC_MINMAX_U8, codes, mm, n, C, param, None, 0.5)
+    for lo, hi in rs:
+        p = np.ones(hi - lo, np.float32)
+        oracle.decompress_sgd_step(0, host(codes[lo:hi]), host(mm[2 * lo // C:2 * ((hi + C - 1) // C)]), hi - lo, C, p, None, 0.5)
+        exact(host(param[lo:hi]), p, "sgd")
+    del codes
+    bits = torch.empty((n + 31) // 32, dtype=torch.int32, device=DEV); sc = torch.empty(nc, device=DEV)
+    bg.bagua_sign_compress_ef(x, None, C, bits, sc)
+    for (lo, hi), (xh, _) in keep.items():
+        b, s = oracle.sign_compress_ef(xh, None, C)
+        exact(host(bits[lo // 32:(hi + 31) // 32]).view(np.uint32), b, "bits"); exact(host(sc[lo // C:(hi + C - 1) // C]), s, "scale")
