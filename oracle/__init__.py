@@ -262,3 +262,14 @@ def drr_topk(idx_in, val_in, server_residual, n, chunk, keep, want_fp32=True):
           None if server_residual is None else _chk(server_residual, np.float32), n, chunk, keep,
           _chk(idx, np.uint16), _chk(val, np.float32), None if out is None else _chk(out, np.float32)), "drr_topk")
     return idx, val, out
+
+
+def centralized_avg_fp(xs):
+    """C_FP_S, averaged: (x_0 + x_1 + ...) * fl(1/k) in ascending order."""
+    k, n = len(xs), xs[0].size
+    out = np.empty(n, np.float32)
+    f = lib().oracle_centralized_avg_fp
+    f.restype = ctypes.c_int
+    f.argtypes = [_c_p, ctypes.c_int, _c_sz, _c_p]
+    _ok(f(_ptr_array(xs, np.float32), k, n, _chk(out, np.float32)), "centralized_avg_fp")
+    return out

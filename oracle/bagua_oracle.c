@@ -713,3 +713,24 @@ int oracle_drr_topk(const uint16_t* const* idx_in, const float* const* val_in, i
     free(d);
     return rc;
 }
+
+/* ----------------------------------------------------------- centralised, full precision */
+
+/*
+ * C_FP_S (Section 3.2, "Centralized, Full Precision": every worker ends up with the sum of all
+ * replicas, the Allreduce result).  With reading R2 the average is returned: the ascending-order
+ * fp32 sum times fl(1/k).  This is C_LP_S with Q = identity and no error state.
+ */
+int oracle_centralized_avg_fp(const float* const* x, int k, size_t n, float* out)
+{
+    if (!x || k < 1 || k > 32 || n == 0 || !out) return 1;
+    for (int j = 0; j < k; ++j)
+        if (!x[j]) return 1;
+    float inv = 1.0f / (float)k;
+    for (size_t i = 0; i < n; ++i) {
+        float s = x[0][i];
+        for (int j = 1; j < k; ++j) s = s + x[j][i];
+        out[i] = s * inv;
+    }
+    return 0;
+}

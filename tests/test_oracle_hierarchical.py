@@ -63,3 +63,34 @@ def test_two_level_pipeline_error_bounds(oracle):
     c, m, out = oracle.drr_minmax_u8([e[0] for e in enc], [e[1] for e in enc], None, C)
     rng_ = np.repeat((m[1::2] - m[0::2]).astype(np.float64), C)[:n]
     assert np.all(np.abs(out - np.mean(sent, 0)) <= rng_ / 255 / 2 * (1 + 1e-4) + 1e-9)
+
+
+@pytest.mark.parametrize("k", [1, 2, 5, 8])
+def test_centralized_full_precision_average(oracle, k):
+    """C_FP_S: the textbook mean (fp64) within fp32 rounding, the left-to-right order made visible, k = 1 the identity,
+    and equal to the server step of C_LP_S on a lossless grid (Q = identity)."""
+    n = 1000
+    xs = [vals(n, 50 * k + j) for j in range(k)]
+    out = oracle.centralized_avg_fp(xs)
+    exact = np.mean(np.stack(xs).astype(np.float64), 0)
+    assert np.max(np.abs(out - exact)) <= 1e-6 * np.max(np.abs(exact)) + 1e-10
+    if k == 1:
+        assert out.tobytes() == xs[0].tobytes()
+    big = np.float32(2.0 ** 24)
+    ys = [np.full(8, t, np.float32) for t in (big, 1.0, 1.0, -big)]
+    assert oracle.centralized_avg_fp(ys)[0] == 0.0                       # ((2^24 + 1) + 1) - 2^24 = 0 in fp32
+    assert oracle.centralized_avg_fp(ys[1:3] + ys[0:1] + ys[3:])[0] == 0.5
+    # lossless grid: MinMax-u8 is the identity, so the C_LP_S server step must decode to the same average
+    C, p = 256, -9
+    rng = np.random.default_rng(k)
+    gs = []
+    for j in range(k):
+        jj = rng.integers(0, 256, 2 * C); jj[::C] = 0; jj[1::C] = 255
+        gs.append((jj * 2.0 ** p).astype(np.float32))
+    enc = [oracle.compress_minmax_u8(g, None, C) for g in gs]
+    avg = oracle.centralized_avg_fp(gs)
+    codes, mm, outq = oracle.drr_minmax_u8([e[0] for e in enc], [e[1] for e in enc], None, C)
+    rng_ = np.repeat((mm[1::2] - mm[0::2]).astype(np.float64), C)
+    assert np.all(np.abs(outq - avg) <= rng_ / 255 / 2 * (1 + 1e-4) + 1e-9)
+    for c in range(2):
+        assert mm[2 * c] == avg[c * C:(c + 1) * C].min() and mm[2 * c + 1] == avg[c * C:(c + 1) * C].max()
