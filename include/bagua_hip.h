@@ -153,6 +153,13 @@ int bagua_decentralized_avg(int mode, const float* const* x_in, float* const* x_
                             void* stream);
 
 /*
+ * C_FP_S (Section 3.2, centralised full precision: every worker receives the aggregate of all replicas, the
+ * Allreduce result), as an average: out = (x[0] + x[1] + ...) * fl(1/k), summed in ascending order.
+ *   x    host[k] of device fp32[n], read only;   out  device fp32[n], must not overlap any input
+ */
+int bagua_centralized_avg_fp(const float* const* x, int k, size_t n, float* out, void* stream);
+
+/*
  * Intra-node stage of the hierarchical variant of C_LP_S (Section 3.5 "Hierarchical Communications": the workers
  * of one node are aggregated without compression, only the node leaders exchange compressed tensors): average the
  * k_local workers' uncompressed buckets in ascending order, then compress as bagua_compress_minmax_u8 does, with

@@ -26,7 +26,7 @@ EXPORTS = (
     "bagua_decentralized_avg", "bagua_sign_compress_ef", "bagua_decompress", "bagua_flatten_compress_minmax_u8",
     "bagua_decompress_sgd_step", "bagua_decentralized_avg_peers", "bagua_reduce_compress_minmax_u8",
     "bagua_bucket_unflatten_run", "bagua_compress_topk_ef", "bagua_decompress_reduce_recompress_topk",
-    "bagua_decompress_topk",
+    "bagua_decompress_topk", "bagua_centralized_avg_fp",
 )
 
 
@@ -60,6 +60,7 @@ def _load():
     lib.bagua_decompress.argtypes = [i32, vp, vp, sz, sz, vp, vp]
     lib.bagua_flatten_compress_minmax_u8.argtypes = [vp, sz, vp, sz, sz, vp, vp, vp, vp]
     lib.bagua_reduce_compress_minmax_u8.argtypes = [vp, i32, vp, sz, sz, vp, vp, vp]
+    lib.bagua_centralized_avg_fp.argtypes = [vp, i32, sz, vp, vp]
     lib.bagua_decentralized_avg_peers.argtypes = [vp, vp, vp, i32, sz, vp]
     lib.bagua_decompress_sgd_step.argtypes = [i32, vp, vp, sz, sz, vp, vp, ctypes.c_float, ctypes.c_float,
                                               ctypes.c_float, vp]
@@ -185,6 +186,11 @@ def bagua_reduce_compress_minmax_u8(xs, residual, chunk, codes, minmax, stream=N
     _check("bagua_reduce_compress_minmax_u8", _lib.bagua_reduce_compress_minmax_u8(
         _ptr_array(xs, torch.float32), len(xs), _ptr(residual, torch.float32), xs[0].numel(), chunk,
         _ptr(codes, torch.uint8), _ptr(minmax, torch.float32), _stream(stream)))
+
+
+def bagua_centralized_avg_fp(xs, out, stream=None):
+    _check("bagua_centralized_avg_fp", _lib.bagua_centralized_avg_fp(_ptr_array(xs, torch.float32), len(xs), xs[0].numel(),
+                                                                     _ptr(out, torch.float32), _stream(stream)))
 
 
 def bagua_decentralized_avg_peers(x_in, x_out, peer, stream=None):

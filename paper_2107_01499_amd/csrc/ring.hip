@@ -373,3 +373,48 @@ extern "C" int bagua_decentralized_avg_peers(const float* const* x_in, float* co
                        static_cast<hipStream_t>(stream), jobs, n);
     return launch_status();
 }
+
+// ------------------------------------------------------------------------------------------ C_FP_S
+// Centralised full-precision average of k replicas: out = (x_0 + x_1 + ...) * inv_k, ascending order.
+// One wave per row; the loads of four workers are in flight together.
+namespace bagua {
+
+__global__ void __launch_bounds__(256)
+k_centralized_avg_fp(PtrTable xs, int k, float inv_k, size_t n, float* __restrict__ out)
+{
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const size_t e0 = row * kRow;
+    if (e0 >= n) return;
+    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    f4 s = load_row(static_cast<const float*>(xs.p[0]) + e0, lane, remain, 0.0f);
+    int j = 1;
+    for (; j + 4 <= k; j += 4) {
+        f4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = load_row(static_cast<const float*>(xs.p[j + u]) + e0, lane, remain, 0.0f);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s = add4(s, v[u]);
+    }
+    for (; j < k; ++j) s = add4(s, load_row(static_cast<const float*>(xs.p[j]) + e0, lane, remain, 0.0f));
+    store_row(out + e0, lane, remain, mul4(s, inv_k));
+}
+
+}  // namespace bagua
+
+extern "C" int bagua_centralized_avg_fp(const float* const* x, int k, size_t n, float* out, void* stream)
+{
+    if (!x || k < 1 || k > BAGUA_MAX_WORKERS || n == 0 || !out) return BAGUA_ERR_INVALID_ARG;
+    for (int j = 0; j < k; ++j)
+        if (!x[j] || overlaps(x[j], out, n * sizeof(float))) return BAGUA_ERR_INVALID_ARG;
+    for (int j = 0; j < k; ++j)
+        if (!aligned16(x[j])) return BAGUA_ERR_ALIGNMENT;
+    if (!aligned16(out)) return BAGUA_ERR_ALIGNMENT;
+    const size_t rows = (n + kRow - 1) / kRow;
+    if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    PtrTable xt{};
+    for (int j = 0; j < k; ++j) xt.p[j] = x[j];
+    hipLaunchKernelGGL(k_centralized_avg_fp, dim3(static_cast<unsigned>((rows + 3) / 4)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), xt, k, 1.0f / static_cast<float>(k), n, out);
+    return launch_status();
+}

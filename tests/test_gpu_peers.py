@@ -47,3 +47,16 @@ def test_hypercube_rounds_on_gpu_equal_global_mean(bg):
         cur, nxt = nxt, cur
     for i in range(k):
         assert np.max(np.abs(cur[i].cpu().numpy() - mean)) <= 4e-7 * max(1.0, np.max(np.abs(mean)))
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5, 8, 9, 32])
+@pytest.mark.parametrize("n", [1, 255, 1027, 70001])
+def test_centralized_avg_fp(bg, oracle, k, n):
+    """C_FP_S average against the oracle, bit for bit (values chosen so that the summation order matters)."""
+    r = np.random.default_rng(n + k)
+    xs = [(r.standard_normal(n) * 10.0 ** r.integers(-3, 4)).astype(np.float32) for _ in range(k)]
+    want = oracle.centralized_avg_fp(xs)
+    out = torch.full((n,), float("nan"), device="cuda")
+    bg.bagua_centralized_avg_fp([torch.from_numpy(x).cuda() for x in xs], out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), want.view(np.uint32))
