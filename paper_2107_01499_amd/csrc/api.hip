@@ -25,7 +25,17 @@ extern "C" int bagua_decompress_reduce_recompress(int codec, const void* const* 
         return BAGUA_ERR_INVALID_ARG;
     for (int j = 0; j < k; ++j) {
         if (!codes_in[j] || !meta_in[j]) return BAGUA_ERR_INVALID_ARG;
-        if (codes_in[j] == codes_out || meta_in[j] == meta_out) return BAGUA_ERR_INVALID_ARG;
+    }
+    // outputs must not overlap any input (byte ranges, not just equal base pointers)
+    const size_t nc = num_chunks(n, chunk);
+    const size_t code_bytes = codec == BAGUA_CODEC_MINMAX_U8 ? n : ((n + 31) / 32) * sizeof(uint32_t);
+    const size_t meta_bytes = (codec == BAGUA_CODEC_MINMAX_U8 ? 2 * nc : nc) * sizeof(float);
+    for (int j = 0; j < k; ++j) {
+        if (ranges_overlap(codes_in[j], code_bytes, codes_out, code_bytes) ||
+            ranges_overlap(meta_in[j], meta_bytes, meta_out, meta_bytes) ||
+            (out_fp32 && ranges_overlap(codes_in[j], code_bytes, out_fp32, n * sizeof(float))) ||
+            (server_residual && ranges_overlap(codes_in[j], code_bytes, server_residual, n * sizeof(float))))
+            return BAGUA_ERR_INVALID_ARG;
     }
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     for (int j = 0; j < k; ++j)

@@ -179,6 +179,11 @@ __device__ __forceinline__ float minmax_step(float mn, float mx)
 inline bool chunk_ok(size_t chunk) { return chunk >= 256 && chunk <= 16384 && chunk % 256 == 0; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t num_chunks(size_t n, size_t chunk) { return (n + chunk - 1) / chunk; }
+inline bool ranges_overlap(const void* a, size_t abytes, const void* b, size_t bbytes)
+{
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y + bbytes && y < x + abytes;
+}
 constexpr size_t kMaxGrid = 0x7fffffffu;
 
 // Rows per wave actually used: the preferred value, doubled until the chunk fits kMaxWaves waves.
