@@ -11,7 +11,7 @@ struct TensorDesc {
 };
 
 #ifndef BAGUA_FLATTEN_TILE
-#define BAGUA_FLATTEN_TILE 2048
+#define BAGUA_FLATTEN_TILE 1024
 #endif
 constexpr int kTile = BAGUA_FLATTEN_TILE;  // bucket elements per workgroup (256 lanes x kTile/1024 groups of four)
 static_assert(kTile % 1024 == 0, "a tile is a whole number of 256-lane groups of four elements");
