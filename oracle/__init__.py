@@ -273,3 +273,19 @@ def centralized_avg_fp(xs):
     f.argtypes = [_c_p, ctypes.c_int, _c_sz, _c_p]
     _ok(f(_ptr_array(xs, np.float32), k, n, _chk(out, np.float32)), "centralized_avg_fp")
     return out
+
+
+def peer_avg_lp(x_in, xhat, peer, chunk):
+    """D_LP_S with one chosen peer per worker. xhat (list) is updated in place. Returns (x_out, codes, minmax) lists."""
+    k, n = len(x_in), x_in[0].size
+    nc = num_chunks(n, chunk)
+    outs = [np.empty(n, np.float32) for _ in range(k)]
+    codes = [np.empty(n, np.uint8) for _ in range(k)]
+    minmax = [np.empty(2 * nc, np.float32) for _ in range(k)]
+    f = lib().oracle_peer_avg_lp
+    f.restype = ctypes.c_int
+    f.argtypes = [_c_p, _c_p, _c_p, _c_p, _c_p, _c_p, ctypes.c_int, _c_sz, _c_sz]
+    pa = (ctypes.c_int * k)(*[int(p) for p in peer])
+    _ok(f(_ptr_array(x_in, np.float32), _ptr_array(outs, np.float32), _ptr_array(xhat, np.float32),
+          _ptr_array(codes, np.uint8), _ptr_array(minmax, np.float32), pa, k, n, chunk), "peer_avg_lp")
+    return outs, codes, minmax

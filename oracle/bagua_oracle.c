@@ -734,3 +734,41 @@ int oracle_centralized_avg_fp(const float* const* x, int k, size_t n, float* out
     }
     return 0;
 }
+
+/*
+ * D_LP_S with the random peer allocation (Section 3.4: the low-precision primitive uses the same
+ * peer selection as the full-precision one and compresses before sending).  Readings R8 and R17
+ * combined: every peer publishes Q(x_i - xhat_i) and all holders advance xhat_i, then
+ *     x_i' = (xhat_i + xhat_peer[i]) * 0.5f + (x_i - xhat_i)        (updated xhat).
+ */
+int oracle_peer_avg_lp(const float* const* x_in, float* const* x_out, float* const* xhat,
+                       uint8_t* const* codes, float* const* minmax, const int* peer, int k, size_t n,
+                       size_t chunk)
+{
+    if (!x_in || !x_out || !xhat || !codes || !minmax || !peer || k < 1 || k > 32 || n == 0 || !chunk_ok(chunk))
+        return 1;
+    for (int i = 0; i < k; ++i)
+        if (!x_in[i] || !x_out[i] || !xhat[i] || !codes[i] || !minmax[i] || peer[i] < 0 || peer[i] >= k) return 1;
+    float* d = (float*)malloc(n * sizeof(float));
+    float* q = (float*)malloc(n * sizeof(float));
+    if (!d || !q) { free(d); free(q); return 1; }
+    for (int i = 0; i < k; ++i) {
+        for (size_t e = 0; e < n; ++e) d[e] = x_in[i][e] - xhat[i][e];
+        oracle_compress_minmax_u8(d, NULL, n, chunk, codes[i], minmax[i]);
+        oracle_decompress_minmax_u8(codes[i], minmax[i], n, chunk, q);
+        for (size_t e = 0; e < n; ++e) xhat[i][e] = xhat[i][e] + q[e];
+    }
+    free(d);
+    free(q);
+    for (int i = 0; i < k; ++i) {
+        const float* a = xhat[i];
+        const float* b = xhat[peer[i]];
+        for (size_t e = 0; e < n; ++e) {
+            float s = a[e] + b[e];
+            float avg = s * 0.5f;
+            float own = x_in[i][e] - a[e];
+            x_out[i][e] = avg + own;
+        }
+    }
+    return 0;
+}
