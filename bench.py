@@ -58,7 +58,7 @@ def parse_args():
     ap.add_argument("--only", default="", help="comma list of primitives to run in the step (profiling aid)")
     ap.add_argument("--extras", default="", help="comma list of additional primitives appended to the step: sgd_step "
                     "(decode of the server's codes fused into an SGD-momentum update of every worker's replica), "
-                    "peer_fp (full-precision averaging with one chosen peer per worker), reduce_compress (intra-node "
+                    "peer_fp / peer_lp (full- / low-precision averaging with one chosen peer per worker), reduce_compress (intra-node "
                     "stage of hierarchical C_LP_S: 4 local workers averaged uncompressed, leader compresses), topk (C_LP_S with "
                     "the per-chunk top-K codec, keep = chunk/32: worker side and server side)")
     ap.add_argument("--fused-flatten", action="store_true",
@@ -90,6 +90,8 @@ class Workload:
             self.prims = self.prims + ["compress_topk", "drr_topk"]
         if "peer_fp" in extras and "ring_fp" in self.prims:
             self.prims = self.prims + ["peer_fp"]
+        if "peer_lp" in extras and "ring_lp" in self.prims:
+            self.prims = self.prims + ["peer_lp"]
         k, C, SC, cfg = self.k, self.C, self.SC, w["cfg"]
         dev = torch.device("cuda:0")
         f32 = dict(dtype=torch.float32, device=dev)
@@ -237,7 +239,7 @@ class Workload:
         wb = 4.0 if "sign_compress" in self.prims else 0.0   # the fused call also writes the bucket if it is needed later
         return {"flatten": 8.0, "flatten_compress": 13.0 + wb + 8.0 / C, "compress_minmax": 13.0 + 8.0 / C, "drr_minmax": k + 13.0 + 8.0 * (k + 1) / C,
                 "compress_topk": 12.0 + 6.0 * keep / C, "drr_topk": 12.0 + 6.0 * (k + 1) * keep / C,
-                "sgd_step": 17.0 + 8.0 / C, "reduce_compress": 4.0 * 4 + 9.0 + 8.0 / C, "peer_fp": 8.0, "ring_fp": 8.0, "ring_lp": 17.0 + 8.0 / C, "sign_compress": 12.125 + 4.0 / SC,
+                "sgd_step": 17.0 + 8.0 / C, "reduce_compress": 4.0 * 4 + 9.0 + 8.0 / C, "peer_fp": 8.0, "peer_lp": 17.0 + 8.0 / C, "ring_fp": 8.0, "ring_lp": 17.0 + 8.0 / C, "sign_compress": 12.125 + 4.0 / SC,
                 "drr_sign": k / 8.0 + 12.125 + 4.0 * (k + 1) / SC}
 
     def grad_bytes(self):
@@ -247,7 +249,7 @@ class Workload:
     def algo_bytes(self):
         n, k = self.n_elems, self.k
         units = {"flatten": n * k, "flatten_compress": n * k, "compress_minmax": n * k, "drr_minmax": n, "ring_fp": n * k, "ring_lp": n * k,
-                 "sign_compress": n * k, "drr_sign": n, "sgd_step": n * k, "peer_fp": n * k, "reduce_compress": n * (k // 4),
+                 "sign_compress": n * k, "drr_sign": n, "sgd_step": n * k, "peer_fp": n * k, "peer_lp": n * k, "reduce_compress": n * (k // 4),
                  "compress_topk": n * k, "drr_topk": n}
         bpe = self.bytes_per_element()
         return {p: bpe[p] * units[p] for p in self.prims}
@@ -255,7 +257,7 @@ class Workload:
     def launches(self):
         U, k = len(self.units), self.k
         per = {"flatten": U * k, "flatten_compress": U * k, "compress_minmax": U * k, "drr_minmax": U, "ring_fp": U, "ring_lp": U,
-               "sign_compress": U * k, "drr_sign": U, "sgd_step": U * k, "peer_fp": U, "reduce_compress": U * (k // 4),
+               "sign_compress": U * k, "drr_sign": U, "sgd_step": U * k, "peer_fp": U, "peer_lp": U, "reduce_compress": U * (k // 4),
                "compress_topk": U * k, "drr_topk": U}
         return {p: per[p] for p in self.prims}
 
@@ -265,7 +267,7 @@ class Workload:
                 "drr_minmax": "k_drr_minmax<4,true,true>", "ring_fp": "k_ring_avg_fp<%d>" % self.k,
                 "ring_lp": "k_ring_avg_lp<%d,2>" % self.k, "sign_compress": "k_sign_compress<2,true>",
                 "drr_sign": "k_drr_sign<4,true,true>", "sgd_step": "k_decompress_sgd<0,true,false>",
-                "peer_fp": "k_peer_avg_fp", "reduce_compress": "k_reduce_compress_minmax<2,true>",
+                "peer_fp": "k_peer_avg_fp", "peer_lp": "k_peer_avg_lp<2>", "reduce_compress": "k_reduce_compress_minmax<2,true>",
                 "compress_topk": "k_compress_topk<2,true>", "drr_topk": "k_drr_topk<2,true,true>"}[p]
 
     # ---- one pass of the hot path ------------------------------------------------------------------
@@ -330,6 +332,14 @@ class Workload:
                 for u in range(U):     # a fixed perfect matching (0,1)(2,3)...; reads what ring_fp just wrote
                     bg.bagua_decentralized_avg_peers([self.rep_fp[dst][i][u] for i in range(k)],
                                                      [self.rep_fp[src][i][u] for i in range(k)], [i ^ 1 for i in range(k)])
+            elif p == "peer_lp":
+                for u in range(U):     # same matching, low precision; continues from what ring_lp just wrote
+                    bg.bagua_decentralized_avg_peers_lp([self.rep_lp[dst][i][u] for i in range(k)],
+                                                        [self.rep_lp[src][i][u] for i in range(k)],
+                                                        [self.xhat[i][u] for i in range(k)],
+                                                        [self.lp_codes[i][u] for i in range(k)],
+                                                        [self.lp_minmax[i][u] for i in range(k)],
+                                                        [i ^ 1 for i in range(k)], C)
             elif p == "ring_fp":
                 for u in range(U):
                     bg.bagua_decentralized_avg(bg.AVG_FP, [self.rep_fp[src][i][u] for i in range(k)],

@@ -183,6 +183,19 @@ int bagua_decentralized_avg_peers(const float* const* x_in, float* const* x_out,
                                   void* stream);
 
 /*
+ * Decentralised low-precision averaging with a chosen peer per worker (Section 3.2, D_LP_S, with the peer selection
+ * of Section 3.4; the compressed-difference reading used by bagua_decentralized_avg in LP mode):
+ *   codes[i], minmax[i] = Q(x_in[i] - xhat[i])  (no error feedback);  xhat[i] <- xhat[i] + decode(codes[i]);
+ *   x_out[i] = (xhat[i] + xhat[peer[i]]) * 0.5f + (x_in[i] - xhat[i])        with the updated xhat.
+ *   peer    host[k], peer[i] in [0,k).  When the map is a perfect matching (peer[i] != i, peer[peer[i]] == i for
+ *           all i) and chunk <= 4096 each pair is processed in one pass; any other map takes two passes.
+ *   x_in, x_out, xhat, codes, minmax as in bagua_decentralized_avg (LP mode); same aliasing and alignment rules.
+ */
+int bagua_decentralized_avg_peers_lp(const float* const* x_in, float* const* x_out, float* const* xhat,
+                                     uint8_t* const* codes, float* const* minmax, const int* peer, int k, size_t n,
+                                     size_t chunk, void* stream);
+
+/*
  * Worker side of C_LP_S with Q = 1-bit sign and per-chunk scale (the compression of "1-bit
  * Adam", Section 4.1 "Bagua Algorithms"):
  *   v = x + residual (v = x if NULL);  scale_c = mean over the chunk of |v| (fixed summation order);

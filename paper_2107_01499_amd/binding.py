@@ -26,7 +26,7 @@ EXPORTS = (
     "bagua_decentralized_avg", "bagua_sign_compress_ef", "bagua_decompress", "bagua_flatten_compress_minmax_u8",
     "bagua_decompress_sgd_step", "bagua_decentralized_avg_peers", "bagua_reduce_compress_minmax_u8",
     "bagua_bucket_unflatten_run", "bagua_compress_topk_ef", "bagua_decompress_reduce_recompress_topk",
-    "bagua_decompress_topk", "bagua_centralized_avg_fp",
+    "bagua_decompress_topk", "bagua_centralized_avg_fp", "bagua_decentralized_avg_peers_lp",
 )
 
 
@@ -62,6 +62,7 @@ def _load():
     lib.bagua_reduce_compress_minmax_u8.argtypes = [vp, i32, vp, sz, sz, vp, vp, vp]
     lib.bagua_centralized_avg_fp.argtypes = [vp, i32, sz, vp, vp]
     lib.bagua_decentralized_avg_peers.argtypes = [vp, vp, vp, i32, sz, vp]
+    lib.bagua_decentralized_avg_peers_lp.argtypes = [vp, vp, vp, vp, vp, vp, i32, sz, sz, vp]
     lib.bagua_decompress_sgd_step.argtypes = [i32, vp, vp, sz, sz, vp, vp, ctypes.c_float, ctypes.c_float,
                                               ctypes.c_float, vp]
     for name in EXPORTS[2:]:
@@ -198,6 +199,15 @@ def bagua_decentralized_avg_peers(x_in, x_out, peer, stream=None):
     pa = (ctypes.c_int * k)(*[int(p) for p in peer])
     _check("bagua_decentralized_avg_peers", _lib.bagua_decentralized_avg_peers(
         _ptr_array(x_in, torch.float32), _ptr_array(x_out, torch.float32), pa, k, x_in[0].numel(), _stream(stream)))
+
+
+def bagua_decentralized_avg_peers_lp(x_in, x_out, xhat, codes, minmax, peer, chunk, stream=None):
+    k = len(x_in)
+    pa = (ctypes.c_int * k)(*[int(p) for p in peer])
+    _check("bagua_decentralized_avg_peers_lp", _lib.bagua_decentralized_avg_peers_lp(
+        _ptr_array(x_in, torch.float32), _ptr_array(x_out, torch.float32), _ptr_array(xhat, torch.float32),
+        _ptr_array(codes, torch.uint8), _ptr_array(minmax, torch.float32), pa, k, x_in[0].numel(), chunk,
+        _stream(stream)))
 
 
 def bagua_sign_compress_ef(x, residual, chunk, bits, scale, stream=None):

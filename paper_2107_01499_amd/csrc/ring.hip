@@ -418,3 +418,168 @@ extern "C" int bagua_centralized_avg_fp(const float* const* x, int k, size_t n, 
                        static_cast<hipStream_t>(stream), xt, k, 1.0f / static_cast<float>(k), n, out);
     return launch_status();
 }
+
+// ------------------------------------------------------------------------------------------ chosen peers, LP
+// D_LP_S with one chosen peer per worker (Sections 3.2 and 3.4): every worker publishes Q(x - xhat),
+// all holders advance xhat, then x_out[i] = (xhat[i] + xhat[peer[i]]) * 0.5 + (x[i] - xhat[i]).
+// A matched pair is one fused job: a workgroup owns one chunk of both partners, so x and xhat of
+// each are read once and out, xhat, codes written once (17 bytes per element per peer).  Any other
+// peer map takes two passes: k_lp_encode per worker, then a mix over the advanced public copies.
+namespace bagua {
+
+struct PeerLpJobs {
+    const float* x[2][BAGUA_MAX_WORKERS / 2];
+    float* out[2][BAGUA_MAX_WORKERS / 2];
+    float* hat[2][BAGUA_MAX_WORKERS / 2];
+    uint8_t* codes[2][BAGUA_MAX_WORKERS / 2];
+    float* minmax[2][BAGUA_MAX_WORKERS / 2];
+};
+
+template <int RPW>
+__global__ void __launch_bounds__(64 * ((16 + RPW - 1) / RPW))
+k_peer_avg_lp(PeerLpJobs jobs, size_t n, uint32_t chunk)
+{
+    __shared__ float s_red[2][2 * kMaxWaves];
+    const int job = blockIdx.y;
+    const size_t c = blockIdx.x;
+    const size_t base = c * static_cast<size_t>(chunk);
+    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+
+    f4 h[2][RPW], own[2][RPW];
+#pragma unroll
+    for (int sd = 0; sd < 2; ++sd) {
+        const float* __restrict__ xp = jobs.x[sd][job];
+        float* __restrict__ hp = jobs.hat[sd][job];
+        f4 x[RPW], d[RPW];
+        float mn, mx;
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+            const long off = static_cast<long>(wave * RPW + r) * kRow;
+            const long remain = len - off;
+            x[r] = f4{0.f, 0.f, 0.f, 0.f};
+            h[sd][r] = x[r];
+            if (remain > 0) {
+                x[r] = load_row(xp + base + off, lane, remain, 0.0f);
+                h[sd][r] = load_row(hp + base + off, lane, remain, 0.0f);
+            }
+            d[r] = sub4(x[r], h[sd][r]);
+        }
+        chunk_minmax_partial<RPW>(d, len, wave, lane, nwaves, s_red[sd], mn, mx);
+        if (nwaves > 1) __syncthreads();
+        chunk_minmax_finish(nwaves, s_red[sd], mn, mx);
+        minmax_quantise_chunk<RPW, false, false, true>(d, mn, mx, len, wave, lane, nullptr, jobs.codes[sd][job] + base,
+                                                       jobs.minmax[sd][job] + 2 * c, nullptr);
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+            const long off = static_cast<long>(wave * RPW + r) * kRow;
+            const long remain = len - off;
+            h[sd][r] = add4(h[sd][r], d[r]);
+            own[sd][r] = sub4(x[r], h[sd][r]);
+            if (remain > 0) store_row(hp + base + off, lane, remain, h[sd][r]);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) {
+        const long off = static_cast<long>(wave * RPW + r) * kRow;
+        const long remain = len - off;
+        if (remain <= 0) continue;
+        const f4 avg = mul4(add4(h[0][r], h[1][r]), 0.5f);
+        store_row(jobs.out[0][job] + base + off, lane, remain, add4(avg, own[0][r]));
+        store_row(jobs.out[1][job] + base + off, lane, remain, add4(avg, own[1][r]));
+    }
+}
+
+// Second pass of the general case: worker i = blockIdx.y reads the advanced xhat of itself and of its peer.
+struct PeerMixJobs {
+    const float* x[BAGUA_MAX_WORKERS];
+    const float* hat_own[BAGUA_MAX_WORKERS];
+    const float* hat_peer[BAGUA_MAX_WORKERS];
+    float* out[BAGUA_MAX_WORKERS];
+};
+
+__global__ void __launch_bounds__(256)
+k_peer_mix_lp(PeerMixJobs jobs, size_t n)
+{
+    const int i = blockIdx.y;
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const size_t e0 = row * kRow;
+    if (e0 >= n) return;
+    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const f4 a = load_row(jobs.hat_own[i] + e0, lane, remain, 0.0f);
+    const f4 b = load_row(jobs.hat_peer[i] + e0, lane, remain, 0.0f);
+    const f4 xi = load_row(jobs.x[i] + e0, lane, remain, 0.0f);
+    store_row(jobs.out[i] + e0, lane, remain, add4(mul4(add4(a, b), 0.5f), sub4(xi, a)));
+}
+
+}  // namespace bagua
+
+extern "C" int bagua_decentralized_avg_peers_lp(const float* const* x_in, float* const* x_out, float* const* xhat,
+                                                uint8_t* const* codes, float* const* minmax, const int* peer, int k,
+                                                size_t n, size_t chunk, void* stream)
+{
+    if (!x_in || !x_out || !xhat || !codes || !minmax || !peer || k < 1 || k > BAGUA_MAX_WORKERS || n == 0 ||
+        !chunk_ok(chunk))
+        return BAGUA_ERR_INVALID_ARG;
+    for (int i = 0; i < k; ++i)
+        if (!x_in[i] || !x_out[i] || !xhat[i] || !codes[i] || !minmax[i] || peer[i] < 0 || peer[i] >= k)
+            return BAGUA_ERR_INVALID_ARG;
+    const size_t bytes = n * sizeof(float);
+    for (int i = 0; i < k; ++i)
+        for (int j = 0; j < k; ++j) {
+            if (overlaps(x_out[i], x_in[j], bytes) || overlaps(x_out[i], xhat[j], bytes) ||
+                overlaps(xhat[i], x_in[j], bytes))
+                return BAGUA_ERR_INVALID_ARG;
+            if (j != i && (overlaps(x_out[i], x_out[j], bytes) || overlaps(xhat[i], xhat[j], bytes)))
+                return BAGUA_ERR_INVALID_ARG;
+        }
+    for (int i = 0; i < k; ++i)
+        if (!aligned16(x_in[i]) || !aligned16(x_out[i]) || !aligned16(xhat[i]) || !aligned16(codes[i]) ||
+            !aligned16(minmax[i]))
+            return BAGUA_ERR_ALIGNMENT;
+    const size_t nrows = (n + kRow - 1) / kRow;
+    if ((nrows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t nc = num_chunks(n, chunk);
+    const int rows = static_cast<int>(chunk / kRow);
+    const uint32_t ch = static_cast<uint32_t>(chunk);
+
+    bool matching = true;  // every worker is in a pair with a distinct partner
+    for (int i = 0; i < k; ++i) matching = matching && peer[i] != i && peer[peer[i]] == i;
+    if (matching && rows <= 16) {
+        PeerLpJobs jobs{};
+        int nj = 0;
+        for (int i = 0; i < k; ++i) {
+            const int p = peer[i];
+            if (p < i) continue;
+            const int side[2] = {i, p};
+            for (int sd = 0; sd < 2; ++sd) {
+                jobs.x[sd][nj] = x_in[side[sd]];
+                jobs.out[sd][nj] = x_out[side[sd]];
+                jobs.hat[sd][nj] = xhat[side[sd]];
+                jobs.codes[sd][nj] = codes[side[sd]];
+                jobs.minmax[sd][nj] = minmax[side[sd]];
+            }
+            ++nj;
+        }
+        dim3 grid(static_cast<unsigned>(nc), nj), block(64 * ((rows + BAGUA_RPW_LP - 1) / BAGUA_RPW_LP));
+        hipLaunchKernelGGL((k_peer_avg_lp<BAGUA_RPW_LP>), grid, block, 0, s, jobs, n, ch);
+        return launch_status();
+    }
+    const int rpw = pick_rpw(rows, BAGUA_RPW_COMPRESS);
+    dim3 grid(static_cast<unsigned>(nc)), block(64 * ((rows + rpw - 1) / rpw));
+    for (int i = 0; i < k; ++i) {
+        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_lp_encode<RPW>), grid, block, 0, s, x_in[i], xhat[i], n, ch,
+                                                   codes[i], minmax[i]))
+    }
+    PeerMixJobs mix{};
+    for (int i = 0; i < k; ++i) {
+        mix.x[i] = x_in[i];
+        mix.hat_own[i] = xhat[i];
+        mix.hat_peer[i] = xhat[peer[i]];
+        mix.out[i] = x_out[i];
+    }
+    hipLaunchKernelGGL(k_peer_mix_lp, dim3(static_cast<unsigned>((nrows + 3) / 4), k), dim3(256), 0, s, mix, n);
+    return launch_status();
+}

@@ -90,6 +90,17 @@ def test_peer_validation_without_gpu(bg):
     assert lib.bagua_decentralized_avg_peers(xin, xout, (ctypes.c_int * 2)(1, 2), 2, 16, None) == 1    # peer out of range
     assert lib.bagua_decentralized_avg_peers(xin, xin, (ctypes.c_int * 2)(1, 0), 2, 16, None) == 1     # aliasing
     assert lib.bagua_decentralized_avg_peers(xin, xout, None, 2, 16, None) == 1
+    hat = (ctypes.c_void_p * 2)(0x50000, 0x60000)
+    cd = (ctypes.c_void_p * 2)(0x70000, 0x80000)
+    mm = (ctypes.c_void_p * 2)(0x90000, 0xa0000)
+    ok_peer = (ctypes.c_int * 2)(1, 0)
+    lp = lib.bagua_decentralized_avg_peers_lp
+    assert lp(xin, xout, hat, cd, mm, (ctypes.c_int * 2)(1, -1), 2, 16, 256, None) == 1   # peer out of range
+    assert lp(xin, xout, xin, cd, mm, ok_peer, 2, 16, 256, None) == 1                      # xhat aliases x_in
+    assert lp(xin, xout, xout, cd, mm, ok_peer, 2, 16, 256, None) == 1                     # xhat aliases x_out
+    assert lp(xin, xout, hat, cd, mm, ok_peer, 2, 16, 100, None) == 1                      # bad chunk
+    assert lp(xin, xout, None, cd, mm, ok_peer, 2, 16, 256, None) == 1
+    assert lp(xin, xout, hat, (ctypes.c_void_p * 2)(0x70004, 0x80000), mm, ok_peer, 2, 16, 256, None) == 2
     assert lib.bagua_decompress_sgd_step(0, 0x1000, 0x1000, 16, 256, 0x2000, 0x2000, 0.1, 0.9, 0.0, None) == 1  # param aliases momentum
     assert lib.bagua_decompress_sgd_step(3, 0x1000, 0x1000, 16, 256, 0x2000, None, 0.1, 0.9, 0.0, None) == 1
     assert lib.bagua_flatten_compress_minmax_u8(None, 1, None, 16, 256, 0x1000, 0x1000, None, None) == 1
