@@ -289,3 +289,28 @@ def peer_avg_lp(x_in, xhat, peer, chunk):
     _ok(f(_ptr_array(x_in, np.float32), _ptr_array(outs, np.float32), _ptr_array(xhat, np.float32),
           _ptr_array(codes, np.uint8), _ptr_array(minmax, np.float32), pa, k, n, chunk), "peer_avg_lp")
     return outs, codes, minmax
+
+
+def decompress_adam_step(codec, codes, meta, n, chunk, param, m, v, lr, beta1=0.9, beta2=0.999, eps=1e-8,
+                         weight_decay=0.0, variance_frozen=False):
+    """Decode a compressed bucket and apply the Adam-type update in place on param, m (and v unless frozen)."""
+    f = lib().oracle_decompress_adam_step
+    f.restype = ctypes.c_int
+    cf = ctypes.c_float
+    f.argtypes = [ctypes.c_int, _c_p, _c_p, _c_sz, _c_sz, _c_p, _c_p, _c_p, cf, cf, cf, cf, cf, ctypes.c_int]
+    cp = _chk(codes, np.uint8) if codec == 0 else _chk(codes, np.uint32)
+    _ok(f(codec, cp, _chk(meta, np.float32), n, chunk, _chk(param, np.float32), _chk(m, np.float32),
+          _chk(v, np.float32), lr, beta1, beta2, eps, weight_decay, int(bool(variance_frozen))), "decompress_adam_step")
+
+
+def momentum_sign_compress_ef(g, m, beta1, residual, chunk):
+    """Sign-compress beta1*m + (1-beta1)*g with error feedback (residual updated in place). Returns (bits, scale)."""
+    n = g.size
+    bits = np.empty((n + 31) // 32, np.uint32)
+    scale = np.empty(num_chunks(n, chunk), np.float32)
+    f = lib().oracle_momentum_sign_compress_ef
+    f.restype = ctypes.c_int
+    f.argtypes = [_c_p, _c_p, ctypes.c_float, _c_p, _c_sz, _c_sz, _c_p, _c_p]
+    _ok(f(_chk(g, np.float32), _chk(m, np.float32), beta1, None if residual is None else _chk(residual, np.float32),
+          n, chunk, _chk(bits, np.uint32), _chk(scale, np.float32)), "momentum_sign_compress_ef")
+    return bits, scale

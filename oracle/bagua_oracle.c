@@ -62,6 +62,11 @@
  *  R17 Random peer strategy: N(i) = {i, peer[i]}, weight 1/2 (oracle_peer_avg_fp).
  *  R18 Hierarchical C_LP_S, intra-node stage: uncompressed average of the local workers, then
  *      the leader's Q with its error state (oracle_reduce_compress_minmax_u8).
+ *  R20 1-bit Adam (Section 4.1 names it as C_LP_S with error compensation; its steps are those of
+ *      the published algorithm it cites): Adam without bias correction; after the warm-up the
+ *      variance is frozen, every worker forms its local momentum beta1*m + (1-beta1)*g and
+ *      compresses that; the decoded average replaces the momentum and drives the update
+ *      (oracle_momentum_sign_compress_ef, oracle_decompress_adam_step).
  *
  * Status codes: 0 ok, 1 invalid argument.
  */
@@ -771,4 +776,80 @@ int oracle_peer_avg_lp(const float* const* x_in, float* const* x_out, float* con
         }
     }
     return 0;
+}
+
+
+/* ------------------------------------------------------------------ Adam-type bucket optimizer */
+
+/*
+ * Decode fused into an Adam-type update of the flattened bucket (Section 3.5: the optimizer runs on
+ * the bucket; Section 4.1: QSGD and 1-bit Adam are C_LP_S followed by the optimizer).  Reading R20,
+ * one rounding per operation, in this order, with omb = 1.0f - beta in fp32:
+ *   d = decode(codes, meta)
+ *   variance_frozen == 0 (d is the averaged gradient):
+ *       m = beta1*m + omb1*d ;  v = beta2*v + omb2*(d*d)
+ *   variance_frozen != 0 (compression stage of 1-bit Adam, d is the averaged momentum):
+ *       m = d ;  v unchanged
+ *   u = m / (sqrtf(v) + eps) ;  if weight_decay != 0:  u = u + weight_decay*p ;  p = p - lr*u
+ */
+int oracle_decompress_adam_step(int codec, const void* codes, const float* meta, size_t n, size_t chunk,
+                                float* param, float* m, float* v, float lr, float beta1, float beta2, float eps,
+                                float weight_decay, int variance_frozen)
+{
+    if ((codec != 0 && codec != 1) || !codes || !meta || !param || !m || !v || n == 0 || !chunk_ok(chunk)) return 1;
+    float* d = (float*)malloc(n * sizeof(float));
+    if (!d) return 1;
+    int rc = codec == 0 ? oracle_decompress_minmax_u8((const uint8_t*)codes, meta, n, chunk, d)
+                        : oracle_decompress_sign((const uint32_t*)codes, meta, n, chunk, d);
+    if (rc) { free(d); return rc; }
+    const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
+    for (size_t i = 0; i < n; ++i) {
+        float mi, vi = v[i];
+        if (variance_frozen) {
+            mi = d[i];
+        } else {
+            float a = beta1 * m[i];
+            float b = omb1 * d[i];
+            mi = a + b;
+            float c = beta2 * vi;
+            float dd = d[i] * d[i];
+            float e = omb2 * dd;
+            vi = c + e;
+            v[i] = vi;
+        }
+        m[i] = mi;
+        float root = sqrtf(vi);
+        float denom = root + eps;
+        float u = mi / denom;
+        if (weight_decay != 0.0f) {
+            float w = weight_decay * param[i];
+            u = u + w;
+        }
+        float step = lr * u;
+        param[i] = param[i] - step;
+    }
+    free(d);
+    return 0;
+}
+
+/*
+ * Worker side of the compression stage of 1-bit Adam (reading R20): the local momentum
+ *   u = beta1*m + omb1*g        (m: the momentum all workers share after the previous step; not written)
+ * is compressed with the sign codec and the worker's error state exactly as oracle_sign_compress_ef does.
+ */
+int oracle_momentum_sign_compress_ef(const float* g, const float* m, float beta1, float* residual, size_t n,
+                                     size_t chunk, uint32_t* bits, float* scale)
+{
+    if (!g || !m || !bits || !scale || n == 0 || !chunk_ok(chunk)) return 1;
+    float* u = (float*)malloc(n * sizeof(float));
+    if (!u) return 1;
+    const float omb1 = 1.0f - beta1;
+    for (size_t i = 0; i < n; ++i) {
+        float a = beta1 * m[i];
+        float b = omb1 * g[i];
+        u[i] = a + b;
+    }
+    int rc = oracle_sign_compress_ef(u, residual, n, chunk, bits, scale);
+    free(u);
+    return rc;
 }
