@@ -58,6 +58,8 @@ def parse_args():
     ap.add_argument("--only", default="", help="comma list of primitives to run in the step (profiling aid)")
     ap.add_argument("--extras", default="", help="comma list of additional primitives appended to the step: sgd_step "
                     "(decode of the server's codes fused into an SGD-momentum update of every worker's replica), "
+                    "adam_step (the same decode fused into an Adam update), onebit_adam (compression stage of 1-bit Adam: momentum "
+                    "sign compression on every worker and the decode + frozen-variance update), "
                     "peer_fp / peer_lp (full- / low-precision averaging with one chosen peer per worker), reduce_compress (intra-node "
                     "stage of hierarchical C_LP_S: 4 local workers averaged uncompressed, leader compresses), topk (C_LP_S with "
                     "the per-chunk top-K codec, keep = chunk/32: worker side and server side)")
@@ -84,6 +86,10 @@ class Workload:
             self.prims = ["flatten_compress" if p == "flatten" else p for p in self.prims if p != "compress_minmax"]
         if "sgd_step" in extras and "drr_minmax" in self.prims:
             self.prims = self.prims + ["sgd_step"]
+        if "adam_step" in extras and "drr_minmax" in self.prims:
+            self.prims = self.prims + ["adam_step"]
+        if "onebit_adam" in extras and "drr_sign" in self.prims and "sign_compress" in self.prims:
+            self.prims = self.prims + ["momentum_sign", "adam_frozen_step"]
         if "reduce_compress" in extras and ("flatten" in self.prims or "flatten_compress" in self.prims):
             self.prims = self.prims + ["reduce_compress"]
         if "topk" in extras and ("flatten" in self.prims or "flatten_compress" in self.prims):
@@ -195,9 +201,17 @@ class Workload:
             self.tidx_out = views(z(nc * self.keep, dtype=torch.int16, device=dev), C, self.keep)
             self.tval_out = views(z(nc * self.keep, **f32), C, self.keep)
             self.tout = views(z(n, **f32))
-        if has("sgd_step"):
+        if has("sgd_step", "adam_step", "adam_frozen_step"):
             self.param = [views(draw("normal", n, seed_for(cfg, 50, j), dev, 0.02)) for j in range(k)]
             self.mbuf = [views(z(n, **f32)) for _ in range(k)]
+        if has("adam_step"):
+            self.vbuf = [views(z(n, **f32)) for _ in range(k)]
+        if has("momentum_sign"):
+            self.shared_m = views(draw("normal", n, seed_for(cfg, 51, SHARED), dev, scale))
+            self.frozen_v = views(draw("normal", n, seed_for(cfg, 52, SHARED), dev, scale).square_())
+            self.msdelta = [views(z(n, **f32)) for _ in range(k)]
+            self.mbits = [views(z((n + 31) // 32, **i32), 32) for _ in range(k)]
+            self.mscale = [views(z(ncs, **f32), SC) for _ in range(k)]
         if has("sign_compress", "drr_sign"):
             self.sdelta = [views(z(n, **f32)) for _ in range(k)]
             self.bits = [views(z((n + 31) // 32, **i32), 32) for _ in range(k)]
@@ -239,7 +253,8 @@ class Workload:
         wb = 4.0 if "sign_compress" in self.prims else 0.0   # the fused call also writes the bucket if it is needed later
         return {"flatten": 8.0, "flatten_compress": 13.0 + wb + 8.0 / C, "compress_minmax": 13.0 + 8.0 / C, "drr_minmax": k + 13.0 + 8.0 * (k + 1) / C,
                 "compress_topk": 12.0 + 6.0 * keep / C, "drr_topk": 12.0 + 6.0 * (k + 1) * keep / C,
-                "sgd_step": 17.0 + 8.0 / C, "reduce_compress": 4.0 * 4 + 9.0 + 8.0 / C, "peer_fp": 8.0, "peer_lp": 17.0 + 8.0 / C, "ring_fp": 8.0, "ring_lp": 17.0 + 8.0 / C, "sign_compress": 12.125 + 4.0 / SC,
+                "sgd_step": 17.0 + 8.0 / C, "adam_step": 25.0 + 8.0 / C, "momentum_sign": 16.125 + 4.0 / SC,
+                "adam_frozen_step": 16.125 + 4.0 / SC, "reduce_compress": 4.0 * 4 + 9.0 + 8.0 / C, "peer_fp": 8.0, "peer_lp": 17.0 + 8.0 / C, "ring_fp": 8.0, "ring_lp": 17.0 + 8.0 / C, "sign_compress": 12.125 + 4.0 / SC,
                 "drr_sign": k / 8.0 + 12.125 + 4.0 * (k + 1) / SC}
 
     def grad_bytes(self):
@@ -249,7 +264,7 @@ class Workload:
     def algo_bytes(self):
         n, k = self.n_elems, self.k
         units = {"flatten": n * k, "flatten_compress": n * k, "compress_minmax": n * k, "drr_minmax": n, "ring_fp": n * k, "ring_lp": n * k,
-                 "sign_compress": n * k, "drr_sign": n, "sgd_step": n * k, "peer_fp": n * k, "peer_lp": n * k, "reduce_compress": n * (k // 4),
+                 "sign_compress": n * k, "drr_sign": n, "sgd_step": n * k, "adam_step": n * k, "momentum_sign": n * k, "adam_frozen_step": n * k, "peer_fp": n * k, "peer_lp": n * k, "reduce_compress": n * (k // 4),
                  "compress_topk": n * k, "drr_topk": n}
         bpe = self.bytes_per_element()
         return {p: bpe[p] * units[p] for p in self.prims}
@@ -257,7 +272,7 @@ class Workload:
     def launches(self):
         U, k = len(self.units), self.k
         per = {"flatten": U * k, "flatten_compress": U * k, "compress_minmax": U * k, "drr_minmax": U, "ring_fp": U, "ring_lp": U,
-               "sign_compress": U * k, "drr_sign": U, "sgd_step": U * k, "peer_fp": U, "peer_lp": U, "reduce_compress": U * (k // 4),
+               "sign_compress": U * k, "drr_sign": U, "sgd_step": U * k, "adam_step": U * k, "momentum_sign": U * k, "adam_frozen_step": U * k, "peer_fp": U, "peer_lp": U, "reduce_compress": U * (k // 4),
                "compress_topk": U * k, "drr_topk": U}
         return {p: per[p] for p in self.prims}
 
@@ -267,6 +282,8 @@ class Workload:
                 "drr_minmax": "k_drr_minmax<4,true,true>", "ring_fp": "k_ring_avg_fp<%d>" % self.k,
                 "ring_lp": "k_ring_avg_lp<%d,2>" % self.k, "sign_compress": "k_sign_compress<2,true>",
                 "drr_sign": "k_drr_sign<4,true,true>", "sgd_step": "k_decompress_sgd<0,true,false>",
+                "adam_step": "k_decompress_adam<0,false,false>", "momentum_sign": "k_sign_compress<2,true,true>",
+                "adam_frozen_step": "k_decompress_adam<1,true,false>",
                 "peer_fp": "k_peer_avg_fp", "peer_lp": "k_peer_avg_lp<2>", "reduce_compress": "k_reduce_compress_minmax<2,true>",
                 "compress_topk": "k_compress_topk<2,true>", "drr_topk": "k_drr_topk<2,true,true>"}[p]
 
@@ -312,6 +329,23 @@ class Workload:
                     for u in range(U):
                         bg.bagua_decompress_sgd_step(bg.CODEC_MINMAX_U8, self.codes_out[u], self.minmax_out[u],
                                                      self.units[u][1], C, self.param[j][u], self.mbuf[j][u], 0.01, 0.9, 0.0)
+            elif p == "adam_step":
+                for j in range(k):
+                    for u in range(U):
+                        bg.bagua_decompress_adam_step(bg.CODEC_MINMAX_U8, self.codes_out[u], self.minmax_out[u],
+                                                      self.units[u][1], C, self.param[j][u], self.mbuf[j][u],
+                                                      self.vbuf[j][u], 1e-3, 0.9, 0.999, 1e-8, 0.0, False)
+            elif p == "momentum_sign":
+                for j in range(k):
+                    for u in range(U):
+                        bg.bagua_momentum_sign_compress_ef(self.bucket[j][u], self.shared_m[u], 0.9, self.msdelta[j][u],
+                                                           SC, self.mbits[j][u], self.mscale[j][u])
+            elif p == "adam_frozen_step":
+                for j in range(k):
+                    for u in range(U):
+                        bg.bagua_decompress_adam_step(bg.CODEC_SIGN1, self.bits_out[u], self.scale_out[u],
+                                                      self.units[u][1], SC, self.param[j][u], self.mbuf[j][u],
+                                                      self.frozen_v[u], 1e-3, 0.9, 0.999, 1e-8, 0.0, True)
             elif p == "compress_topk":
                 for j in range(k):
                     for u in range(U):

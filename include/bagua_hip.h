@@ -255,6 +255,29 @@ int bagua_decompress_sgd_step(int codec, const void* codes, const float* meta, s
                               float* param, float* momentum_buf, float lr, float momentum, float weight_decay,
                               void* stream);
 
+/*
+ * Decode fused into an Adam-type update of the flattened bucket (Section 3.5: the optimizer runs on the bucket;
+ * Section 4.1: QSGD and 1-bit Adam are C_LP_S followed by the optimizer; the steps of 1-bit Adam are those of the
+ * published algorithm the paper cites).  Adam without bias correction, one rounding per operation:
+ *   d = decode(codes, meta)                                        (codec as in bagua_decompress)
+ *   variance_frozen == 0 (d = averaged gradient):   m = beta1*m + (1-beta1)*d ;  v = beta2*v + (1-beta2)*(d*d)
+ *   variance_frozen != 0 (compression stage of 1-bit Adam, d = averaged momentum):   m = d ;  v only read
+ *   u = m / (sqrtf(v) + eps) ;  if weight_decay != 0: u = u + weight_decay*p ;  p = p - lr*u
+ * (1-beta) is formed in fp32.  param, m, v: device fp32[n], in-out, 16-byte aligned, pairwise disjoint.
+ */
+int bagua_decompress_adam_step(int codec, const void* codes, const float* meta, size_t n, size_t chunk, float* param,
+                               float* m, float* v, float lr, float beta1, float beta2, float eps, float weight_decay,
+                               int variance_frozen, void* stream);
+
+/*
+ * Worker side of the compression stage of 1-bit Adam (Section 4.1: 1-bit Adam = C_LP_S with error compensation,
+ * applied to the momentum): compresses the local momentum u = beta1*m + (1-beta1)*g exactly as
+ * bagua_sign_compress_ef compresses x (same codec, error state, layouts and limits).
+ *   g  device fp32[n] gradient, read only;   m  device fp32[n], the momentum shared after the previous step, read only
+ */
+int bagua_momentum_sign_compress_ef(const float* g, const float* m, float beta1, float* residual, size_t n,
+                                    size_t chunk, uint32_t* bits, float* scale, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,6 +27,7 @@ EXPORTS = (
     "bagua_decompress_sgd_step", "bagua_decentralized_avg_peers", "bagua_reduce_compress_minmax_u8",
     "bagua_bucket_unflatten_run", "bagua_compress_topk_ef", "bagua_decompress_reduce_recompress_topk",
     "bagua_decompress_topk", "bagua_centralized_avg_fp", "bagua_decentralized_avg_peers_lp",
+    "bagua_decompress_adam_step", "bagua_momentum_sign_compress_ef",
 )
 
 
@@ -65,6 +66,9 @@ def _load():
     lib.bagua_decentralized_avg_peers_lp.argtypes = [vp, vp, vp, vp, vp, vp, i32, sz, sz, vp]
     lib.bagua_decompress_sgd_step.argtypes = [i32, vp, vp, sz, sz, vp, vp, ctypes.c_float, ctypes.c_float,
                                               ctypes.c_float, vp]
+    cf = ctypes.c_float
+    lib.bagua_decompress_adam_step.argtypes = [i32, vp, vp, sz, sz, vp, vp, vp, cf, cf, cf, cf, cf, i32, vp]
+    lib.bagua_momentum_sign_compress_ef.argtypes = [vp, vp, cf, vp, sz, sz, vp, vp, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = i32
     return lib
@@ -208,6 +212,19 @@ def bagua_decentralized_avg_peers_lp(x_in, x_out, xhat, codes, minmax, peer, chu
         _ptr_array(x_in, torch.float32), _ptr_array(x_out, torch.float32), _ptr_array(xhat, torch.float32),
         _ptr_array(codes, torch.uint8), _ptr_array(minmax, torch.float32), pa, k, x_in[0].numel(), chunk,
         _stream(stream)))
+
+
+def bagua_decompress_adam_step(codec, codes, meta, n, chunk, param, m, v, lr, beta1=0.9, beta2=0.999, eps=1e-8,
+                               weight_decay=0.0, variance_frozen=False, stream=None):
+    _check("bagua_decompress_adam_step", _lib.bagua_decompress_adam_step(
+        codec, _ptr(codes), _ptr(meta, torch.float32), n, chunk, _ptr(param, torch.float32), _ptr(m, torch.float32),
+        _ptr(v, torch.float32), lr, beta1, beta2, eps, weight_decay, int(bool(variance_frozen)), _stream(stream)))
+
+
+def bagua_momentum_sign_compress_ef(g, m, beta1, residual, chunk, bits, scale, stream=None):
+    _check("bagua_momentum_sign_compress_ef", _lib.bagua_momentum_sign_compress_ef(
+        _ptr(g, torch.float32), _ptr(m, torch.float32), beta1, _ptr(residual, torch.float32), g.numel(), chunk,
+        _ptr(bits, torch.int32), _ptr(scale, torch.float32), _stream(stream)))
 
 
 def bagua_sign_compress_ef(x, residual, chunk, bits, scale, stream=None):

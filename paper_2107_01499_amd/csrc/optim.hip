@@ -1,30 +1,18 @@
 // Decode fused into the bucket-level optimizer step: the last step of C_LP_S on every worker
-// (decode the tensor the server sent back) and the stochastic-gradient update of the flattened
-// bucket (Section 3.5 of the paper) in one pass.  The decoded gradient is never written to memory:
-// 1 (or 1/8) + 8 (+ 8 with momentum) bytes per element instead of 4 + 4 more.
+// (decode the tensor the server sent back) and the update of the flattened bucket (Section 3.5 of
+// the paper) in one pass.  The decoded tensor is never written to memory.  SGD: 1 (or 1/8) + 8
+// (+ 8 with momentum) bytes per element; Adam: 1 + 24 (full), 1/8 + 16 (frozen variance).
 #include "launchers.hpp"
 
 #pragma clang fp contract(off)
 
 namespace bagua {
 
-// One wave per 256-element row, four rows per workgroup.
-template <int CODEC, bool MOM, bool WD>
-__global__ void __launch_bounds__(256)
-k_decompress_sgd(const void* __restrict__ codes, const float* __restrict__ meta, size_t n, uint32_t chunk,
-                 float* __restrict__ param, float* __restrict__ mbuf, float lr, float mu, float wd)
+// Decoded values of the row starting at element e0 (chunk c): four per lane.
+template <int CODEC>
+__device__ __forceinline__ f4 decode_row(const void* __restrict__ codes, const float* __restrict__ meta, size_t e0,
+                                         size_t c, int lane, long remain)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    const size_t e0 = row * kRow;
-    if (e0 >= n) return;
-    const size_t c = e0 / chunk;
-    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
-
-    f4 p = load_row(param + e0, lane, remain, 0.0f);
-    f4 m = f4{0.f, 0.f, 0.f, 0.f};
-    if (MOM) m = load_row(mbuf + e0, lane, remain, 0.0f);
-
     f4 g;
     if (CODEC == BAGUA_CODEC_MINMAX_U8) {
         const float mn = meta[2 * c], step = minmax_step(mn, meta[2 * c + 1]);
@@ -44,6 +32,27 @@ k_decompress_sgd(const void* __restrict__ codes, const float* __restrict__ meta,
         g.z = (nib & 4u) ? sc : neg;
         g.w = (nib & 8u) ? sc : neg;
     }
+    return g;
+}
+
+// One wave per 256-element row, four rows per workgroup.
+template <int CODEC, bool MOM, bool WD>
+__global__ void __launch_bounds__(256)
+k_decompress_sgd(const void* __restrict__ codes, const float* __restrict__ meta, size_t n, uint32_t chunk,
+                 float* __restrict__ param, float* __restrict__ mbuf, float lr, float mu, float wd)
+{
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const size_t e0 = row * kRow;
+    if (e0 >= n) return;
+    const size_t c = e0 / chunk;
+    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+
+    f4 p = load_row(param + e0, lane, remain, 0.0f);
+    f4 m = f4{0.f, 0.f, 0.f, 0.f};
+    if (MOM) m = load_row(mbuf + e0, lane, remain, 0.0f);
+
+    f4 g = decode_row<CODEC>(codes, meta, e0, c, lane, remain);
     if (WD) {
         g.x = g.x + wd * p.x;
         g.y = g.y + wd * p.y;
@@ -58,6 +67,56 @@ k_decompress_sgd(const void* __restrict__ codes, const float* __restrict__ meta,
         m.w = mu * m.w + g.w;
         store_row(mbuf + e0, lane, remain, m);
         u = m;
+    }
+    p.x = p.x - lr * u.x;
+    p.y = p.y - lr * u.y;
+    p.z = p.z - lr * u.z;
+    p.w = p.w - lr * u.w;
+    store_row(param + e0, lane, remain, p);
+}
+
+// Adam-type update (no bias correction).  FROZEN: the decoded tensor is the averaged momentum of the
+// compression stage of 1-bit Adam: it replaces m, and v is only read.
+template <int CODEC, bool FROZEN, bool WD>
+__global__ void __launch_bounds__(256)
+k_decompress_adam(const void* __restrict__ codes, const float* __restrict__ meta, size_t n, uint32_t chunk,
+                  float* __restrict__ param, float* __restrict__ mbuf, float* __restrict__ vbuf, float lr, float beta1,
+                  float omb1, float beta2, float omb2, float eps, float wd)
+{
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const size_t e0 = row * kRow;
+    if (e0 >= n) return;
+    const size_t c = e0 / chunk;
+    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+
+    f4 p = load_row(param + e0, lane, remain, 0.0f);
+    f4 v = load_row(vbuf + e0, lane, remain, 1.0f);
+    const f4 d = decode_row<CODEC>(codes, meta, e0, c, lane, remain);
+    f4 m = d;
+    if (!FROZEN) {
+        const f4 mo = load_row(mbuf + e0, lane, remain, 0.0f);
+        m.x = beta1 * mo.x + omb1 * d.x;
+        m.y = beta1 * mo.y + omb1 * d.y;
+        m.z = beta1 * mo.z + omb1 * d.z;
+        m.w = beta1 * mo.w + omb1 * d.w;
+        v.x = beta2 * v.x + omb2 * (d.x * d.x);
+        v.y = beta2 * v.y + omb2 * (d.y * d.y);
+        v.z = beta2 * v.z + omb2 * (d.z * d.z);
+        v.w = beta2 * v.w + omb2 * (d.w * d.w);
+        store_row(vbuf + e0, lane, remain, v);
+    }
+    store_row(mbuf + e0, lane, remain, m);
+    f4 u;
+    u.x = m.x / (sqrtf(v.x) + eps);
+    u.y = m.y / (sqrtf(v.y) + eps);
+    u.z = m.z / (sqrtf(v.z) + eps);
+    u.w = m.w / (sqrtf(v.w) + eps);
+    if (WD) {
+        u.x = u.x + wd * p.x;
+        u.y = u.y + wd * p.y;
+        u.z = u.z + wd * p.z;
+        u.w = u.w + wd * p.w;
     }
     p.x = p.x - lr * u.x;
     p.y = p.y - lr * u.y;
@@ -96,5 +155,39 @@ extern "C" int bagua_decompress_sgd_step(int codec, const void* codes, const flo
     else { BAGUA_SGD_CODEC(BAGUA_CODEC_SIGN1) }
 #undef BAGUA_SGD_CODEC
 #undef BAGUA_SGD
+    return launch_status();
+}
+
+extern "C" int bagua_decompress_adam_step(int codec, const void* codes, const float* meta, size_t n, size_t chunk,
+                                          float* param, float* m, float* v, float lr, float beta1, float beta2,
+                                          float eps, float weight_decay, int variance_frozen, void* stream)
+{
+    if (codec != BAGUA_CODEC_MINMAX_U8 && codec != BAGUA_CODEC_SIGN1) return BAGUA_ERR_INVALID_ARG;
+    if (!codes || !meta || !param || !m || !v || n == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
+    const size_t bytes = n * sizeof(float);
+    if (ranges_overlap(param, bytes, m, bytes) || ranges_overlap(param, bytes, v, bytes) ||
+        ranges_overlap(m, bytes, v, bytes))
+        return BAGUA_ERR_INVALID_ARG;
+    const size_t rows = (n + kRow - 1) / kRow;
+    if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (!aligned16(codes) || !aligned16(meta) || !aligned16(param) || !aligned16(m) || !aligned16(v))
+        return BAGUA_ERR_ALIGNMENT;
+    dim3 grid(static_cast<unsigned>((rows + 3) / 4)), block(256);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint32_t ch = static_cast<uint32_t>(chunk);
+    const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
+    const bool frozen = variance_frozen != 0, wd = weight_decay != 0.0f;
+#define BAGUA_ADAM(CODEC, FRv, WDv)                                                                            \
+    hipLaunchKernelGGL((k_decompress_adam<CODEC, FRv, WDv>), grid, block, 0, s, codes, meta, n, ch, param, m, \
+                       v, lr, beta1, omb1, beta2, omb2, eps, weight_decay)
+#define BAGUA_ADAM_CODEC(CODEC)                        \
+    if (frozen && wd) BAGUA_ADAM(CODEC, true, true);   \
+    else if (frozen) BAGUA_ADAM(CODEC, true, false);   \
+    else if (wd) BAGUA_ADAM(CODEC, false, true);       \
+    else BAGUA_ADAM(CODEC, false, false);
+    if (codec == BAGUA_CODEC_MINMAX_U8) { BAGUA_ADAM_CODEC(BAGUA_CODEC_MINMAX_U8) }
+    else { BAGUA_ADAM_CODEC(BAGUA_CODEC_SIGN1) }
+#undef BAGUA_ADAM_CODEC
+#undef BAGUA_ADAM
     return launch_status();
 }

@@ -103,10 +103,13 @@ __device__ __forceinline__ void sign_encode_chunk(f4 (&v)[RPW], long len, uint32
 }
 
 // ------------------------------------------------------------------------------------------
-template <int RPW, bool EF>
+// MOM: the compressed tensor is the local momentum beta1*m + omb1*x of the compression stage of
+// 1-bit Adam (x is then the gradient; m is read only).
+template <int RPW, bool EF, bool MOM = false>
 __global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
 k_sign_compress(const float* __restrict__ x, float* __restrict__ residual, size_t n, uint32_t chunk,
-                uint32_t* __restrict__ bits, float* __restrict__ scale)
+                uint32_t* __restrict__ bits, float* __restrict__ scale, const float* __restrict__ mom, float beta1,
+                float omb1)
 {
     extern __shared__ float s_q[];
     const size_t c = blockIdx.x;
@@ -121,6 +124,20 @@ k_sign_compress(const float* __restrict__ x, float* __restrict__ residual, size_
         const long remain = len - off;
         v[i] = f4{0.f, 0.f, 0.f, 0.f};
         if (remain > 0) v[i] = load_row(x + base + off, lane, remain, 0.0f);
+    }
+    if (MOM) {
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const long off = static_cast<long>(wave * RPW + i) * kRow;
+            const long remain = len - off;
+            if (remain > 0) {
+                const f4 m = load_row(mom + base + off, lane, remain, 0.0f);
+                v[i].x = beta1 * m.x + omb1 * v[i].x;
+                v[i].y = beta1 * m.y + omb1 * v[i].y;
+                v[i].z = beta1 * m.z + omb1 * v[i].z;
+                v[i].w = beta1 * m.w + omb1 * v[i].w;
+            }
+        }
     }
     if (EF) {
 #pragma unroll
@@ -277,10 +294,10 @@ int launch_sign_compress(const float* x, float* residual, size_t n, size_t chunk
     const uint32_t ch = static_cast<uint32_t>(chunk);
     if (residual) {
         BAGUA_DISPATCH_RPW(g.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, true>), g.grid, g.block, g.lds, stream, x,
-                                                     residual, n, ch, bits, scale))
+                                                     residual, n, ch, bits, scale, nullptr, 0.0f, 0.0f))
     } else {
         BAGUA_DISPATCH_RPW(g.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, false>), g.grid, g.block, g.lds, stream, x,
-                                                     residual, n, ch, bits, scale))
+                                                     residual, n, ch, bits, scale, nullptr, 0.0f, 0.0f))
     }
     return launch_status();
 }
@@ -327,4 +344,28 @@ extern "C" int bagua_sign_compress_ef(const float* x, float* residual, size_t n,
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(residual) || !aligned16(bits) || !aligned16(scale)) return BAGUA_ERR_ALIGNMENT;
     return launch_sign_compress(x, residual, n, chunk, bits, scale, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int bagua_momentum_sign_compress_ef(const float* g, const float* m, float beta1, float* residual, size_t n,
+                                               size_t chunk, uint32_t* bits, float* scale, void* stream)
+{
+    if (!g || !m || !bits || !scale || n == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
+    if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    const size_t bytes = n * sizeof(float);
+    if (residual && (ranges_overlap(residual, bytes, g, bytes) || ranges_overlap(residual, bytes, m, bytes)))
+        return BAGUA_ERR_INVALID_ARG;
+    if (!aligned16(g) || !aligned16(m) || !aligned16(residual) || !aligned16(bits) || !aligned16(scale))
+        return BAGUA_ERR_ALIGNMENT;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const SignGeometry geo = sign_geometry(n, chunk, BAGUA_RPW_SIGN);
+    const uint32_t ch = static_cast<uint32_t>(chunk);
+    const float omb1 = 1.0f - beta1;
+    if (residual) {
+        BAGUA_DISPATCH_RPW(geo.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, true, true>), geo.grid, geo.block, geo.lds,
+                                                       s, g, residual, n, ch, bits, scale, m, beta1, omb1))
+    } else {
+        BAGUA_DISPATCH_RPW(geo.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, false, true>), geo.grid, geo.block, geo.lds,
+                                                       s, g, residual, n, ch, bits, scale, m, beta1, omb1))
+    }
+    return launch_status();
 }

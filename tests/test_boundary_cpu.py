@@ -104,6 +104,17 @@ def test_peer_validation_without_gpu(bg):
     assert lib.bagua_decompress_sgd_step(0, 0x1000, 0x1000, 16, 256, 0x2000, 0x2000, 0.1, 0.9, 0.0, None) == 1  # param aliases momentum
     assert lib.bagua_decompress_sgd_step(3, 0x1000, 0x1000, 16, 256, 0x2000, None, 0.1, 0.9, 0.0, None) == 1
     assert lib.bagua_flatten_compress_minmax_u8(None, 1, None, 16, 256, 0x1000, 0x1000, None, None) == 1
+    adam = lib.bagua_decompress_adam_step
+    assert adam(0, 0x1000, 0x1000, 16, 256, 0x2000, 0x2000, 0x4000, 0.1, 0.9, 0.999, 1e-8, 0.0, 0, None) == 1  # m aliases param
+    assert adam(0, 0x1000, 0x1000, 16, 256, 0x2000, 0x3000, 0x3020, 0.1, 0.9, 0.999, 1e-8, 0.0, 0, None) == 1  # v overlaps m
+    assert adam(0, 0x1000, 0x1000, 16, 256, 0x2000, 0x3000, None, 0.1, 0.9, 0.999, 1e-8, 0.0, 1, None) == 1
+    assert adam(2, 0x1000, 0x1000, 16, 256, 0x2000, 0x3000, 0x4000, 0.1, 0.9, 0.999, 1e-8, 0.0, 0, None) == 1
+    assert adam(0, 0x1000, 0x1000, 16, 256, 0x2004, 0x3000, 0x4000, 0.1, 0.9, 0.999, 1e-8, 0.0, 0, None) == 2
+    ms = lib.bagua_momentum_sign_compress_ef
+    assert ms(0x1000, None, 0.9, None, 16, 256, 0x5000, 0x6000, None) == 1
+    assert ms(0x1000, 0x2000, 0.9, 0x1000, 16, 256, 0x5000, 0x6000, None) == 1      # residual aliases g
+    assert ms(0x1000, 0x2000, 0.9, 0x3000, 16, 100, 0x5000, 0x6000, None) == 1
+    assert ms(0x1000, 0x2008, 0.9, 0x3000, 16, 256, 0x5000, 0x6000, None) == 2
 
 
 def test_header_is_valid_c_and_cpp(tmp_path):

@@ -1,0 +1,119 @@
+"""GPU parity of the decode + Adam-type bucket step and of the momentum sign compression against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def bg():
+    import paper_2107_01499_amd as b
+    assert torch.cuda.is_available()
+    return b
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def bit_equal(t, a, what):
+    got = t.cpu().numpy()
+    err = np.abs(got.astype(np.float64) - a.astype(np.float64))
+    assert np.all(err <= 1e-6 * np.abs(a.astype(np.float64)) + 1e-7), what
+    assert np.array_equal(got.view(np.uint32), a.view(np.uint32)), what
+
+
+@pytest.mark.parametrize("codec", [0, 1])
+@pytest.mark.parametrize("n,C", [(1, 256), (257, 256), (3 * 4096 + 77, 4096), (70001, 2048), (40000, 16384)])
+@pytest.mark.parametrize("frozen,wd", [(False, 0.0), (True, 0.0), (False, 1e-2), (True, 1e-2)])
+def test_decompress_adam_step(bg, oracle, codec, n, C, frozen, wd):
+    print("adam codec=%d n=%d C=%d frozen=%s wd=%g" % (codec, n, C, frozen, wd), flush=True)
+    r = np.random.default_rng(n + C + codec)
+    p_o = r.standard_normal(n).astype(np.float32)
+    m_o = (r.standard_normal(n) * 1e-3).astype(np.float32)
+    v_o = (r.random(n) * 1e-5).astype(np.float32)
+    v_o[::7] = 0.0                       # a zero variance: the update is m / eps there
+    p_g, m_g, v_g = dev(p_o), dev(m_o), dev(v_o)
+    for it in range(3):                  # state carried across steps on both sides, fresh codes every step
+        x = (r.standard_t(3, n) * 1e-3).astype(np.float32)
+        if codec == 0:
+            codes, meta = oracle.compress_minmax_u8(x, None, C)
+            cg = dev(codes)
+        else:
+            codes, meta = oracle.sign_compress_ef(x, None, C)
+            cg = dev(codes.view(np.int32))
+        oracle.decompress_adam_step(codec, codes, meta, n, C, p_o, m_o, v_o, 1e-3, 0.9, 0.999, 1e-8, wd, frozen)
+        bg.bagua_decompress_adam_step(codec, cg, dev(meta), n, C, p_g, m_g, v_g, 1e-3, 0.9, 0.999, 1e-8, wd, frozen)
+        torch.cuda.synchronize()
+        bit_equal(p_g, p_o, "param step %d" % it)
+        bit_equal(m_g, m_o, "m step %d" % it)
+        bit_equal(v_g, v_o, "v step %d" % it)
+
+
+@pytest.mark.parametrize("n,C", [(1, 256), (255, 256), (4096 * 3 + 1027, 4096), (70001, 2048), (70001, 1024),
+                                 (16384 * 2 + 5, 16384), (100000, 8192)])
+@pytest.mark.parametrize("ef", [True, False])
+@pytest.mark.parametrize("beta", [0.9, 0.0, 1.0])
+def test_momentum_sign_compress(bg, oracle, n, C, ef, beta):
+    print("momentum_sign n=%d C=%d ef=%s beta=%g" % (n, C, ef, beta), flush=True)
+    r = np.random.default_rng(n + C)
+    m = (r.laplace(0, 1e-3, n)).astype(np.float32)
+    res_o = (r.standard_normal(n) * 1e-4).astype(np.float32) if ef else None
+    res_g = dev(res_o) if ef else None
+    nc = (n + C - 1) // C
+    m_g = dev(m)
+    for it in range(2):
+        g = (r.laplace(0, 1e-3, n)).astype(np.float32)
+        bits_o, scale_o = oracle.momentum_sign_compress_ef(g, m, beta, res_o, C)
+        g_g = dev(g)
+        bits_g = torch.full(((n + 31) // 32,), 0x5a5a5a5a, dtype=torch.int32, device="cuda")
+        scale_g = torch.full((nc,), float("nan"), device="cuda")
+        bg.bagua_momentum_sign_compress_ef(g_g, m_g, beta, res_g, C, bits_g, scale_g)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits_g.cpu().numpy().view(np.uint32), bits_o), "bits step %d" % it
+        assert np.array_equal(scale_g.cpu().numpy().view(np.uint32), scale_o.view(np.uint32)), "scale step %d" % it
+        if ef:
+            bit_equal(res_g, res_o, "residual step %d" % it)
+        assert np.array_equal(g_g.cpu().numpy(), g) and np.array_equal(m_g.cpu().numpy(), m)
+
+
+def test_one_bit_adam_iteration_end_to_end(bg, oracle):
+    """One compression-stage iteration of 1-bit Adam over k workers through the library (momentum compress ->
+    server step -> decode + frozen-variance update) equals the same chain in the oracle, bit for bit."""
+    k, n, C = 4, 5 * 2048 + 300, 2048
+    r = np.random.default_rng(11)
+    m = (r.standard_normal(n) * 1e-3).astype(np.float32)
+    v = (r.random(n) * 1e-6 + 1e-8).astype(np.float32)
+    p = r.standard_normal(n).astype(np.float32)
+    gs = [(r.standard_normal(n) * 1e-3).astype(np.float32) for _ in range(k)]
+    delta = [np.zeros(n, np.float32) for _ in range(k)]
+    eps = np.zeros(n, np.float32)
+    nc = (n + C - 1) // C
+    # GPU
+    m_g, v_g = dev(m), dev(v)
+    p_g = [dev(p) for _ in range(k)]
+    mm_g = [dev(m) for _ in range(k)]
+    delta_g = [dev(d) for d in delta]
+    eps_g = dev(eps)
+    bits_g = [torch.zeros((n + 31) // 32, dtype=torch.int32, device="cuda") for _ in range(k)]
+    sc_g = [torch.zeros(nc, device="cuda") for _ in range(k)]
+    bo, so = torch.zeros((n + 31) // 32, dtype=torch.int32, device="cuda"), torch.zeros(nc, device="cuda")
+    for j in range(k):
+        bg.bagua_momentum_sign_compress_ef(dev(gs[j]), m_g, 0.9, delta_g[j], C, bits_g[j], sc_g[j])
+    bg.bagua_decompress_reduce_recompress(bg.CODEC_SIGN1, bits_g, sc_g, eps_g, n, C, bo, so, None)
+    for j in range(k):
+        bg.bagua_decompress_adam_step(bg.CODEC_SIGN1, bo, so, n, C, p_g[j], mm_g[j], v_g, 1e-3, 0.9, 0.999, 1e-8, 0.0, True)
+    torch.cuda.synchronize()
+    # oracle
+    packed = [oracle.momentum_sign_compress_ef(gs[j], m, 0.9, delta[j], C) for j in range(k)]
+    bits_out, scale_out, _ = oracle.drr_sign([b for b, _ in packed], [s for _, s in packed], eps, n, C)
+    p_o, m_o, v_o = p.copy(), m.copy(), v.copy()
+    oracle.decompress_adam_step(1, bits_out, scale_out, n, C, p_o, m_o, v_o, 1e-3, 0.9, 0.999, 1e-8, 0.0, True)
+    assert np.array_equal(bo.cpu().numpy().view(np.uint32), bits_out)
+    for j in range(k):
+        bit_equal(p_g[j], p_o, "param worker %d" % j)
+        bit_equal(mm_g[j], m_o, "m worker %d" % j)
+        bit_equal(delta_g[j], delta[j], "delta worker %d" % j)
+    bit_equal(eps_g, eps, "eps")
+    bit_equal(v_g, v, "v untouched")
