@@ -280,7 +280,7 @@ class Workload:
         return {"flatten": "k_flatten", "flatten_compress": "k_flatten_compress_minmax<2,true,%s>" %
                 ("true" if "sign_compress" in self.prims else "false"), "compress_minmax": "k_compress_minmax<2,true>",
                 "drr_minmax": "k_drr_minmax<4,true,true>", "ring_fp": "k_ring_avg_fp<%d>" % self.k,
-                "ring_lp": "k_ring_avg_lp<%d,2>" % self.k, "sign_compress": "k_sign_compress<2,true>",
+                "ring_lp": "k_ring_avg_lp<%d,2>" % self.k, "sign_compress": "k_sign_compress<2,true,false>",
                 "drr_sign": "k_drr_sign<4,true,true>", "sgd_step": "k_decompress_sgd<0,true,false>",
                 "adam_step": "k_decompress_adam<0,false,false>", "momentum_sign": "k_sign_compress<2,true,true>",
                 "adam_frozen_step": "k_decompress_adam<1,true,false>",
