@@ -400,7 +400,8 @@ class Workload:
 
 def cpu_baseline(wl, torch):
     """The oracle, as it stands, on the host cores: one step of the default workload (every bucket, all workers,
-    the same primitives), timed once.  Returns the dict for the JSON line."""
+    the same primitives), timed once.  Returns the cpu_baseline dict for the JSON line and, from the one-core leg's
+    outputs, the parity report of the HIP path on the same bucket."""
     import numpy as np
     import oracle
     threads = max(1, min(16, oracle.max_threads(), os.cpu_count() or 1))
@@ -428,20 +429,73 @@ def cpu_baseline(wl, torch):
     oracle.set_threads(1)
     bk = wl.buckets[-1]
     n1, lo = bk.n_pad, wl.bases[len(wl.buckets) - 1]
-    flats = [torch.cat(wl.bucket[j])[lo:lo + n1].cpu().numpy() for j in range(k)]
+    flats_g = [torch.cat(wl.bucket[j])[lo:lo + n1].contiguous() for j in range(k)]
+    flats = [f.cpu().numpy() for f in flats_g]
+    d_o = [np.zeros(n1, np.float32) for _ in range(k)]
+    sd_o = [np.zeros(n1, np.float32) for _ in range(k)]
+    eps_o, seps_o = np.zeros(n1, np.float32), np.zeros(n1, np.float32)
     t0 = time.perf_counter()
-    enc = [oracle.compress_minmax_u8(flats[j], np.zeros(n1, np.float32), C) for j in range(k)]
-    oracle.drr_minmax_u8([e[0] for e in enc], [e[1] for e in enc], np.zeros(n1, np.float32), C)
-    senc = [oracle.sign_compress_ef(flats[j], np.zeros(n1, np.float32), SC) for j in range(k)]
-    oracle.drr_sign([e[0] for e in senc], [e[1] for e in senc], np.zeros(n1, np.float32), n1, SC)
+    enc = [oracle.compress_minmax_u8(flats[j], d_o[j], C) for j in range(k)]
+    drr = oracle.drr_minmax_u8([e[0] for e in enc], [e[1] for e in enc], eps_o, C)
+    senc = [oracle.sign_compress_ef(flats[j], sd_o[j], SC) for j in range(k)]
+    sdrr = oracle.drr_sign([e[0] for e in senc], [e[1] for e in senc], seps_o, n1, SC)
     dt1 = time.perf_counter() - t0
+    parity = parity_sample(torch, wl.bg, flats_g, C, SC, enc, d_o, drr, eps_o, senc, sd_o, sdrr, seps_o)
     oracle.set_threads(threads)
     return {"value": round(grad_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": "one full step of the same workload (%d elements x %d workers, all seven primitives), "
                       "%.1f s wall on %d threads" % (wl.n_elems, k, dt, threads),
             "one_core_value": round(4.0 * n1 * k * 4 / dt1 / 1e9, 3),
             "one_core_sample": "compress_minmax, drr_minmax, sign_compress, drr_sign on the last bucket "
-                               "(%d elements x %d workers), %.1f s on 1 thread" % (n1, k, dt1)}
+                               "(%d elements x %d workers), %.1f s on 1 thread" % (n1, k, dt1)}, parity
+
+
+def parity_sample(torch, bg, xs, C, SC, enc, d_o, drr, eps_o, senc, sd_o, sdrr, seps_o):
+    """The HIP path on the buckets the one-core oracle leg just processed (same bits, zero initial error state),
+    compared word for word with the oracle's outputs.  Integer outputs must be equal; fp32 outputs are counted twice:
+    words that are not bit-identical, and words outside 1e-6 relative + 1e-7 absolute."""
+    import numpy as np
+    k, n = len(xs), xs[0].numel()
+    dev = xs[0].device
+    nc, ncs = (n + C - 1) // C, (n + SC - 1) // SC
+    f32 = dict(dtype=torch.float32, device=dev)
+    cnt = {"int_words": 0, "int_mismatch": 0, "fp32_words": 0, "fp32_not_bit_exact": 0, "fp32_out_of_tolerance": 0}
+
+    def ints(t, ref):
+        a = t.cpu().numpy().view(ref.dtype).reshape(-1)
+        cnt["int_words"] += a.size
+        cnt["int_mismatch"] += int(np.count_nonzero(a != ref.reshape(-1)))
+
+    def floats(t, ref):
+        a = t.cpu().numpy()
+        cnt["fp32_words"] += a.size
+        cnt["fp32_not_bit_exact"] += int(np.count_nonzero(a.view(np.uint32) != ref.view(np.uint32)))
+        err = np.abs(a.astype(np.float64) - ref.astype(np.float64))
+        cnt["fp32_out_of_tolerance"] += int(np.count_nonzero(~(err <= 1e-6 * np.abs(ref.astype(np.float64)) + 1e-7)))
+
+    codes = [torch.empty(n, dtype=torch.uint8, device=dev) for _ in range(k)]
+    mm = [torch.empty(2 * nc, **f32) for _ in range(k)]
+    delta = [torch.zeros(n, **f32) for _ in range(k)]
+    bits = [torch.empty((n + 31) // 32, dtype=torch.int32, device=dev) for _ in range(k)]
+    scale = [torch.empty(ncs, **f32) for _ in range(k)]
+    sdelta = [torch.zeros(n, **f32) for _ in range(k)]
+    for j in range(k):
+        bg.bagua_compress_minmax_u8(xs[j], delta[j], C, codes[j], mm[j])
+        bg.bagua_sign_compress_ef(xs[j], sdelta[j], SC, bits[j], scale[j])
+    eps, seps = torch.zeros(n, **f32), torch.zeros(n, **f32)
+    c2, m2, o2 = torch.empty(n, dtype=torch.uint8, device=dev), torch.empty(2 * nc, **f32), torch.empty(n, **f32)
+    b2, s2, so2 = torch.empty((n + 31) // 32, dtype=torch.int32, device=dev), torch.empty(ncs, **f32), torch.empty(n, **f32)
+    bg.bagua_decompress_reduce_recompress(bg.CODEC_MINMAX_U8, codes, mm, eps, n, C, c2, m2, o2)
+    bg.bagua_decompress_reduce_recompress(bg.CODEC_SIGN1, bits, scale, seps, n, SC, b2, s2, so2)
+    torch.cuda.synchronize()
+    for j in range(k):
+        ints(codes[j], enc[j][0]); floats(mm[j], enc[j][1]); floats(delta[j], d_o[j])
+        ints(bits[j], senc[j][0]); floats(scale[j], senc[j][1]); floats(sdelta[j], sd_o[j])
+    ints(c2, drr[0]); floats(m2, drr[1]); floats(o2, drr[2]); floats(eps, eps_o)
+    ints(b2, sdrr[0]); floats(s2, sdrr[1]); floats(so2, sdrr[2]); floats(seps, seps_o)
+    cnt["sample"] = ("compress_minmax, drr_minmax, sign_compress, drr_sign on the last bucket (%d elements x %d workers), "
+                     "HIP path against the oracle" % (n, k))
+    return cnt
 
 
 def copy_ceiling(torch, bg):
@@ -550,7 +604,7 @@ def main():
                      "avg_launch_us": round(dom_t * 1e6, 3), "algorithmic_bytes_per_launch": ab[dom] / nl[dom]},
     }
     if not args.no_cpu_baseline and args.workload == "resnet50" and only is None and not args.fused_flatten and not args.extras:
-        result["cpu_baseline"] = cpu_baseline(wl, torch)
+        result["cpu_baseline"], result["parity"] = cpu_baseline(wl, torch)
     print(json.dumps(result))
 
 
