@@ -92,25 +92,39 @@ def _stream(stream):
     return ctypes.c_void_p(stream.cuda_stream)
 
 
-def _ptr(t, dtype=None):
+def _ptr(t, dtype=None, nbytes=None):
+    """Device pointer of a tensor (None passes through).  nbytes: the number of bytes the entry point will read or
+    write through this pointer; a smaller tensor is refused here, because the C side sees only the pointer."""
     if t is None:
         return None
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError("expected a contiguous GPU tensor")
     if dtype is not None and t.dtype != dtype:
         raise ValueError("expected dtype %s, got %s" % (dtype, t.dtype))
+    if nbytes is not None and t.numel() * t.element_size() < nbytes:
+        raise ValueError("tensor of %d bytes is too small: the call needs %d bytes" % (t.numel() * t.element_size(), nbytes))
     return ctypes.c_void_p(t.data_ptr())
 
 
-def _ptr_array(tensors, dtype=None):
+def _ptr_array(tensors, dtype=None, nbytes=None):
     arr = (ctypes.c_void_p * len(tensors))()
     for i, t in enumerate(tensors):
-        arr[i] = None if t is None else _ptr(t, dtype).value
+        arr[i] = None if t is None else _ptr(t, dtype, nbytes).value
     return arr
 
 
 def num_chunks(n, chunk):
-    return (n + chunk - 1) // chunk
+    return (n + chunk - 1) // chunk if chunk > 0 else 0
+
+
+def _code_bytes(codec, n):
+    """Bytes of the code stream of n elements: one byte each (MinMax-u8) or one bit each in 32-bit words (sign)."""
+    return n if codec == CODEC_MINMAX_U8 else 4 * ((n + 31) // 32)
+
+
+def _meta_bytes(codec, n, chunk):
+    """Bytes of the per-chunk metadata: (min, max) pairs (MinMax-u8) or one scale (sign)."""
+    return 4 * num_chunks(n, chunk) * (2 if codec == CODEC_MINMAX_U8 else 1)
 
 
 def bagua_flatten_workspace_bytes(T, bucket_numel):
@@ -159,109 +173,127 @@ def bagua_bucket_flatten(srcs, dst_offset, bucket, workspace, stream=None):
 
 def bagua_compress_minmax_u8(x, residual, chunk, codes, minmax, stream=None):
     _check("bagua_compress_minmax_u8", _lib.bagua_compress_minmax_u8(
-        _ptr(x, torch.float32), _ptr(residual, torch.float32), x.numel(), chunk, _ptr(codes, torch.uint8),
-        _ptr(minmax, torch.float32), _stream(stream)))
+        _ptr(x, torch.float32), _ptr(residual, torch.float32, 4 * x.numel()), x.numel(), chunk,
+        _ptr(codes, torch.uint8, x.numel()), _ptr(minmax, torch.float32, 8 * num_chunks(x.numel(), chunk)),
+        _stream(stream)))
 
 
 def bagua_flatten_compress_minmax_u8(workspace, T, residual, n, chunk, codes, minmax, bucket_out=None, stream=None):
     _check("bagua_flatten_compress_minmax_u8", _lib.bagua_flatten_compress_minmax_u8(
-        _ptr(workspace), T, _ptr(residual, torch.float32), n, chunk, _ptr(codes, torch.uint8),
-        _ptr(minmax, torch.float32), _ptr(bucket_out, torch.float32), _stream(stream)))
+        _ptr(workspace), T, _ptr(residual, torch.float32, 4 * n), n, chunk, _ptr(codes, torch.uint8, n),
+        _ptr(minmax, torch.float32, 8 * num_chunks(n, chunk)), _ptr(bucket_out, torch.float32, 4 * n), _stream(stream)))
 
 
 def bagua_decompress_reduce_recompress(codec, codes_in, meta_in, server_residual, n, chunk, codes_out, meta_out,
                                        out_fp32=None, stream=None):
     k = len(codes_in)
     _check("bagua_decompress_reduce_recompress", _lib.bagua_decompress_reduce_recompress(
-        codec, _ptr_array(codes_in), _ptr_array(meta_in, torch.float32), k, _ptr(server_residual, torch.float32),
-        n, chunk, _ptr(codes_out), _ptr(meta_out, torch.float32), _ptr(out_fp32, torch.float32), _stream(stream)))
+        codec, _ptr_array(codes_in, None, _code_bytes(codec, n)),
+        _ptr_array(meta_in, torch.float32, _meta_bytes(codec, n, chunk)), k, _ptr(server_residual, torch.float32, 4 * n),
+        n, chunk, _ptr(codes_out, None, _code_bytes(codec, n)), _ptr(meta_out, torch.float32, _meta_bytes(codec, n, chunk)),
+        _ptr(out_fp32, torch.float32, 4 * n), _stream(stream)))
 
 
 def bagua_decentralized_avg(mode, x_in, x_out, xhat=None, codes=None, minmax=None, chunk=0, stream=None):
     k = len(x_in)
     n = x_in[0].numel()
     _check("bagua_decentralized_avg", _lib.bagua_decentralized_avg(
-        mode, _ptr_array(x_in, torch.float32), _ptr_array(x_out, torch.float32),
-        None if xhat is None else _ptr_array(xhat, torch.float32),
-        None if codes is None else _ptr_array(codes, torch.uint8),
-        None if minmax is None else _ptr_array(minmax, torch.float32), k, n, chunk, _stream(stream)))
+        mode, _ptr_array(x_in, torch.float32, 4 * n), _ptr_array(x_out, torch.float32, 4 * n),
+        None if xhat is None else _ptr_array(xhat, torch.float32, 4 * n),
+        None if codes is None else _ptr_array(codes, torch.uint8, n),
+        None if minmax is None else _ptr_array(minmax, torch.float32, 8 * num_chunks(n, chunk)), k, n, chunk,
+        _stream(stream)))
 
 
 def bagua_reduce_compress_minmax_u8(xs, residual, chunk, codes, minmax, stream=None):
+    n = xs[0].numel()
     _check("bagua_reduce_compress_minmax_u8", _lib.bagua_reduce_compress_minmax_u8(
-        _ptr_array(xs, torch.float32), len(xs), _ptr(residual, torch.float32), xs[0].numel(), chunk,
-        _ptr(codes, torch.uint8), _ptr(minmax, torch.float32), _stream(stream)))
+        _ptr_array(xs, torch.float32, 4 * n), len(xs), _ptr(residual, torch.float32, 4 * n), n, chunk,
+        _ptr(codes, torch.uint8, n), _ptr(minmax, torch.float32, 8 * num_chunks(n, chunk)), _stream(stream)))
 
 
 def bagua_centralized_avg_fp(xs, out, stream=None):
-    _check("bagua_centralized_avg_fp", _lib.bagua_centralized_avg_fp(_ptr_array(xs, torch.float32), len(xs), xs[0].numel(),
-                                                                     _ptr(out, torch.float32), _stream(stream)))
+    n = xs[0].numel()
+    _check("bagua_centralized_avg_fp", _lib.bagua_centralized_avg_fp(_ptr_array(xs, torch.float32, 4 * n), len(xs), n,
+                                                                     _ptr(out, torch.float32, 4 * n), _stream(stream)))
 
 
 def bagua_decentralized_avg_peers(x_in, x_out, peer, stream=None):
-    k = len(x_in)
+    k, n = len(x_in), x_in[0].numel()
+    if len(peer) != k:
+        raise ValueError("peer must name one peer per worker")
     pa = (ctypes.c_int * k)(*[int(p) for p in peer])
     _check("bagua_decentralized_avg_peers", _lib.bagua_decentralized_avg_peers(
-        _ptr_array(x_in, torch.float32), _ptr_array(x_out, torch.float32), pa, k, x_in[0].numel(), _stream(stream)))
+        _ptr_array(x_in, torch.float32, 4 * n), _ptr_array(x_out, torch.float32, 4 * n), pa, k, n, _stream(stream)))
 
 
 def bagua_decentralized_avg_peers_lp(x_in, x_out, xhat, codes, minmax, peer, chunk, stream=None):
-    k = len(x_in)
+    k, n = len(x_in), x_in[0].numel()
+    if len(peer) != k:
+        raise ValueError("peer must name one peer per worker")
     pa = (ctypes.c_int * k)(*[int(p) for p in peer])
     _check("bagua_decentralized_avg_peers_lp", _lib.bagua_decentralized_avg_peers_lp(
-        _ptr_array(x_in, torch.float32), _ptr_array(x_out, torch.float32), _ptr_array(xhat, torch.float32),
-        _ptr_array(codes, torch.uint8), _ptr_array(minmax, torch.float32), pa, k, x_in[0].numel(), chunk,
-        _stream(stream)))
+        _ptr_array(x_in, torch.float32, 4 * n), _ptr_array(x_out, torch.float32, 4 * n),
+        _ptr_array(xhat, torch.float32, 4 * n), _ptr_array(codes, torch.uint8, n),
+        _ptr_array(minmax, torch.float32, 8 * num_chunks(n, chunk)), pa, k, n, chunk, _stream(stream)))
 
 
 def bagua_decompress_adam_step(codec, codes, meta, n, chunk, param, m, v, lr, beta1=0.9, beta2=0.999, eps=1e-8,
                                weight_decay=0.0, variance_frozen=False, stream=None):
     _check("bagua_decompress_adam_step", _lib.bagua_decompress_adam_step(
-        codec, _ptr(codes), _ptr(meta, torch.float32), n, chunk, _ptr(param, torch.float32), _ptr(m, torch.float32),
-        _ptr(v, torch.float32), lr, beta1, beta2, eps, weight_decay, int(bool(variance_frozen)), _stream(stream)))
+        codec, _ptr(codes, None, _code_bytes(codec, n)), _ptr(meta, torch.float32, _meta_bytes(codec, n, chunk)), n, chunk,
+        _ptr(param, torch.float32, 4 * n), _ptr(m, torch.float32, 4 * n), _ptr(v, torch.float32, 4 * n), lr, beta1, beta2, eps, weight_decay, int(bool(variance_frozen)), _stream(stream)))
 
 
 def bagua_momentum_sign_compress_ef(g, m, beta1, residual, chunk, bits, scale, stream=None):
     _check("bagua_momentum_sign_compress_ef", _lib.bagua_momentum_sign_compress_ef(
-        _ptr(g, torch.float32), _ptr(m, torch.float32), beta1, _ptr(residual, torch.float32), g.numel(), chunk,
-        _ptr(bits, torch.int32), _ptr(scale, torch.float32), _stream(stream)))
+        _ptr(g, torch.float32), _ptr(m, torch.float32, 4 * g.numel()), beta1, _ptr(residual, torch.float32, 4 * g.numel()),
+        g.numel(), chunk, _ptr(bits, torch.int32, _code_bytes(CODEC_SIGN1, g.numel())),
+        _ptr(scale, torch.float32, _meta_bytes(CODEC_SIGN1, g.numel(), chunk)), _stream(stream)))
 
 
 def bagua_sign_compress_ef(x, residual, chunk, bits, scale, stream=None):
     _check("bagua_sign_compress_ef", _lib.bagua_sign_compress_ef(
-        _ptr(x, torch.float32), _ptr(residual, torch.float32), x.numel(), chunk, _ptr(bits, torch.int32),
-        _ptr(scale, torch.float32), _stream(stream)))
+        _ptr(x, torch.float32), _ptr(residual, torch.float32, 4 * x.numel()), x.numel(), chunk,
+        _ptr(bits, torch.int32, _code_bytes(CODEC_SIGN1, x.numel())),
+        _ptr(scale, torch.float32, _meta_bytes(CODEC_SIGN1, x.numel(), chunk)), _stream(stream)))
 
 
 def bagua_decompress(codec, codes, meta, n, chunk, out, stream=None):
-    _check("bagua_decompress", _lib.bagua_decompress(codec, _ptr(codes), _ptr(meta, torch.float32), n, chunk,
-                                                     _ptr(out, torch.float32), _stream(stream)))
+    _check("bagua_decompress", _lib.bagua_decompress(codec, _ptr(codes, None, _code_bytes(codec, n)),
+                                                     _ptr(meta, torch.float32, _meta_bytes(codec, n, chunk)), n, chunk,
+                                                     _ptr(out, torch.float32, 4 * n), _stream(stream)))
 
 
 def bagua_decompress_sgd_step(codec, codes, meta, n, chunk, param, momentum_buf, lr, momentum=0.0, weight_decay=0.0,
                               stream=None):
     _check("bagua_decompress_sgd_step", _lib.bagua_decompress_sgd_step(
-        codec, _ptr(codes), _ptr(meta, torch.float32), n, chunk, _ptr(param, torch.float32),
-        _ptr(momentum_buf, torch.float32), lr, momentum, weight_decay, _stream(stream)))
+        codec, _ptr(codes, None, _code_bytes(codec, n)), _ptr(meta, torch.float32, _meta_bytes(codec, n, chunk)), n, chunk,
+        _ptr(param, torch.float32, 4 * n), _ptr(momentum_buf, torch.float32, 4 * n), lr, momentum, weight_decay,
+        _stream(stream)))
 
 
 def bagua_compress_topk_ef(x, residual, chunk, keep, idx, val, stream=None):
     _check("bagua_compress_topk_ef", _lib.bagua_compress_topk_ef(
-        _ptr(x, torch.float32), _ptr(residual, torch.float32), x.numel(), chunk, keep, _ptr(idx, torch.int16),
-        _ptr(val, torch.float32), _stream(stream)))
+        _ptr(x, torch.float32), _ptr(residual, torch.float32, 4 * x.numel()), x.numel(), chunk, keep,
+        _ptr(idx, torch.int16, 2 * keep * num_chunks(x.numel(), chunk)),
+        _ptr(val, torch.float32, 4 * keep * num_chunks(x.numel(), chunk)), _stream(stream)))
 
 
 def bagua_decompress_reduce_recompress_topk(idx_in, val_in, keep, server_residual, n, chunk, idx_out, val_out,
                                             out_fp32=None, stream=None):
     _check("bagua_decompress_reduce_recompress_topk", _lib.bagua_decompress_reduce_recompress_topk(
-        _ptr_array(idx_in, torch.int16), _ptr_array(val_in, torch.float32), len(idx_in), keep,
-        _ptr(server_residual, torch.float32), n, chunk, _ptr(idx_out, torch.int16), _ptr(val_out, torch.float32),
-        _ptr(out_fp32, torch.float32), _stream(stream)))
+        _ptr_array(idx_in, torch.int16, 2 * keep * num_chunks(n, chunk)),
+        _ptr_array(val_in, torch.float32, 4 * keep * num_chunks(n, chunk)), len(idx_in), keep,
+        _ptr(server_residual, torch.float32, 4 * n), n, chunk, _ptr(idx_out, torch.int16, 2 * keep * num_chunks(n, chunk)),
+        _ptr(val_out, torch.float32, 4 * keep * num_chunks(n, chunk)), _ptr(out_fp32, torch.float32, 4 * n),
+        _stream(stream)))
 
 
 def bagua_decompress_topk(idx, val, n, chunk, keep, out, stream=None):
-    _check("bagua_decompress_topk", _lib.bagua_decompress_topk(_ptr(idx, torch.int16), _ptr(val, torch.float32), n, chunk,
-                                                               keep, _ptr(out, torch.float32), _stream(stream)))
+    _check("bagua_decompress_topk", _lib.bagua_decompress_topk(
+        _ptr(idx, torch.int16, 2 * keep * num_chunks(n, chunk)), _ptr(val, torch.float32, 4 * keep * num_chunks(n, chunk)),
+        n, chunk, keep, _ptr(out, torch.float32, 4 * n), _stream(stream)))
 
 
 def raw():

@@ -551,3 +551,27 @@ def test_unflatten_inverts_flatten(bg, oracle, aligned):
         covered += w.size
     assert int((arena != 777.0).sum().item()) <= covered          # nothing outside the tensors was written
     assert int((arena == 777.0).sum().item()) >= arena.numel() - covered
+
+
+def test_binding_refuses_undersized_buffers(bg):
+    """The C entry points see only pointers; the binding refuses tensors smaller than what the call reads or writes."""
+    n, C = 3 * 4096 + 5, 4096
+    x = torch.zeros(n, device="cuda")
+    ok_codes, ok_mm = torch.empty(n, dtype=torch.uint8, device="cuda"), torch.empty(2 * 4, device="cuda")
+    bg.bagua_compress_minmax_u8(x, None, C, ok_codes, ok_mm)
+    with pytest.raises(ValueError):
+        bg.bagua_compress_minmax_u8(x, None, C, ok_codes[:-1].clone(), ok_mm)
+    with pytest.raises(ValueError):
+        bg.bagua_compress_minmax_u8(x, None, C, ok_codes, ok_mm[:-1].clone())
+    with pytest.raises(ValueError):
+        bg.bagua_compress_minmax_u8(x, torch.zeros(n - 1, device="cuda"), C, ok_codes, ok_mm)
+    with pytest.raises(ValueError):
+        bg.bagua_sign_compress_ef(x, None, C, torch.empty((n + 31) // 32 - 1, dtype=torch.int32, device="cuda"),
+                                  torch.empty(4, device="cuda"))
+    with pytest.raises(ValueError):
+        bg.bagua_decompress(bg.CODEC_MINMAX_U8, ok_codes, ok_mm, n, C, torch.empty(n - 1, device="cuda"))
+    with pytest.raises(ValueError):
+        bg.bagua_decentralized_avg(bg.AVG_FP, [x, x.clone()], [torch.empty(n, device="cuda"), torch.empty(n - 1, device="cuda")])
+    with pytest.raises(ValueError):
+        bg.bagua_decentralized_avg_peers([x, x.clone()], [torch.empty_like(x), torch.empty_like(x)], [1])
+    torch.cuda.synchronize()
