@@ -16,6 +16,9 @@
  *     allocates no device memory and keeps no state between calls.
  *   - Bucket-level buffers (x, residual, codes, bits, minmax, scale, replicas, bucket) must be
  *     16-byte aligned (BAGUA_ERR_ALIGNMENT otherwise).
+ *   - Aliasing: a buffer that a call writes (outputs and in-out state) must not overlap, by byte
+ *     range, any other buffer passed to the same call (BAGUA_ERR_INVALID_ARG otherwise); buffers
+ *     that are only read may overlap each other.  Tensors named in a flatten plan are not checked.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
  *     work and return without synchronising unless stated otherwise.
  *   - n = number of fp32 elements of the bucket; chunk = C = elements per statistics chunk,

@@ -26,17 +26,19 @@ extern "C" int bagua_decompress_reduce_recompress(int codec, const void* const* 
     for (int j = 0; j < k; ++j) {
         if (!codes_in[j] || !meta_in[j]) return BAGUA_ERR_INVALID_ARG;
     }
-    // outputs must not overlap any input (byte ranges, not just equal base pointers)
     const size_t nc = num_chunks(n, chunk);
     const size_t code_bytes = codec == BAGUA_CODEC_MINMAX_U8 ? n : ((n + 31) / 32) * sizeof(uint32_t);
     const size_t meta_bytes = (codec == BAGUA_CODEC_MINMAX_U8 ? 2 * nc : nc) * sizeof(float);
+    RangeCheck rc;
     for (int j = 0; j < k; ++j) {
-        if (ranges_overlap(codes_in[j], code_bytes, codes_out, code_bytes) ||
-            ranges_overlap(meta_in[j], meta_bytes, meta_out, meta_bytes) ||
-            (out_fp32 && ranges_overlap(codes_in[j], code_bytes, out_fp32, n * sizeof(float))) ||
-            (server_residual && ranges_overlap(codes_in[j], code_bytes, server_residual, n * sizeof(float))))
-            return BAGUA_ERR_INVALID_ARG;
+        rc.reads(codes_in[j], code_bytes);
+        rc.reads(meta_in[j], meta_bytes);
     }
+    rc.writes(server_residual, n * sizeof(float));
+    rc.writes(codes_out, code_bytes);
+    rc.writes(meta_out, meta_bytes);
+    rc.writes(out_fp32, n * sizeof(float));
+    if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     for (int j = 0; j < k; ++j)
         if (!aligned16(codes_in[j]) || !aligned16(meta_in[j])) return BAGUA_ERR_ALIGNMENT;
@@ -55,6 +57,14 @@ extern "C" int bagua_decompress(int codec, const void* codes, const float* meta,
 {
     if (codec != BAGUA_CODEC_MINMAX_U8 && codec != BAGUA_CODEC_SIGN1) return BAGUA_ERR_INVALID_ARG;
     if (!codes || !meta || !out || n == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
+    {
+        const size_t nc = num_chunks(n, chunk);
+        RangeCheck rc;
+        rc.reads(codes, codec == BAGUA_CODEC_MINMAX_U8 ? n : ((n + 31) / 32) * sizeof(uint32_t));
+        rc.reads(meta, (codec == BAGUA_CODEC_MINMAX_U8 ? 2 * nc : nc) * sizeof(float));
+        rc.writes(out, n * sizeof(float));
+        if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    }
     if (((n + kRow - 1) / kRow + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(codes) || !aligned16(meta) || !aligned16(out)) return BAGUA_ERR_ALIGNMENT;
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -186,6 +186,30 @@ inline bool ranges_overlap(const void* a, size_t abytes, const void* b, size_t b
 }
 constexpr size_t kMaxGrid = 0x7fffffffu;
 
+// Aliasing rule of every entry point: a buffer the call writes must not overlap, by byte range, any
+// other buffer of the same call (buffers that are only read may overlap each other).
+struct ByteRange {
+    const void* p;
+    size_t bytes;
+};
+struct RangeCheck {
+    ByteRange w[4 * BAGUA_MAX_WORKERS + 8];  // written (or read-modify-written) buffers
+    ByteRange r[2 * BAGUA_MAX_WORKERS + 4];  // read-only buffers
+    int nw = 0, nr = 0;
+    void writes(const void* p, size_t bytes) { if (p) w[nw++] = ByteRange{p, bytes}; }
+    void reads(const void* p, size_t bytes) { if (p) r[nr++] = ByteRange{p, bytes}; }
+    bool disjoint() const
+    {
+        for (int i = 0; i < nw; ++i) {
+            for (int j = i + 1; j < nw; ++j)
+                if (ranges_overlap(w[i].p, w[i].bytes, w[j].p, w[j].bytes)) return false;
+            for (int j = 0; j < nr; ++j)
+                if (ranges_overlap(w[i].p, w[i].bytes, r[j].p, r[j].bytes)) return false;
+        }
+        return true;
+    }
+};
+
 // Rows per wave actually used: the preferred value, doubled until the chunk fits kMaxWaves waves.
 inline int pick_rpw(int rows, int preferred)
 {

@@ -124,6 +124,12 @@ extern "C" int bagua_flatten_compress_minmax_u8(const void* workspace, size_t T,
                                                 void* stream)
 {
     if (!workspace || !codes || !minmax || bucket_numel == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
+    RangeCheck rc;
+    rc.writes(residual, bucket_numel * sizeof(float));
+    rc.writes(codes, bucket_numel);
+    rc.writes(minmax, 2 * num_chunks(bucket_numel, chunk) * sizeof(float));
+    rc.writes(bucket_out, bucket_numel * sizeof(float));
+    if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     if (T > 0xfffffff0u || num_chunks(bucket_numel, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(workspace) || !aligned16(residual) || !aligned16(codes) || !aligned16(minmax) ||
         !aligned16(bucket_out))
@@ -151,8 +157,15 @@ extern "C" int bagua_reduce_compress_minmax_u8(const float* const* x, int k_loca
 {
     if (!x || k_local < 1 || k_local > BAGUA_MAX_WORKERS || !codes || !minmax || n == 0 || !chunk_ok(chunk))
         return BAGUA_ERR_INVALID_ARG;
-    for (int j = 0; j < k_local; ++j)
-        if (!x[j] || x[j] == residual) return BAGUA_ERR_INVALID_ARG;
+    RangeCheck rc;
+    for (int j = 0; j < k_local; ++j) {
+        if (!x[j]) return BAGUA_ERR_INVALID_ARG;
+        rc.reads(x[j], n * sizeof(float));
+    }
+    rc.writes(residual, n * sizeof(float));
+    rc.writes(codes, n);
+    rc.writes(minmax, 2 * num_chunks(n, chunk) * sizeof(float));
+    if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     for (int j = 0; j < k_local; ++j)
         if (!aligned16(x[j])) return BAGUA_ERR_ALIGNMENT;

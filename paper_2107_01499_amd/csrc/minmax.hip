@@ -227,6 +227,12 @@ extern "C" int bagua_compress_minmax_u8(const float* x, float* residual, size_t 
                                         uint8_t* codes, float* minmax, void* stream)
 {
     if (!x || !codes || !minmax || n == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
+    RangeCheck rc;
+    rc.reads(x, n * sizeof(float));
+    rc.writes(residual, n * sizeof(float));
+    rc.writes(codes, n);
+    rc.writes(minmax, 2 * num_chunks(n, chunk) * sizeof(float));
+    if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(residual) || !aligned16(codes) || !aligned16(minmax)) return BAGUA_ERR_ALIGNMENT;
     return launch_compress_minmax(x, residual, n, chunk, codes, minmax, static_cast<hipStream_t>(stream));

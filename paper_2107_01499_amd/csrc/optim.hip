@@ -135,7 +135,15 @@ extern "C" int bagua_decompress_sgd_step(int codec, const void* codes, const flo
 {
     if (codec != BAGUA_CODEC_MINMAX_U8 && codec != BAGUA_CODEC_SIGN1) return BAGUA_ERR_INVALID_ARG;
     if (!codes || !meta || !param || n == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
-    if (param == momentum_buf) return BAGUA_ERR_INVALID_ARG;
+    {
+        const size_t nc = num_chunks(n, chunk);
+        RangeCheck rc;
+        rc.reads(codes, codec == BAGUA_CODEC_MINMAX_U8 ? n : ((n + 31) / 32) * sizeof(uint32_t));
+        rc.reads(meta, (codec == BAGUA_CODEC_MINMAX_U8 ? 2 * nc : nc) * sizeof(float));
+        rc.writes(param, n * sizeof(float));
+        rc.writes(momentum_buf, n * sizeof(float));
+        if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    }
     const size_t rows = (n + kRow - 1) / kRow;
     if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(codes) || !aligned16(meta) || !aligned16(param) || !aligned16(momentum_buf)) return BAGUA_ERR_ALIGNMENT;
@@ -164,10 +172,16 @@ extern "C" int bagua_decompress_adam_step(int codec, const void* codes, const fl
 {
     if (codec != BAGUA_CODEC_MINMAX_U8 && codec != BAGUA_CODEC_SIGN1) return BAGUA_ERR_INVALID_ARG;
     if (!codes || !meta || !param || !m || !v || n == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
-    const size_t bytes = n * sizeof(float);
-    if (ranges_overlap(param, bytes, m, bytes) || ranges_overlap(param, bytes, v, bytes) ||
-        ranges_overlap(m, bytes, v, bytes))
-        return BAGUA_ERR_INVALID_ARG;
+    {
+        const size_t nc = num_chunks(n, chunk);
+        RangeCheck rc;
+        rc.reads(codes, codec == BAGUA_CODEC_MINMAX_U8 ? n : ((n + 31) / 32) * sizeof(uint32_t));
+        rc.reads(meta, (codec == BAGUA_CODEC_MINMAX_U8 ? 2 * nc : nc) * sizeof(float));
+        rc.writes(param, n * sizeof(float));
+        rc.writes(m, n * sizeof(float));
+        rc.writes(v, n * sizeof(float));
+        if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    }
     const size_t rows = (n + kRow - 1) / kRow;
     if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(codes) || !aligned16(meta) || !aligned16(param) || !aligned16(m) || !aligned16(v))

@@ -271,12 +271,6 @@ static int launch_ring_lp(const float* const* x_in, float* const* x_out, float* 
 
 using namespace bagua;
 
-static bool overlaps(const void* a, const void* b, size_t bytes)
-{
-    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
-    return x < y + bytes && y < x + bytes;
-}
-
 extern "C" int bagua_decentralized_avg(int mode, const float* const* x_in, float* const* x_out, float* const* xhat,
                                        uint8_t* const* codes, float* const* minmax, int k, size_t n, size_t chunk,
                                        void* stream)
@@ -289,15 +283,19 @@ extern "C" int bagua_decentralized_avg(int mode, const float* const* x_in, float
         if (!x_in[i] || !x_out[i]) return BAGUA_ERR_INVALID_ARG;
         if (lp && (!xhat[i] || !codes[i] || !minmax[i])) return BAGUA_ERR_INVALID_ARG;
     }
-    const size_t bytes = n * sizeof(float);
-    for (int i = 0; i < k; ++i) {
-        for (int j = 0; j < k; ++j) {
-            if (overlaps(x_out[i], x_in[j], bytes)) return BAGUA_ERR_INVALID_ARG;
-            if (j != i && overlaps(x_out[i], x_out[j], bytes)) return BAGUA_ERR_INVALID_ARG;
-            if (lp && overlaps(x_out[i], xhat[j], bytes)) return BAGUA_ERR_INVALID_ARG;
-            if (lp && overlaps(xhat[i], x_in[j], bytes)) return BAGUA_ERR_INVALID_ARG;
-            if (lp && j != i && overlaps(xhat[i], xhat[j], bytes)) return BAGUA_ERR_INVALID_ARG;
+    {
+        const size_t bytes = n * sizeof(float);
+        RangeCheck rc;
+        for (int i = 0; i < k; ++i) {
+            rc.reads(x_in[i], bytes);
+            rc.writes(x_out[i], bytes);
+            if (lp) {
+                rc.writes(xhat[i], bytes);
+                rc.writes(codes[i], n);
+                rc.writes(minmax[i], 2 * num_chunks(n, chunk) * sizeof(float));
+            }
         }
+        if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     }
     for (int i = 0; i < k; ++i) {
         if (!aligned16(x_in[i]) || !aligned16(x_out[i])) return BAGUA_ERR_ALIGNMENT;
@@ -347,12 +345,14 @@ extern "C" int bagua_decentralized_avg_peers(const float* const* x_in, float* co
     if (!x_in || !x_out || !peer || k < 1 || k > BAGUA_MAX_WORKERS || n == 0) return BAGUA_ERR_INVALID_ARG;
     for (int i = 0; i < k; ++i)
         if (!x_in[i] || !x_out[i] || peer[i] < 0 || peer[i] >= k) return BAGUA_ERR_INVALID_ARG;
-    const size_t bytes = n * sizeof(float);
-    for (int i = 0; i < k; ++i)
-        for (int j = 0; j < k; ++j) {
-            if (overlaps(x_out[i], x_in[j], bytes)) return BAGUA_ERR_INVALID_ARG;
-            if (j != i && overlaps(x_out[i], x_out[j], bytes)) return BAGUA_ERR_INVALID_ARG;
+    {
+        RangeCheck rc;
+        for (int i = 0; i < k; ++i) {
+            rc.reads(x_in[i], n * sizeof(float));
+            rc.writes(x_out[i], n * sizeof(float));
         }
+        if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    }
     for (int i = 0; i < k; ++i)
         if (!aligned16(x_in[i]) || !aligned16(x_out[i])) return BAGUA_ERR_ALIGNMENT;
     const size_t rows = (n + kRow - 1) / kRow;
@@ -405,8 +405,15 @@ k_centralized_avg_fp(PtrTable xs, int k, float inv_k, size_t n, float* __restric
 extern "C" int bagua_centralized_avg_fp(const float* const* x, int k, size_t n, float* out, void* stream)
 {
     if (!x || k < 1 || k > BAGUA_MAX_WORKERS || n == 0 || !out) return BAGUA_ERR_INVALID_ARG;
-    for (int j = 0; j < k; ++j)
-        if (!x[j] || overlaps(x[j], out, n * sizeof(float))) return BAGUA_ERR_INVALID_ARG;
+    {
+        RangeCheck rc;
+        for (int j = 0; j < k; ++j) {
+            if (!x[j]) return BAGUA_ERR_INVALID_ARG;
+            rc.reads(x[j], n * sizeof(float));
+        }
+        rc.writes(out, n * sizeof(float));
+        if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    }
     for (int j = 0; j < k; ++j)
         if (!aligned16(x[j])) return BAGUA_ERR_ALIGNMENT;
     if (!aligned16(out)) return BAGUA_ERR_ALIGNMENT;
@@ -525,15 +532,18 @@ extern "C" int bagua_decentralized_avg_peers_lp(const float* const* x_in, float*
     for (int i = 0; i < k; ++i)
         if (!x_in[i] || !x_out[i] || !xhat[i] || !codes[i] || !minmax[i] || peer[i] < 0 || peer[i] >= k)
             return BAGUA_ERR_INVALID_ARG;
-    const size_t bytes = n * sizeof(float);
-    for (int i = 0; i < k; ++i)
-        for (int j = 0; j < k; ++j) {
-            if (overlaps(x_out[i], x_in[j], bytes) || overlaps(x_out[i], xhat[j], bytes) ||
-                overlaps(xhat[i], x_in[j], bytes))
-                return BAGUA_ERR_INVALID_ARG;
-            if (j != i && (overlaps(x_out[i], x_out[j], bytes) || overlaps(xhat[i], xhat[j], bytes)))
-                return BAGUA_ERR_INVALID_ARG;
+    {
+        const size_t bytes = n * sizeof(float);
+        RangeCheck rc;
+        for (int i = 0; i < k; ++i) {
+            rc.reads(x_in[i], bytes);
+            rc.writes(x_out[i], bytes);
+            rc.writes(xhat[i], bytes);
+            rc.writes(codes[i], n);
+            rc.writes(minmax[i], 2 * num_chunks(n, chunk) * sizeof(float));
         }
+        if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    }
     for (int i = 0; i < k; ++i)
         if (!aligned16(x_in[i]) || !aligned16(x_out[i]) || !aligned16(xhat[i]) || !aligned16(codes[i]) ||
             !aligned16(minmax[i]))

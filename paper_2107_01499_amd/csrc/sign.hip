@@ -341,6 +341,12 @@ extern "C" int bagua_sign_compress_ef(const float* x, float* residual, size_t n,
                                       float* scale, void* stream)
 {
     if (!x || !bits || !scale || n == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
+    RangeCheck rc;
+    rc.reads(x, n * sizeof(float));
+    rc.writes(residual, n * sizeof(float));
+    rc.writes(bits, ((n + 31) / 32) * sizeof(uint32_t));
+    rc.writes(scale, num_chunks(n, chunk) * sizeof(float));
+    if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(residual) || !aligned16(bits) || !aligned16(scale)) return BAGUA_ERR_ALIGNMENT;
     return launch_sign_compress(x, residual, n, chunk, bits, scale, static_cast<hipStream_t>(stream));
@@ -351,9 +357,13 @@ extern "C" int bagua_momentum_sign_compress_ef(const float* g, const float* m, f
 {
     if (!g || !m || !bits || !scale || n == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
-    const size_t bytes = n * sizeof(float);
-    if (residual && (ranges_overlap(residual, bytes, g, bytes) || ranges_overlap(residual, bytes, m, bytes)))
-        return BAGUA_ERR_INVALID_ARG;
+    RangeCheck rc;
+    rc.reads(g, n * sizeof(float));
+    rc.reads(m, n * sizeof(float));
+    rc.writes(residual, n * sizeof(float));
+    rc.writes(bits, ((n + 31) / 32) * sizeof(uint32_t));
+    rc.writes(scale, num_chunks(n, chunk) * sizeof(float));
+    if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     if (!aligned16(g) || !aligned16(m) || !aligned16(residual) || !aligned16(bits) || !aligned16(scale))
         return BAGUA_ERR_ALIGNMENT;
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -326,6 +326,15 @@ extern "C" int bagua_compress_topk_ef(const float* x, float* residual, size_t n,
                                       uint16_t* idx, float* val, void* stream)
 {
     if (!x || !idx || !val || !topk_args_ok(n, chunk, keep)) return BAGUA_ERR_INVALID_ARG;
+    {
+        const size_t slots = num_chunks(n, chunk) * keep;
+        RangeCheck rc;
+        rc.reads(x, n * sizeof(float));
+        rc.writes(residual, n * sizeof(float));
+        rc.writes(idx, slots * sizeof(uint16_t));
+        rc.writes(val, slots * sizeof(float));
+        if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    }
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(residual) || !aligned16(idx) || !aligned16(val)) return BAGUA_ERR_ALIGNMENT;
     const int rows = static_cast<int>(chunk / kRow);
@@ -350,8 +359,19 @@ extern "C" int bagua_decompress_reduce_recompress_topk(const uint16_t* const* id
 {
     if (!idx_in || !val_in || k < 1 || k > BAGUA_MAX_WORKERS || !idx_out || !val_out || !topk_args_ok(n, chunk, keep))
         return BAGUA_ERR_INVALID_ARG;
-    for (int j = 0; j < k; ++j) {
-        if (!idx_in[j] || !val_in[j] || idx_in[j] == idx_out || val_in[j] == val_out) return BAGUA_ERR_INVALID_ARG;
+    {
+        const size_t slots = num_chunks(n, chunk) * keep;
+        RangeCheck rc;
+        for (int j = 0; j < k; ++j) {
+            if (!idx_in[j] || !val_in[j]) return BAGUA_ERR_INVALID_ARG;
+            rc.reads(idx_in[j], slots * sizeof(uint16_t));
+            rc.reads(val_in[j], slots * sizeof(float));
+        }
+        rc.writes(server_residual, n * sizeof(float));
+        rc.writes(idx_out, slots * sizeof(uint16_t));
+        rc.writes(val_out, slots * sizeof(float));
+        rc.writes(out_fp32, n * sizeof(float));
+        if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     }
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     for (int j = 0; j < k; ++j)
@@ -386,6 +406,14 @@ extern "C" int bagua_decompress_topk(const uint16_t* idx, const float* val, size
                                      float* out, void* stream)
 {
     if (!idx || !val || !out || !topk_args_ok(n, chunk, keep)) return BAGUA_ERR_INVALID_ARG;
+    {
+        const size_t slots = num_chunks(n, chunk) * keep;
+        RangeCheck rc;
+        rc.reads(idx, slots * sizeof(uint16_t));
+        rc.reads(val, slots * sizeof(float));
+        rc.writes(out, n * sizeof(float));
+        if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    }
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(idx) || !aligned16(val) || !aligned16(out)) return BAGUA_ERR_ALIGNMENT;
     hipLaunchKernelGGL(k_decompress_topk, dim3(static_cast<unsigned>(num_chunks(n, chunk))), dim3(256),

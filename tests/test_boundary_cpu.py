@@ -41,25 +41,33 @@ def test_status_strings(bg):
 
 def test_validation_errors_without_gpu(bg):
     lib = bg.binding.raw()
-    A = 0x1000  # a fake, 16-byte aligned "device pointer"; validation fails before it is ever used
+    # fake, 16-byte aligned "device pointers", far enough apart not to overlap; validation fails before any is used
+    A, B, Cc, D, E = 0x100000, 0x200000, 0x300000, 0x400000, 0x500000
     INVALID, ALIGN = 1, 2
-    # compress: NULL, n == 0, bad chunk sizes, misalignment
-    assert lib.bagua_compress_minmax_u8(None, None, 10, 256, A, A, None) == INVALID
-    assert lib.bagua_compress_minmax_u8(A, None, 0, 256, A, A, None) == INVALID
+    # compress: NULL, n == 0, bad chunk sizes, misalignment, aliasing
+    assert lib.bagua_compress_minmax_u8(None, None, 10, 256, B, Cc, None) == INVALID
+    assert lib.bagua_compress_minmax_u8(A, None, 0, 256, B, Cc, None) == INVALID
     for chunk in (0, 100, 255, 300, 16384 + 256):
-        assert lib.bagua_compress_minmax_u8(A, None, 10, chunk, A, A, None) == INVALID
-    assert lib.bagua_compress_minmax_u8(A + 4, None, 10, 256, A, A, None) == ALIGN
-    assert lib.bagua_compress_minmax_u8(A, A + 8, 10, 256, A, A, None) == ALIGN
-    assert lib.bagua_sign_compress_ef(A, None, 10, 128, A, A, None) == INVALID
-    assert lib.bagua_sign_compress_ef(A, None, 10, 256, A + 1, A, None) == ALIGN
-    # d-r-r: k range, codec enum, NULL entries
-    arr = (ctypes.c_void_p * 33)(*([A] * 33))
-    assert lib.bagua_decompress_reduce_recompress(0, arr, arr, 0, None, 10, 256, A + 16, A + 32, None, None) == INVALID
-    assert lib.bagua_decompress_reduce_recompress(0, arr, arr, 33, None, 10, 256, A + 16, A + 32, None, None) == INVALID
-    assert lib.bagua_decompress_reduce_recompress(2, arr, arr, 2, None, 10, 256, A + 16, A + 32, None, None) == INVALID
-    assert lib.bagua_decompress_reduce_recompress(0, arr, arr, 2, None, 10, 256, A, A + 32, None, None) == INVALID  # out aliases in
+        assert lib.bagua_compress_minmax_u8(A, None, 10, chunk, B, Cc, None) == INVALID
+    assert lib.bagua_compress_minmax_u8(A + 4, None, 10, 256, B, Cc, None) == ALIGN
+    assert lib.bagua_compress_minmax_u8(A, D + 8, 10, 256, B, Cc, None) == ALIGN
+    assert lib.bagua_compress_minmax_u8(A, A, 10, 256, B, Cc, None) == INVALID           # residual aliases x
+    assert lib.bagua_compress_minmax_u8(A, D, 64, 256, A + 32, Cc, None) == INVALID      # codes inside x
+    assert lib.bagua_compress_minmax_u8(A, D, 64, 256, B, D + 16, None) == INVALID       # minmax inside residual
+    assert lib.bagua_sign_compress_ef(A, None, 10, 128, B, Cc, None) == INVALID
+    assert lib.bagua_sign_compress_ef(A, None, 10, 256, B + 1, Cc, None) == ALIGN
+    assert lib.bagua_sign_compress_ef(A, None, 64, 256, A, Cc, None) == INVALID          # bits alias x
+    # d-r-r: k range, codec enum, NULL entries, outputs overlapping inputs
+    arr = (ctypes.c_void_p * 33)(*[A + 0x1000 * i for i in range(33)])
+    marr = (ctypes.c_void_p * 33)(*[B + 0x1000 * i for i in range(33)])
+    assert lib.bagua_decompress_reduce_recompress(0, arr, marr, 0, None, 10, 256, Cc, D, None, None) == INVALID
+    assert lib.bagua_decompress_reduce_recompress(0, arr, marr, 33, None, 10, 256, Cc, D, None, None) == INVALID
+    assert lib.bagua_decompress_reduce_recompress(2, arr, marr, 2, None, 10, 256, Cc, D, None, None) == INVALID
+    assert lib.bagua_decompress_reduce_recompress(0, arr, marr, 2, None, 10, 256, A + 0x1000, D, None, None) == INVALID  # out aliases in
+    assert lib.bagua_decompress_reduce_recompress(0, arr, marr, 2, E, 10, 256, Cc, D, E + 16, None) == INVALID  # out overlaps eps
     arr2 = (ctypes.c_void_p * 2)(A, None)
-    assert lib.bagua_decompress_reduce_recompress(0, arr2, arr, 2, None, 10, 256, A + 16, A + 32, None, None) == INVALID
+    assert lib.bagua_decompress_reduce_recompress(0, arr2, marr, 2, None, 10, 256, Cc, D, None, None) == INVALID
+    assert lib.bagua_decompress(0, A, B, 64, 256, A + 16, None) == INVALID                # out overlaps codes
     # decentralised: aliasing and mode
     xin = (ctypes.c_void_p * 2)(0x10000, 0x20000)
     xout = (ctypes.c_void_p * 2)(0x30000, 0x40000)
@@ -67,6 +75,10 @@ def test_validation_errors_without_gpu(bg):
     assert lib.bagua_decentralized_avg(0, xin, xin, None, None, None, 2, 16, 0, None) == INVALID
     assert lib.bagua_decentralized_avg(1, xin, xout, None, None, None, 2, 16, 256, None) == INVALID  # LP needs xhat
     assert lib.bagua_decentralized_avg(0, xin, xout, None, None, None, 0, 16, 0, None) == INVALID
+    # LP mode: codes of one peer inside another peer's replica
+    hat = (ctypes.c_void_p * 2)(0x50000, 0x60000)
+    mm = (ctypes.c_void_p * 2)(0x90000, 0xa0000)
+    assert lib.bagua_decentralized_avg(1, xin, xout, hat, (ctypes.c_void_p * 2)(0x70000, 0x10010), mm, 2, 16, 256, None) == INVALID
     # flatten: overlap, overflow, workspace too small
     src = (ctypes.c_void_p * 2)(A, A)
     numel = (ctypes.c_size_t * 2)(10, 10)
