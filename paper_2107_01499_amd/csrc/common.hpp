@@ -11,6 +11,8 @@
 
 #include <hip/hip_runtime.h>
 #include <math.h>
+
+#include <algorithm>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -179,32 +181,36 @@ __device__ __forceinline__ float minmax_step(float mn, float mx)
 inline bool chunk_ok(size_t chunk) { return chunk >= 256 && chunk <= 16384 && chunk % 256 == 0; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t num_chunks(size_t n, size_t chunk) { return (n + chunk - 1) / chunk; }
-inline bool ranges_overlap(const void* a, size_t abytes, const void* b, size_t bbytes)
-{
-    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
-    return x < y + bbytes && y < x + abytes;
-}
 constexpr size_t kMaxGrid = 0x7fffffffu;
 
 // Aliasing rule of every entry point: a buffer the call writes must not overlap, by byte range, any
 // other buffer of the same call (buffers that are only read may overlap each other).
-struct ByteRange {
-    const void* p;
-    size_t bytes;
-};
 struct RangeCheck {
-    ByteRange w[4 * BAGUA_MAX_WORKERS + 8];  // written (or read-modify-written) buffers
-    ByteRange r[2 * BAGUA_MAX_WORKERS + 4];  // read-only buffers
-    int nw = 0, nr = 0;
-    void writes(const void* p, size_t bytes) { if (p) w[nw++] = ByteRange{p, bytes}; }
-    void reads(const void* p, size_t bytes) { if (p) r[nr++] = ByteRange{p, bytes}; }
-    bool disjoint() const
+    struct Item {
+        uintptr_t lo, hi;  // [lo, hi)
+        bool written;
+    };
+    Item item[6 * BAGUA_MAX_WORKERS + 12];
+    int count = 0;
+    void add(const void* p, size_t bytes, bool written)
     {
-        for (int i = 0; i < nw; ++i) {
-            for (int j = i + 1; j < nw; ++j)
-                if (ranges_overlap(w[i].p, w[i].bytes, w[j].p, w[j].bytes)) return false;
-            for (int j = 0; j < nr; ++j)
-                if (ranges_overlap(w[i].p, w[i].bytes, r[j].p, r[j].bytes)) return false;
+        if (!p || bytes == 0) return;
+        const uintptr_t lo = reinterpret_cast<uintptr_t>(p);
+        item[count++] = Item{lo, lo + bytes, written};
+    }
+    void writes(const void* p, size_t bytes) { add(p, bytes, true); }
+    void reads(const void* p, size_t bytes) { add(p, bytes, false); }
+    // Sweep over the ranges in address order: a written range must start at or after the end of every
+    // earlier range, a read-only range at or after the end of every earlier written range.
+    bool disjoint()
+    {
+        std::sort(item, item + count, [](const Item& a, const Item& b) { return a.lo < b.lo; });
+        uintptr_t end_any = 0, end_written = 0;
+        for (int i = 0; i < count; ++i) {
+            const Item& r = item[i];
+            if (r.lo < (r.written ? end_any : end_written)) return false;
+            if (r.hi > end_any) end_any = r.hi;
+            if (r.written && r.hi > end_written) end_written = r.hi;
         }
         return true;
     }
