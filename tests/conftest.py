@@ -10,6 +10,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: test needs a real MI355X (run with -m gpu)")
+    import __graft_entry__
+    __graft_entry__.ensure_built()   # loads what is built; compiles only if a library is missing altogether
 
 
 @pytest.fixture(scope="session")
