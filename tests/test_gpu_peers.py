@@ -71,7 +71,7 @@ def _matching(r, k):
 
 
 @pytest.mark.parametrize("n,chunk", [(1, 256), (255, 256), (4096 * 3 + 1027, 4096), (70001, 1024), (70001, 2048),
-                                     (8192 * 2 + 300, 8192), (16384 + 5, 16384)])
+                                     (5000, 768), (2816 * 3 + 2000, 2816), (8192 * 2 + 300, 8192), (16384 + 5, 16384)])
 @pytest.mark.parametrize("k,peer", [(2, [1, 0]), (6, [3, 4, 5, 0, 1, 2]), (8, "matching"), (32, "matching"),
                                     (1, [0]), (4, [0, 0, 0, 0]), (5, [1, 2, 3, 4, 0]), (7, [1, 0, 2, 4, 3, 6, 5])])
 def test_peer_avg_lp(bg, oracle, n, chunk, k, peer):
