@@ -73,9 +73,19 @@ __device__ __forceinline__ void find_digit(const uint32_t* h, int lane, uint32_t
     above = t;
 }
 
+// Zero the histograms (128-bit LDS stores) and synchronise.  Called while the chunk's global loads are
+// still in flight, so the clear costs no extra latency.
+__device__ __forceinline__ void topk_clear_lds(uint32_t* smem)
+{
+    static_assert((256 * kCopies + 4 * 256) % 4 == 0, "histogram words come in groups of four");
+    uint4* q = reinterpret_cast<uint4*>(smem);
+    for (int t = threadIdx.x; t < (256 * kCopies + 4 * 256) / 4; t += blockDim.x) q[t] = uint4{0u, 0u, 0u, 0u};
+    __syncthreads();
+}
+
 // Encode the chunk held in v (absent elements are ignored).  idx_c/val_c point at the chunk's `keep`
 // output slots, residual/out at the chunk's first element (nullptr = not wanted).
-// smem: kTopkLdsWords words of LDS; the function starts with a barrier-protected clear of it.
+// smem: kTopkLdsWords words of LDS, cleared by topk_clear_lds (all waves must have passed its barrier).
 template <int RPW>
 __device__ __forceinline__ void topk_encode_chunk(const f4 (&v)[RPW], long len, uint32_t keep, int wave, int lane,
                                                   int nwaves, float* __restrict__ residual,
@@ -86,8 +96,6 @@ __device__ __forceinline__ void topk_encode_chunk(const f4 (&v)[RPW], long len, 
     uint32_t* hist = smem + 256 * kCopies;    // [4][256]
     uint32_t* tot = hist + 4 * 256;
     const uint32_t keff = (static_cast<long>(keep) < len) ? keep : static_cast<uint32_t>(len);
-    for (int t = threadIdx.x; t < 256 * kCopies + 4 * 256; t += blockDim.x) smem[t] = 0;
-    __syncthreads();
 
     uint32_t key[RPW][4];
     bool valid[RPW][4];
@@ -219,21 +227,26 @@ k_compress_topk(const float* __restrict__ x, float* __restrict__ residual, size_
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
-    f4 v[RPW];
+    f4 v[RPW], d[RPW];
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
         const long off = static_cast<long>(wave * RPW + i) * kRow;
         const long remain = len - off;
         v[i] = f4{0.f, 0.f, 0.f, 0.f};
+        d[i] = v[i];
         if (remain > 0) {
             v[i] = load_row(x + base + off, lane, remain, 0.0f);
-            if (EF) {
-                const f4 d = load_row(residual + base + off, lane, remain, 0.0f);
-                v[i].x = v[i].x + d.x;
-                v[i].y = v[i].y + d.y;
-                v[i].z = v[i].z + d.z;
-                v[i].w = v[i].w + d.w;
-            }
+            if (EF) d[i] = load_row(residual + base + off, lane, remain, 0.0f);
+        }
+    }
+    topk_clear_lds(smem);
+    if (EF) {
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            v[i].x = v[i].x + d[i].x;
+            v[i].y = v[i].y + d[i].y;
+            v[i].z = v[i].z + d[i].z;
+            v[i].w = v[i].w + d[i].w;
         }
     }
     topk_encode_chunk<RPW>(v, len, keep, wave, lane, nwaves, EF ? residual + base : nullptr, idx + c * keep,
@@ -289,6 +302,7 @@ k_drr_topk(PtrTable idx_in, PtrTable val_in, int k, float inv_k, uint32_t keep, 
         }
     }
     __syncthreads();  // the dense copy is dead: its LDS is reused by the selection
+    topk_clear_lds(smem);
     topk_encode_chunk<RPW>(v, len, keep, wave, lane, nwaves, EF ? eps + base : nullptr, idx_out + c * keep,
                            val_out + c * keep, OUT ? out + base : nullptr, smem);
 }
