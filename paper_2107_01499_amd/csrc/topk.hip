@@ -269,16 +269,54 @@ k_drr_topk(PtrTable idx_in, PtrTable val_in, int k, float inv_k, uint32_t keep, 
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
-    for (uint32_t t = threadIdx.x; t < chunk; t += blockDim.x) dense[t] = 0.0f;
-    __syncthreads();
-    for (int j = 0; j < k; ++j) {
-        const uint16_t* ij = static_cast<const uint16_t*>(idx_in.p[j]) + c * keep;
-        const float* vj = static_cast<const float*>(val_in.p[j]) + c * keep;
-        for (uint32_t t = threadIdx.x; t < keep; t += blockDim.x) {
-            const uint32_t p = ij[t];
-            if (static_cast<long>(p) < len) dense[p] = dense[p] + vj[t];
+    // The error state of this wave's rows is requested first: it is not needed before the sparse sums are done.
+    f4 e[RPW];
+    if (EF) {
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const long off = static_cast<long>(wave * RPW + i) * kRow;
+            const long remain = len - off;
+            e[i] = f4{0.f, 0.f, 0.f, 0.f};
+            if (remain > 0) e[i] = load_row(eps + base + off, lane, remain, 0.0f);
+        }
+    }
+    for (uint32_t t = threadIdx.x; t < chunk / 4; t += blockDim.x) reinterpret_cast<f4*>(dense)[t] = f4{0.f, 0.f, 0.f, 0.f};
+    if (keep <= blockDim.x) {
+        // one entry per thread and worker: the entries of up to eight workers are fetched together, so the
+        // chain of k dependent steps pays one memory latency per group instead of one per worker
+        constexpr int G = 8;
+        const uint32_t t = threadIdx.x;
+        for (int j0 = 0; j0 < k; j0 += G) {
+            uint32_t p[G];
+            float a[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                p[g] = 0xFFFFu;
+                a[g] = 0.0f;
+                if (j0 + g < k && t < keep) {
+                    p[g] = static_cast<const uint16_t*>(idx_in.p[j0 + g])[c * keep + t];
+                    a[g] = static_cast<const float*>(val_in.p[j0 + g])[c * keep + t];
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                if (j0 + g >= k) break;
+                __syncthreads();  // the previous worker's sums (or the clear) are complete
+                if (static_cast<long>(p[g]) < len) dense[p[g]] = dense[p[g]] + a[g];
+            }
         }
         __syncthreads();
+    } else {
+        __syncthreads();
+        for (int j = 0; j < k; ++j) {
+            const uint16_t* ij = static_cast<const uint16_t*>(idx_in.p[j]) + c * keep;
+            const float* vj = static_cast<const float*>(val_in.p[j]) + c * keep;
+            for (uint32_t t = threadIdx.x; t < keep; t += blockDim.x) {
+                const uint32_t p = ij[t];
+                if (static_cast<long>(p) < len) dense[p] = dense[p] + vj[t];
+            }
+            __syncthreads();
+        }
     }
     f4 v[RPW];
 #pragma unroll
@@ -293,11 +331,10 @@ k_drr_topk(PtrTable idx_in, PtrTable val_in, int k, float inv_k, uint32_t keep, 
             v[i].z = a.z * inv_k;
             v[i].w = a.w * inv_k;
             if (EF) {
-                const f4 d = load_row(eps + base + off, lane, remain, 0.0f);
-                v[i].x = v[i].x + d.x;
-                v[i].y = v[i].y + d.y;
-                v[i].z = v[i].z + d.z;
-                v[i].w = v[i].w + d.w;
+                v[i].x = v[i].x + e[i].x;
+                v[i].y = v[i].y + e[i].y;
+                v[i].z = v[i].z + e[i].z;
+                v[i].w = v[i].w + e[i].w;
             }
         }
     }
