@@ -484,6 +484,86 @@ def test_hip_graph_replay_matches_eager(bg, oracle):
             assert np.array_equal(host(delta[j]).view(np.uint32), d_o[j].view(np.uint32))
 
 
+def test_hip_graph_replay_of_the_widened_rows(bg, oracle):
+    """One compression-stage iteration of 1-bit Adam, a top-K round and a low-precision peer round captured in one
+    HIP graph; three replays with fresh inputs, each equal to the oracle's chain with the state carried along."""
+    n, C, k, keep = 3 * 2048 + 77, 2048, 4, 64
+    nc, nw = bg.num_chunks(n, C), (n + 31) // 32
+    f = lambda *shape: torch.zeros(*shape, device="cuda")
+    g_in = [f(n) for _ in range(k)]
+    m_g, v_g, p_g = f(n), f(n), f(n)
+    delta, eps = [f(n) for _ in range(k)], f(n)
+    bits = [torch.zeros(nw, dtype=torch.int32, device="cuda") for _ in range(k)]
+    scale = [f(nc) for _ in range(k)]
+    b2, s2 = torch.zeros(nw, dtype=torch.int32, device="cuda"), f(nc)
+    tdelta = [f(n) for _ in range(k)]
+    tidx = [torch.zeros(nc * keep, dtype=torch.int16, device="cuda") for _ in range(k)]
+    tval = [f(nc * keep) for _ in range(k)]
+    teps, ti2, tv2, tout = f(n), torch.zeros(nc * keep, dtype=torch.int16, device="cuda"), f(nc * keep), f(n)
+    hat = [f(n) for _ in range(k)]
+    lp_out = [f(n) for _ in range(k)]
+    lp_codes = [torch.zeros(n, dtype=torch.uint8, device="cuda") for _ in range(k)]
+    lp_mm = [f(2 * nc) for _ in range(k)]
+    peer = [1, 0, 3, 2]
+
+    def step():
+        for j in range(k):
+            bg.bagua_momentum_sign_compress_ef(g_in[j], m_g, 0.9, delta[j], C, bits[j], scale[j])
+        bg.bagua_decompress_reduce_recompress(bg.CODEC_SIGN1, bits, scale, eps, n, C, b2, s2, None)
+        bg.bagua_decompress_adam_step(bg.CODEC_SIGN1, b2, s2, n, C, p_g, m_g, v_g, 1e-3, 0.9, 0.999, 1e-8, 0.0, True)
+        for j in range(k):
+            bg.bagua_compress_topk_ef(g_in[j], tdelta[j], C, keep, tidx[j], tval[j])
+        bg.bagua_decompress_reduce_recompress_topk(tidx, tval, keep, teps, n, C, ti2, tv2, tout)
+        bg.bagua_decentralized_avg_peers_lp(g_in, lp_out, hat, lp_codes, lp_mm, peer, C)
+
+    state = [m_g, v_g, p_g, eps, teps] + delta + tdelta + hat
+    v0, p0 = np.abs(vals(n, 1)).astype(np.float32) * np.float32(1e-3) + np.float32(1e-8), vals(n, 2)
+
+    def reset():
+        for t in state:
+            t.zero_()
+        v_g.copy_(torch.from_numpy(v0)); p_g.copy_(torch.from_numpy(p0))
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    reset()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    reset()
+    torch.cuda.synchronize()
+    z = lambda: np.zeros(n, np.float32)
+    m_o, v_o, p_o, eps_o, teps_o = z(), v0.copy(), p0.copy(), z(), z()
+    d_o, td_o, hat_o = [z() for _ in range(k)], [z() for _ in range(k)], [z() for _ in range(k)]
+    for it in range(3):
+        gs = [vals(n, 900 + 10 * it + j) for j in range(k)]
+        for j in range(k):
+            g_in[j].copy_(torch.from_numpy(gs[j]))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        enc = [oracle.momentum_sign_compress_ef(gs[j], m_o, 0.9, d_o[j], C) for j in range(k)]
+        bo, so, _ = oracle.drr_sign([e[0] for e in enc], [e[1] for e in enc], eps_o, n, C, want_fp32=False)
+        oracle.decompress_adam_step(1, bo, so, n, C, p_o, m_o, v_o, 1e-3, 0.9, 0.999, 1e-8, 0.0, True)
+        tenc = [oracle.compress_topk(gs[j], td_o[j], C, keep) for j in range(k)]
+        io2, vo2, oo = oracle.drr_topk([e[0] for e in tenc], [e[1] for e in tenc], teps_o, n, C, keep)
+        want, wc, wm = oracle.peer_avg_lp(gs, hat_o, peer, C)
+        tag = "replay %d" % it
+        assert np.array_equal(host(b2).view(np.uint32), bo), tag
+        for got, ref in ((p_g, p_o), (m_g, m_o), (v_g, v_o), (eps, eps_o), (tout, oo), (teps, teps_o), (tv2, vo2)):
+            assert np.array_equal(host(got).view(np.uint32), ref.view(np.uint32)), tag
+        assert np.array_equal(host(ti2).view(np.uint16), io2), tag
+        for j in range(k):
+            assert np.array_equal(host(delta[j]).view(np.uint32), d_o[j].view(np.uint32)), tag
+            assert np.array_equal(host(tdelta[j]).view(np.uint32), td_o[j].view(np.uint32)), tag
+            assert np.array_equal(host(lp_out[j]).view(np.uint32), want[j].view(np.uint32)), tag
+            assert np.array_equal(host(hat[j]).view(np.uint32), hat_o[j].view(np.uint32)), tag
+            assert np.array_equal(host(lp_codes[j]), wc[j]), tag
+
+
 def test_flatten_thousands_of_tiny_tensors(bg, oracle):
     """Many tensors of 0-5 elements with random gaps: every tile holds hundreds of tensors, so the per-lane
     binary search and the element-wise walk of both the flatten kernel and the fused gather are exercised."""
