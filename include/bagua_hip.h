@@ -14,8 +14,10 @@
  *   - Pointers named "device" point to GPU memory owned by the caller; "host[k]" arrays are
  *     host arrays of k device pointers and are only read during the call.  The library
  *     allocates no device memory and keeps no state between calls.
- *   - Bucket-level buffers (x, residual, codes, bits, minmax, scale, replicas, bucket) must be
- *     16-byte aligned (BAGUA_ERR_ALIGNMENT otherwise).
+ *   - Bucket-sized buffers (x, residual, codes, sign words, replicas, parameters, optimizer state,
+ *     bucket) must be 16-byte aligned (BAGUA_ERR_ALIGNMENT otherwise).  Per-chunk metadata (minmax,
+ *     scale) and the top-K entry arrays need only the alignment of their element type, so the slice
+ *     that belongs to a partition of whole chunks can be passed as it is.
  *   - Aliasing: a buffer that a call writes (outputs and in-out state) must not overlap, by byte
  *     range, any other buffer passed to the same call (BAGUA_ERR_INVALID_ARG otherwise); buffers
  *     that are only read may overlap each other.  Tensors named in a flatten plan are not checked.
@@ -43,7 +45,7 @@ extern "C" {
 enum {
     BAGUA_OK = 0,
     BAGUA_ERR_INVALID_ARG = 1, /* NULL where required, n == 0, k outside [1,32], bad chunk, bad enum, aliasing */
-    BAGUA_ERR_ALIGNMENT = 2,   /* a bucket-level pointer is not 16-byte aligned */
+    BAGUA_ERR_ALIGNMENT = 2,   /* a pointer is not aligned as stated under "Conventions" */
     BAGUA_ERR_LAUNCH = 3,      /* the HIP runtime reported an error for a copy or a launch */
     BAGUA_ERR_UNSUPPORTED = 4  /* valid request outside what this build implements */
 };

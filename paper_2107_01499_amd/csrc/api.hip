@@ -41,8 +41,8 @@ extern "C" int bagua_decompress_reduce_recompress(int codec, const void* const* 
     if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     for (int j = 0; j < k; ++j)
-        if (!aligned16(codes_in[j]) || !aligned16(meta_in[j])) return BAGUA_ERR_ALIGNMENT;
-    if (!aligned16(server_residual) || !aligned16(codes_out) || !aligned16(meta_out) || !aligned16(out_fp32))
+        if (!aligned16(codes_in[j]) || !aligned4(meta_in[j])) return BAGUA_ERR_ALIGNMENT;
+    if (!aligned16(server_residual) || !aligned16(codes_out) || !aligned4(meta_out) || !aligned16(out_fp32))
         return BAGUA_ERR_ALIGNMENT;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (codec == BAGUA_CODEC_MINMAX_U8)
@@ -66,7 +66,7 @@ extern "C" int bagua_decompress(int codec, const void* codes, const float* meta,
         if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     }
     if (((n + kRow - 1) / kRow + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
-    if (!aligned16(codes) || !aligned16(meta) || !aligned16(out)) return BAGUA_ERR_ALIGNMENT;
+    if (!aligned16(codes) || !aligned4(meta) || !aligned16(out)) return BAGUA_ERR_ALIGNMENT;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (codec == BAGUA_CODEC_MINMAX_U8)
         return launch_decompress_minmax(static_cast<const uint8_t*>(codes), meta, n, chunk, out, s);

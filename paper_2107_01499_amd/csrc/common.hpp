@@ -180,6 +180,10 @@ __device__ __forceinline__ float minmax_step(float mn, float mx)
 // ---------------------------------------------------------------- host-side argument checks
 inline bool chunk_ok(size_t chunk) { return chunk >= 256 && chunk <= 16384 && chunk % 256 == 0; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+// Per-chunk metadata and top-K entry arrays are accessed element by element: natural alignment suffices, so a
+// partition's slice of them (any whole number of chunks) can be passed as it is.
+inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+inline bool aligned2(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 1u) == 0; }
 inline size_t num_chunks(size_t n, size_t chunk) { return (n + chunk - 1) / chunk; }
 constexpr size_t kMaxGrid = 0x7fffffffu;
 

@@ -131,7 +131,7 @@ extern "C" int bagua_flatten_compress_minmax_u8(const void* workspace, size_t T,
     rc.writes(bucket_out, bucket_numel * sizeof(float));
     if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     if (T > 0xfffffff0u || num_chunks(bucket_numel, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
-    if (!aligned16(workspace) || !aligned16(residual) || !aligned16(codes) || !aligned16(minmax) ||
+    if (!aligned16(workspace) || !aligned16(residual) || !aligned16(codes) || !aligned4(minmax) ||
         !aligned16(bucket_out))
         return BAGUA_ERR_ALIGNMENT;
     const FlattenPlanView pv = plan_view(workspace, T);
@@ -169,7 +169,7 @@ extern "C" int bagua_reduce_compress_minmax_u8(const float* const* x, int k_loca
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     for (int j = 0; j < k_local; ++j)
         if (!aligned16(x[j])) return BAGUA_ERR_ALIGNMENT;
-    if (!aligned16(residual) || !aligned16(codes) || !aligned16(minmax)) return BAGUA_ERR_ALIGNMENT;
+    if (!aligned16(residual) || !aligned16(codes) || !aligned4(minmax)) return BAGUA_ERR_ALIGNMENT;
     PtrTable xt{};
     for (int j = 0; j < k_local; ++j) xt.p[j] = x[j];
     const int rows = static_cast<int>(chunk / kRow);

@@ -234,6 +234,6 @@ extern "C" int bagua_compress_minmax_u8(const float* x, float* residual, size_t 
     rc.writes(minmax, 2 * num_chunks(n, chunk) * sizeof(float));
     if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
-    if (!aligned16(x) || !aligned16(residual) || !aligned16(codes) || !aligned16(minmax)) return BAGUA_ERR_ALIGNMENT;
+    if (!aligned16(x) || !aligned16(residual) || !aligned16(codes) || !aligned4(minmax)) return BAGUA_ERR_ALIGNMENT;
     return launch_compress_minmax(x, residual, n, chunk, codes, minmax, static_cast<hipStream_t>(stream));
 }

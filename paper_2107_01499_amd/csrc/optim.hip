@@ -146,7 +146,7 @@ extern "C" int bagua_decompress_sgd_step(int codec, const void* codes, const flo
     }
     const size_t rows = (n + kRow - 1) / kRow;
     if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
-    if (!aligned16(codes) || !aligned16(meta) || !aligned16(param) || !aligned16(momentum_buf)) return BAGUA_ERR_ALIGNMENT;
+    if (!aligned16(codes) || !aligned4(meta) || !aligned16(param) || !aligned16(momentum_buf)) return BAGUA_ERR_ALIGNMENT;
     dim3 grid(static_cast<unsigned>((rows + 3) / 4)), block(256);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint32_t ch = static_cast<uint32_t>(chunk);
@@ -184,7 +184,7 @@ extern "C" int bagua_decompress_adam_step(int codec, const void* codes, const fl
     }
     const size_t rows = (n + kRow - 1) / kRow;
     if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
-    if (!aligned16(codes) || !aligned16(meta) || !aligned16(param) || !aligned16(m) || !aligned16(v))
+    if (!aligned16(codes) || !aligned4(meta) || !aligned16(param) || !aligned16(m) || !aligned16(v))
         return BAGUA_ERR_ALIGNMENT;
     dim3 grid(static_cast<unsigned>((rows + 3) / 4)), block(256);
     hipStream_t s = static_cast<hipStream_t>(stream);

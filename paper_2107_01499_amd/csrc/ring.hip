@@ -299,7 +299,7 @@ extern "C" int bagua_decentralized_avg(int mode, const float* const* x_in, float
     }
     for (int i = 0; i < k; ++i) {
         if (!aligned16(x_in[i]) || !aligned16(x_out[i])) return BAGUA_ERR_ALIGNMENT;
-        if (lp && (!aligned16(xhat[i]) || !aligned16(codes[i]) || !aligned16(minmax[i]))) return BAGUA_ERR_ALIGNMENT;
+        if (lp && (!aligned16(xhat[i]) || !aligned16(codes[i]) || !aligned4(minmax[i]))) return BAGUA_ERR_ALIGNMENT;
     }
     const size_t rows = (n + kRow - 1) / kRow;
     if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
@@ -546,7 +546,7 @@ extern "C" int bagua_decentralized_avg_peers_lp(const float* const* x_in, float*
     }
     for (int i = 0; i < k; ++i)
         if (!aligned16(x_in[i]) || !aligned16(x_out[i]) || !aligned16(xhat[i]) || !aligned16(codes[i]) ||
-            !aligned16(minmax[i]))
+            !aligned4(minmax[i]))
             return BAGUA_ERR_ALIGNMENT;
     const size_t nrows = (n + kRow - 1) / kRow;
     if ((nrows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;

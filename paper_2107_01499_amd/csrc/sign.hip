@@ -348,7 +348,7 @@ extern "C" int bagua_sign_compress_ef(const float* x, float* residual, size_t n,
     rc.writes(scale, num_chunks(n, chunk) * sizeof(float));
     if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
-    if (!aligned16(x) || !aligned16(residual) || !aligned16(bits) || !aligned16(scale)) return BAGUA_ERR_ALIGNMENT;
+    if (!aligned16(x) || !aligned16(residual) || !aligned16(bits) || !aligned4(scale)) return BAGUA_ERR_ALIGNMENT;
     return launch_sign_compress(x, residual, n, chunk, bits, scale, static_cast<hipStream_t>(stream));
 }
 
@@ -364,7 +364,7 @@ extern "C" int bagua_momentum_sign_compress_ef(const float* g, const float* m, f
     rc.writes(bits, ((n + 31) / 32) * sizeof(uint32_t));
     rc.writes(scale, num_chunks(n, chunk) * sizeof(float));
     if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
-    if (!aligned16(g) || !aligned16(m) || !aligned16(residual) || !aligned16(bits) || !aligned16(scale))
+    if (!aligned16(g) || !aligned16(m) || !aligned16(residual) || !aligned16(bits) || !aligned4(scale))
         return BAGUA_ERR_ALIGNMENT;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const SignGeometry geo = sign_geometry(n, chunk, BAGUA_RPW_SIGN);

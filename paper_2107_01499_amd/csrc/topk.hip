@@ -387,7 +387,7 @@ extern "C" int bagua_compress_topk_ef(const float* x, float* residual, size_t n,
         if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     }
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
-    if (!aligned16(x) || !aligned16(residual) || !aligned16(idx) || !aligned16(val)) return BAGUA_ERR_ALIGNMENT;
+    if (!aligned16(x) || !aligned16(residual) || !aligned2(idx) || !aligned4(val)) return BAGUA_ERR_ALIGNMENT;
     const int rows = static_cast<int>(chunk / kRow);
     const int rpw = pick_rpw(rows, BAGUA_RPW_TOPK);
     dim3 grid(static_cast<unsigned>(num_chunks(n, chunk))), block(64 * ((rows + rpw - 1) / rpw));
@@ -426,8 +426,8 @@ extern "C" int bagua_decompress_reduce_recompress_topk(const uint16_t* const* id
     }
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     for (int j = 0; j < k; ++j)
-        if (!aligned16(idx_in[j]) || !aligned16(val_in[j])) return BAGUA_ERR_ALIGNMENT;
-    if (!aligned16(server_residual) || !aligned16(idx_out) || !aligned16(val_out) || !aligned16(out_fp32))
+        if (!aligned2(idx_in[j]) || !aligned4(val_in[j])) return BAGUA_ERR_ALIGNMENT;
+    if (!aligned16(server_residual) || !aligned2(idx_out) || !aligned4(val_out) || !aligned16(out_fp32))
         return BAGUA_ERR_ALIGNMENT;
     PtrTable it{}, vt{};
     for (int j = 0; j < k; ++j) {
@@ -466,7 +466,7 @@ extern "C" int bagua_decompress_topk(const uint16_t* idx, const float* val, size
         if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     }
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
-    if (!aligned16(idx) || !aligned16(val) || !aligned16(out)) return BAGUA_ERR_ALIGNMENT;
+    if (!aligned2(idx) || !aligned4(val) || !aligned16(out)) return BAGUA_ERR_ALIGNMENT;
     hipLaunchKernelGGL(k_decompress_topk, dim3(static_cast<unsigned>(num_chunks(n, chunk))), dim3(256),
                        chunk * sizeof(float), static_cast<hipStream_t>(stream), idx, val, n, static_cast<uint32_t>(chunk),
                        static_cast<uint32_t>(keep), out);

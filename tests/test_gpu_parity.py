@@ -431,6 +431,44 @@ def test_error_state_checkpoint_round_trip(bg):
         assert torch.equal(a.view(torch.int32), b.view(torch.int32))
 
 
+@pytest.mark.parametrize("codec", [0, 1])
+def test_server_step_on_partition_slices(bg, oracle, codec):
+    """ScatterReduce view: server p processes partition p only.  Running the server step on the k partition slices
+    (three chunks each, so the metadata slices are only 8- or 4-byte aligned) equals one pass over the whole bucket."""
+    k, C, per = 4, 256, 3
+    n = k * per * C
+    nc = n // C
+    xs = [vals(n, 70 + j) for j in range(k)]
+    if codec == 0:
+        enc = [oracle.compress_minmax_u8(x, None, C) for x in xs]
+        codes_g = [torch.from_numpy(e[0]).cuda() for e in enc]
+        want = oracle.drr_minmax_u8([e[0] for e in enc], [e[1] for e in enc], np.zeros(n, np.float32), C)
+        cw, mw = 1, 2          # code units and metadata floats per element / per chunk
+        codes_out = torch.empty(n, dtype=torch.uint8, device="cuda")
+    else:
+        enc = [oracle.sign_compress_ef(x, None, C) for x in xs]
+        codes_g = [torch.from_numpy(e[0].view(np.int32)).cuda() for e in enc]
+        want = oracle.drr_sign([e[0] for e in enc], [e[1] for e in enc], np.zeros(n, np.float32), n, C)
+        cw, mw = 1.0 / 32, 1
+        codes_out = torch.empty(n // 32, dtype=torch.int32, device="cuda")
+    meta_g = [torch.from_numpy(e[1]).cuda() for e in enc]
+    meta_out = torch.empty(mw * nc, device="cuda")
+    eps, out = torch.zeros(n, device="cuda"), torch.empty(n, device="cuda")
+    odd_slices = 0
+    for p in range(k):
+        lo, hi = p * per * C, (p + 1) * per * C
+        cl, ch = int(lo * cw), int(hi * cw)
+        ml, mh = mw * p * per, mw * (p + 1) * per
+        odd_slices += meta_g[0][ml:mh].data_ptr() % 16 != 0
+        bg.bagua_decompress_reduce_recompress(codec, [c[cl:ch] for c in codes_g], [m[ml:mh] for m in meta_g], eps[lo:hi],
+                                              hi - lo, C, codes_out[cl:ch], meta_out[ml:mh], out[lo:hi])
+    torch.cuda.synchronize()
+    assert odd_slices > 0      # the case this test is about did occur
+    assert np.array_equal(host(codes_out).view(want[0].dtype), want[0])
+    assert np.array_equal(host(meta_out).view(np.uint32), want[1].view(np.uint32))
+    assert np.array_equal(host(out).view(np.uint32), want[2].view(np.uint32))
+
+
 def test_hip_graph_replay_matches_eager(bg, oracle):
     """The entry points allocate nothing and only enqueue kernels, so a step can be captured into a HIP graph.
     Replayed several times with eager work and synchronisation in between, every replay must equal the oracle."""
