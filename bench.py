@@ -60,6 +60,7 @@ def parse_args():
                     "(decode of the server's codes fused into an SGD-momentum update of every worker's replica), "
                     "adam_step (the same decode fused into an Adam update), onebit_adam (compression stage of 1-bit Adam: momentum "
                     "sign compression on every worker and the decode + frozen-variance update), "
+                    "lp_shares (D_LP_S on a ring as the k single-peer shares a sharded run would execute: encode, then apply + mix), "
                     "peer_fp / peer_lp (full- / low-precision averaging with one chosen peer per worker), reduce_compress (intra-node "
                     "stage of hierarchical C_LP_S: 4 local workers averaged uncompressed, leader compresses), topk (C_LP_S with "
                     "the per-chunk top-K codec, keep = chunk/32: worker side and server side)")
@@ -98,6 +99,8 @@ class Workload:
             self.prims = self.prims + ["peer_fp"]
         if "peer_lp" in extras and "ring_lp" in self.prims:
             self.prims = self.prims + ["peer_lp"]
+        if "lp_shares" in extras and "ring_lp" in self.prims:
+            self.prims = self.prims + ["lp_encode", "lp_apply_mix"]
         k, C, SC, cfg = self.k, self.C, self.SC, w["cfg"]
         dev = torch.device("cuda:0")
         f32 = dict(dtype=torch.float32, device=dev)
@@ -243,6 +246,10 @@ class Workload:
             if has("ring_lp"):
                 self.lp_codes = [views(z(n, **u8)) for _ in range(k)]
                 self.lp_minmax = [views(z(2 * nc, **f32), C, 2) for _ in range(k)]
+            if has("lp_encode"):       # every peer's own copies of its two neighbours' public replicas
+                self.nb_left = [views(base.clone()) for _ in range(k)]
+                self.nb_right = [views(base.clone()) for _ in range(k)]
+                self.sh_hat = [views(base.clone()) for _ in range(k)]
         self.step_no = 0
         torch.cuda.synchronize()
 
@@ -254,7 +261,7 @@ class Workload:
         return {"flatten": 8.0, "flatten_compress": 13.0 + wb + 8.0 / C, "compress_minmax": 13.0 + 8.0 / C, "drr_minmax": k + 13.0 + 8.0 * (k + 1) / C,
                 "compress_topk": 12.0 + 6.0 * keep / C, "drr_topk": 12.0 + 6.0 * (k + 1) * keep / C,
                 "sgd_step": 17.0 + 8.0 / C, "adam_step": 25.0 + 8.0 / C, "momentum_sign": 16.125 + 4.0 / SC,
-                "adam_frozen_step": 16.125 + 4.0 / SC, "reduce_compress": 4.0 * 4 + 9.0 + 8.0 / C, "peer_fp": 8.0, "peer_lp": 17.0 + 8.0 / C, "ring_fp": 8.0, "ring_lp": 17.0 + 8.0 / C, "sign_compress": 12.125 + 4.0 / SC,
+                "adam_frozen_step": 16.125 + 4.0 / SC, "reduce_compress": 4.0 * 4 + 9.0 + 8.0 / C, "peer_fp": 8.0, "peer_lp": 17.0 + 8.0 / C, "lp_encode": 13.0 + 8.0 / C, "lp_apply_mix": 30.0 + 16.0 / C, "ring_fp": 8.0, "ring_lp": 17.0 + 8.0 / C, "sign_compress": 12.125 + 4.0 / SC,
                 "drr_sign": k / 8.0 + 12.125 + 4.0 * (k + 1) / SC}
 
     def grad_bytes(self):
@@ -264,7 +271,7 @@ class Workload:
     def algo_bytes(self):
         n, k = self.n_elems, self.k
         units = {"flatten": n * k, "flatten_compress": n * k, "compress_minmax": n * k, "drr_minmax": n, "ring_fp": n * k, "ring_lp": n * k,
-                 "sign_compress": n * k, "drr_sign": n, "sgd_step": n * k, "adam_step": n * k, "momentum_sign": n * k, "adam_frozen_step": n * k, "peer_fp": n * k, "peer_lp": n * k, "reduce_compress": n * (k // 4),
+                 "sign_compress": n * k, "drr_sign": n, "sgd_step": n * k, "adam_step": n * k, "momentum_sign": n * k, "adam_frozen_step": n * k, "peer_fp": n * k, "peer_lp": n * k, "lp_encode": n * k, "lp_apply_mix": n * k, "reduce_compress": n * (k // 4),
                  "compress_topk": n * k, "drr_topk": n}
         bpe = self.bytes_per_element()
         return {p: bpe[p] * units[p] for p in self.prims}
@@ -272,7 +279,7 @@ class Workload:
     def launches(self):
         U, k = len(self.units), self.k
         per = {"flatten": U * k, "flatten_compress": U * k, "compress_minmax": U * k, "drr_minmax": U, "ring_fp": U, "ring_lp": U,
-               "sign_compress": U * k, "drr_sign": U, "sgd_step": U * k, "adam_step": U * k, "momentum_sign": U * k, "adam_frozen_step": U * k, "peer_fp": U, "peer_lp": U, "reduce_compress": U * (k // 4),
+               "sign_compress": U * k, "drr_sign": U, "sgd_step": U * k, "adam_step": U * k, "momentum_sign": U * k, "adam_frozen_step": U * k, "peer_fp": U, "peer_lp": U, "lp_encode": U * k, "lp_apply_mix": U * k, "reduce_compress": U * (k // 4),
                "compress_topk": U * k, "drr_topk": U}
         return {p: per[p] for p in self.prims}
 
@@ -284,7 +291,7 @@ class Workload:
                 "drr_sign": "k_drr_sign<4,true,true>", "sgd_step": "k_decompress_sgd<0,true,false>",
                 "adam_step": "k_decompress_adam<0,false,false>", "momentum_sign": "k_sign_compress<2,true,true>",
                 "adam_frozen_step": "k_decompress_adam<1,true,false>",
-                "peer_fp": "k_peer_avg_fp", "peer_lp": "k_peer_avg_lp<2>", "reduce_compress": "k_reduce_compress_minmax<2,true>",
+                "peer_fp": "k_peer_avg_fp", "peer_lp": "k_peer_avg_lp<2>", "lp_encode": "k_lp_encode<2>", "lp_apply_mix": "k_lp_apply_mix<true,true,false>", "reduce_compress": "k_reduce_compress_minmax<2,true>",
                 "compress_topk": "k_compress_topk<2,true>", "drr_topk": "k_drr_topk<2,true,true>"}[p]
 
     # ---- one pass of the hot path ------------------------------------------------------------------
@@ -374,6 +381,17 @@ class Workload:
                                                         [self.lp_codes[i][u] for i in range(k)],
                                                         [self.lp_minmax[i][u] for i in range(k)],
                                                         [i ^ 1 for i in range(k)], C)
+            elif p == "lp_encode":
+                for i in range(k):
+                    for u in range(U):
+                        bg.bagua_lp_encode(self.rep_lp[dst][i][u], self.sh_hat[i][u], C, self.lp_codes[i][u], self.lp_minmax[i][u])
+            elif p == "lp_apply_mix":
+                for i in range(k):
+                    le, ri = (i - 1) % k, (i + 1) % k
+                    for u in range(U):
+                        bg.bagua_lp_apply_mix(self.rep_lp[dst][i][u], self.sh_hat[i][u], self.nb_left[i][u], self.nb_right[i][u],
+                                              self.lp_codes[le][u], self.lp_minmax[le][u], self.lp_codes[ri][u],
+                                              self.lp_minmax[ri][u], C, self.rep_lp[src][i][u])
             elif p == "ring_fp":
                 for u in range(U):
                     bg.bagua_decentralized_avg(bg.AVG_FP, [self.rep_fp[src][i][u] for i in range(k)],

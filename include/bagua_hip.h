@@ -158,6 +158,28 @@ int bagua_decentralized_avg(int mode, const float* const* x_in, float* const* x_
                             void* stream);
 
 /*
+ * One peer's share of D_LP_S on a ring (Section 3.2, D_LP_S; Section 3.4: a peer compresses before sending and
+ * decompresses after receiving), i.e. what a single GPU runs when every peer has a GPU of its own.  Same arithmetic
+ * as bagua_decentralized_avg in LP mode, which is these two steps for all k peers at once.
+ *
+ * bagua_lp_encode: the peer publishes its difference and advances its own public copy:
+ *   codes, minmax = Q(x - xhat)  (no error feedback);   xhat <- xhat + decode(codes, minmax).
+ *
+ * bagua_lp_apply_mix: after the neighbours' codes have arrived, the peer advances its copies of their public
+ * replicas and forms its new replica (xhat_own is the copy bagua_lp_encode has already advanced):
+ *   xhat_left <- xhat_left + decode(codes_left);   xhat_right <- xhat_right + decode(codes_right);
+ *   x_out = ((xhat_left + xhat_own) + xhat_right) * fl(1/3) + (x - xhat_own).
+ *   left = peer i-1, right = peer i+1.  codes_* / minmax_* may be NULL together: that copy is current and only read.
+ *   Ring of two: pass the other peer's copy as both xhat_left and xhat_right with codes_right = NULL; it is
+ *   advanced once and counted twice.  Ring of one: pass xhat_own for both neighbours, no codes.
+ *   x, xhat_*, x_out: device fp32[n]; codes_*: device u8[n]; minmax_*: device fp32[2*nc].
+ */
+int bagua_lp_encode(const float* x, float* xhat, size_t n, size_t chunk, uint8_t* codes, float* minmax, void* stream);
+int bagua_lp_apply_mix(const float* x, const float* xhat_own, float* xhat_left, float* xhat_right,
+                       const uint8_t* codes_left, const float* minmax_left, const uint8_t* codes_right,
+                       const float* minmax_right, size_t n, size_t chunk, float* x_out, void* stream);
+
+/*
  * C_FP_S (Section 3.2, centralised full precision: every worker receives the aggregate of all replicas, the
  * Allreduce result), as an average: out = (x[0] + x[1] + ...) * fl(1/k), summed in ascending order.
  *   x    host[k] of device fp32[n], read only;   out  device fp32[n], must not overlap any input

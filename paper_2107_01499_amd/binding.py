@@ -27,7 +27,7 @@ EXPORTS = (
     "bagua_decompress_sgd_step", "bagua_decentralized_avg_peers", "bagua_reduce_compress_minmax_u8",
     "bagua_bucket_unflatten_run", "bagua_compress_topk_ef", "bagua_decompress_reduce_recompress_topk",
     "bagua_decompress_topk", "bagua_centralized_avg_fp", "bagua_decentralized_avg_peers_lp",
-    "bagua_decompress_adam_step", "bagua_momentum_sign_compress_ef",
+    "bagua_decompress_adam_step", "bagua_momentum_sign_compress_ef", "bagua_lp_encode", "bagua_lp_apply_mix",
 )
 
 
@@ -69,6 +69,8 @@ def _load():
     cf = ctypes.c_float
     lib.bagua_decompress_adam_step.argtypes = [i32, vp, vp, sz, sz, vp, vp, vp, cf, cf, cf, cf, cf, i32, vp]
     lib.bagua_momentum_sign_compress_ef.argtypes = [vp, vp, cf, vp, sz, sz, vp, vp, vp]
+    lib.bagua_lp_encode.argtypes = [vp, vp, sz, sz, vp, vp, vp]
+    lib.bagua_lp_apply_mix.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, sz, vp, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = i32
     return lib
@@ -203,6 +205,24 @@ def bagua_decentralized_avg(mode, x_in, x_out, xhat=None, codes=None, minmax=Non
         None if codes is None else _ptr_array(codes, torch.uint8, n),
         None if minmax is None else _ptr_array(minmax, torch.float32, 8 * num_chunks(n, chunk)), k, n, chunk,
         _stream(stream)))
+
+
+def bagua_lp_encode(x, xhat, chunk, codes, minmax, stream=None):
+    n = x.numel()
+    _check("bagua_lp_encode", _lib.bagua_lp_encode(
+        _ptr(x, torch.float32), _ptr(xhat, torch.float32, 4 * n), n, chunk, _ptr(codes, torch.uint8, n),
+        _ptr(minmax, torch.float32, 8 * num_chunks(n, chunk)), _stream(stream)))
+
+
+def bagua_lp_apply_mix(x, xhat_own, xhat_left, xhat_right, codes_left, minmax_left, codes_right, minmax_right, chunk,
+                       x_out, stream=None):
+    n = x.numel()
+    mb = 8 * num_chunks(n, chunk)
+    _check("bagua_lp_apply_mix", _lib.bagua_lp_apply_mix(
+        _ptr(x, torch.float32), _ptr(xhat_own, torch.float32, 4 * n), _ptr(xhat_left, torch.float32, 4 * n),
+        _ptr(xhat_right, torch.float32, 4 * n), _ptr(codes_left, torch.uint8, n), _ptr(minmax_left, torch.float32, mb),
+        _ptr(codes_right, torch.uint8, n), _ptr(minmax_right, torch.float32, mb), n, chunk,
+        _ptr(x_out, torch.float32, 4 * n), _stream(stream)))
 
 
 def bagua_reduce_compress_minmax_u8(xs, residual, chunk, codes, minmax, stream=None):

@@ -593,3 +593,112 @@ extern "C" int bagua_decentralized_avg_peers_lp(const float* const* x_in, float*
     hipLaunchKernelGGL(k_peer_mix_lp, dim3(static_cast<unsigned>((nrows + 3) / 4), k), dim3(256), 0, s, mix, n);
     return launch_status();
 }
+
+// ------------------------------------------------------------------------------------------ one peer's share of D_LP_S
+// What a single GPU does in a sharded run of the low-precision ring (Sections 3.2 and 3.4): it encodes
+// its own difference and advances its own public copy (k_lp_encode, 13 bytes per element), receives the
+// two neighbours' codes, advances its copies of their public replicas and forms its own new replica
+// (k_lp_apply_mix, 30 bytes per element).  The arithmetic is that of the all-peers kernel above.
+namespace bagua {
+
+// APPLY_L / APPLY_R: that neighbour's codes are decoded into its copy (otherwise the copy is current).
+// SAME: both neighbours are one peer (ring of two): one copy, advanced once, counted twice.
+template <bool APPLY_L, bool APPLY_R, bool SAME>
+__global__ void __launch_bounds__(256)
+k_lp_apply_mix(const float* __restrict__ x, const float* __restrict__ h_own, float* h_left, float* h_right,
+               const uint8_t* __restrict__ c_left, const float* __restrict__ m_left,
+               const uint8_t* __restrict__ c_right, const float* __restrict__ m_right, size_t n, uint32_t chunk,
+               float third, float* __restrict__ x_out)
+{
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const size_t e0 = row * kRow;
+    if (e0 >= n) return;
+    const size_t c = e0 / chunk;
+    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const f4 xi = load_row(x + e0, lane, remain, 0.0f);
+    const f4 ho = load_row(h_own + e0, lane, remain, 0.0f);
+    auto advanced = [&](float* h, const uint8_t* codes, const float* mm, bool apply) {
+        f4 v = load_row(h + e0, lane, remain, 0.0f);
+        if (apply) {
+            const float mn = mm[2 * c], step = minmax_step(mn, mm[2 * c + 1]);
+            const uint32_t w = load_codes_row(codes + e0, lane, remain);
+            v.x = v.x + (mn + byte_to_float(w, 0) * step);
+            v.y = v.y + (mn + byte_to_float(w, 1) * step);
+            v.z = v.z + (mn + byte_to_float(w, 2) * step);
+            v.w = v.w + (mn + byte_to_float(w, 3) * step);
+            store_row(h + e0, lane, remain, v);
+        }
+        return v;
+    };
+    const f4 hl = advanced(h_left, c_left, m_left, APPLY_L);
+    const f4 hr = SAME ? hl : advanced(h_right, c_right, m_right, APPLY_R);
+    const f4 s = add4(add4(hl, ho), hr);
+    store_row(x_out + e0, lane, remain, add4(mul4(s, third), sub4(xi, ho)));
+}
+
+}  // namespace bagua
+
+extern "C" int bagua_lp_encode(const float* x, float* xhat, size_t n, size_t chunk, uint8_t* codes, float* minmax,
+                               void* stream)
+{
+    if (!x || !xhat || !codes || !minmax || n == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
+    RangeCheck rc;
+    rc.reads(x, n * sizeof(float));
+    rc.writes(xhat, n * sizeof(float));
+    rc.writes(codes, n);
+    rc.writes(minmax, 2 * num_chunks(n, chunk) * sizeof(float));
+    if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(xhat) || !aligned16(codes) || !aligned4(minmax)) return BAGUA_ERR_ALIGNMENT;
+    const int rows = static_cast<int>(chunk / kRow);
+    const int rpw = pick_rpw(rows, BAGUA_RPW_COMPRESS);
+    dim3 grid(static_cast<unsigned>(num_chunks(n, chunk))), block(64 * ((rows + rpw - 1) / rpw));
+    BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_lp_encode<RPW>), grid, block, 0, static_cast<hipStream_t>(stream), x, xhat,
+                                               n, static_cast<uint32_t>(chunk), codes, minmax))
+    return launch_status();
+}
+
+extern "C" int bagua_lp_apply_mix(const float* x, const float* xhat_own, float* xhat_left, float* xhat_right,
+                                  const uint8_t* codes_left, const float* minmax_left, const uint8_t* codes_right,
+                                  const float* minmax_right, size_t n, size_t chunk, float* x_out, void* stream)
+{
+    if (!x || !xhat_own || !xhat_left || !xhat_right || !x_out || n == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
+    if ((codes_left == nullptr) != (minmax_left == nullptr) || (codes_right == nullptr) != (minmax_right == nullptr))
+        return BAGUA_ERR_INVALID_ARG;
+    const bool same = xhat_left == xhat_right;
+    if (same && codes_right) return BAGUA_ERR_INVALID_ARG;  // one copy is advanced once, through codes_left
+    const size_t bytes = n * sizeof(float), mbytes = 2 * num_chunks(n, chunk) * sizeof(float);
+    RangeCheck rc;
+    rc.reads(x, bytes);
+    rc.reads(codes_left, n);
+    rc.reads(minmax_left, mbytes);
+    rc.reads(codes_right, n);
+    rc.reads(minmax_right, mbytes);
+    rc.writes(x_out, bytes);
+    // a neighbour copy that is not advanced is only read (on a ring of one it is the peer's own copy)
+    if (codes_left) rc.writes(xhat_left, bytes); else rc.reads(xhat_left, bytes);
+    if (!same) { if (codes_right) rc.writes(xhat_right, bytes); else rc.reads(xhat_right, bytes); }
+    rc.reads(xhat_own, bytes);
+    if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    const size_t rows = (n + kRow - 1) / kRow;
+    if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(xhat_own) || !aligned16(xhat_left) || !aligned16(xhat_right) || !aligned16(codes_left) ||
+        !aligned16(codes_right) || !aligned4(minmax_left) || !aligned4(minmax_right) || !aligned16(x_out))
+        return BAGUA_ERR_ALIGNMENT;
+    dim3 grid(static_cast<unsigned>((rows + 3) / 4)), block(256);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint32_t ch = static_cast<uint32_t>(chunk);
+    const float third = 1.0f / 3.0f;
+#define BAGUA_MIX(L, R, S)                                                                                            \
+    hipLaunchKernelGGL((k_lp_apply_mix<L, R, S>), grid, block, 0, s, x, xhat_own, xhat_left, xhat_right, codes_left, \
+                       minmax_left, codes_right, minmax_right, n, ch, third, x_out)
+    const bool al = codes_left != nullptr, ar = codes_right != nullptr;
+    if (same) { if (al) BAGUA_MIX(true, false, true); else BAGUA_MIX(false, false, true); }
+    else if (al && ar) BAGUA_MIX(true, true, false);
+    else if (al) BAGUA_MIX(true, false, false);
+    else if (ar) BAGUA_MIX(false, true, false);
+    else BAGUA_MIX(false, false, false);
+#undef BAGUA_MIX
+    return launch_status();
+}

@@ -122,6 +122,16 @@ def test_peer_validation_without_gpu(bg):
     assert adam(0, 0x1000, 0x1000, 16, 256, 0x2000, 0x3000, None, 0.1, 0.9, 0.999, 1e-8, 0.0, 1, None) == 1
     assert adam(2, 0x1000, 0x1000, 16, 256, 0x2000, 0x3000, 0x4000, 0.1, 0.9, 0.999, 1e-8, 0.0, 0, None) == 1
     assert adam(0, 0x1000, 0x1000, 16, 256, 0x2004, 0x3000, 0x4000, 0.1, 0.9, 0.999, 1e-8, 0.0, 0, None) == 2
+    enc, mix = lib.bagua_lp_encode, lib.bagua_lp_apply_mix
+    X, H, HL, HR, CL, ML, CR, MR, O = (0x100000 * i for i in range(1, 10))
+    assert enc(X, X, 64, 256, CL, ML, None) == 1                                  # xhat aliases x
+    assert enc(X, H, 64, 100, CL, ML, None) == 1
+    assert enc(X, H + 4, 64, 256, CL, ML, None) == 2
+    assert mix(X, H, HL, HR, CL, None, CR, MR, 64, 256, O, None) == 1             # codes without statistics
+    assert mix(X, H, HL, HL, CL, ML, CR, MR, 64, 256, O, None) == 1               # one copy, two code streams
+    assert mix(X, H, HL, HR, CL, ML, CR, MR, 64, 256, HL, None) == 1              # output aliases a copy
+    assert mix(X, H, H, HR, CL, ML, CR, MR, 64, 256, O, None) == 1                # own copy would be advanced twice
+    assert mix(X, H, HL, HR, CL, ML + 2, CR, MR, 64, 256, O, None) == 2
     ms = lib.bagua_momentum_sign_compress_ef
     assert ms(0x1000, None, 0.9, None, 16, 256, 0x5000, 0x6000, None) == 1
     assert ms(0x1000, 0x2000, 0.9, 0x1000, 16, 256, 0x5000, 0x6000, None) == 1      # residual aliases g
