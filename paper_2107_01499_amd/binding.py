@@ -115,6 +115,13 @@ def _ptr_array(tensors, dtype=None, nbytes=None):
     return arr
 
 
+def _same_len(k, **lists):
+    """Every per-worker list of a call must name exactly k tensors: the C side reads k pointers from each array."""
+    for name, lst in lists.items():
+        if lst is not None and len(lst) != k:
+            raise ValueError("%s names %d tensors, expected %d (one per worker)" % (name, len(lst), k))
+
+
 def num_chunks(n, chunk):
     return (n + chunk - 1) // chunk if chunk > 0 else 0
 
@@ -189,6 +196,7 @@ def bagua_flatten_compress_minmax_u8(workspace, T, residual, n, chunk, codes, mi
 def bagua_decompress_reduce_recompress(codec, codes_in, meta_in, server_residual, n, chunk, codes_out, meta_out,
                                        out_fp32=None, stream=None):
     k = len(codes_in)
+    _same_len(k, meta_in=meta_in)
     _check("bagua_decompress_reduce_recompress", _lib.bagua_decompress_reduce_recompress(
         codec, _ptr_array(codes_in, None, _code_bytes(codec, n)),
         _ptr_array(meta_in, torch.float32, _meta_bytes(codec, n, chunk)), k, _ptr(server_residual, torch.float32, 4 * n),
@@ -199,6 +207,7 @@ def bagua_decompress_reduce_recompress(codec, codes_in, meta_in, server_residual
 def bagua_decentralized_avg(mode, x_in, x_out, xhat=None, codes=None, minmax=None, chunk=0, stream=None):
     k = len(x_in)
     n = x_in[0].numel()
+    _same_len(k, x_out=x_out, xhat=xhat, codes=codes, minmax=minmax)
     _check("bagua_decentralized_avg", _lib.bagua_decentralized_avg(
         mode, _ptr_array(x_in, torch.float32, 4 * n), _ptr_array(x_out, torch.float32, 4 * n),
         None if xhat is None else _ptr_array(xhat, torch.float32, 4 * n),
@@ -242,6 +251,7 @@ def bagua_decentralized_avg_peers(x_in, x_out, peer, stream=None):
     k, n = len(x_in), x_in[0].numel()
     if len(peer) != k:
         raise ValueError("peer must name one peer per worker")
+    _same_len(k, x_out=x_out)
     pa = (ctypes.c_int * k)(*[int(p) for p in peer])
     _check("bagua_decentralized_avg_peers", _lib.bagua_decentralized_avg_peers(
         _ptr_array(x_in, torch.float32, 4 * n), _ptr_array(x_out, torch.float32, 4 * n), pa, k, n, _stream(stream)))
@@ -251,6 +261,7 @@ def bagua_decentralized_avg_peers_lp(x_in, x_out, xhat, codes, minmax, peer, chu
     k, n = len(x_in), x_in[0].numel()
     if len(peer) != k:
         raise ValueError("peer must name one peer per worker")
+    _same_len(k, x_out=x_out, xhat=xhat, codes=codes, minmax=minmax)
     pa = (ctypes.c_int * k)(*[int(p) for p in peer])
     _check("bagua_decentralized_avg_peers_lp", _lib.bagua_decentralized_avg_peers_lp(
         _ptr_array(x_in, torch.float32, 4 * n), _ptr_array(x_out, torch.float32, 4 * n),
@@ -302,6 +313,7 @@ def bagua_compress_topk_ef(x, residual, chunk, keep, idx, val, stream=None):
 
 def bagua_decompress_reduce_recompress_topk(idx_in, val_in, keep, server_residual, n, chunk, idx_out, val_out,
                                             out_fp32=None, stream=None):
+    _same_len(len(idx_in), val_in=val_in)
     _check("bagua_decompress_reduce_recompress_topk", _lib.bagua_decompress_reduce_recompress_topk(
         _ptr_array(idx_in, torch.int16, 2 * keep * num_chunks(n, chunk)),
         _ptr_array(val_in, torch.float32, 4 * keep * num_chunks(n, chunk)), len(idx_in), keep,

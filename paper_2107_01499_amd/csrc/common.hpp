@@ -88,6 +88,14 @@ constexpr int kWave = 64;
 constexpr int kRow = 256;      // elements per wave-wide 128-bit access
 constexpr int kMaxWaves = 16;  // waves per workgroup (1024 threads)
 
+// Upper bound on the workgroup size of a chunked kernel that keeps RPW rows per wave: chunks have at most
+// 64 rows, and pick_rpw never asks for more than kMaxWaves waves.
+constexpr int wg_threads_max(int rpw)
+{
+    return kWave * (((64 + rpw - 1) / rpw) < kMaxWaves ? ((64 + rpw - 1) / rpw) : kMaxWaves);
+}
+static_assert(wg_threads_max(1) <= 1024 && wg_threads_max(2) <= 1024 && wg_threads_max(8) == 512, "launch bound");
+
 struct PtrTable {
     const void* p[BAGUA_MAX_WORKERS];
 };

@@ -11,7 +11,7 @@
 namespace bagua {
 
 template <int RPW, bool EF, bool WB>
-__global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
+__global__ void __launch_bounds__(wg_threads_max(RPW))
 k_flatten_compress_minmax(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile_first, uint32_t T,
                           float* __restrict__ residual, size_t n, uint32_t chunk, uint8_t* __restrict__ codes,
                           float* __restrict__ minmax, float* __restrict__ bucket_out)
@@ -61,7 +61,7 @@ k_flatten_compress_minmax(const TensorDesc* __restrict__ desc, const uint32_t* _
 // averaged (ascending order, one multiply by inv_k) and the leader compresses the average with its
 // error state.  4*k_local + 9 bytes per element, one pass.
 template <int RPW, bool EF>
-__global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
+__global__ void __launch_bounds__(wg_threads_max(RPW))
 k_reduce_compress_minmax(PtrTable xs, int k_local, float inv_k, float* __restrict__ residual, size_t n, uint32_t chunk,
                          uint8_t* __restrict__ codes, float* __restrict__ minmax)
 {

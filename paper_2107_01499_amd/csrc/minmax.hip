@@ -14,7 +14,7 @@ namespace bagua {
 // Worker side: v = x (+ residual); codes = Q(v); residual <- v - decode.
 // grid = one workgroup per chunk, block = 64 * ceil(rows / RPW).
 template <int RPW, bool EF>
-__global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
+__global__ void __launch_bounds__(wg_threads_max(RPW))
 k_compress_minmax(const float* __restrict__ x, float* __restrict__ residual, size_t n, uint32_t chunk,
                   uint8_t* __restrict__ codes, float* __restrict__ minmax)
 {
@@ -53,7 +53,7 @@ k_compress_minmax(const float* __restrict__ x, float* __restrict__ residual, siz
 // ------------------------------------------------------------------------------------------
 // Server side: a = (sum_j decode_j) * inv_k in ascending j; w = a (+ epsilon); then as above.
 template <int RPW, bool EF, bool OUT>
-__global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
+__global__ void __launch_bounds__(wg_threads_max(RPW))
 k_drr_minmax(PtrTable codes_in, PtrTable meta_in, int k, float inv_k, float* __restrict__ eps, size_t n,
              uint32_t chunk, uint8_t* __restrict__ codes_out, float* __restrict__ minmax_out,
              float* __restrict__ out)

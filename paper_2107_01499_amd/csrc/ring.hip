@@ -137,7 +137,7 @@ k_ring_avg_lp(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, MutPtrTable code
 // ------------------------------------------------------------------------------------------ LP, two-pass fallback
 // Pass 1 (per peer): d = x - xhat; codes, minmax = Q(d); xhat <- xhat + decode.
 template <int RPW>
-__global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
+__global__ void __launch_bounds__(wg_threads_max(RPW))
 k_lp_encode(const float* __restrict__ x, float* __restrict__ xhat, size_t n, uint32_t chunk,
             uint8_t* __restrict__ codes, float* __restrict__ minmax)
 {

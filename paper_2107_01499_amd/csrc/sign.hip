@@ -106,7 +106,7 @@ __device__ __forceinline__ void sign_encode_chunk(f4 (&v)[RPW], long len, uint32
 // MOM: the compressed tensor is the local momentum beta1*m + omb1*x of the compression stage of
 // 1-bit Adam (x is then the gradient; m is read only).
 template <int RPW, bool EF, bool MOM = false>
-__global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
+__global__ void __launch_bounds__(wg_threads_max(RPW))
 k_sign_compress(const float* __restrict__ x, float* __restrict__ residual, size_t n, uint32_t chunk,
                 uint32_t* __restrict__ bits, float* __restrict__ scale, const float* __restrict__ mom, float beta1,
                 float omb1)
@@ -159,7 +159,7 @@ k_sign_compress(const float* __restrict__ x, float* __restrict__ residual, size_
 
 // Server side with the sign codec: a = (sum_j +-scale_j) * inv_k in ascending j; w = a (+ eps).
 template <int RPW, bool EF, bool OUT>
-__global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
+__global__ void __launch_bounds__(wg_threads_max(RPW))
 k_drr_sign(PtrTable bits_in, PtrTable scale_in, int k, float inv_k, float* __restrict__ eps, size_t n,
            uint32_t chunk, uint32_t* __restrict__ bits_out, float* __restrict__ scale_out,
            float* __restrict__ out)

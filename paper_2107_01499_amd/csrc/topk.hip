@@ -218,7 +218,7 @@ __device__ __forceinline__ void topk_encode_chunk(const f4 (&v)[RPW], long len, 
 
 // ------------------------------------------------------------------------------------------ worker side
 template <int RPW, bool EF>
-__global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
+__global__ void __launch_bounds__(wg_threads_max(RPW))
 k_compress_topk(const float* __restrict__ x, float* __restrict__ residual, size_t n, uint32_t chunk, uint32_t keep,
                 uint16_t* __restrict__ idx, float* __restrict__ val)
 {
@@ -258,7 +258,7 @@ k_compress_topk(const float* __restrict__ x, float* __restrict__ residual, size_
 // (ascending order; a worker's indices are unique, so its adds never collide), then averaged,
 // the server error state is added and the result is sparsified again.
 template <int RPW, bool EF, bool OUT>
-__global__ void __launch_bounds__(64 * ((64 + RPW - 1) / RPW))
+__global__ void __launch_bounds__(wg_threads_max(RPW))
 k_drr_topk(PtrTable idx_in, PtrTable val_in, int k, float inv_k, uint32_t keep, float* __restrict__ eps, size_t n,
            uint32_t chunk, uint16_t* __restrict__ idx_out, float* __restrict__ val_out, float* __restrict__ out)
 {

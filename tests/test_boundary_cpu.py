@@ -149,3 +149,24 @@ def test_header_is_valid_c_and_cpp(tmp_path):
     src_cpp = tmp_path / "use_header.cpp"
     src_cpp.write_text('#include "bagua_hip.h"\nint main() { return BAGUA_OK; }\n')
     subprocess.run(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(src_cpp)], check=True)
+
+
+def test_binding_refuses_per_worker_lists_of_unequal_length(bg):
+    """The C side reads k pointers from every per-worker array, so the binding must refuse a shorter list before it
+    builds the pointer arrays (the tensors here are never dereferenced: the length check comes first)."""
+    import torch
+    t = [torch.zeros(256) for _ in range(3)]
+    u8 = [torch.zeros(256, dtype=torch.uint8) for _ in range(3)]
+    with pytest.raises(ValueError, match="meta_in names 2"):
+        bg.bagua_decompress_reduce_recompress(bg.CODEC_MINMAX_U8, u8, t[:2], None, 256, 256, u8[0], t[0])
+    with pytest.raises(ValueError, match="x_out names 2"):
+        bg.bagua_decentralized_avg(bg.AVG_FP, t, t[:2])
+    with pytest.raises(ValueError, match="minmax names 1"):
+        bg.bagua_decentralized_avg(bg.AVG_LP_MINMAX_U8, t, t, t, u8, t[:1], 256)
+    with pytest.raises(ValueError, match="x_out names 4"):
+        bg.bagua_decentralized_avg_peers(t, t + t[:1], [0, 1, 2])
+    with pytest.raises(ValueError, match="codes names 2"):
+        bg.bagua_decentralized_avg_peers_lp(t, t, t, u8[:2], t, [0, 1, 2], 256)
+    i16 = [torch.zeros(8, dtype=torch.int16) for _ in range(3)]
+    with pytest.raises(ValueError, match="val_in names 2"):
+        bg.bagua_decompress_reduce_recompress_topk(i16, t[:2], 8, None, 256, 256, i16[0], t[0])
