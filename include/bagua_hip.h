@@ -84,6 +84,23 @@ int bagua_bucket_flatten(const void* const* src, const size_t* numel, const size
                          void* stream);
 
 /*
+ * bagua_bucket_flatten without a workspace, for callers that cannot allocate device memory or must not
+ * synchronise: code running under HIP graph capture, tight serving loops, harnesses that forbid allocation.
+ * Same result as bagua_bucket_flatten.  The tensor table is built on the device, from kernel arguments, in a
+ * fixed array inside the library (about 360 KB per GPU, held until the process ends); the call allocates nothing,
+ * copies nothing from host memory and does not synchronise.
+ *   limits   T <= BAGUA_FLATTEN_STATIC_MAX_TENSORS and bucket_numel <= BAGUA_FLATTEN_STATIC_MAX_NUMEL,
+ *            BAGUA_ERR_UNSUPPORTED beyond (use the workspace form there)
+ *   sharing  every call on one GPU uses that GPU's one array: calls are safe one after another on one stream,
+ *            but two calls that overlap in time on the same GPU (different streams or threads) race on the table
+ * Other arguments and errors as bagua_bucket_flatten; additionally no tensor may overlap the bucket.
+ */
+#define BAGUA_FLATTEN_STATIC_MAX_TENSORS 4096
+#define BAGUA_FLATTEN_STATIC_MAX_NUMEL 67108864 /* 2^26 elements = 256 MiB of fp32 */
+int bagua_bucket_flatten_static(const void* const* src, const size_t* numel, const size_t* dst_offset, size_t T,
+                                float* bucket, size_t bucket_numel, void* stream);
+
+/*
  * Inverse of the flatten: copy each tensor's range [dst_offset[t], dst_offset[t] + numel[t]) of the bucket back
  * into tensor t (for callers whose layer tensors are not views of the bucket).  Uses a workspace planned by
  * bagua_flatten_plan; the tensor pointers given to the plan are written through, so they must be writable.

@@ -27,7 +27,7 @@ EXPORTS = (
     "bagua_decompress_sgd_step", "bagua_decentralized_avg_peers", "bagua_reduce_compress_minmax_u8",
     "bagua_bucket_unflatten_run", "bagua_compress_topk_ef", "bagua_decompress_reduce_recompress_topk",
     "bagua_decompress_topk", "bagua_centralized_avg_fp", "bagua_decentralized_avg_peers_lp",
-    "bagua_decompress_adam_step", "bagua_momentum_sign_compress_ef", "bagua_lp_encode", "bagua_lp_apply_mix",
+    "bagua_decompress_adam_step", "bagua_momentum_sign_compress_ef", "bagua_lp_encode", "bagua_lp_apply_mix", "bagua_bucket_flatten_static",
 )
 
 
@@ -54,6 +54,7 @@ def _load():
     lib.bagua_decompress_topk.argtypes = [vp, vp, sz, sz, sz, vp, vp]
     lib.bagua_bucket_unflatten_run.argtypes = [vp, sz, vp, sz, vp]
     lib.bagua_bucket_flatten.argtypes = [vp, vp, vp, sz, vp, sz, vp, sz, vp]
+    lib.bagua_bucket_flatten_static.argtypes = [vp, vp, vp, sz, vp, sz, vp]
     lib.bagua_compress_minmax_u8.argtypes = [vp, vp, sz, sz, vp, vp, vp]
     lib.bagua_decompress_reduce_recompress.argtypes = [i32, vp, vp, i32, vp, sz, sz, vp, vp, vp, vp]
     lib.bagua_decentralized_avg.argtypes = [i32, vp, vp, vp, vp, vp, i32, sz, sz, vp]
@@ -178,6 +179,13 @@ def bagua_bucket_flatten(srcs, dst_offset, bucket, workspace, stream=None):
                                                              bucket.numel(), _ptr(workspace),
                                                              workspace.numel() * workspace.element_size(),
                                                              _stream(stream)))
+
+
+def bagua_bucket_flatten_static(srcs, dst_offset, bucket, stream=None):
+    """bagua_bucket_flatten with the tensor table in the library's own fixed device array (no workspace)."""
+    T, ptrs, numel, offs = _flatten_args(srcs, dst_offset)
+    _check("bagua_bucket_flatten_static", _lib.bagua_bucket_flatten_static(
+        ptrs, numel, offs, T, _ptr(bucket, torch.float32), bucket.numel(), _stream(stream)))
 
 
 def bagua_compress_minmax_u8(x, residual, chunk, codes, minmax, stream=None):

@@ -5,6 +5,7 @@
 // bucket elements and looks up which tensor covers them, so every bucket byte is written exactly
 // once with 128-bit stores (8 bytes of traffic per element).  A host-built table in the
 // caller's workspace gives, for every tile of the bucket, the first tensor that can intersect it.
+#include <mutex>
 #include <vector>
 
 #include "flatten_device.hpp"
@@ -200,6 +201,112 @@ extern "C" int bagua_bucket_flatten(const void* const* src, const size_t* numel,
     const int rc = bagua_flatten_plan(src, numel, dst_offset, T, bucket_numel, workspace, workspace_bytes, stream);
     if (rc != BAGUA_OK) return rc;
     return bagua_bucket_flatten_run(workspace, T, bucket, bucket_numel, stream);
+}
+
+// ------------------------------------------------------------------------------------------ no allocation
+// bagua_bucket_flatten_static: the tensor table lives in a fixed device array of this library instead of a
+// caller-provided workspace, and is built on the device from kernel arguments, so the call allocates
+// nothing, copies nothing from host memory and never synchronises.
+namespace bagua {
+
+constexpr size_t kStaticMaxT = BAGUA_FLATTEN_STATIC_MAX_TENSORS;
+constexpr size_t kStaticMaxNumel = BAGUA_FLATTEN_STATIC_MAX_NUMEL;
+constexpr size_t kStaticDescBytes = kStaticMaxT * sizeof(TensorDesc);
+constexpr size_t kStaticTileBytes = (kStaticMaxNumel / kTile + 2) * sizeof(uint32_t);
+static_assert(kStaticDescBytes % 16 == 0, "the tile table starts 16-byte aligned");
+
+// One copy of this array exists on every GPU the library runs on.  In host code the name is only a handle:
+// the device address is looked up once per device (static_scratch_ptr) and that pointer is what kernels get.
+static __device__ __align__(256) unsigned char scratch[kStaticDescBytes + kStaticTileBytes];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];   // per device, nullptr until looked up
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (nullptr on error).
+static unsigned char* static_scratch_ptr()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return static_cast<unsigned char*>(g_scratch_ptr[dev]);
+}
+
+// Up to kDescPerLaunch descriptors travel as kernel arguments and are written into the table.
+constexpr int kDescPerLaunch = 64;
+struct DescBatch {
+    TensorDesc d[kDescPerLaunch];
+};
+__global__ void __launch_bounds__(kDescPerLaunch)
+k_table_desc(DescBatch batch, uint32_t count, TensorDesc* __restrict__ desc)
+{
+    if (threadIdx.x < count) desc[threadIdx.x] = batch.d[threadIdx.x];
+}
+
+// tile_first[i] = first tensor whose end lies beyond the start of tile i (T if none), i in [0, tiles]:
+// the ends are ascending, so a binary search gives what the host loop of bagua_flatten_plan gives.
+__global__ void __launch_bounds__(256)
+k_table_tiles(const TensorDesc* __restrict__ desc, uint32_t T, uint32_t* __restrict__ tile_first, size_t tiles)
+{
+    const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i > tiles) return;
+    const size_t e = i * static_cast<size_t>(kTile);
+    uint32_t lo = 0, hi = T;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (desc[mid].dst + desc[mid].numel <= e) lo = mid + 1;
+        else hi = mid;
+    }
+    tile_first[i] = lo;
+}
+
+}  // namespace bagua
+
+extern "C" int bagua_bucket_flatten_static(const void* const* src, const size_t* numel, const size_t* dst_offset,
+                                           size_t T, float* bucket, size_t bucket_numel, void* stream)
+{
+    if (!bucket || bucket_numel == 0 || (T && (!src || !numel || !dst_offset))) return BAGUA_ERR_INVALID_ARG;
+    if (T > kStaticMaxT || bucket_numel > kStaticMaxNumel) return BAGUA_ERR_UNSUPPORTED;
+    if (!aligned16(bucket)) return BAGUA_ERR_ALIGNMENT;
+    size_t prev_end = 0;
+    for (size_t t = 0; t < T; ++t) {
+        if (numel[t] && !src[t]) return BAGUA_ERR_INVALID_ARG;
+        if (dst_offset[t] < prev_end) return BAGUA_ERR_INVALID_ARG;
+        if (numel[t] > bucket_numel || dst_offset[t] > bucket_numel - numel[t]) return BAGUA_ERR_INVALID_ARG;
+        if (reinterpret_cast<uintptr_t>(src[t]) & 3u) return BAGUA_ERR_ALIGNMENT;
+        prev_end = dst_offset[t] + numel[t];
+    }
+    {
+        // the bucket is written, the tensors are read: none may overlap it
+        const uintptr_t blo = reinterpret_cast<uintptr_t>(bucket), bhi = blo + bucket_numel * sizeof(float);
+        for (size_t t = 0; t < T; ++t) {
+            const uintptr_t lo = reinterpret_cast<uintptr_t>(src[t]), hi = lo + numel[t] * sizeof(float);
+            if (numel[t] && lo < bhi && blo < hi) return BAGUA_ERR_INVALID_ARG;
+        }
+    }
+    unsigned char* table = static_scratch_ptr();
+    if (!table) return BAGUA_ERR_LAUNCH;
+    TensorDesc* desc = reinterpret_cast<TensorDesc*>(table);
+    uint32_t* tile_first = reinterpret_cast<uint32_t*>(table + kStaticDescBytes);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (size_t t0 = 0; t0 < T; t0 += kDescPerLaunch) {
+        DescBatch batch{};
+        const uint32_t count = static_cast<uint32_t>(std::min<size_t>(kDescPerLaunch, T - t0));
+        for (uint32_t i = 0; i < count; ++i)
+            batch.d[i] = TensorDesc{static_cast<const float*>(src[t0 + i]), numel[t0 + i], dst_offset[t0 + i]};
+        hipLaunchKernelGGL(k_table_desc, dim3(1), dim3(kDescPerLaunch), 0, s, batch, count, desc + t0);
+    }
+    const size_t tiles = num_tiles(bucket_numel);
+    hipLaunchKernelGGL(k_table_tiles, dim3(static_cast<unsigned>((tiles + 1 + 255) / 256)), dim3(256), 0, s, desc,
+                       static_cast<uint32_t>(T), tile_first, tiles);
+    hipLaunchKernelGGL(k_flatten, dim3(static_cast<unsigned>(tiles)), dim3(256), 0, s, desc, tile_first,
+                       static_cast<uint32_t>(T), bucket, bucket_numel);
+    return launch_status();
 }
 
 extern "C" int bagua_bucket_unflatten_run(const void* workspace, size_t T, const float* bucket, size_t bucket_numel,
