@@ -49,8 +49,8 @@ __device__ __forceinline__ void st_stream(T* p, T v)
 
 // Preferred rows (of 256 elements) per wave for each chunked kernel (compile-time tuning knobs).
 // Measured on MI355X: two rows per wave (512 elements, 8 waves for a 4096-element chunk) stream
-// fastest in the worker-side kernels and the fused ring kernel; the server-side kernels and the
-// top-K kernels prefer four.  Larger values are used only when a chunk would need more than 16 waves.
+// fastest in the worker-side kernels, the fused ring kernel and the sign codec's server kernel; the MinMax
+// server kernel and the top-K kernels prefer four.  Larger values are used only when a chunk would need more than 16 waves.
 #ifndef BAGUA_RPW_COMPRESS
 #define BAGUA_RPW_COMPRESS 2
 #endif
@@ -61,7 +61,7 @@ __device__ __forceinline__ void st_stream(T* p, T v)
 #define BAGUA_RPW_SIGN 2
 #endif
 #ifndef BAGUA_RPW_DRR_SIGN
-#define BAGUA_RPW_DRR_SIGN 4
+#define BAGUA_RPW_DRR_SIGN 2
 #endif
 #ifndef BAGUA_RPW_TOPK
 #define BAGUA_RPW_TOPK 4
@@ -81,7 +81,7 @@ __device__ __forceinline__ void st_stream(T* p, T v)
 #define BAGUA_DRR_NJ 1
 #endif
 #ifndef BAGUA_DRR_SIGN_NJ
-#define BAGUA_DRR_SIGN_NJ 4
+#define BAGUA_DRR_SIGN_NJ 8
 #endif
 
 constexpr int kWave = 64;

@@ -171,11 +171,16 @@ k_drr_sign(PtrTable bits_in, PtrTable scale_in, int k, float inv_k, float* __res
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
     const int sh = 4 * (lane & 7);
 
+    // Scales of this chunk: lane j fetches worker j's (one memory round trip for all workers instead of a chain
+    // of k dependent ones), broadcast below with readlane.
+    float lane_scale = 0.0f;
+    if (lane < k) lane_scale = static_cast<const float*>(scale_in.p[lane])[c];
+
     f4 v[RPW];
     // Workers are summed in ascending order; the sign words of NJ workers are fetched together.
     constexpr int NJ = BAGUA_DRR_SIGN_NJ;
     auto accumulate = [&](int j, uint32_t (&w)[RPW]) {
-        const float sc = static_cast<const float*>(scale_in.p[j])[c];
+        const float sc = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(lane_scale), j));
         const float neg = -sc;
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
