@@ -322,6 +322,40 @@ int bagua_decompress_adam_step(int codec, const void* codes, const float* meta, 
 int bagua_momentum_sign_compress_ef(const float* g, const float* m, float beta1, float* residual, size_t n,
                                     size_t chunk, uint32_t* bits, float* scale, void* stream);
 
+/*
+ * Batched forms: B buckets that need not be contiguous in memory are processed by ONE launch, so a worker whose
+ * buckets are separate allocations runs at the rate of one large launch instead of paying a launch (and its ramp-up
+ * and drain) per 25 MiB bucket (Section 3.1 "Bucketing": the unit handed to the communication primitive is a bucket;
+ * Section 3.5: primitives run on the flattened bucket).  Every bucket is processed exactly as the unbatched entry
+ * point would process it (own chunk grid starting at its first element, own ragged last chunk), so results are
+ * identical bit for bit to B separate calls.
+ *   per-bucket arguments   host arrays of length B (pointers: device pointers; n: elements, each > 0)
+ *   residual / server_residual / out_fp32   either NULL (none for any bucket) or an array with B non-NULL entries
+ *   codes_in, meta_in (server step)   host[B*k], bucket-major: entry b*k + j is worker j's buffer for bucket b
+ *   workspace   device, >= bagua_batch_workspace_bytes(B, k) bytes (k = 0 for the calls without workers),
+ *               16-byte aligned; holds the bucket table, written by small launches on `stream` before the main
+ *               launch (no host-to-device copy, no synchronisation; the host arrays may be reused on return).
+ *               It must stay untouched until the call's work on `stream` has finished.
+ * Alignment, aliasing and error rules as for the unbatched calls, applied over all buckets of the call.
+ * bagua_bucket_flatten_batched_run launches the copy of B planned buckets (plans[b] from bagua_flatten_plan with
+ * T[b] and bucket_numel[b]).
+ */
+size_t bagua_batch_workspace_bytes(size_t B, int k);
+int bagua_compress_minmax_u8_batched(const float* const* x, float* const* residual, const size_t* n, size_t B,
+                                     size_t chunk, uint8_t* const* codes, float* const* minmax, void* workspace,
+                                     size_t workspace_bytes, void* stream);
+int bagua_sign_compress_ef_batched(const float* const* x, float* const* residual, const size_t* n, size_t B,
+                                   size_t chunk, uint32_t* const* bits, float* const* scale, void* workspace,
+                                   size_t workspace_bytes, void* stream);
+int bagua_decompress_reduce_recompress_batched(int codec, const void* const* codes_in, const float* const* meta_in,
+                                               int k, float* const* server_residual, const size_t* n, size_t B,
+                                               size_t chunk, void* const* codes_out, float* const* meta_out,
+                                               float* const* out_fp32, void* workspace, size_t workspace_bytes,
+                                               void* stream);
+int bagua_bucket_flatten_batched_run(const void* const* plans, const size_t* T, float* const* bucket,
+                                     const size_t* bucket_numel, size_t B, void* workspace, size_t workspace_bytes,
+                                     void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,6 +28,8 @@ EXPORTS = (
     "bagua_bucket_unflatten_run", "bagua_compress_topk_ef", "bagua_decompress_reduce_recompress_topk",
     "bagua_decompress_topk", "bagua_centralized_avg_fp", "bagua_decentralized_avg_peers_lp",
     "bagua_decompress_adam_step", "bagua_momentum_sign_compress_ef", "bagua_lp_encode", "bagua_lp_apply_mix", "bagua_bucket_flatten_static",
+    "bagua_batch_workspace_bytes", "bagua_compress_minmax_u8_batched", "bagua_sign_compress_ef_batched",
+    "bagua_decompress_reduce_recompress_batched", "bagua_bucket_flatten_batched_run",
 )
 
 
@@ -72,8 +74,15 @@ def _load():
     lib.bagua_momentum_sign_compress_ef.argtypes = [vp, vp, cf, vp, sz, sz, vp, vp, vp]
     lib.bagua_lp_encode.argtypes = [vp, vp, sz, sz, vp, vp, vp]
     lib.bagua_lp_apply_mix.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, sz, vp, vp]
+    lib.bagua_batch_workspace_bytes.argtypes = [sz, i32]
+    lib.bagua_compress_minmax_u8_batched.argtypes = [vp, vp, vp, sz, sz, vp, vp, vp, sz, vp]
+    lib.bagua_sign_compress_ef_batched.argtypes = [vp, vp, vp, sz, sz, vp, vp, vp, sz, vp]
+    lib.bagua_decompress_reduce_recompress_batched.argtypes = [i32, vp, vp, i32, vp, vp, sz, sz, vp, vp, vp, vp, sz, vp]
+    lib.bagua_bucket_flatten_batched_run.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp]
     for name in EXPORTS[2:]:
-        getattr(lib, name).restype = i32
+        if name != "bagua_batch_workspace_bytes":
+            getattr(lib, name).restype = i32
+    lib.bagua_batch_workspace_bytes.restype = sz
     return lib
 
 
@@ -334,6 +343,79 @@ def bagua_decompress_topk(idx, val, n, chunk, keep, out, stream=None):
     _check("bagua_decompress_topk", _lib.bagua_decompress_topk(
         _ptr(idx, torch.int16, 2 * keep * num_chunks(n, chunk)), _ptr(val, torch.float32, 4 * keep * num_chunks(n, chunk)),
         n, chunk, keep, _ptr(out, torch.float32, 4 * n), _stream(stream)))
+
+
+# ---------------------------------------------------------------------------------------------- batched forms
+def bagua_batch_workspace_bytes(B, k=0):
+    return int(_lib.bagua_batch_workspace_bytes(B, k))
+
+
+def _sizes(ns):
+    return (ctypes.c_size_t * len(ns))(*[int(v) for v in ns])
+
+
+def _ws(workspace):
+    return _ptr(workspace), workspace.numel() * workspace.element_size()
+
+
+def bagua_compress_minmax_u8_batched(xs, residuals, chunk, codes, minmaxs, workspace, stream=None):
+    """B buckets in one launch; xs/codes/minmaxs are lists of B tensors, residuals a list of B tensors or None."""
+    B = len(xs)
+    _same_len(B, residuals=residuals, codes=codes, minmaxs=minmaxs)
+    ns = [x.numel() for x in xs]
+    wp, wb = _ws(workspace)
+    arrs = [_ptr(x, torch.float32) for x in xs]
+    xa = (ctypes.c_void_p * B)(*[a.value for a in arrs])
+    ra = None if residuals is None else (ctypes.c_void_p * B)(*[_ptr(r, torch.float32, 4 * n).value for r, n in zip(residuals, ns)])
+    ca = (ctypes.c_void_p * B)(*[_ptr(c, torch.uint8, n).value for c, n in zip(codes, ns)])
+    ma = (ctypes.c_void_p * B)(*[_ptr(m, torch.float32, 8 * num_chunks(n, chunk)).value for m, n in zip(minmaxs, ns)])
+    _check("bagua_compress_minmax_u8_batched", _lib.bagua_compress_minmax_u8_batched(
+        xa, ra, _sizes(ns), B, chunk, ca, ma, wp, wb, _stream(stream)))
+
+
+def bagua_sign_compress_ef_batched(xs, residuals, chunk, bits, scales, workspace, stream=None):
+    B = len(xs)
+    _same_len(B, residuals=residuals, bits=bits, scales=scales)
+    ns = [x.numel() for x in xs]
+    wp, wb = _ws(workspace)
+    xa = (ctypes.c_void_p * B)(*[_ptr(x, torch.float32).value for x in xs])
+    ra = None if residuals is None else (ctypes.c_void_p * B)(*[_ptr(r, torch.float32, 4 * n).value for r, n in zip(residuals, ns)])
+    ba = (ctypes.c_void_p * B)(*[_ptr(b, torch.int32, _code_bytes(CODEC_SIGN1, n)).value for b, n in zip(bits, ns)])
+    sa = (ctypes.c_void_p * B)(*[_ptr(s, torch.float32, _meta_bytes(CODEC_SIGN1, n, chunk)).value for s, n in zip(scales, ns)])
+    _check("bagua_sign_compress_ef_batched", _lib.bagua_sign_compress_ef_batched(
+        xa, ra, _sizes(ns), B, chunk, ba, sa, wp, wb, _stream(stream)))
+
+
+def bagua_decompress_reduce_recompress_batched(codec, codes_in, meta_in, server_residuals, ns, chunk, codes_out, meta_out,
+                                               outs, workspace, stream=None):
+    """codes_in / meta_in: list over buckets of lists over the k workers."""
+    B = len(ns)
+    _same_len(B, codes_in=codes_in, meta_in=meta_in, server_residuals=server_residuals, codes_out=codes_out,
+              meta_out=meta_out, outs=outs)
+    k = len(codes_in[0])
+    for b in range(B):
+        _same_len(k, codes_in_b=codes_in[b], meta_in_b=meta_in[b])
+    wp, wb = _ws(workspace)
+    ci = (ctypes.c_void_p * (B * k))(*[_ptr(codes_in[b][j], None, _code_bytes(codec, ns[b])).value
+                                       for b in range(B) for j in range(k)])
+    mi = (ctypes.c_void_p * (B * k))(*[_ptr(meta_in[b][j], torch.float32, _meta_bytes(codec, ns[b], chunk)).value
+                                       for b in range(B) for j in range(k)])
+    ea = None if server_residuals is None else (ctypes.c_void_p * B)(*[_ptr(e, torch.float32, 4 * n).value for e, n in zip(server_residuals, ns)])
+    co = (ctypes.c_void_p * B)(*[_ptr(c, None, _code_bytes(codec, n)).value for c, n in zip(codes_out, ns)])
+    mo = (ctypes.c_void_p * B)(*[_ptr(m, torch.float32, _meta_bytes(codec, n, chunk)).value for m, n in zip(meta_out, ns)])
+    oa = None if outs is None else (ctypes.c_void_p * B)(*[_ptr(o, torch.float32, 4 * n).value for o, n in zip(outs, ns)])
+    _check("bagua_decompress_reduce_recompress_batched", _lib.bagua_decompress_reduce_recompress_batched(
+        codec, ci, mi, k, ea, _sizes(ns), B, chunk, co, mo, oa, wp, wb, _stream(stream)))
+
+
+def bagua_bucket_flatten_batched_run(plans, Ts, buckets, workspace, stream=None):
+    B = len(plans)
+    _same_len(B, Ts=Ts, buckets=buckets)
+    wp, wb = _ws(workspace)
+    pa = (ctypes.c_void_p * B)(*[_ptr(p).value for p in plans])
+    ba = (ctypes.c_void_p * B)(*[_ptr(b, torch.float32).value for b in buckets])
+    _check("bagua_bucket_flatten_batched_run", _lib.bagua_bucket_flatten_batched_run(
+        pa, _sizes(Ts), ba, _sizes([b.numel() for b in buckets]), B, wp, wb, _stream(stream)))
 
 
 def raw():

@@ -8,16 +8,17 @@
 #include <mutex>
 #include <vector>
 
+#include "batch.hpp"
 #include "flatten_device.hpp"
 
 namespace bagua {
 
-__global__ void __launch_bounds__(256)
-k_flatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile_first, uint32_t T,
-          float* __restrict__ bucket, size_t bucket_numel)
+// One tile (kTile elements) of one bucket; `tile` = index of the tile in its bucket.
+__device__ __forceinline__ void flatten_tile(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile_first,
+                                             uint32_t T, float* __restrict__ bucket, size_t bucket_numel, size_t tile)
 {
-    const size_t tile0 = static_cast<size_t>(blockIdx.x) * kTile;
-    const uint32_t lo0 = tile_first[blockIdx.x], hi0 = tile_first[blockIdx.x + 1];
+    const size_t tile0 = tile * kTile;
+    const uint32_t lo0 = tile_first[tile], hi0 = tile_first[tile + 1];
 
     // Fast path (almost every tile of a large tensor): the whole tile lies inside one tensor whose
     // source is 16-byte congruent with the bucket -> a plain streaming copy with a uniform base pointer.
@@ -78,6 +79,26 @@ k_flatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile
             if (e + 2 < bucket_numel) bucket[e + 2] = v.z;
         }
     }
+}
+
+__global__ void __launch_bounds__(256)
+k_flatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile_first, uint32_t T,
+          float* __restrict__ bucket, size_t bucket_numel)
+{
+    flatten_tile(desc, tile_first, T, bucket, bucket_numel, blockIdx.x);
+}
+
+// Batched: entry = [planned workspace, T, bucket, bucket_numel]; unit = tile.
+__global__ void __launch_bounds__(256)
+k_flatten_batched(BatchView bv)
+{
+    const uint32_t b = batch_find(bv, blockIdx.x);
+    const uint64_t* e = bv.entries + static_cast<size_t>(b) * bv.entry_words;
+    const size_t T = e[1];
+    const unsigned char* ws = reinterpret_cast<const unsigned char*>(e[0]);
+    const size_t desc_bytes = ((T ? T : 1) * sizeof(TensorDesc) + 15) & ~static_cast<size_t>(15);
+    flatten_tile(reinterpret_cast<const TensorDesc*>(ws), reinterpret_cast<const uint32_t*>(ws + desc_bytes),
+                 static_cast<uint32_t>(T), reinterpret_cast<float*>(e[2]), e[3], blockIdx.x - bv.first_unit[b]);
 }
 
 // Inverse scatter: copy every tensor's range of the bucket back into the tensor (same table as the
@@ -201,6 +222,42 @@ extern "C" int bagua_bucket_flatten(const void* const* src, const size_t* numel,
     const int rc = bagua_flatten_plan(src, numel, dst_offset, T, bucket_numel, workspace, workspace_bytes, stream);
     if (rc != BAGUA_OK) return rc;
     return bagua_bucket_flatten_run(workspace, T, bucket, bucket_numel, stream);
+}
+
+extern "C" int bagua_bucket_flatten_batched_run(const void* const* plans, const size_t* T, float* const* bucket,
+                                                const size_t* bucket_numel, size_t B, void* workspace,
+                                                size_t workspace_bytes, void* stream)
+{
+    if (!plans || !T || !bucket || !bucket_numel || !workspace || B == 0 || B > 0xffffffffu) return BAGUA_ERR_INVALID_ARG;
+    if (workspace_bytes < bagua_batch_workspace_bytes(B, 0)) return BAGUA_ERR_INVALID_ARG;
+    if (!aligned16(workspace)) return BAGUA_ERR_ALIGNMENT;
+    const size_t ew = batch_entry_words_for(0);
+    std::vector<uint64_t> table(batch_table_words(B, ew), 0);
+    uint64_t* entries = table.data() + batch_first_words(B);
+    RangeList rl;
+    size_t total = 0;
+    for (size_t b = 0; b < B; ++b) {
+        if (!plans[b] || !bucket[b] || bucket_numel[b] == 0) return BAGUA_ERR_INVALID_ARG;
+        if (T[b] > 0xfffffff0u) return BAGUA_ERR_UNSUPPORTED;
+        if (!aligned16(plans[b]) || !aligned16(bucket[b])) return BAGUA_ERR_ALIGNMENT;
+        rl.reads(plans[b], bagua_flatten_workspace_bytes(T[b], bucket_numel[b]));
+        rl.writes(bucket[b], bucket_numel[b] * sizeof(float));
+        table[b] = total;
+        uint64_t* e = entries + b * ew;
+        e[0] = reinterpret_cast<uintptr_t>(plans[b]);
+        e[1] = T[b];
+        e[2] = reinterpret_cast<uintptr_t>(bucket[b]);
+        e[3] = bucket_numel[b];
+        total += num_tiles(bucket_numel[b]);
+    }
+    table[B] = total;
+    rl.writes(workspace, table.size() * sizeof(uint64_t));
+    if (!rl.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    if (total > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (batch_upload(table.data(), table.size(), static_cast<uint64_t*>(workspace), s) != BAGUA_OK) return BAGUA_ERR_LAUNCH;
+    hipLaunchKernelGGL(k_flatten_batched, dim3(static_cast<unsigned>(total)), dim3(256), 0, s, batch_view(workspace, B, ew));
+    return launch_status();
 }
 
 // ------------------------------------------------------------------------------------------ no allocation

@@ -3,6 +3,7 @@
 //
 // All three are single-pass streaming kernels bound by HBM bandwidth: a chunk lives in
 // registers between the statistics phase and the quantisation phase.
+#include "batch.hpp"
 #include "launchers.hpp"
 #include "minmax_device.hpp"
 
@@ -12,14 +13,12 @@ namespace bagua {
 
 // ------------------------------------------------------------------------------------------
 // Worker side: v = x (+ residual); codes = Q(v); residual <- v - decode.
-// grid = one workgroup per chunk, block = 64 * ceil(rows / RPW).
+// One workgroup per chunk, block = 64 * ceil(rows / RPW); c = index of the chunk in its bucket.
 template <int RPW, bool EF>
-__global__ void __launch_bounds__(wg_threads_max(RPW))
-k_compress_minmax(const float* __restrict__ x, float* __restrict__ residual, size_t n, uint32_t chunk,
-                  uint8_t* __restrict__ codes, float* __restrict__ minmax)
+__device__ __forceinline__ void compress_minmax_chunk(const float* __restrict__ x, float* __restrict__ residual, size_t n,
+                                                      uint32_t chunk, uint8_t* __restrict__ codes,
+                                                      float* __restrict__ minmax, size_t c, float* s_red)
 {
-    __shared__ float s_red[2 * kMaxWaves];
-    const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
@@ -50,24 +49,57 @@ k_compress_minmax(const float* __restrict__ x, float* __restrict__ residual, siz
                                         codes + base, minmax + 2 * c, nullptr, s_red);
 }
 
-// ------------------------------------------------------------------------------------------
-// Server side: a = (sum_j decode_j) * inv_k in ascending j; w = a (+ epsilon); then as above.
-template <int RPW, bool EF, bool OUT>
+template <int RPW, bool EF>
 __global__ void __launch_bounds__(wg_threads_max(RPW))
-k_drr_minmax(PtrTable codes_in, PtrTable meta_in, int k, float inv_k, float* __restrict__ eps, size_t n,
-             uint32_t chunk, uint8_t* __restrict__ codes_out, float* __restrict__ minmax_out,
-             float* __restrict__ out)
+k_compress_minmax(const float* __restrict__ x, float* __restrict__ residual, size_t n, uint32_t chunk,
+                  uint8_t* __restrict__ codes, float* __restrict__ minmax)
 {
     __shared__ float s_red[2 * kMaxWaves];
-    __shared__ float s_mn[BAGUA_MAX_WORKERS], s_step[BAGUA_MAX_WORKERS];
-    const size_t c = blockIdx.x;
+    compress_minmax_chunk<RPW, EF>(x, residual, n, chunk, codes, minmax, blockIdx.x, s_red);
+}
+
+// Batched: entry = [x, residual, codes, minmax, n]; unit = chunk.
+template <int RPW, bool EF>
+__global__ void __launch_bounds__(wg_threads_max(RPW))
+k_compress_minmax_batched(BatchView bv, uint32_t chunk)
+{
+    __shared__ float s_red[2 * kMaxWaves];
+    const uint32_t b = batch_find(bv, blockIdx.x);
+    const uint64_t* e = bv.entries + static_cast<size_t>(b) * bv.entry_words;
+    compress_minmax_chunk<RPW, EF>(reinterpret_cast<const float*>(e[0]), reinterpret_cast<float*>(e[1]), e[4], chunk,
+                                   reinterpret_cast<uint8_t*>(e[2]), reinterpret_cast<float*>(e[3]),
+                                   blockIdx.x - bv.first_unit[b], s_red);
+}
+
+// ------------------------------------------------------------------------------------------
+// Server side: a = (sum_j decode_j) * inv_k in ascending j; w = a (+ epsilon); then as above.
+// SRC names the workers' inputs: code(j) -> u8 codes of worker j, meta(j) -> its (min, max) pairs.
+struct DrrTableSrc {   // pointers in the kernel arguments
+    const PtrTable& codes;
+    const PtrTable& metas;
+    __device__ __forceinline__ const void* code(int j) const { return codes.p[j]; }
+    __device__ __forceinline__ const float* meta(int j) const { return static_cast<const float*>(metas.p[j]); }
+};
+struct DrrEntrySrc {   // pointers in a batch entry: [eps, codes_out, meta_out, out, n, code[0..k), meta[0..k)]
+    const uint64_t* e;
+    int k;
+    __device__ __forceinline__ const void* code(int j) const { return reinterpret_cast<const void*>(e[5 + j]); }
+    __device__ __forceinline__ const float* meta(int j) const { return reinterpret_cast<const float*>(e[5 + k + j]); }
+};
+
+template <int RPW, bool EF, bool OUT, typename SRC>
+__device__ __forceinline__ void drr_minmax_chunk(const SRC& src, int k, float inv_k, float* __restrict__ eps, size_t n,
+                                                 uint32_t chunk, uint8_t* __restrict__ codes_out,
+                                                 float* __restrict__ minmax_out, float* __restrict__ out, size_t c,
+                                                 float* s_red, float* s_mn, float* s_step)
+{
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     // per-worker (min, step) of this chunk: one lane per worker, so the k divisions run side by side
     if (static_cast<int>(threadIdx.x) < k) {
-        const float* m = static_cast<const float*>(meta_in.p[threadIdx.x]);
+        const float* m = src.meta(threadIdx.x);
         const float mn = m[2 * c], mx = m[2 * c + 1];
         s_mn[threadIdx.x] = mn;
         s_step[threadIdx.x] = minmax_step(mn, mx);
@@ -98,7 +130,7 @@ k_drr_minmax(PtrTable codes_in, PtrTable meta_in, int k, float inv_k, float* __r
         }
     };
     auto fetch = [&](int j, uint32_t (&w)[RPW]) {
-        const uint8_t* cj = static_cast<const uint8_t*>(codes_in.p[j]) + base;
+        const uint8_t* cj = static_cast<const uint8_t*>(src.code(j)) + base;
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
             const long off = static_cast<long>(wave * RPW + i) * kRow;
@@ -143,6 +175,31 @@ k_drr_minmax(PtrTable codes_in, PtrTable meta_in, int k, float inv_k, float* __r
     }
     minmax_encode_chunk<RPW, EF, OUT>(v, len, wave, lane, nwaves, EF ? eps + base : nullptr,
                                       codes_out + base, minmax_out + 2 * c, OUT ? out + base : nullptr, s_red);
+}
+
+template <int RPW, bool EF, bool OUT>
+__global__ void __launch_bounds__(wg_threads_max(RPW))
+k_drr_minmax(PtrTable codes_in, PtrTable meta_in, int k, float inv_k, float* __restrict__ eps, size_t n,
+             uint32_t chunk, uint8_t* __restrict__ codes_out, float* __restrict__ minmax_out,
+             float* __restrict__ out)
+{
+    __shared__ float s_red[2 * kMaxWaves];
+    __shared__ float s_mn[BAGUA_MAX_WORKERS], s_step[BAGUA_MAX_WORKERS];
+    drr_minmax_chunk<RPW, EF, OUT>(DrrTableSrc{codes_in, meta_in}, k, inv_k, eps, n, chunk, codes_out, minmax_out, out,
+                                   blockIdx.x, s_red, s_mn, s_step);
+}
+
+template <int RPW, bool EF, bool OUT>
+__global__ void __launch_bounds__(wg_threads_max(RPW))
+k_drr_minmax_batched(BatchView bv, int k, float inv_k, uint32_t chunk)
+{
+    __shared__ float s_red[2 * kMaxWaves];
+    __shared__ float s_mn[BAGUA_MAX_WORKERS], s_step[BAGUA_MAX_WORKERS];
+    const uint32_t b = batch_find(bv, blockIdx.x);
+    const uint64_t* e = bv.entries + static_cast<size_t>(b) * bv.entry_words;
+    drr_minmax_chunk<RPW, EF, OUT>(DrrEntrySrc{e, k}, k, inv_k, reinterpret_cast<float*>(e[0]), e[4], chunk,
+                                   reinterpret_cast<uint8_t*>(e[1]), reinterpret_cast<float*>(e[2]),
+                                   reinterpret_cast<float*>(e[3]), blockIdx.x - bv.first_unit[b], s_red, s_mn, s_step);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -209,6 +266,26 @@ int launch_drr_minmax(const void* const* codes_in, const float* const* meta_in, 
     return launch_status();
 }
 
+int launch_drr_minmax_batched(const void* workspace, size_t B, int k, size_t total_chunks, size_t chunk, bool ef,
+                              bool with_out, hipStream_t stream)
+{
+    const BatchView bv = batch_view(workspace, B, 5 + 2 * static_cast<size_t>(k));
+    const int rows = static_cast<int>(chunk / kRow);
+    const int rpw = pick_rpw(rows, BAGUA_RPW_DRR);
+    dim3 grid(static_cast<unsigned>(total_chunks)), block(64 * ((rows + rpw - 1) / rpw));
+    const float inv_k = 1.0f / static_cast<float>(k);
+    const uint32_t ch = static_cast<uint32_t>(chunk);
+#define BAGUA_DRR(EFv, OUTv)                                                                                       \
+    BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_drr_minmax_batched<RPW, EFv, OUTv>), grid, block, 0, stream, bv, \
+                                               k, inv_k, ch))
+    if (ef && with_out) { BAGUA_DRR(true, true) }
+    else if (ef) { BAGUA_DRR(true, false) }
+    else if (with_out) { BAGUA_DRR(false, true) }
+    else { BAGUA_DRR(false, false) }
+#undef BAGUA_DRR
+    return launch_status();
+}
+
 int launch_decompress_minmax(const uint8_t* codes, const float* minmax, size_t n, size_t chunk, float* out,
                              hipStream_t stream)
 {
@@ -236,4 +313,55 @@ extern "C" int bagua_compress_minmax_u8(const float* x, float* residual, size_t 
     if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(residual) || !aligned16(codes) || !aligned4(minmax)) return BAGUA_ERR_ALIGNMENT;
     return launch_compress_minmax(x, residual, n, chunk, codes, minmax, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int bagua_compress_minmax_u8_batched(const float* const* x, float* const* residual, const size_t* n, size_t B,
+                                                size_t chunk, uint8_t* const* codes, float* const* minmax,
+                                                void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !n || !codes || !minmax || !workspace || B == 0 || B > 0xffffffffu || !chunk_ok(chunk))
+        return BAGUA_ERR_INVALID_ARG;
+    if (workspace_bytes < bagua_batch_workspace_bytes(B, 0)) return BAGUA_ERR_INVALID_ARG;
+    if (!aligned16(workspace)) return BAGUA_ERR_ALIGNMENT;
+    const bool ef = residual != nullptr;
+    const size_t ew = batch_entry_words_for(0);
+    std::vector<uint64_t> table(batch_table_words(B, ew), 0);
+    uint64_t* entries = table.data() + batch_first_words(B);
+    RangeList rl;
+    size_t total = 0;
+    for (size_t b = 0; b < B; ++b) {
+        if (!x[b] || !codes[b] || !minmax[b] || n[b] == 0 || (ef && !residual[b])) return BAGUA_ERR_INVALID_ARG;
+        float* r = ef ? residual[b] : nullptr;
+        if (!aligned16(x[b]) || !aligned16(r) || !aligned16(codes[b]) || !aligned4(minmax[b])) return BAGUA_ERR_ALIGNMENT;
+        const size_t nc = num_chunks(n[b], chunk);
+        rl.reads(x[b], n[b] * sizeof(float));
+        rl.writes(r, n[b] * sizeof(float));
+        rl.writes(codes[b], n[b]);
+        rl.writes(minmax[b], 2 * nc * sizeof(float));
+        table[b] = total;
+        uint64_t* e = entries + b * ew;
+        e[0] = reinterpret_cast<uintptr_t>(x[b]);
+        e[1] = reinterpret_cast<uintptr_t>(r);
+        e[2] = reinterpret_cast<uintptr_t>(codes[b]);
+        e[3] = reinterpret_cast<uintptr_t>(minmax[b]);
+        e[4] = n[b];
+        total += nc;
+    }
+    table[B] = total;
+    rl.writes(workspace, table.size() * sizeof(uint64_t));
+    if (!rl.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    if (total > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (batch_upload(table.data(), table.size(), static_cast<uint64_t*>(workspace), s) != BAGUA_OK) return BAGUA_ERR_LAUNCH;
+    const BatchView bv = batch_view(workspace, B, ew);
+    const int rows = static_cast<int>(chunk / kRow);
+    const int rpw = pick_rpw(rows, BAGUA_RPW_COMPRESS);
+    dim3 grid(static_cast<unsigned>(total)), block(64 * ((rows + rpw - 1) / rpw));
+    const uint32_t ch = static_cast<uint32_t>(chunk);
+    if (ef) {
+        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_compress_minmax_batched<RPW, true>), grid, block, 0, s, bv, ch))
+    } else {
+        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_compress_minmax_batched<RPW, false>), grid, block, 0, s, bv, ch))
+    }
+    return launch_status();
 }

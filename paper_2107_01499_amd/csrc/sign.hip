@@ -5,6 +5,7 @@
 // Lane l of a wave owns elements 4l..4l+3 of every 256-element row, so the group of four that the
 // fixed |v| summation order is defined on is exactly one lane's 128-bit load, accumulator m mod 64
 // is lane m mod 64, and the final xor butterfly is a wave-level shuffle reduction.
+#include "batch.hpp"
 #include "launchers.hpp"
 
 #pragma clang fp contract(off)
@@ -105,14 +106,12 @@ __device__ __forceinline__ void sign_encode_chunk(f4 (&v)[RPW], long len, uint32
 // ------------------------------------------------------------------------------------------
 // MOM: the compressed tensor is the local momentum beta1*m + omb1*x of the compression stage of
 // 1-bit Adam (x is then the gradient; m is read only).
-template <int RPW, bool EF, bool MOM = false>
-__global__ void __launch_bounds__(wg_threads_max(RPW))
-k_sign_compress(const float* __restrict__ x, float* __restrict__ residual, size_t n, uint32_t chunk,
-                uint32_t* __restrict__ bits, float* __restrict__ scale, const float* __restrict__ mom, float beta1,
-                float omb1)
+template <int RPW, bool EF, bool MOM>
+__device__ __forceinline__ void sign_compress_chunk(const float* __restrict__ x, float* __restrict__ residual, size_t n,
+                                                    uint32_t chunk, uint32_t* __restrict__ bits,
+                                                    float* __restrict__ scale, const float* __restrict__ mom,
+                                                    float beta1, float omb1, size_t c, float* s_q)
 {
-    extern __shared__ float s_q[];
-    const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
@@ -157,15 +156,50 @@ k_sign_compress(const float* __restrict__ x, float* __restrict__ residual, size_
                                       bits + (base >> 5), scale + c, nullptr, s_q);
 }
 
-// Server side with the sign codec: a = (sum_j +-scale_j) * inv_k in ascending j; w = a (+ eps).
-template <int RPW, bool EF, bool OUT>
+template <int RPW, bool EF, bool MOM = false>
 __global__ void __launch_bounds__(wg_threads_max(RPW))
-k_drr_sign(PtrTable bits_in, PtrTable scale_in, int k, float inv_k, float* __restrict__ eps, size_t n,
-           uint32_t chunk, uint32_t* __restrict__ bits_out, float* __restrict__ scale_out,
-           float* __restrict__ out)
+k_sign_compress(const float* __restrict__ x, float* __restrict__ residual, size_t n, uint32_t chunk,
+                uint32_t* __restrict__ bits, float* __restrict__ scale, const float* __restrict__ mom, float beta1,
+                float omb1)
 {
     extern __shared__ float s_q[];
-    const size_t c = blockIdx.x;
+    sign_compress_chunk<RPW, EF, MOM>(x, residual, n, chunk, bits, scale, mom, beta1, omb1, blockIdx.x, s_q);
+}
+
+// Batched: entry = [x, residual, bits, scale, n]; unit = chunk.
+template <int RPW, bool EF>
+__global__ void __launch_bounds__(wg_threads_max(RPW))
+k_sign_compress_batched(BatchView bv, uint32_t chunk)
+{
+    extern __shared__ float s_q[];
+    const uint32_t b = batch_find(bv, blockIdx.x);
+    const uint64_t* e = bv.entries + static_cast<size_t>(b) * bv.entry_words;
+    sign_compress_chunk<RPW, EF, false>(reinterpret_cast<const float*>(e[0]), reinterpret_cast<float*>(e[1]), e[4], chunk,
+                                        reinterpret_cast<uint32_t*>(e[2]), reinterpret_cast<float*>(e[3]), nullptr, 0.0f,
+                                        0.0f, blockIdx.x - bv.first_unit[b], s_q);
+}
+
+// Server side with the sign codec: a = (sum_j +-scale_j) * inv_k in ascending j; w = a (+ eps).
+// SRC names the workers' inputs: code(j) -> sign words of worker j, meta(j) -> its per-chunk scales.
+struct SignTableSrc {   // pointers in the kernel arguments
+    const PtrTable& bits;
+    const PtrTable& scales;
+    __device__ __forceinline__ const void* code(int j) const { return bits.p[j]; }
+    __device__ __forceinline__ const float* meta(int j) const { return static_cast<const float*>(scales.p[j]); }
+};
+struct SignEntrySrc {   // pointers in a batch entry: [eps, bits_out, scale_out, out, n, bits[0..k), scale[0..k)]
+    const uint64_t* e;
+    int k;
+    __device__ __forceinline__ const void* code(int j) const { return reinterpret_cast<const void*>(e[5 + j]); }
+    __device__ __forceinline__ const float* meta(int j) const { return reinterpret_cast<const float*>(e[5 + k + j]); }
+};
+
+template <int RPW, bool EF, bool OUT, typename SRC>
+__device__ __forceinline__ void drr_sign_chunk(const SRC& src, int k, float inv_k, float* __restrict__ eps, size_t n,
+                                               uint32_t chunk, uint32_t* __restrict__ bits_out,
+                                               float* __restrict__ scale_out, float* __restrict__ out, size_t c,
+                                               float* s_q)
+{
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
@@ -174,7 +208,7 @@ k_drr_sign(PtrTable bits_in, PtrTable scale_in, int k, float inv_k, float* __res
     // Scales of this chunk: lane j fetches worker j's (one memory round trip for all workers instead of a chain
     // of k dependent ones), broadcast below with readlane.
     float lane_scale = 0.0f;
-    if (lane < k) lane_scale = static_cast<const float*>(scale_in.p[lane])[c];
+    if (lane < k) lane_scale = src.meta(lane)[c];
 
     f4 v[RPW];
     // Workers are summed in ascending order; the sign words of NJ workers are fetched together.
@@ -201,7 +235,7 @@ k_drr_sign(PtrTable bits_in, PtrTable scale_in, int k, float inv_k, float* __res
         }
     };
     auto fetch = [&](int j, uint32_t (&w)[RPW]) {
-        const uint32_t* bj = static_cast<const uint32_t*>(bits_in.p[j]) + (base >> 5);
+        const uint32_t* bj = static_cast<const uint32_t*>(src.code(j)) + (base >> 5);
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
             const long off = static_cast<long>(wave * RPW + i) * kRow;
@@ -250,6 +284,29 @@ k_drr_sign(PtrTable bits_in, PtrTable scale_in, int k, float inv_k, float* __res
     }
     sign_encode_chunk<RPW, EF, OUT>(v, len, chunk, wave, lane, nwaves, EF ? eps + base : nullptr,
                                     bits_out + (base >> 5), scale_out + c, OUT ? out + base : nullptr, s_q);
+}
+
+template <int RPW, bool EF, bool OUT>
+__global__ void __launch_bounds__(wg_threads_max(RPW))
+k_drr_sign(PtrTable bits_in, PtrTable scale_in, int k, float inv_k, float* __restrict__ eps, size_t n,
+           uint32_t chunk, uint32_t* __restrict__ bits_out, float* __restrict__ scale_out,
+           float* __restrict__ out)
+{
+    extern __shared__ float s_q[];
+    drr_sign_chunk<RPW, EF, OUT>(SignTableSrc{bits_in, scale_in}, k, inv_k, eps, n, chunk, bits_out, scale_out, out,
+                                 blockIdx.x, s_q);
+}
+
+template <int RPW, bool EF, bool OUT>
+__global__ void __launch_bounds__(wg_threads_max(RPW))
+k_drr_sign_batched(BatchView bv, int k, float inv_k, uint32_t chunk)
+{
+    extern __shared__ float s_q[];
+    const uint32_t b = batch_find(bv, blockIdx.x);
+    const uint64_t* e = bv.entries + static_cast<size_t>(b) * bv.entry_words;
+    drr_sign_chunk<RPW, EF, OUT>(SignEntrySrc{e, k}, k, inv_k, reinterpret_cast<float*>(e[0]), e[4], chunk,
+                                 reinterpret_cast<uint32_t*>(e[1]), reinterpret_cast<float*>(e[2]),
+                                 reinterpret_cast<float*>(e[3]), blockIdx.x - bv.first_unit[b], s_q);
 }
 
 __global__ void __launch_bounds__(256)
@@ -329,6 +386,25 @@ int launch_drr_sign(const void* const* bits_in, const float* const* scale_in, in
     return launch_status();
 }
 
+int launch_drr_sign_batched(const void* workspace, size_t B, int k, size_t total_chunks, size_t chunk, bool ef,
+                            bool with_out, hipStream_t stream)
+{
+    const BatchView bv = batch_view(workspace, B, 5 + 2 * static_cast<size_t>(k));
+    SignGeometry g = sign_geometry(chunk, chunk, BAGUA_RPW_DRR_SIGN);
+    g.grid = dim3(static_cast<unsigned>(total_chunks));
+    const float inv_k = 1.0f / static_cast<float>(k);
+    const uint32_t ch = static_cast<uint32_t>(chunk);
+#define BAGUA_DRR(EFv, OUTv)                                                                                           \
+    BAGUA_DISPATCH_RPW(g.rpw, hipLaunchKernelGGL((k_drr_sign_batched<RPW, EFv, OUTv>), g.grid, g.block, g.lds, stream, \
+                                                 bv, k, inv_k, ch))
+    if (ef && with_out) { BAGUA_DRR(true, true) }
+    else if (ef) { BAGUA_DRR(true, false) }
+    else if (with_out) { BAGUA_DRR(false, true) }
+    else { BAGUA_DRR(false, false) }
+#undef BAGUA_DRR
+    return launch_status();
+}
+
 int launch_decompress_sign(const uint32_t* bits, const float* scale, size_t n, size_t chunk, float* out,
                            hipStream_t stream)
 {
@@ -381,6 +457,56 @@ extern "C" int bagua_momentum_sign_compress_ef(const float* g, const float* m, f
     } else {
         BAGUA_DISPATCH_RPW(geo.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, false, true>), geo.grid, geo.block, geo.lds,
                                                        s, g, residual, n, ch, bits, scale, m, beta1, omb1))
+    }
+    return launch_status();
+}
+
+extern "C" int bagua_sign_compress_ef_batched(const float* const* x, float* const* residual, const size_t* n, size_t B,
+                                              size_t chunk, uint32_t* const* bits, float* const* scale, void* workspace,
+                                              size_t workspace_bytes, void* stream)
+{
+    if (!x || !n || !bits || !scale || !workspace || B == 0 || B > 0xffffffffu || !chunk_ok(chunk))
+        return BAGUA_ERR_INVALID_ARG;
+    if (workspace_bytes < bagua_batch_workspace_bytes(B, 0)) return BAGUA_ERR_INVALID_ARG;
+    if (!aligned16(workspace)) return BAGUA_ERR_ALIGNMENT;
+    const bool ef = residual != nullptr;
+    const size_t ew = batch_entry_words_for(0);
+    std::vector<uint64_t> table(batch_table_words(B, ew), 0);
+    uint64_t* entries = table.data() + batch_first_words(B);
+    RangeList rl;
+    size_t total = 0;
+    for (size_t b = 0; b < B; ++b) {
+        if (!x[b] || !bits[b] || !scale[b] || n[b] == 0 || (ef && !residual[b])) return BAGUA_ERR_INVALID_ARG;
+        float* r = ef ? residual[b] : nullptr;
+        if (!aligned16(x[b]) || !aligned16(r) || !aligned16(bits[b]) || !aligned4(scale[b])) return BAGUA_ERR_ALIGNMENT;
+        const size_t nc = num_chunks(n[b], chunk);
+        rl.reads(x[b], n[b] * sizeof(float));
+        rl.writes(r, n[b] * sizeof(float));
+        rl.writes(bits[b], ((n[b] + 31) / 32) * sizeof(uint32_t));
+        rl.writes(scale[b], nc * sizeof(float));
+        table[b] = total;
+        uint64_t* e = entries + b * ew;
+        e[0] = reinterpret_cast<uintptr_t>(x[b]);
+        e[1] = reinterpret_cast<uintptr_t>(r);
+        e[2] = reinterpret_cast<uintptr_t>(bits[b]);
+        e[3] = reinterpret_cast<uintptr_t>(scale[b]);
+        e[4] = n[b];
+        total += nc;
+    }
+    table[B] = total;
+    rl.writes(workspace, table.size() * sizeof(uint64_t));
+    if (!rl.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    if (total > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (batch_upload(table.data(), table.size(), static_cast<uint64_t*>(workspace), s) != BAGUA_OK) return BAGUA_ERR_LAUNCH;
+    const BatchView bv = batch_view(workspace, B, ew);
+    SignGeometry g = sign_geometry(chunk, chunk, BAGUA_RPW_SIGN);
+    g.grid = dim3(static_cast<unsigned>(total));
+    const uint32_t ch = static_cast<uint32_t>(chunk);
+    if (ef) {
+        BAGUA_DISPATCH_RPW(g.rpw, hipLaunchKernelGGL((k_sign_compress_batched<RPW, true>), g.grid, g.block, g.lds, s, bv, ch))
+    } else {
+        BAGUA_DISPATCH_RPW(g.rpw, hipLaunchKernelGGL((k_sign_compress_batched<RPW, false>), g.grid, g.block, g.lds, s, bv, ch))
     }
     return launch_status();
 }
