@@ -1,25 +1,31 @@
 #!/usr/bin/env python3
 """Benchmark of the compression hot path on one MI355X.
 
-Default workload (the one the headline metric is quoted on): ResNet-50-shaped gradients for 8 simulated
-workers (8 sets of buffers in one GPU's HBM) in greedy 25 MiB buckets.  One "step" is one pass of the whole
-hot path over one batch of gradients:
+Default run (`python bench.py`): every primitive is timed at the LARGEST benchmark configuration that names it,
+one configuration after another (buffers freed in between), each with --warmup untimed and --steps timed steps:
 
-  flatten            per worker     layer tensors -> contiguous buckets
-  compress_minmax    per worker     MinMax-u8 with the worker error state (delta)
-  drr_minmax         once           decode + average the 8 workers + server error state (epsilon) + recompress
-                                    + decode to fp32
-  ring_fp            once           ring averaging of 8 replicas, full precision
-  ring_lp            once           ring averaging with u8-compressed differences
-  sign_compress      per worker     1-bit sign + per-chunk scale with error state
-  drr_sign           once           the server step with the sign codec
+  configs[2]  BERT-large-shaped gradients, 16 workers, C = 8192     flatten, compress_minmax, drr_minmax
+  configs[3]  8 peers x BERT-base-shaped replicas on a ring           ring_fp, ring_lp
+  configs[4]  1.5e9 elements x 8 workers, 1-bit sign codec, C = 2048  sign_compress, drr_sign (one launch per worker)
 
-A launch covers all buckets of one worker (they sit back to back in one flat allocation and every bucket is
-padded to a multiple of k*chunk, so the result is bit-identical to bucket-by-bucket launches, which
---per-bucket-launch times instead).  Inputs are generated on the GPU before the timed region and stay
-resident in HBM.  Prints ONE JSON line.  --workload selects the other benchmark configurations' shapes
-(bert_large: k=16, C=8192, Student-t; bert_base_ring: 8 peers x 109.5M; onebit: 1.5e9 Laplace elements, C=2048),
-each restricted to the primitives that configuration names.  --gpus N with N > 1 is refused.
+One "step" is one pass of the whole hot path: all seven primitives, each over its configuration's batch.  The
+headline `value` is 4 B x fp32 gradient elements consumed, summed over the seven primitives, over the summed wall time
+of one step of each of the three blocks.  Reported in addition (own timing, not part of `value`): configs[4] as 229
+separately allocated buckets per worker through the batched entry points, configs[1] (ResNet-50 shapes, all seven
+primitives) and configs[0] replicated 32 times (plus the latency of one cache-resident instance).
+
+Per primitive: ms, launches, gradient GB/s, algorithmic HBM GB/s, fraction of the 8 TB/s peak and of the measured copy
+ceiling.  `roofline` is the kernel with the largest share of the timed GPU time; `roofline_per_config` has the dominant
+kernel of every block.  `cpu_baseline` times the CPU oracle on a bounded sample (>= 1 GiB of fp32 input where the
+configuration is that large) of every block on the host cores; `parity` compares the HIP path with the oracle's
+outputs on those same samples, all primitives, word for word.  Inputs are generated on the GPU before the timed
+region and stay resident in HBM.  Prints ONE JSON line.
+
+--workload W runs one block only (resnet50, bert_large, bert_base_ring, onebit, single_bucket_x32); --layout chooses
+how a worker's buckets are launched: flat (default: back to back in one allocation, one launch per worker; every bucket
+is padded to a multiple of k*chunk, so results equal bucket-by-bucket launches bit for bit), per_bucket (one launch per
+bucket) or buckets (separately allocated buckets, one batched launch per worker).  --verify-all streams EVERY element
+of configs[2], [3] (5 rounds) and [4] through the oracle instead of timing.  --gpus N with N > 1 is refused.
 """
 import argparse
 import json
@@ -45,16 +51,27 @@ WORKLOADS = {
                            label="configs[3]: 8 peers x BERT-base-shaped replicas (109,482,240 fp32), base + drift"),
     "onebit": dict(cfg=4, k=8, chunk=4096, sign_chunk=2048, dist="laplace", sets=1, prims=["sign_compress", "drr_sign"],
                    label="configs[4]: 1.5e9 fp32 per worker, Laplace(0,1e-3), 1-bit sign codec"),
+    "single_bucket_x32": dict(cfg=0, k=4, chunk=4096, sign_chunk=2048, dist="normal", sets=3,
+                              prims=["compress_minmax", "drr_minmax"],
+                              label="configs[0] x 32 independent instances: 1,048,576 fp32 per worker and instance, N(0,1e-3)"),
 }
+ONEBIT_N = 1500000000
+INSTANCES = 32
+# the default run: (workload, layout, counts towards the headline)
+DEFAULT_PLAN = [("bert_large", "flat", True), ("bert_base_ring", "flat", True), ("onebit", "flat", True),
+                ("onebit", "buckets", False), ("resnet50", "flat", False), ("single_bucket_x32", "flat", False)]
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="resnet50", choices=sorted(WORKLOADS))
-    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="all", choices=["all"] + sorted(WORKLOADS))
+    ap.add_argument("--layout", default="flat", choices=["flat", "per_bucket", "buckets"],
+                    help="with --workload: flat = one launch per worker over its contiguous buckets; per_bucket = one "
+                         "launch per bucket; buckets = separately allocated buckets, one batched launch per worker")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and parity leg")
     ap.add_argument("--only", default="", help="comma list of primitives to run in the step (profiling aid)")
     ap.add_argument("--extras", default="", help="comma list of additional primitives appended to the step: sgd_step "
                     "(decode of the server's codes fused into an SGD-momentum update of every worker's replica), "
@@ -66,19 +83,22 @@ def parse_args():
                     "the per-chunk top-K codec, keep = chunk/32: worker side and server side)")
     ap.add_argument("--fused-flatten", action="store_true",
                     help="replace flatten + compress_minmax by the fused bagua_flatten_compress_minmax_u8")
-    ap.add_argument("--per-bucket-launch", action="store_true",
-                    help="one launch per 25 MiB bucket instead of one per worker covering all its buckets")
+    ap.add_argument("--per-bucket-launch", action="store_true", help="same as --layout per_bucket")
+    ap.add_argument("--verify-all", action="store_true",
+                    help="no timing: compare EVERY element of configs[2], configs[3] (5 rounds) and configs[4] with the oracle")
     return ap.parse_args()
 
 
 class Workload:
     """Synthetic gradients / replicas of one benchmark configuration, all state resident on the GPU."""
 
-    def __init__(self, torch, bg, name, per_bucket=False, only=None, fused=False, extras=()):
+    def __init__(self, torch, bg, name, layout="flat", only=None, fused=False, extras=()):
         from bagua_workloads import resnet50_shapes, bert_shapes, pack_buckets, draw, seed_for, layer_sigmas
         from bagua_workloads.shapes import numel
         from bagua_workloads.generators import SHARED
-        self.torch, self.bg, self.name = torch, bg, name
+        self.torch, self.bg, self.name, self.layout = torch, bg, name, layout
+        per_bucket = layout in ("per_bucket", "buckets")
+        self.batched = layout == "buckets"
         w = WORKLOADS[name]
         self.w = w
         self.k, self.C, self.SC = w["k"], w["chunk"], w["sign_chunk"]
@@ -111,14 +131,22 @@ class Workload:
 
         # ---- shapes, buckets, launch units
         if name == "onebit":
-            shapes = [("momentum", (1500000000,))]
-            n = 1500000000
+            shapes = [("momentum", (ONEBIT_N,))]
+            n = ONEBIT_N
             self.buckets, self.bases = [], [0, n]
-            self.units = [(0, n, [0], [0])]
+            if per_bucket:      # 229 buckets of 25 MiB, the last one short
+                from bagua_workloads import BUCKET_ELEMS
+                self.units = [(lo, min(BUCKET_ELEMS, n - lo), [0], [0]) for lo in range(0, n, BUCKET_ELEMS)]
+            else:
+                self.units = [(0, n, [0], [0])]
         else:
-            shapes = {"resnet50": resnet50_shapes, "bert_large": lambda: bert_shapes(24, 1024, 4096),
-                      "bert_base_ring": lambda: bert_shapes(12, 768, 3072)}[name]()
-            self.buckets = pack_buckets(shapes, k, C)
+            if name == "single_bucket_x32":
+                shapes = [("instance%d" % i, (1048576,)) for i in range(INSTANCES)]
+                self.buckets = pack_buckets(shapes, k, C, cap=1048576)
+            else:
+                shapes = {"resnet50": resnet50_shapes, "bert_large": lambda: bert_shapes(24, 1024, 4096),
+                          "bert_base_ring": lambda: bert_shapes(12, 768, 3072)}[name]()
+                self.buckets = pack_buckets(shapes, k, C)
             self.bases = [0]
             for bk in self.buckets:
                 self.bases.append(self.bases[-1] + bk.n_pad)
@@ -138,8 +166,10 @@ class Workload:
         nc, ncs = (n + C - 1) // C, (n + SC - 1) // SC
 
         def views(t, div=1, mul=1):
-            """Per-unit views of a flat tensor whose index is element_index * mul / div."""
-            return [t[lo * mul // div:-(-(lo + ln) * mul // div)] for lo, ln, _, _ in self.units]
+            """Per-unit views of a flat tensor whose index is element_index * mul / div; in the "buckets" layout every
+            unit gets an allocation of its own instead (the flat tensor is dropped by the caller)."""
+            vs = [t[lo * mul // div:-(-(lo + ln) * mul // div)] for lo, ln, _, _ in self.units]
+            return [v.clone() for v in vs] if self.batched else vs
 
         # ---- gradients: layer tensors (when flatten runs) or ready-made flat buckets
         self.sets = w["sets"]
@@ -250,6 +280,10 @@ class Workload:
                 self.nb_left = [views(base.clone()) for _ in range(k)]
                 self.nb_right = [views(base.clone()) for _ in range(k)]
                 self.sh_hat = [views(base.clone()) for _ in range(k)]
+        if self.batched:
+            self.bws = torch.empty(bg.bagua_batch_workspace_bytes(U, 0), **u8)
+            self.bws_k = torch.empty(bg.bagua_batch_workspace_bytes(U, k), **u8)
+            self.unit_n = [ln for _, ln, _, _ in self.units]
         self.step_no = 0
         torch.cuda.synchronize()
 
@@ -277,7 +311,7 @@ class Workload:
         return {p: bpe[p] * units[p] for p in self.prims}
 
     def launches(self):
-        U, k = len(self.units), self.k
+        U, k = (1 if self.batched else len(self.units)), self.k
         per = {"flatten": U * k, "flatten_compress": U * k, "compress_minmax": U * k, "drr_minmax": U, "ring_fp": U, "ring_lp": U,
                "sign_compress": U * k, "drr_sign": U, "sgd_step": U * k, "adam_step": U * k, "momentum_sign": U * k, "adam_frozen_step": U * k, "peer_fp": U, "peer_lp": U, "lp_encode": U * k, "lp_apply_mix": U * k, "reduce_compress": U * (k // 4),
                "compress_topk": U * k, "drr_topk": U}
@@ -310,7 +344,9 @@ class Workload:
 
         mark("start")
         for p in self.prims:
-            if p == "flatten":
+            if self.batched and p in ("flatten", "compress_minmax", "drr_minmax", "sign_compress", "drr_sign"):
+                self.step_batched(p, it)
+            elif p == "flatten":
                 for j in range(k):
                     for u in range(U):
                         bg.bagua_bucket_flatten_run(self.plans[it][j][u], len(self.units[u][2]), self.bucket[j][u])
@@ -416,109 +452,234 @@ class Workload:
         self.step_no += 1
 
 
-def cpu_baseline(wl, torch):
-    """The oracle, as it stands, on the host cores: one step of the default workload (every bucket, all workers,
-    the same primitives), timed once.  Returns the cpu_baseline dict for the JSON line and, from the one-core leg's
-    outputs, the parity report of the HIP path on the same bucket."""
-    import numpy as np
-    import oracle
-    threads = max(1, min(16, oracle.max_threads(), os.cpu_count() or 1))
-    oracle.set_threads(threads)
-    k, C, SC = wl.k, wl.C, wl.SC
-    dt = 0.0
-    for b, bk in enumerate(wl.buckets):
-        n, lo = bk.n_pad, wl.bases[b]
-        srcs = [[wl.layers[0][j][t].cpu().numpy() for t in bk.tensors] for j in range(k)]
-        reps = [torch.cat(wl.rep_fp[wl.step_no % 2][i])[lo:lo + n].cpu().numpy() for i in range(k)]
-        hats = [torch.cat(wl.xhat[i])[lo:lo + n].cpu().numpy().copy() for i in range(k)]
-        t0 = time.perf_counter()
-        flats = [oracle.bucket_flatten(srcs[j], bk.offsets, n) for j in range(k)]
-        deltas = [np.zeros(n, np.float32) for _ in range(k)]
-        enc = [oracle.compress_minmax_u8(flats[j], deltas[j], C) for j in range(k)]
-        oracle.drr_minmax_u8([e[0] for e in enc], [e[1] for e in enc], np.zeros(n, np.float32), C)
-        oracle.ring_avg_fp(reps)
-        oracle.ring_avg_lp(reps, hats, C)
-        sd = [np.zeros(n, np.float32) for _ in range(k)]
-        senc = [oracle.sign_compress_ef(flats[j], sd[j], SC) for j in range(k)]
-        oracle.drr_sign([e[0] for e in senc], [e[1] for e in senc], np.zeros(n, np.float32), n, SC)
-        dt += time.perf_counter() - t0
-    grad_bytes = 4.0 * wl.n_elems * k * len(ALL_PRIMS)
-    # the same on one core, on the last (smallest) bucket only
-    oracle.set_threads(1)
-    bk = wl.buckets[-1]
-    n1, lo = bk.n_pad, wl.bases[len(wl.buckets) - 1]
-    flats_g = [torch.cat(wl.bucket[j])[lo:lo + n1].contiguous() for j in range(k)]
-    flats = [f.cpu().numpy() for f in flats_g]
-    d_o = [np.zeros(n1, np.float32) for _ in range(k)]
-    sd_o = [np.zeros(n1, np.float32) for _ in range(k)]
-    eps_o, seps_o = np.zeros(n1, np.float32), np.zeros(n1, np.float32)
-    t0 = time.perf_counter()
-    enc = [oracle.compress_minmax_u8(flats[j], d_o[j], C) for j in range(k)]
-    drr = oracle.drr_minmax_u8([e[0] for e in enc], [e[1] for e in enc], eps_o, C)
-    senc = [oracle.sign_compress_ef(flats[j], sd_o[j], SC) for j in range(k)]
-    sdrr = oracle.drr_sign([e[0] for e in senc], [e[1] for e in senc], seps_o, n1, SC)
-    dt1 = time.perf_counter() - t0
-    parity = parity_sample(torch, wl.bg, flats_g, C, SC, enc, d_o, drr, eps_o, senc, sd_o, sdrr, seps_o)
-    oracle.set_threads(threads)
-    return {"value": round(grad_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "sample": "one full step of the same workload (%d elements x %d workers, all seven primitives), "
-                      "%.1f s wall on %d threads" % (wl.n_elems, k, dt, threads),
-            "one_core_value": round(4.0 * n1 * k * 4 / dt1 / 1e9, 3),
-            "one_core_sample": "compress_minmax, drr_minmax, sign_compress, drr_sign on the last bucket "
-                               "(%d elements x %d workers), %.1f s on 1 thread" % (n1, k, dt1)}, parity
+    def step_batched(self, p, it):
+        """One primitive over all separately allocated buckets: one batched launch per worker (or one in all)."""
+        bg, k, U, C, SC = self.bg, self.k, len(self.units), self.C, self.SC
+        if p == "flatten":
+            for j in range(k):
+                bg.bagua_bucket_flatten_batched_run(self.plans[it][j], [len(u[2]) for u in self.units], self.bucket[j], self.bws)
+        elif p == "compress_minmax":
+            for j in range(k):
+                bg.bagua_compress_minmax_u8_batched(self.bucket[j], self.delta[j], C, self.codes[j], self.minmax[j], self.bws)
+        elif p == "sign_compress":
+            for j in range(k):
+                bg.bagua_sign_compress_ef_batched(self.bucket[j], self.sdelta[j], SC, self.bits[j], self.scale[j], self.bws)
+        elif p == "drr_minmax":
+            bg.bagua_decompress_reduce_recompress_batched(
+                bg.CODEC_MINMAX_U8, [[self.codes[j][u] for j in range(k)] for u in range(U)],
+                [[self.minmax[j][u] for j in range(k)] for u in range(U)], self.eps, self.unit_n, C, self.codes_out,
+                self.minmax_out, self.out, self.bws_k)
+        elif p == "drr_sign":
+            bg.bagua_decompress_reduce_recompress_batched(
+                bg.CODEC_SIGN1, [[self.bits[j][u] for j in range(k)] for u in range(U)],
+                [[self.scale[j][u] for j in range(k)] for u in range(U)], self.seps, self.unit_n, SC, self.bits_out,
+                self.scale_out, self.sout, self.bws_k)
 
 
-def parity_sample(torch, bg, xs, C, SC, enc, d_o, drr, eps_o, senc, sd_o, sdrr, seps_o):
-    """The HIP path on the buckets the one-core oracle leg just processed (same bits, zero initial error state),
-    compared word for word with the oracle's outputs.  Integer outputs must be equal; fp32 outputs are counted twice:
-    words that are not bit-identical, and words outside 1e-6 relative + 1e-7 absolute."""
+GIB = 1 << 30
+
+
+class Counts:
+    """Word-for-word comparison of HIP outputs with oracle outputs: integer words must be equal; fp32 words are
+    counted twice: not bit-identical, and outside 1e-6 relative + 1e-7 absolute."""
+
+    def __init__(self):
+        self.c = {"int_words": 0, "int_mismatch": 0, "fp32_words": 0, "fp32_not_bit_exact": 0, "fp32_out_of_tolerance": 0}
+
+    def ints(self, t, ref):
+        import numpy as np
+        a = t.cpu().numpy().view(ref.dtype).reshape(-1)
+        self.c["int_words"] += a.size
+        self.c["int_mismatch"] += int(np.count_nonzero(a != ref.reshape(-1)))
+
+    def floats(self, t, ref):
+        import numpy as np
+        a = t.cpu().numpy().reshape(-1)
+        ref = ref.reshape(-1)
+        self.c["fp32_words"] += a.size
+        nb = int(np.count_nonzero(a.view(np.uint32) != ref.view(np.uint32)))
+        self.c["fp32_not_bit_exact"] += nb
+        if nb:
+            err = np.abs(a.astype(np.float64) - ref.astype(np.float64))
+            self.c["fp32_out_of_tolerance"] += int(np.count_nonzero(~(err <= 1e-6 * np.abs(ref.astype(np.float64)) + 1e-7)))
+
+    def add(self, other):
+        for k_ in self.c:
+            self.c[k_] += other.c[k_]
+
+    def clean(self):
+        return self.c["int_mismatch"] == 0 and self.c["fp32_not_bit_exact"] == 0
+
+
+def c_lp_s_sample(torch, bg, oracle, xs, C, SC, want_minmax, want_sign, cnt, layers=None):
+    """Oracle and HIP path on one sample (k flat buckets xs, zero initial error states): MinMax C_LP_S (worker + server)
+    and / or sign C_LP_S.  layers = (per-worker tensor lists, offsets): the buckets are first assembled by the flatten on
+    both sides.  Returns the oracle's wall time; comparison counts go to cnt."""
     import numpy as np
-    k, n = len(xs), xs[0].numel()
+    k = len(xs)
+    n = xs[0].numel()
     dev = xs[0].device
     nc, ncs = (n + C - 1) // C, (n + SC - 1) // SC
     f32 = dict(dtype=torch.float32, device=dev)
-    cnt = {"int_words": 0, "int_mismatch": 0, "fp32_words": 0, "fp32_not_bit_exact": 0, "fp32_out_of_tolerance": 0}
+    xh = [x.cpu().numpy() for x in xs]
+    dt = 0.0
+    if layers is not None:
+        per_worker, offs = layers
+        lay_h = [[t.cpu().numpy() for t in per_worker[j]] for j in range(k)]
+        t0 = time.perf_counter()
+        flats = [oracle.bucket_flatten(lay_h[j], offs, n) for j in range(k)]
+        dt += time.perf_counter() - t0
+        ws = torch.empty(bg.bagua_flatten_workspace_bytes(len(offs), n), dtype=torch.uint8, device=dev)
+        for j in range(k):
+            got = torch.full((n,), float("nan"), **f32)
+            bg.bagua_bucket_flatten(per_worker[j], offs, got, ws)
+            cnt.ints(got.view(torch.int32), flats[j].view(np.int32))     # a copy: compared as words
+            cnt.ints(xs[j].view(torch.int32), flats[j].view(np.int32))   # the resident bucket the timed flatten wrote
+        xh = flats
+    if want_minmax:
+        d_o = [np.zeros(n, np.float32) for _ in range(k)]
+        eps_o = np.zeros(n, np.float32)
+        t0 = time.perf_counter()
+        enc = [oracle.compress_minmax_u8(xh[j], d_o[j], C) for j in range(k)]
+        drr = oracle.drr_minmax_u8([e[0] for e in enc], [e[1] for e in enc], eps_o, C)
+        dt += time.perf_counter() - t0
+        codes = [torch.empty(n, dtype=torch.uint8, device=dev) for _ in range(k)]
+        mm = [torch.empty(2 * nc, **f32) for _ in range(k)]
+        delta = [torch.zeros(n, **f32) for _ in range(k)]
+        for j in range(k):
+            bg.bagua_compress_minmax_u8(xs[j], delta[j], C, codes[j], mm[j])
+        eps = torch.zeros(n, **f32)
+        c2, m2, o2 = torch.empty(n, dtype=torch.uint8, device=dev), torch.empty(2 * nc, **f32), torch.empty(n, **f32)
+        bg.bagua_decompress_reduce_recompress(bg.CODEC_MINMAX_U8, codes, mm, eps, n, C, c2, m2, o2)
+        for j in range(k):
+            cnt.ints(codes[j], enc[j][0]); cnt.floats(mm[j], enc[j][1]); cnt.floats(delta[j], d_o[j])
+        cnt.ints(c2, drr[0]); cnt.floats(m2, drr[1]); cnt.floats(o2, drr[2]); cnt.floats(eps, eps_o)
+        del codes, mm, delta, eps, c2, m2, o2, enc, drr, d_o
+    if want_sign:
+        sd_o = [np.zeros(n, np.float32) for _ in range(k)]
+        seps_o = np.zeros(n, np.float32)
+        t0 = time.perf_counter()
+        senc = [oracle.sign_compress_ef(xh[j], sd_o[j], SC) for j in range(k)]
+        sdrr = oracle.drr_sign([e[0] for e in senc], [e[1] for e in senc], seps_o, n, SC)
+        dt += time.perf_counter() - t0
+        bits = [torch.empty((n + 31) // 32, dtype=torch.int32, device=dev) for _ in range(k)]
+        scale = [torch.empty(ncs, **f32) for _ in range(k)]
+        sdelta = [torch.zeros(n, **f32) for _ in range(k)]
+        for j in range(k):
+            bg.bagua_sign_compress_ef(xs[j], sdelta[j], SC, bits[j], scale[j])
+        seps = torch.zeros(n, **f32)
+        b2, s2, so2 = torch.empty((n + 31) // 32, dtype=torch.int32, device=dev), torch.empty(ncs, **f32), torch.empty(n, **f32)
+        bg.bagua_decompress_reduce_recompress(bg.CODEC_SIGN1, bits, scale, seps, n, SC, b2, s2, so2)
+        for j in range(k):
+            cnt.ints(bits[j], senc[j][0]); cnt.floats(scale[j], senc[j][1]); cnt.floats(sdelta[j], sd_o[j])
+        cnt.ints(b2, sdrr[0]); cnt.floats(s2, sdrr[1]); cnt.floats(so2, sdrr[2]); cnt.floats(seps, seps_o)
+    return dt
 
-    def ints(t, ref):
-        a = t.cpu().numpy().view(ref.dtype).reshape(-1)
-        cnt["int_words"] += a.size
-        cnt["int_mismatch"] += int(np.count_nonzero(a != ref.reshape(-1)))
 
-    def floats(t, ref):
-        a = t.cpu().numpy()
-        cnt["fp32_words"] += a.size
-        cnt["fp32_not_bit_exact"] += int(np.count_nonzero(a.view(np.uint32) != ref.view(np.uint32)))
-        err = np.abs(a.astype(np.float64) - ref.astype(np.float64))
-        cnt["fp32_out_of_tolerance"] += int(np.count_nonzero(~(err <= 1e-6 * np.abs(ref.astype(np.float64)) + 1e-7)))
+def ring_sample(torch, bg, oracle, reps, hats, C, want_fp, want_lp, cnt):
+    """One ring round in full and / or low precision on k replica slices, oracle and HIP path; returns oracle time."""
+    import numpy as np
+    k, n = len(reps), reps[0].numel()
+    dev = reps[0].device
+    nc = (n + C - 1) // C
+    rh = [r.cpu().numpy() for r in reps]
+    dt = 0.0
+    if want_fp:
+        t0 = time.perf_counter()
+        ref = oracle.ring_avg_fp(rh)
+        dt += time.perf_counter() - t0
+        outs = [torch.empty(n, device=dev) for _ in range(k)]
+        bg.bagua_decentralized_avg(bg.AVG_FP, reps, outs)
+        for i in range(k):
+            cnt.floats(outs[i], ref[i])
+        del outs, ref
+    if want_lp:
+        hh = [h.cpu().numpy().copy() for h in hats]
+        t0 = time.perf_counter()
+        ro, rc, rm = oracle.ring_avg_lp(rh, hh, C)
+        dt += time.perf_counter() - t0
+        hg = [h.clone() for h in hats]
+        outs = [torch.empty(n, device=dev) for _ in range(k)]
+        codes = [torch.empty(n, dtype=torch.uint8, device=dev) for _ in range(k)]
+        mm = [torch.empty(2 * nc, device=dev) for _ in range(k)]
+        bg.bagua_decentralized_avg(bg.AVG_LP_MINMAX_U8, reps, outs, hg, codes, mm, C)
+        for i in range(k):
+            cnt.floats(outs[i], ro[i]); cnt.ints(codes[i], rc[i]); cnt.floats(mm[i], rm[i]); cnt.floats(hg[i], hh[i])
+    return dt
 
-    codes = [torch.empty(n, dtype=torch.uint8, device=dev) for _ in range(k)]
-    mm = [torch.empty(2 * nc, **f32) for _ in range(k)]
-    delta = [torch.zeros(n, **f32) for _ in range(k)]
-    bits = [torch.empty((n + 31) // 32, dtype=torch.int32, device=dev) for _ in range(k)]
-    scale = [torch.empty(ncs, **f32) for _ in range(k)]
-    sdelta = [torch.zeros(n, **f32) for _ in range(k)]
-    for j in range(k):
-        bg.bagua_compress_minmax_u8(xs[j], delta[j], C, codes[j], mm[j])
-        bg.bagua_sign_compress_ef(xs[j], sdelta[j], SC, bits[j], scale[j])
-    eps, seps = torch.zeros(n, **f32), torch.zeros(n, **f32)
-    c2, m2, o2 = torch.empty(n, dtype=torch.uint8, device=dev), torch.empty(2 * nc, **f32), torch.empty(n, **f32)
-    b2, s2, so2 = torch.empty((n + 31) // 32, dtype=torch.int32, device=dev), torch.empty(ncs, **f32), torch.empty(n, **f32)
-    bg.bagua_decompress_reduce_recompress(bg.CODEC_MINMAX_U8, codes, mm, eps, n, C, c2, m2, o2)
-    bg.bagua_decompress_reduce_recompress(bg.CODEC_SIGN1, bits, scale, seps, n, SC, b2, s2, so2)
+
+def cpu_baseline(wl, torch):
+    """The oracle, as it stands, on the host cores, on a bounded sample of the block's own resident inputs (at least
+    1 GiB of fp32 input where the block is that large), and the HIP path compared with the oracle's outputs on that
+    same sample (every primitive of the block, zero initial error states).  Flat layout only."""
+    import oracle
+    bg = wl.bg
+    threads = max(1, min(16, oracle.max_threads(), os.cpu_count() or 1))
+    oracle.set_threads(threads)
+    k, C, SC = wl.k, wl.C, wl.SC
+    cnt = Counts()
+    has = lambda *ps: any(p in wl.prims for p in ps)
+    dt, elems, nprims, what = 0.0, 0, 0, ""
+    if has("flatten", "compress_minmax", "drr_minmax", "sign_compress", "drr_sign"):
+        if wl.buckets:      # whole buckets from the front until the sample holds >= 1 GiB of input (or everything)
+            nb = 0
+            while nb < len(wl.buckets) and 4 * k * wl.bases[nb] < GIB:
+                nb += 1
+            m = wl.bases[nb]
+            what = "the first %d of %d buckets" % (nb, len(wl.buckets))
+        else:
+            m = min(wl.n_elems, -(-GIB // (4 * k)) // SC * SC)
+            what = "the first %d elements of every worker" % m
+        xs = [wl.bucket[j][0][:m] for j in range(k)]
+        layers = None
+        if has("flatten"):
+            ids = [t for bk in wl.buckets[:nb] for t in bk.tensors]
+            offs = [wl.bases[b] + o for b, bk in enumerate(wl.buckets[:nb]) for o in bk.offsets]
+            # the resident buckets hold what the LAST timed flatten wrote: gradient set (step_no - 1) % sets
+            it = (wl.step_no - 1) % wl.sets
+            layers = ([[wl.layers[it][j][t] for t in ids] for j in range(k)], offs)
+        mm_p, sg_p = has("compress_minmax", "drr_minmax"), has("sign_compress", "drr_sign")
+        dt += c_lp_s_sample(torch, bg, oracle, xs, C, SC, mm_p, sg_p, cnt, layers)
+        nprims += (1 if layers else 0) + (2 if mm_p else 0) + (2 if sg_p else 0)
+        elems = m
+    if has("ring_fp", "ring_lp"):
+        m = min(wl.n_elems, -(-GIB // (4 * k)) // C * C)
+        src = wl.step_no % 2
+        which = wl.rep_fp if has("ring_fp") else wl.rep_lp
+        reps = [which[src][i][0][:m] for i in range(k)]
+        hats = [wl.xhat[i][0][:m] for i in range(k)] if has("ring_lp") else None
+        dt += ring_sample(torch, bg, oracle, reps, hats, C, has("ring_fp"), has("ring_lp"), cnt)
+        nprims += int(has("ring_fp")) + int(has("ring_lp"))
+        what = (what + "; " if what else "") + "the first %d elements of every replica" % m
+        elems = max(elems, m)
     torch.cuda.synchronize()
-    for j in range(k):
-        ints(codes[j], enc[j][0]); floats(mm[j], enc[j][1]); floats(delta[j], d_o[j])
-        ints(bits[j], senc[j][0]); floats(scale[j], senc[j][1]); floats(sdelta[j], sd_o[j])
-    ints(c2, drr[0]); floats(m2, drr[1]); floats(o2, drr[2]); floats(eps, eps_o)
-    ints(b2, sdrr[0]); floats(s2, sdrr[1]); floats(so2, sdrr[2]); floats(seps, seps_o)
-    cnt["sample"] = ("compress_minmax, drr_minmax, sign_compress, drr_sign on the last bucket (%d elements x %d workers), "
-                     "HIP path against the oracle" % (n, k))
-    return cnt
+    grad_bytes = 4.0 * elems * k * nprims
+    base = {"value": round(grad_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "seconds": round(dt, 2), "gradient_bytes": grad_bytes,
+            "sample": "%s (%d elements x %d workers, %.2f GiB of fp32 input), %d primitives, %.1f s on %d threads" %
+                      (what, elems, k, 4.0 * elems * k / GIB, nprims, dt, threads)}
+    par = dict(cnt.c)
+    par["sample"] = "every primitive of the block on " + what + ", HIP path against the oracle"
+    return base, par
 
 
-def copy_ceiling(torch, bg):
-    """Throughput of a plain 128-bit copy on this GPU, for context next to the roofline: bagua_bucket_flatten_run with
-    a single tensor covering the whole bucket is exactly that (read 4 B, write 4 B per element).  GB/s."""
+def time_fn(torch, fn, reps):
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for i in range(3):
+        fn(i)
+    ev[0].record()
+    for i in range(reps):
+        fn(i + 3)
+    ev[1].record()
+    torch.cuda.synchronize()
+    return ev[0].elapsed_time(ev[1]) * 1e-3 / reps
+
+
+def ceilings(torch, bg):
+    """What the memory system of this GPU delivers for plain access patterns, GB/s: a 128-bit copy
+    (bagua_bucket_flatten_run with one tensor covering the bucket), a read-only reduction, and stream mixes of the
+    ring kernels' traffic shape (one wave per row: 8 reads + 8 writes; the 2 reads + 2 writes + 1 byte stream of one
+    ring-LP peer; the same for 8 peers one after another in every wave)."""
     n = 128 * 1024 * 1024
     bufs = [(torch.zeros(n, device="cuda"), torch.empty(n, device="cuda")) for _ in range(2)]   # 2 GiB rotated
     plans = []
@@ -526,50 +687,51 @@ def copy_ceiling(torch, bg):
         ws = torch.empty(bg.bagua_flatten_workspace_bytes(1, n), dtype=torch.uint8, device="cuda")
         bg.bagua_flatten_plan([src], [0], n, ws)
         plans.append(ws)
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    for i in range(4):
-        bg.bagua_bucket_flatten_run(plans[i % 2], 1, bufs[i % 2][1])
-    ev[0].record()
-    reps = 20
-    for i in range(reps):
-        bg.bagua_bucket_flatten_run(plans[i % 2], 1, bufs[i % 2][1])
-    ev[1].record()
-    torch.cuda.synchronize()
-    return 8.0 * n * reps / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+    out = {}
+    t = time_fn(torch, lambda i: bg.bagua_bucket_flatten_run(plans[i % 2], 1, bufs[i % 2][1]), 20)
+    out["copy_kernel_GBps"] = round(8.0 * n / t / 1e9, 1)
+    sums = torch.empty(n // 4096, device="cuda")
+    t = time_fn(torch, lambda i: bg.bagua_probe_read(bufs[i % 2][i % 2], sums), 20)
+    out["read_kernel_GBps"] = round(4.0 * n / t / 1e9, 1)
+    del bufs, plans
+    m = 32 * 1024 * 1024          # 8 peers x (x, xhat, out fp32 + codes u8) = 3.6 GB per launch
+    x = [torch.zeros(m, device="cuda") for _ in range(8)]
+    h = [torch.zeros(m, device="cuda") for _ in range(8)]
+    o = [torch.empty(m, device="cuda") for _ in range(8)]
+    c = [torch.empty(m, dtype=torch.uint8, device="cuda") for _ in range(8)]
+    t = time_fn(torch, lambda i: bg.bagua_probe_streams(x, o, [], 8, 8, 0, 1, m), 10)
+    out["mix_8R8W_GBps"] = round(64.0 * m / t / 1e9, 1)
+
+    def one_peer_at_a_time(i):
+        for p in range(8):
+            bg.bagua_probe_streams([x[p], h[p]], [h[p], o[p]], [c[p]], 2, 2, 1, 1, m)
+    t = time_fn(torch, one_peer_at_a_time, 10)
+    out["mix_2R2W1B_one_peer_per_wave_GBps"] = round(17.0 * 8 * m / t / 1e9, 1)
+    ins = [t_ for p in range(8) for t_ in (x[p], h[p])]
+    outs = [t_ for p in range(8) for t_ in (h[p], o[p])]
+    t = time_fn(torch, lambda i: bg.bagua_probe_streams(ins, outs, c, 2, 2, 1, 8, m), 10)
+    out["mix_2R2W1B_eight_peers_per_wave_GBps"] = round(17.0 * 8 * m / t / 1e9, 1)
+    return out
 
 
-def read_traffic():
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, if present."""
-    path = os.path.join(ROOT, "profiles", "compress_minmax_resnet50_traffic.txt")
+def read_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary of this workload, if there is
+    one: profiles/traffic_<workload>.txt, lines `traffic_bytes_per_launch <kernel> <bytes>`."""
+    path = os.path.join(ROOT, "profiles", "traffic_%s.txt" % workload)
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":", 1)[1])
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and f[1] == kernel:
+                return float(f[2])
     except OSError:
         pass
     return None
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build is the single-GPU share of the path (the k workers are k buffers in one GPU's "
-              "HBM); --gpus %d is not supported, run with --gpus 1" % args.gpus, file=sys.stderr)
-        sys.exit(2)
-    import torch
-    import __graft_entry__
-    __graft_entry__.ensure_built()        # uses what is built; compiles only if a library is missing altogether
-    import paper_2107_01499_amd as bg     # fails loudly if the HIP library cannot be loaded
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(2)
-    torch.cuda.set_device(0)
-    only = set(p for p in args.only.split(",") if p) or None
-    ceiling = copy_ceiling(torch, bg)
-    wl = Workload(torch, bg, args.workload, per_bucket=args.per_bucket_launch, only=only, fused=args.fused_flatten,
-                  extras=tuple(e for e in args.extras.split(",") if e))
+def run_block(torch, bg, args, name, layout, only, extras):
+    """Build one workload, time --warmup + --steps steps of it, then (flat layout) the oracle sample and parity."""
+    wl = Workload(torch, bg, name, layout=layout, only=only, fused=args.fused_flatten, extras=extras)
     prims = wl.prims
-
     for _ in range(args.warmup):
         wl.step()
     torch.cuda.synchronize()
@@ -585,46 +747,263 @@ def main():
     # per-primitive GPU time from the events recorded on the launch stream inside the timed region
     prim_ms = {p: 0.0 for p in prims}
     for marks in all_marks:
-        for (_, e0), (name, e1) in zip(marks[:-1], marks[1:]):
-            prim_ms[name] += e0.elapsed_time(e1)
+        for (_, e0), (pname, e1) in zip(marks[:-1], marks[1:]):
+            prim_ms[pname] += e0.elapsed_time(e1)
     gpu_ms = sum(m[0][1].elapsed_time(m[-1][1]) for m in all_marks)
     for p in prims:
         prim_ms[p] /= args.steps
-    ms_per_step = wall * 1e3 / args.steps
-
     gb, ab, nl = wl.grad_bytes(), wl.algo_bytes(), wl.launches()
-    total_grad = sum(gb[p] for p in prims)
     per_prim = {}
     for p in prims:
         t = prim_ms[p] * 1e-3
         per_prim[p] = {"ms": round(prim_ms[p], 4), "launches": nl[p], "gradient_GBps": round(gb[p] / t / 1e9, 1),
                        "hbm_GBps": round(ab[p] / t / 1e9, 1), "frac_of_peak": round(ab[p] / t / 1e9 / HBM_PEAK_GBS, 4),
-                       "frac_of_copy_kernel": round(ab[p] / t / 1e9 / ceiling, 4)}
-    dom = next((p for p in ("compress_minmax", "flatten_compress") if p in prims), None) or max(prims, key=lambda p: prim_ms[p])
+                       "kernel": wl.kernel_name(p), "gradient_bytes": gb[p], "algorithmic_bytes": ab[p]}
+        if p in ("drr_minmax", "drr_sign", "drr_topk"):
+            per_prim[p]["note"] = ("gradient_GBps counts the 4*k*n bytes of fp32 gradient the k compressed inputs "
+                                   "represent, not bytes moved; hbm_GBps is the bandwidth figure")
+    dom = max(prims, key=lambda p: prim_ms[p])
     dom_t = prim_ms[dom] * 1e-3 / nl[dom]
     achieved = ab[dom] / nl[dom] / dom_t / 1e9
-    traffic = read_traffic() if (dom == "compress_minmax" and args.workload == "resnet50" and not args.per_bucket_launch) else None
+    traffic = read_traffic(name, wl.kernel_name(dom)) if layout == "flat" else None
+    roof = {"bound": "hbm", "kernel": wl.kernel_name(dom), "primitive": dom, "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+            "avg_launch_us": round(dom_t * 1e6, 3), "algorithmic_bytes_per_launch": ab[dom] / nl[dom]}
+    if traffic is not None:
+        roof["traffic_source"] = ("profiles/traffic_%s.txt: rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier run of this "
+                                  "workload, scaled by what the same counters read for k_flatten (a copy of known size)" % name)
+    launch = {"flat": "one launch per worker over all its buckets (contiguous)", "per_bucket": "one launch per bucket",
+              "buckets": "separately allocated buckets, one batched launch per worker"}[layout]
+    block = {"workload": "%s; %d buckets, %d padded elements per worker, %d simulated workers, chunk %d (sign codec %d); "
+                         "primitives per step: %s" % (wl.w["label"], len(wl.units) if layout != "flat" else max(1, len(wl.buckets)),
+                                                      wl.n_elems, wl.k, wl.C, wl.SC, ", ".join(prims)),
+             "launch": launch, "ms_per_step": round(wall * 1e3 / args.steps, 4), "gpu_ms_per_step": round(gpu_ms / args.steps, 4),
+             "per_primitive": per_prim, "roofline": roof}
+    if name == "single_bucket_x32":
+        block["single_instance_latency_us"] = single_instance_latency(torch, bg, wl)
+    if not args.no_cpu_baseline and layout == "flat" and only is None and not args.fused_flatten and not extras:
+        block["cpu_baseline"], block["parity"] = cpu_baseline(wl, torch)
+    del wl
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+    return block, wall / args.steps
+
+
+def single_instance_latency(torch, bg, wl):
+    """configs[0] as it stands (one 1,048,576-element bucket, 4 workers): 4 compress launches + the server step, data
+    resident in the caches; microseconds per pass, launch gaps included."""
+    n, k, C = 1048576, wl.k, wl.C
+    nc = n // C
+    xs = [wl.bucket[j][0][:n] for j in range(k)]
+    delta = [torch.zeros(n, device="cuda") for _ in range(k)]
+    codes = [torch.empty(n, dtype=torch.uint8, device="cuda") for _ in range(k)]
+    mm = [torch.empty(2 * nc, device="cuda") for _ in range(k)]
+    eps, out = torch.zeros(n, device="cuda"), torch.empty(n, device="cuda")
+    c2, m2 = torch.empty(n, dtype=torch.uint8, device="cuda"), torch.empty(2 * nc, device="cuda")
+
+    def once(i):
+        for j in range(k):
+            bg.bagua_compress_minmax_u8(xs[j], delta[j], C, codes[j], mm[j])
+        bg.bagua_decompress_reduce_recompress(bg.CODEC_MINMAX_U8, codes, mm, eps, n, C, c2, m2, out)
+    return round(time_fn(torch, once, 50) * 1e6, 2)
+
+
+def verify_all(torch, bg):
+    """Every element of configs[2], configs[3] (5 rounds, full and low precision) and configs[4]: the HIP path at full
+    size in the launch configuration the benchmark times, against the oracle streamed span by span over the same
+    bits.  Stops at the first span that differs.  Prints one JSON line with the three counts per configuration."""
+    import numpy as np
+    import oracle
+    oracle.set_threads(max(1, min(16, oracle.max_threads(), os.cpu_count() or 1)))
+    report = {}
+
+    def done(name, cnt, t0):
+        report[name] = dict(cnt.c, seconds=round(time.perf_counter() - t0, 1))
+        print("verify-all: %s %s" % (name, report[name]), file=sys.stderr, flush=True)
+        return cnt.clean()
+
+    # ---- configs[2]: flatten, compress, server step, bucket by bucket
+    t0 = time.perf_counter()
+    wl = Workload(torch, bg, "bert_large")
+    wl.step()
+    torch.cuda.synchronize()
+    k, C = wl.k, wl.C
+    cnt = Counts()
+    for b, bk in enumerate(wl.buckets):
+        lo, hi = wl.bases[b], wl.bases[b + 1]
+        flats, enc, d_o = [], [], []
+        for j in range(k):
+            lay = [wl.layers[0][j][t].cpu().numpy() for t in bk.tensors]
+            f = oracle.bucket_flatten(lay, list(bk.offsets), bk.n_pad)
+            cnt.ints(wl.bucket[j][0][lo:hi].view(torch.int32), f.view(np.int32))
+            d = np.zeros(bk.n_pad, np.float32)
+            c, m = oracle.compress_minmax_u8(f, d, C)
+            cnt.ints(wl.codes[j][0][lo:hi], c)
+            cnt.floats(wl.minmax[j][0][2 * lo // C:2 * hi // C], m)
+            cnt.floats(wl.delta[j][0][lo:hi], d)
+            enc.append((c, m))
+        e = np.zeros(bk.n_pad, np.float32)
+        c2, m2, o2 = oracle.drr_minmax_u8([x[0] for x in enc], [x[1] for x in enc], e, C)
+        cnt.ints(wl.codes_out[0][lo:hi], c2)
+        cnt.floats(wl.minmax_out[0][2 * lo // C:2 * hi // C], m2)
+        cnt.floats(wl.out[0][lo:hi], o2)
+        cnt.floats(wl.eps[0][lo:hi], e)
+        print("verify-all: configs[2] bucket %d/%d (%d elements x %d workers) %s" %
+              (b + 1, len(wl.buckets), bk.n_pad, k, "ok" if cnt.clean() else "MISMATCH"), file=sys.stderr, flush=True)
+        if not cnt.clean():
+            break
+    ok = done("configs[2]", cnt, t0)
+    del wl
+    torch.cuda.empty_cache()
+
+    # ---- configs[3]: five ring rounds, full and low precision, host state carried round to round
+    if ok:
+        t0 = time.perf_counter()
+        wl = Workload(torch, bg, "bert_base_ring")
+        k, C, n = wl.k, wl.C, wl.n_elems
+        cnt = Counts()
+        x_fp = [wl.rep_fp[0][i][0].cpu().numpy() for i in range(k)]
+        x_lp = [wl.rep_lp[0][i][0].cpu().numpy() for i in range(k)]
+        hat = [wl.xhat[i][0].cpu().numpy().copy() for i in range(k)]
+        for rnd in range(5):
+            src, dst = wl.step_no % 2, (wl.step_no + 1) % 2
+            wl.step()
+            torch.cuda.synchronize()
+            x_fp = oracle.ring_avg_fp(x_fp)
+            x_lp, codes, mm = oracle.ring_avg_lp(x_lp, hat, C)
+            for i in range(k):
+                cnt.floats(wl.rep_fp[dst][i][0], x_fp[i])
+                cnt.floats(wl.rep_lp[dst][i][0], x_lp[i])
+                cnt.floats(wl.xhat[i][0], hat[i])
+                cnt.ints(wl.lp_codes[i][0], codes[i])
+                cnt.floats(wl.lp_minmax[i][0], mm[i])
+            print("verify-all: configs[3] round %d/5 (%d elements x %d peers, FP and LP) %s" %
+                  (rnd + 1, n, k, "ok" if cnt.clean() else "MISMATCH"), file=sys.stderr, flush=True)
+            if not cnt.clean():
+                break
+        ok = done("configs[3]", cnt, t0)
+        del wl, x_fp, x_lp, hat
+        torch.cuda.empty_cache()
+
+    # ---- configs[4]: sign compression and its server step, span by span
+    if ok:
+        t0 = time.perf_counter()
+        wl = Workload(torch, bg, "onebit")
+        wl.step()
+        torch.cuda.synchronize()
+        k, SC, n = wl.k, wl.SC, wl.n_elems
+        cnt = Counts()
+        span = 64 * 1024 * 1024
+        for lo in range(0, n, span):
+            hi = min(n, lo + span)
+            m = hi - lo
+            enc = []
+            for j in range(k):
+                x = wl.bucket[j][0][lo:hi].cpu().numpy()
+                d = np.zeros(m, np.float32)
+                bts, sc = oracle.sign_compress_ef(x, d, SC)
+                cnt.ints(wl.bits[j][0][lo // 32:(hi + 31) // 32], bts)
+                cnt.floats(wl.scale[j][0][lo // SC:(hi + SC - 1) // SC], sc)
+                cnt.floats(wl.sdelta[j][0][lo:hi], d)
+                enc.append((bts, sc))
+            e = np.zeros(m, np.float32)
+            b2, s2, o2 = oracle.drr_sign([x[0] for x in enc], [x[1] for x in enc], e, m, SC)
+            cnt.ints(wl.bits_out[0][lo // 32:(hi + 31) // 32], b2)
+            cnt.floats(wl.scale_out[0][lo // SC:(hi + SC - 1) // SC], s2)
+            cnt.floats(wl.sout[0][lo:hi], o2)
+            cnt.floats(wl.seps[0][lo:hi], e)
+            print("verify-all: configs[4] elements [%d, %d) x %d workers %s" %
+                  (lo, hi, k, "ok" if cnt.clean() else "MISMATCH"), file=sys.stderr, flush=True)
+            if not cnt.clean():
+                break
+        ok = done("configs[4]", cnt, t0)
+    report["all_equal"] = bool(ok)
+    print(json.dumps({"verify_all": report}))
+    return 0 if ok else 1
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is the single-GPU share of the path (the k workers are k buffers in one GPU's "
+              "HBM); --gpus %d is not supported, run with --gpus 1" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import __graft_entry__
+    __graft_entry__.ensure_built()        # uses what is built; rebuilds a library that is older than its sources
+    import paper_2107_01499_amd as bg     # fails loudly if the HIP library cannot be loaded
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    if args.verify_all:
+        sys.exit(verify_all(torch, bg))
+    only = set(p for p in args.only.split(",") if p) or None
+    extras = tuple(e for e in args.extras.split(",") if e)
+    layout = "per_bucket" if args.per_bucket_launch else args.layout
+    ceil = ceilings(torch, bg)
+    plan = DEFAULT_PLAN if args.workload == "all" else [(args.workload, layout, True)]
+    blocks, primary_s = {}, 0.0
+    for name, lay, primary in plan:
+        key = name if lay == "flat" else "%s_%s" % (name, lay)
+        print("bench: block %s" % key, file=sys.stderr, flush=True)
+        blocks[key], step_s = run_block(torch, bg, args, name, lay, only, extras)
+        blocks[key]["counts_towards_value"] = primary
+        if primary:
+            primary_s += step_s
+
+    # the seven primitives, each at the largest configuration that names it (the blocks that count towards `value`)
+    per_prim, total_grad = {}, 0.0
+    for key, b in blocks.items():
+        if not b["counts_towards_value"]:
+            continue
+        for p, v in b["per_primitive"].items():
+            e = dict(v)
+            e["config"] = key
+            e["frac_of_copy_kernel"] = round(v["hbm_GBps"] / ceil["copy_kernel_GBps"], 4)
+            per_prim[p] = e
+            total_grad += v["gradient_bytes"]
+    dom_key = max((k_ for k_ in blocks if blocks[k_]["counts_towards_value"]),
+                  key=lambda k_: blocks[k_]["per_primitive"][blocks[k_]["roofline"]["primitive"]]["ms"])
+    roof = dict(blocks[dom_key]["roofline"])
+    roof["config"] = dom_key
     result = {
         "metric": "gradient GB/s processed per primitive on 1 MI355X; % of HBM roofline",
-        "value": round(total_grad / (wall / args.steps) / 1e9, 1),
+        "value": round(total_grad / primary_s / 1e9, 1),
         "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(primary_s * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s in %d greedy 25 MiB buckets (%d padded elements per worker), %d simulated workers, "
-                               "chunk %d (sign codec %d), error state carried across steps; primitives per step: %s" %
-                               (wl.w["label"], len(wl.buckets), wl.n_elems, wl.k, wl.C, wl.SC, ", ".join(prims)),
-                   "workers": wl.k, "chunk": wl.C, "sign_chunk": wl.SC, "buckets": len(wl.buckets),
-                   "launch": "per bucket" if args.per_bucket_launch else "per worker (all buckets of a worker in one launch)",
-                   "elements_per_worker": wl.n_elems},
-        "gpu_ms_per_step": round(gpu_ms / args.steps, 4),
-        "copy_kernel_GBps": round(ceiling, 1),
+        "config": {"workload": "; ".join("%s [%s]" % (blocks[k_]["workload"], blocks[k_]["launch"])
+                                         for k_ in blocks if blocks[k_]["counts_towards_value"]),
+                   "also_timed": [k_ for k_ in blocks if not blocks[k_]["counts_towards_value"]],
+                   "step": "one pass of every listed primitive over its configuration's batch; ms_per_step and value "
+                           "sum the blocks that count towards the value"},
         "per_primitive": per_prim,
-        "roofline": {"bound": "hbm", "kernel": wl.kernel_name(dom), "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "avg_launch_us": round(dom_t * 1e6, 3), "algorithmic_bytes_per_launch": ab[dom] / nl[dom]},
+        "roofline": roof,
+        "roofline_per_config": {k_: b["roofline"] for k_, b in blocks.items()},
+        "ceilings": ceil,
+        "copy_kernel_GBps": ceil["copy_kernel_GBps"],
+        "read_kernel_GBps": ceil["read_kernel_GBps"],
+        "blocks": blocks,
     }
-    if not args.no_cpu_baseline and args.workload == "resnet50" and only is None and not args.fused_flatten and not args.extras:
-        result["cpu_baseline"], result["parity"] = cpu_baseline(wl, torch)
+    base = [(k_, b["cpu_baseline"]) for k_, b in blocks.items() if "cpu_baseline" in b]
+    if base:
+        main_base = [(k_, c) for k_, c in base if blocks[k_]["counts_towards_value"]] or base
+        secs = sum(c["seconds"] for _, c in main_base)
+        result["cpu_baseline"] = {
+            "value": round(sum(c["gradient_bytes"] for _, c in main_base) / secs / 1e9, 3), "unit": "GB/s",
+            "cores": main_base[0][1]["cores"], "kind": "oracle",
+            "sample": " | ".join("%s: %s" % (k_, c["sample"]) for k_, c in main_base),
+            "per_config": {k_: {"value": c["value"], "seconds": c["seconds"]} for k_, c in base}}
+        total = Counts()
+        for k_, b in blocks.items():
+            if "parity" in b:
+                for f in total.c:
+                    total.c[f] += b["parity"][f]
+        par = dict(total.c)
+        par["sample"] = "every primitive of every block on its oracle sample (see blocks[*].parity), HIP path against the oracle"
+        result["parity"] = par
     print(json.dumps(result))
 
 

@@ -29,7 +29,8 @@ EXPORTS = (
     "bagua_decompress_topk", "bagua_centralized_avg_fp", "bagua_decentralized_avg_peers_lp",
     "bagua_decompress_adam_step", "bagua_momentum_sign_compress_ef", "bagua_lp_encode", "bagua_lp_apply_mix", "bagua_bucket_flatten_static",
     "bagua_batch_workspace_bytes", "bagua_compress_minmax_u8_batched", "bagua_sign_compress_ef_batched",
-    "bagua_decompress_reduce_recompress_batched", "bagua_bucket_flatten_batched_run",
+    "bagua_decompress_reduce_recompress_batched", "bagua_bucket_flatten_batched_run", "bagua_probe_read",
+    "bagua_probe_streams",
 )
 
 
@@ -74,6 +75,8 @@ def _load():
     lib.bagua_momentum_sign_compress_ef.argtypes = [vp, vp, cf, vp, sz, sz, vp, vp, vp]
     lib.bagua_lp_encode.argtypes = [vp, vp, sz, sz, vp, vp, vp]
     lib.bagua_lp_apply_mix.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, sz, vp, vp]
+    lib.bagua_probe_read.argtypes = [vp, sz, vp, vp]
+    lib.bagua_probe_streams.argtypes = [vp, vp, vp, i32, i32, i32, i32, sz, vp]
     lib.bagua_batch_workspace_bytes.argtypes = [sz, i32]
     lib.bagua_compress_minmax_u8_batched.argtypes = [vp, vp, vp, sz, sz, vp, vp, vp, sz, vp]
     lib.bagua_sign_compress_ef_batched.argtypes = [vp, vp, vp, sz, sz, vp, vp, vp, sz, vp]
@@ -416,6 +419,22 @@ def bagua_bucket_flatten_batched_run(plans, Ts, buckets, workspace, stream=None)
     ba = (ctypes.c_void_p * B)(*[_ptr(b, torch.float32).value for b in buckets])
     _check("bagua_bucket_flatten_batched_run", _lib.bagua_bucket_flatten_batched_run(
         pa, _sizes(Ts), ba, _sizes([b.numel() for b in buckets]), B, wp, wb, _stream(stream)))
+
+
+# ---------------------------------------------------------------------------------------------- probes
+def bagua_probe_read(x, tile_sums, stream=None):
+    n = x.numel()
+    _check("bagua_probe_read", _lib.bagua_probe_read(_ptr(x, torch.float32), n, _ptr(tile_sums, torch.float32, 4 * ((n + 4095) // 4096)),
+                                                     _stream(stream)))
+
+
+def bagua_probe_streams(ins, outs, bouts, nr, nw, nb, seq, n, stream=None):
+    _same_len(seq * nr, ins=ins)
+    _same_len(seq * nw, outs=outs)
+    _same_len(seq * nb, bouts=bouts)
+    _check("bagua_probe_streams", _lib.bagua_probe_streams(
+        _ptr_array(ins, torch.float32, 4 * n), _ptr_array(outs, torch.float32, 4 * n) if outs else None,
+        _ptr_array(bouts, torch.uint8, n) if bouts else None, nr, nw, nb, seq, n, _stream(stream)))
 
 
 def raw():

@@ -13,7 +13,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIBDIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIBDIR, "libbagua_hip.so")
-SOURCES = ["api.hip", "batch.hip", "minmax.hip", "sign.hip", "ring.hip", "flatten.hip", "fused.hip", "optim.hip", "topk.hip"]
+SOURCES = ["api.hip", "batch.hip", "minmax.hip", "sign.hip", "ring.hip", "flatten.hip", "fused.hip", "optim.hip", "topk.hip", "probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
