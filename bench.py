@@ -809,22 +809,21 @@ def single_instance_latency(torch, bg, wl):
     return round(time_fn(torch, once, 50) * 1e6, 2)
 
 
-def verify_all(torch, bg):
-    """Every element of configs[2], configs[3] (5 rounds, full and low precision) and configs[4]: the HIP path at full
-    size in the launch configuration the benchmark times, against the oracle streamed span by span over the same
-    bits.  Stops at the first span that differs.  Prints one JSON line with the three counts per configuration."""
-    import numpy as np
+def _verify_setup():
     import oracle
     oracle.set_threads(max(1, min(16, oracle.max_threads(), os.cpu_count() or 1)))
-    report = {}
+    return oracle
 
-    def done(name, cnt, t0):
-        report[name] = dict(cnt.c, seconds=round(time.perf_counter() - t0, 1))
-        print("verify-all: %s %s" % (name, report[name]), file=sys.stderr, flush=True)
-        return cnt.clean()
 
-    # ---- configs[2]: flatten, compress, server step, bucket by bucket
-    t0 = time.perf_counter()
+def _say(msg):
+    print("verify-all: " + msg, file=sys.stderr, flush=True)
+
+
+def verify_config2(torch, bg):
+    """configs[2] at full size: flatten, compress, server step from zero error states; every bucket of every worker
+    against the oracle.  Returns the comparison counts (stops at the first bucket that differs)."""
+    import numpy as np
+    oracle = _verify_setup()
     wl = Workload(torch, bg, "bert_large")
     wl.step()
     torch.cuda.synchronize()
@@ -832,7 +831,7 @@ def verify_all(torch, bg):
     cnt = Counts()
     for b, bk in enumerate(wl.buckets):
         lo, hi = wl.bases[b], wl.bases[b + 1]
-        flats, enc, d_o = [], [], []
+        enc = []
         for j in range(k):
             lay = [wl.layers[0][j][t].cpu().numpy() for t in bk.tensors]
             f = oracle.bucket_flatten(lay, list(bk.offsets), bk.n_pad)
@@ -849,75 +848,96 @@ def verify_all(torch, bg):
         cnt.floats(wl.minmax_out[0][2 * lo // C:2 * hi // C], m2)
         cnt.floats(wl.out[0][lo:hi], o2)
         cnt.floats(wl.eps[0][lo:hi], e)
-        print("verify-all: configs[2] bucket %d/%d (%d elements x %d workers) %s" %
-              (b + 1, len(wl.buckets), bk.n_pad, k, "ok" if cnt.clean() else "MISMATCH"), file=sys.stderr, flush=True)
+        _say("configs[2] bucket %d/%d (%d elements x %d workers) %s" %
+             (b + 1, len(wl.buckets), bk.n_pad, k, "ok" if cnt.clean() else "MISMATCH"))
         if not cnt.clean():
             break
-    ok = done("configs[2]", cnt, t0)
     del wl
     torch.cuda.empty_cache()
+    return cnt
 
-    # ---- configs[3]: five ring rounds, full and low precision, host state carried round to round
-    if ok:
-        t0 = time.perf_counter()
-        wl = Workload(torch, bg, "bert_base_ring")
-        k, C, n = wl.k, wl.C, wl.n_elems
-        cnt = Counts()
-        x_fp = [wl.rep_fp[0][i][0].cpu().numpy() for i in range(k)]
-        x_lp = [wl.rep_lp[0][i][0].cpu().numpy() for i in range(k)]
-        hat = [wl.xhat[i][0].cpu().numpy().copy() for i in range(k)]
-        for rnd in range(5):
-            src, dst = wl.step_no % 2, (wl.step_no + 1) % 2
-            wl.step()
-            torch.cuda.synchronize()
-            x_fp = oracle.ring_avg_fp(x_fp)
-            x_lp, codes, mm = oracle.ring_avg_lp(x_lp, hat, C)
-            for i in range(k):
-                cnt.floats(wl.rep_fp[dst][i][0], x_fp[i])
-                cnt.floats(wl.rep_lp[dst][i][0], x_lp[i])
-                cnt.floats(wl.xhat[i][0], hat[i])
-                cnt.ints(wl.lp_codes[i][0], codes[i])
-                cnt.floats(wl.lp_minmax[i][0], mm[i])
-            print("verify-all: configs[3] round %d/5 (%d elements x %d peers, FP and LP) %s" %
-                  (rnd + 1, n, k, "ok" if cnt.clean() else "MISMATCH"), file=sys.stderr, flush=True)
-            if not cnt.clean():
-                break
-        ok = done("configs[3]", cnt, t0)
-        del wl, x_fp, x_lp, hat
-        torch.cuda.empty_cache()
 
-    # ---- configs[4]: sign compression and its server step, span by span
-    if ok:
-        t0 = time.perf_counter()
-        wl = Workload(torch, bg, "onebit")
+def verify_config3(torch, bg, rounds=5):
+    """configs[3] at full size: `rounds` ring rounds in full and in low precision, the oracle's state carried on the
+    host from round to round; every output of every round compared."""
+    oracle = _verify_setup()
+    wl = Workload(torch, bg, "bert_base_ring")
+    k, C, n = wl.k, wl.C, wl.n_elems
+    cnt = Counts()
+    x_fp = [wl.rep_fp[0][i][0].cpu().numpy() for i in range(k)]
+    x_lp = [wl.rep_lp[0][i][0].cpu().numpy() for i in range(k)]
+    hat = [wl.xhat[i][0].cpu().numpy().copy() for i in range(k)]
+    for rnd in range(rounds):
+        dst = (wl.step_no + 1) % 2
         wl.step()
         torch.cuda.synchronize()
-        k, SC, n = wl.k, wl.SC, wl.n_elems
-        cnt = Counts()
-        span = 64 * 1024 * 1024
-        for lo in range(0, n, span):
-            hi = min(n, lo + span)
-            m = hi - lo
-            enc = []
-            for j in range(k):
-                x = wl.bucket[j][0][lo:hi].cpu().numpy()
-                d = np.zeros(m, np.float32)
-                bts, sc = oracle.sign_compress_ef(x, d, SC)
-                cnt.ints(wl.bits[j][0][lo // 32:(hi + 31) // 32], bts)
-                cnt.floats(wl.scale[j][0][lo // SC:(hi + SC - 1) // SC], sc)
-                cnt.floats(wl.sdelta[j][0][lo:hi], d)
-                enc.append((bts, sc))
-            e = np.zeros(m, np.float32)
-            b2, s2, o2 = oracle.drr_sign([x[0] for x in enc], [x[1] for x in enc], e, m, SC)
-            cnt.ints(wl.bits_out[0][lo // 32:(hi + 31) // 32], b2)
-            cnt.floats(wl.scale_out[0][lo // SC:(hi + SC - 1) // SC], s2)
-            cnt.floats(wl.sout[0][lo:hi], o2)
-            cnt.floats(wl.seps[0][lo:hi], e)
-            print("verify-all: configs[4] elements [%d, %d) x %d workers %s" %
-                  (lo, hi, k, "ok" if cnt.clean() else "MISMATCH"), file=sys.stderr, flush=True)
-            if not cnt.clean():
-                break
-        ok = done("configs[4]", cnt, t0)
+        x_fp = oracle.ring_avg_fp(x_fp)
+        x_lp, codes, mm = oracle.ring_avg_lp(x_lp, hat, C)
+        for i in range(k):
+            cnt.floats(wl.rep_fp[dst][i][0], x_fp[i])
+            cnt.floats(wl.rep_lp[dst][i][0], x_lp[i])
+            cnt.floats(wl.xhat[i][0], hat[i])
+            cnt.ints(wl.lp_codes[i][0], codes[i])
+            cnt.floats(wl.lp_minmax[i][0], mm[i])
+        _say("configs[3] round %d/%d (%d elements x %d peers, FP and LP) %s" %
+             (rnd + 1, rounds, n, k, "ok" if cnt.clean() else "MISMATCH"))
+        if not cnt.clean():
+            break
+    del wl
+    torch.cuda.empty_cache()
+    return cnt
+
+
+def verify_config4(torch, bg):
+    """configs[4] at full size: sign compression of every worker and the server step from zero error states, the
+    oracle streamed over spans of 64 Mi elements."""
+    import numpy as np
+    oracle = _verify_setup()
+    wl = Workload(torch, bg, "onebit")
+    wl.step()
+    torch.cuda.synchronize()
+    k, SC, n = wl.k, wl.SC, wl.n_elems
+    cnt = Counts()
+    span = 64 * 1024 * 1024
+    for lo in range(0, n, span):
+        hi = min(n, lo + span)
+        m = hi - lo
+        enc = []
+        for j in range(k):
+            x = wl.bucket[j][0][lo:hi].cpu().numpy()
+            d = np.zeros(m, np.float32)
+            bts, sc = oracle.sign_compress_ef(x, d, SC)
+            cnt.ints(wl.bits[j][0][lo // 32:(hi + 31) // 32], bts)
+            cnt.floats(wl.scale[j][0][lo // SC:(hi + SC - 1) // SC], sc)
+            cnt.floats(wl.sdelta[j][0][lo:hi], d)
+            enc.append((bts, sc))
+        e = np.zeros(m, np.float32)
+        b2, s2, o2 = oracle.drr_sign([x[0] for x in enc], [x[1] for x in enc], e, m, SC)
+        cnt.ints(wl.bits_out[0][lo // 32:(hi + 31) // 32], b2)
+        cnt.floats(wl.scale_out[0][lo // SC:(hi + SC - 1) // SC], s2)
+        cnt.floats(wl.sout[0][lo:hi], o2)
+        cnt.floats(wl.seps[0][lo:hi], e)
+        _say("configs[4] elements [%d, %d) x %d workers %s" % (lo, hi, k, "ok" if cnt.clean() else "MISMATCH"))
+        if not cnt.clean():
+            break
+    del wl
+    torch.cuda.empty_cache()
+    return cnt
+
+
+def verify_all(torch, bg):
+    """Every element of configs[2], configs[3] (5 rounds, full and low precision) and configs[4]: the HIP path at full
+    size in the launch configuration the benchmark times, against the oracle streamed over the same bits.  Stops at
+    the first configuration that differs.  Prints one JSON line with the three counts per configuration."""
+    report, ok = {}, True
+    for name, fn in (("configs[2]", verify_config2), ("configs[3]", verify_config3), ("configs[4]", verify_config4)):
+        t0 = time.perf_counter()
+        cnt = fn(torch, bg)
+        report[name] = dict(cnt.c, seconds=round(time.perf_counter() - t0, 1))
+        _say("%s %s" % (name, report[name]))
+        ok = cnt.clean()
+        if not ok:
+            break
     report["all_equal"] = bool(ok)
     print(json.dumps({"verify_all": report}))
     return 0 if ok else 1
