@@ -318,15 +318,19 @@ class Workload:
         return {p: per[p] for p in self.prims}
 
     def kernel_name(self, p):
+        if self.batched and p in ("flatten", "compress_minmax", "drr_minmax", "sign_compress", "drr_sign"):
+            return {"flatten": "k_flatten_batched", "compress_minmax": "k_compress_minmax_batched<2,true>",
+                    "drr_minmax": "k_drr_minmax_batched<4,true,true>", "sign_compress": "k_sign_compress_batched<2,true>",
+                    "drr_sign": "k_drr_sign_batched<2,true,true>"}[p]
         return {"flatten": "k_flatten", "flatten_compress": "k_flatten_compress_minmax<2,true,%s>" %
                 ("true" if "sign_compress" in self.prims else "false"), "compress_minmax": "k_compress_minmax<2,true>",
                 "drr_minmax": "k_drr_minmax<4,true,true>", "ring_fp": "k_ring_avg_fp<%d>" % self.k,
                 "ring_lp": "k_ring_avg_lp<%d,2>" % self.k, "sign_compress": "k_sign_compress<2,true,false>",
-                "drr_sign": "k_drr_sign<4,true,true>", "sgd_step": "k_decompress_sgd<0,true,false>",
+                "drr_sign": "k_drr_sign<2,true,true>", "sgd_step": "k_decompress_sgd<0,true,false>",
                 "adam_step": "k_decompress_adam<0,false,false>", "momentum_sign": "k_sign_compress<2,true,true>",
                 "adam_frozen_step": "k_decompress_adam<1,true,false>",
                 "peer_fp": "k_peer_avg_fp", "peer_lp": "k_peer_avg_lp<2>", "lp_encode": "k_lp_encode<2>", "lp_apply_mix": "k_lp_apply_mix<true,true,false>", "reduce_compress": "k_reduce_compress_minmax<2,true>",
-                "compress_topk": "k_compress_topk<2,true>", "drr_topk": "k_drr_topk<2,true,true>"}[p]
+                "compress_topk": "k_compress_topk<4,true>", "drr_topk": "k_drr_topk<4,true,true>"}[p]
 
     # ---- one pass of the hot path ------------------------------------------------------------------
     def step(self, marks=None):
