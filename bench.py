@@ -785,6 +785,8 @@ def run_block(torch, bg, args, name, layout, only, extras):
              "per_primitive": per_prim, "roofline": roof}
     if name == "single_bucket_x32":
         block["single_instance_latency_us"] = single_instance_latency(torch, bg, wl)
+    if "flatten" in prims and layout == "flat" and only is None:
+        block["flatten_misaligned"] = misaligned_flatten(torch, bg, wl)
     if not args.no_cpu_baseline and layout == "flat" and only is None and not args.fused_flatten and not extras:
         block["cpu_baseline"], block["parity"] = cpu_baseline(wl, torch)
     del wl
@@ -792,6 +794,37 @@ def run_block(torch, bg, args, name, layout, only, extras):
     gc.collect()
     torch.cuda.empty_cache()
     return block, wall / args.steps
+
+
+def misaligned_flatten(torch, bg, wl, reps=5):
+    """The flatten of the block's layout with every layer tensor at a source address that is only 4-byte aligned (one
+    element past its 16-byte aligned place), so the copy cannot pair 128-bit loads with 128-bit stores directly.  Same
+    launches as the timed flatten.  Returns the per_primitive-style entry."""
+    k, U = wl.k, len(wl.units)
+    starts, pos = [], 1
+    for sz in wl.sizes:
+        starts.append(pos)
+        pos += (sz + 3) // 4 * 4 + 4            # next tensor again at 16-byte boundary + 4 bytes
+    plans = []
+    for j in range(k):                           # every worker reads its own tensors, as in the timed flatten
+        arena = torch.zeros(pos + 8, device="cuda")
+        srcs = [arena[starts[t]:starts[t] + sz] for t, sz in enumerate(wl.sizes)]
+        per_unit = []
+        for u, (lo, ln, ids, offs) in enumerate(wl.units):
+            ws = torch.empty(bg.bagua_flatten_workspace_bytes(len(ids), ln), dtype=torch.uint8, device="cuda")
+            bg.bagua_flatten_plan([srcs[t] for t in ids], offs, ln, ws)
+            per_unit.append((ws, arena))
+        plans.append(per_unit)
+
+    def once(i):
+        for j in range(k):
+            for u in range(U):
+                bg.bagua_bucket_flatten_run(plans[j][u][0], len(wl.units[u][2]), wl.bucket[j][u])
+    t = time_fn(torch, once, reps)
+    ab = 8.0 * wl.n_elems * k
+    return {"ms": round(t * 1e3, 4), "launches": U * k, "hbm_GBps": round(ab / t / 1e9, 1),
+            "frac_of_peak": round(ab / t / 1e9 / HBM_PEAK_GBS, 4), "kernel": "k_flatten", "algorithmic_bytes": ab,
+            "note": "every source tensor 4 bytes past a 16-byte boundary; timed after the step, not part of value"}
 
 
 def single_instance_latency(torch, bg, wl):
@@ -988,6 +1021,10 @@ def main():
             e["frac_of_copy_kernel"] = round(v["hbm_GBps"] / ceil["copy_kernel_GBps"], 4)
             per_prim[p] = e
             total_grad += v["gradient_bytes"]
+        if "flatten_misaligned" in b:
+            e = dict(b["flatten_misaligned"])
+            e["config"] = key
+            per_prim["flatten_misaligned"] = e
     dom_key = max((k_ for k_ in blocks if blocks[k_]["counts_towards_value"]),
                   key=lambda k_: blocks[k_]["per_primitive"][blocks[k_]["roofline"]["primitive"]]["ms"])
     roof = dict(blocks[dom_key]["roofline"])

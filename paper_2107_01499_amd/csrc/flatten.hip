@@ -36,6 +36,12 @@ __device__ __forceinline__ void flatten_tile(const TensorDesc* __restrict__ desc
                 for (int g = 0; g < kTile / 1024; ++g) st_stream(b4 + g * 256 + threadIdx.x, v[g]);
                 return;
             }
+            // same, source only 4-byte aligned: 128-bit loads with 4-byte declared alignment, aligned 128-bit stores
+            f4* b4 = reinterpret_cast<f4*>(bucket + tile0);
+#pragma unroll
+            for (int g = 0; g < kTile / 1024; ++g)
+                st_stream(b4 + g * 256 + threadIdx.x, load_row_shifted(s + g * 1024, threadIdx.x));
+            return;
         }
     }
 
@@ -57,11 +63,8 @@ __device__ __forceinline__ void flatten_tile(const TensorDesc* __restrict__ desc
             const TensorDesc d = desc[t];
             if (d.dst <= e && e + 4 <= d.dst + d.numel) {
                 const float* s = d.src + (e - d.dst);
-                if ((reinterpret_cast<uintptr_t>(s) & 15u) == 0) {
-                    v = ld_stream(reinterpret_cast<const f4*>(s));
-                } else {
-                    v.x = s[0]; v.y = s[1]; v.z = s[2]; v.w = s[3];
-                }
+                const f4_a4 u = __builtin_nontemporal_load(reinterpret_cast<const f4_a4*>(s));   // any 4-byte alignment
+                v = f4{u.x, u.y, u.z, u.w};
                 done = true;
             }
         }
@@ -124,6 +127,15 @@ k_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ ti
                 for (int g = 0; g < kTile / 1024; ++g) st_stream(s4 + g * 256 + threadIdx.x, v[g]);
                 return;
             }
+            // same, tensor only 4-byte aligned: 128-bit stores with 4-byte declared alignment
+            const f4* b4 = reinterpret_cast<const f4*>(bucket + tile0);
+            f4_a4* s4 = reinterpret_cast<f4_a4*>(s);
+#pragma unroll
+            for (int g = 0; g < kTile / 1024; ++g) {
+                const f4 v = ld_stream(b4 + g * 256 + threadIdx.x);
+                __builtin_nontemporal_store(f4_a4{v.x, v.y, v.z, v.w}, s4 + g * 256 + threadIdx.x);
+            }
+            return;
         }
     }
 #pragma unroll
@@ -142,11 +154,7 @@ k_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ ti
             if (d.dst <= e && e + 4 <= d.dst + d.numel) {
                 float* s = const_cast<float*>(d.src) + (e - d.dst);
                 const f4 v = ld_stream(reinterpret_cast<const f4*>(bucket + e));
-                if ((reinterpret_cast<uintptr_t>(s) & 15u) == 0) {
-                    st_stream(reinterpret_cast<f4*>(s), v);
-                } else {
-                    s[0] = v.x; s[1] = v.y; s[2] = v.z; s[3] = v.w;
-                }
+                __builtin_nontemporal_store(f4_a4{v.x, v.y, v.z, v.w}, reinterpret_cast<f4_a4*>(s));   // any 4-byte alignment
                 continue;
             }
         }

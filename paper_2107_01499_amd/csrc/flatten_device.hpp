@@ -28,6 +28,16 @@ __device__ __forceinline__ float element_at(const TensorDesc* __restrict__ desc,
 }
 
 
+// 256 consecutive floats starting at s, where s is only 4-byte aligned: lane l receives s[4l .. 4l+3] with ONE
+// 128-bit load whose declared alignment is 4 bytes (the memory pipeline splits the accesses that straddle a 16-byte
+// boundary; one request per lane instead of four).  All 256 elements must be readable.
+typedef float f4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+__device__ __forceinline__ f4 load_row_shifted(const float* __restrict__ s, int lane)
+{
+    const f4_a4 v = __builtin_nontemporal_load(reinterpret_cast<const f4_a4*>(s) + lane);
+    return f4{v.x, v.y, v.z, v.w};
+}
+
 // The planned workspace: T descriptors, then (tiles + 1) "first tensor" indices.
 struct FlattenPlanView {
     const TensorDesc* desc;
@@ -56,6 +66,7 @@ __device__ __forceinline__ f4 gather_row(const TensorDesc* __restrict__ desc, co
         if (d.dst <= e0 && e0 + kRow <= d.dst + d.numel) {
             const float* s = d.src + (e0 - d.dst);
             if ((reinterpret_cast<uintptr_t>(s) & 15u) == 0) return ld_stream(reinterpret_cast<const f4*>(s) + lane);
+            return load_row_shifted(s, lane);
         }
     }
     uint32_t t = lo;

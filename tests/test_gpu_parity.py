@@ -295,6 +295,41 @@ def test_flatten_gaps_misaligned_and_tiny(bg, oracle):
     assert host(bucket2).tobytes() == want.tobytes()
 
 
+@pytest.mark.parametrize("src_shift", [0, 1, 2, 3])
+@pytest.mark.parametrize("dst_shift", [0, 1, 2, 3])
+def test_flatten_every_source_and_destination_alignment(bg, oracle, src_shift, dst_shift):
+    """Whole tiles inside one tensor whose source is src_shift elements past a 16-byte boundary and whose bucket
+    offset is dst_shift elements past one: the realigning 128-bit path and the element path, also fused into the
+    compression."""
+    r = np.random.default_rng(10 * src_shift + dst_shift)
+    sizes = [5000, 1024 * 3 + 5, 9000]
+    srcs = [(r.standard_normal(s) * 1e-3).astype(np.float32) for s in sizes]
+    offs, pos = [], dst_shift
+    for s in sizes:
+        offs.append(pos)
+        pos += s + 4 - (s % 4) + 0          # next tensor keeps the same destination shift
+    total = pos + 7
+    arena = torch.zeros(sum(sizes) + 64, device="cuda")
+    gs, p_ = [], src_shift
+    for s in srcs:
+        t = arena[p_:p_ + s.size]
+        t.copy_(torch.from_numpy(s))
+        gs.append(t)
+        p_ += (s.size + 3) // 4 * 4 + 4
+        p_ = p_ - (p_ % 4) + src_shift
+    want = oracle.bucket_flatten(srcs, offs, total)
+    bucket = torch.full((total,), float("nan"), device="cuda")
+    ws = torch.empty(bg.bagua_flatten_workspace_bytes(len(gs), total), dtype=torch.uint8, device="cuda")
+    bg.bagua_bucket_flatten(gs, offs, bucket, ws)
+    assert host(bucket).tobytes() == want.tobytes()
+    C = 1024
+    codes = torch.empty(total, dtype=torch.uint8, device="cuda")
+    mm = torch.empty(2 * bg.num_chunks(total, C), device="cuda")
+    bg.bagua_flatten_compress_minmax_u8(ws, len(gs), None, total, C, codes, mm)
+    co, mo = oracle.compress_minmax_u8(want, None, C)
+    assert np.array_equal(host(codes), co) and np.array_equal(host(mm), mo)
+
+
 def test_flatten_empty_table_zero_fills(bg):
     bucket = torch.full((5000,), float("nan"), device="cuda")
     ws = torch.empty(bg.bagua_flatten_workspace_bytes(0, 5000), dtype=torch.uint8, device="cuda")
