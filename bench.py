@@ -80,7 +80,8 @@ def parse_args():
                     "lp_shares (D_LP_S on a ring as the k single-peer shares a sharded run would execute: encode, then apply + mix), "
                     "peer_fp / peer_lp (full- / low-precision averaging with one chosen peer per worker), reduce_compress (intra-node "
                     "stage of hierarchical C_LP_S: 4 local workers averaged uncompressed, leader compresses), topk (C_LP_S with "
-                    "the per-chunk top-K codec, keep = chunk/32: worker side and server side)")
+                    "the per-chunk top-K codec, keep = chunk/32: worker side and server side), unflatten (the server's codes decoded "
+                    "straight into every worker's layer tensors), flatten_sign (gather fused into the sign compression)")
     ap.add_argument("--fused-flatten", action="store_true",
                     help="replace flatten + compress_minmax by the fused bagua_flatten_compress_minmax_u8")
     ap.add_argument("--per-bucket-launch", action="store_true", help="same as --layout per_bucket")
@@ -115,6 +116,10 @@ class Workload:
             self.prims = self.prims + ["reduce_compress"]
         if "topk" in extras and ("flatten" in self.prims or "flatten_compress" in self.prims):
             self.prims = self.prims + ["compress_topk", "drr_topk"]
+        if "unflatten" in extras and "drr_minmax" in self.prims and "flatten" in self.prims:
+            self.prims = self.prims + ["decompress_unflatten"]
+        if "flatten_sign" in extras and "flatten" in self.prims:
+            self.prims = self.prims + ["flatten_sign_compress"]
         if "peer_fp" in extras and "ring_fp" in self.prims:
             self.prims = self.prims + ["peer_fp"]
         if "peer_lp" in extras and "ring_lp" in self.prims:
@@ -220,6 +225,10 @@ class Workload:
             self.codes_out = views(z(n, **u8))
             self.minmax_out = views(z(2 * nc, **f32), C, 2)
             self.out = views(z(n, **f32))
+        if has("flatten_sign_compress"):
+            self.fsdelta = [views(z(n, **f32)) for _ in range(k)]
+            self.fsbits = [views(z((n + 31) // 32, **i32), 32) for _ in range(k)]
+            self.fsscale = [views(z(ncs, **f32), SC) for _ in range(k)]
         if has("reduce_compress"):      # hierarchical C_LP_S: nodes of 4 local workers, one leader each
             self.kl = 4
             self.hdelta = [views(z(n, **f32)) for _ in range(k // self.kl)]
@@ -293,6 +302,7 @@ class Workload:
         keep = getattr(self, "keep", 0)
         wb = 4.0 if "sign_compress" in self.prims else 0.0   # the fused call also writes the bucket if it is needed later
         return {"flatten": 8.0, "flatten_compress": 13.0 + wb + 8.0 / C, "compress_minmax": 13.0 + 8.0 / C, "drr_minmax": k + 13.0 + 8.0 * (k + 1) / C,
+                "decompress_unflatten": 5.0 + 8.0 / C, "flatten_sign_compress": 12.125 + 4.0 / SC,
                 "compress_topk": 12.0 + 6.0 * keep / C, "drr_topk": 12.0 + 6.0 * (k + 1) * keep / C,
                 "sgd_step": 17.0 + 8.0 / C, "adam_step": 25.0 + 8.0 / C, "momentum_sign": 16.125 + 4.0 / SC,
                 "adam_frozen_step": 16.125 + 4.0 / SC, "reduce_compress": 4.0 * 4 + 9.0 + 8.0 / C, "peer_fp": 8.0, "peer_lp": 17.0 + 8.0 / C, "lp_encode": 13.0 + 8.0 / C, "lp_apply_mix": 30.0 + 16.0 / C, "ring_fp": 8.0, "ring_lp": 17.0 + 8.0 / C, "sign_compress": 12.125 + 4.0 / SC,
@@ -306,7 +316,7 @@ class Workload:
         n, k = self.n_elems, self.k
         units = {"flatten": n * k, "flatten_compress": n * k, "compress_minmax": n * k, "drr_minmax": n, "ring_fp": n * k, "ring_lp": n * k,
                  "sign_compress": n * k, "drr_sign": n, "sgd_step": n * k, "adam_step": n * k, "momentum_sign": n * k, "adam_frozen_step": n * k, "peer_fp": n * k, "peer_lp": n * k, "lp_encode": n * k, "lp_apply_mix": n * k, "reduce_compress": n * (k // 4),
-                 "compress_topk": n * k, "drr_topk": n}
+                 "compress_topk": n * k, "drr_topk": n, "decompress_unflatten": n * k, "flatten_sign_compress": n * k}
         bpe = self.bytes_per_element()
         return {p: bpe[p] * units[p] for p in self.prims}
 
@@ -314,7 +324,7 @@ class Workload:
         U, k = (1 if self.batched else len(self.units)), self.k
         per = {"flatten": U * k, "flatten_compress": U * k, "compress_minmax": U * k, "drr_minmax": U, "ring_fp": U, "ring_lp": U,
                "sign_compress": U * k, "drr_sign": U, "sgd_step": U * k, "adam_step": U * k, "momentum_sign": U * k, "adam_frozen_step": U * k, "peer_fp": U, "peer_lp": U, "lp_encode": U * k, "lp_apply_mix": U * k, "reduce_compress": U * (k // 4),
-               "compress_topk": U * k, "drr_topk": U}
+               "compress_topk": U * k, "drr_topk": U, "decompress_unflatten": U * k, "flatten_sign_compress": U * k}
         return {p: per[p] for p in self.prims}
 
     def kernel_name(self, p):
@@ -330,7 +340,8 @@ class Workload:
                 "adam_step": "k_decompress_adam<0,false,false>", "momentum_sign": "k_sign_compress<2,true,true>",
                 "adam_frozen_step": "k_decompress_adam<1,true,false>",
                 "peer_fp": "k_peer_avg_fp", "peer_lp": "k_peer_avg_lp<2>", "lp_encode": "k_lp_encode<2>", "lp_apply_mix": "k_lp_apply_mix<true,true,false>", "reduce_compress": "k_reduce_compress_minmax<2,true>",
-                "compress_topk": "k_compress_topk<4,true>", "drr_topk": "k_drr_topk<4,true,true>"}[p]
+                "compress_topk": "k_compress_topk<4,true>", "drr_topk": "k_drr_topk<4,true,true>",
+                "decompress_unflatten": "k_decompress_unflatten<0>", "flatten_sign_compress": "k_flatten_sign_compress<2,true,false>"}[p]
 
     # ---- one pass of the hot path ------------------------------------------------------------------
     def step(self, marks=None):
@@ -371,6 +382,16 @@ class Workload:
                                                           [self.minmax[j][u] for j in range(k)], self.eps[u],
                                                           self.units[u][1], C, self.codes_out[u], self.minmax_out[u],
                                                           self.out[u])
+            elif p == "decompress_unflatten":   # every worker decodes the server's codes straight into its layer tensors
+                for j in range(k):
+                    for u in range(U):
+                        bg.bagua_decompress_unflatten(bg.CODEC_MINMAX_U8, self.codes_out[u], self.minmax_out[u],
+                                                      self.units[u][1], C, self.plans[it][j][u], len(self.units[u][2]))
+            elif p == "flatten_sign_compress":
+                for j in range(k):
+                    for u in range(U):
+                        bg.bagua_flatten_sign_compress_ef(self.plans[it][j][u], len(self.units[u][2]), self.fsdelta[j][u],
+                                                          self.units[u][1], SC, self.fsbits[j][u], self.fsscale[j][u], None)
             elif p == "sgd_step":
                 for j in range(k):
                     for u in range(U):

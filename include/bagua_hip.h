@@ -139,6 +139,26 @@ int bagua_flatten_compress_minmax_u8(const void* workspace, size_t T, float* res
                                      size_t chunk, uint8_t* codes, float* minmax, float* bucket_out, void* stream);
 
 /*
+ * The same fusion in front of the 1-bit sign codec: exactly bagua_bucket_flatten followed by bagua_sign_compress_ef
+ * on the bucket, with the rows gathered straight from the layer tensors (Section 3.5; the codec of Section 4.1's
+ * 1-bit Adam).  Arguments as bagua_flatten_compress_minmax_u8 with bits u32[ceil(n/32)] and scale fp32[nc].
+ */
+int bagua_flatten_sign_compress_ef(const void* workspace, size_t T, float* residual, size_t bucket_numel, size_t chunk,
+                                   uint32_t* bits, float* scale, float* bucket_out, void* stream);
+
+/*
+ * The last step of C_LP_S on every worker, fused with the inverse of the flatten (Section 3.4 step 5 followed by
+ * Section 3.5's flattening in reverse): the compressed bucket is decoded and every decoded element is written
+ * straight into the layer tensor that covers it; the decoded bucket itself is never stored.  Exactly bagua_decompress
+ * followed by bagua_bucket_unflatten_run.
+ *   codec, codes, meta, n, chunk   as bagua_decompress (n = bucket_numel of the plan)
+ *   workspace, T                   a plan made by bagua_flatten_plan with WRITABLE tensors; they must not overlap
+ *                                  codes or meta (not checked: the table is on the device)
+ */
+int bagua_decompress_unflatten(int codec, const void* codes, const float* meta, size_t n, size_t chunk,
+                               const void* workspace, size_t T, void* stream);
+
+/*
  * Server side of C_LP_S (Section 3.2, x_i' and epsilon_i' of the C_LP_S equations; steps 3-5 of
  * ScatterReduce, Section 3.4): decode the k workers' compressed buckets, average them in
  * ascending worker order, add the server error state, compress again, update the state:

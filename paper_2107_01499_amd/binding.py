@@ -30,7 +30,7 @@ EXPORTS = (
     "bagua_decompress_adam_step", "bagua_momentum_sign_compress_ef", "bagua_lp_encode", "bagua_lp_apply_mix", "bagua_bucket_flatten_static",
     "bagua_batch_workspace_bytes", "bagua_compress_minmax_u8_batched", "bagua_sign_compress_ef_batched",
     "bagua_decompress_reduce_recompress_batched", "bagua_bucket_flatten_batched_run", "bagua_probe_read",
-    "bagua_probe_streams",
+    "bagua_probe_streams", "bagua_flatten_sign_compress_ef", "bagua_decompress_unflatten",
 )
 
 
@@ -75,6 +75,8 @@ def _load():
     lib.bagua_momentum_sign_compress_ef.argtypes = [vp, vp, cf, vp, sz, sz, vp, vp, vp]
     lib.bagua_lp_encode.argtypes = [vp, vp, sz, sz, vp, vp, vp]
     lib.bagua_lp_apply_mix.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, sz, vp, vp]
+    lib.bagua_flatten_sign_compress_ef.argtypes = [vp, sz, vp, sz, sz, vp, vp, vp, vp]
+    lib.bagua_decompress_unflatten.argtypes = [i32, vp, vp, sz, sz, vp, sz, vp]
     lib.bagua_probe_read.argtypes = [vp, sz, vp, vp]
     lib.bagua_probe_streams.argtypes = [vp, vp, vp, i32, i32, i32, i32, sz, vp]
     lib.bagua_batch_workspace_bytes.argtypes = [sz, i32]
@@ -211,6 +213,19 @@ def bagua_flatten_compress_minmax_u8(workspace, T, residual, n, chunk, codes, mi
     _check("bagua_flatten_compress_minmax_u8", _lib.bagua_flatten_compress_minmax_u8(
         _ptr(workspace), T, _ptr(residual, torch.float32, 4 * n), n, chunk, _ptr(codes, torch.uint8, n),
         _ptr(minmax, torch.float32, 8 * num_chunks(n, chunk)), _ptr(bucket_out, torch.float32, 4 * n), _stream(stream)))
+
+
+def bagua_flatten_sign_compress_ef(workspace, T, residual, n, chunk, bits, scale, bucket_out=None, stream=None):
+    _check("bagua_flatten_sign_compress_ef", _lib.bagua_flatten_sign_compress_ef(
+        _ptr(workspace), T, _ptr(residual, torch.float32, 4 * n), n, chunk, _ptr(bits, torch.int32, _code_bytes(CODEC_SIGN1, n)),
+        _ptr(scale, torch.float32, _meta_bytes(CODEC_SIGN1, n, chunk)), _ptr(bucket_out, torch.float32, 4 * n), _stream(stream)))
+
+
+def bagua_decompress_unflatten(codec, codes, meta, n, chunk, workspace, T, stream=None):
+    """Decode a compressed bucket straight into the tensors the workspace was planned with."""
+    _check("bagua_decompress_unflatten", _lib.bagua_decompress_unflatten(
+        codec, _ptr(codes, None, _code_bytes(codec, n)), _ptr(meta, torch.float32, _meta_bytes(codec, n, chunk)), n, chunk,
+        _ptr(workspace), T, _stream(stream)))
 
 
 def bagua_decompress_reduce_recompress(codec, codes_in, meta_in, server_residual, n, chunk, codes_out, meta_out,

@@ -11,6 +11,8 @@
 #include "batch.hpp"
 #include "flatten_device.hpp"
 
+#pragma clang fp contract(off)
+
 namespace bagua {
 
 // One tile (kTile elements) of one bucket; `tile` = index of the tile in its bucket.
@@ -167,6 +169,110 @@ k_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ ti
     }
 }
 
+// Decode fused into the inverse scatter: the decoded value of every bucket element goes straight to the layer tensor
+// that covers it (nothing is written for uncovered elements), so the decoded bucket never exists in memory.
+// CODEC 0: MinMax-u8 (codes u8[n], meta = (min, max) pairs); CODEC 1: sign (codes = sign words, meta = scales).
+constexpr int kDecodeTiles = 4;   // tiles per workgroup of the decode + scatter kernel
+template <int CODEC>
+__global__ void __launch_bounds__(256)
+k_decompress_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile_first, uint32_t T,
+                       const void* __restrict__ codes, const float* __restrict__ meta, size_t n, uint32_t chunk)
+{
+    static_assert(kTile == 1024, "one 256-element row per wave and tile");
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const size_t ntiles = (n + kTile - 1) / kTile;
+    const size_t first = static_cast<size_t>(blockIdx.x) * kDecodeTiles;
+
+    // 1. everything that does not depend on the tensor table: codes and per-chunk metadata of this wave's rows
+    uint32_t w[kDecodeTiles];
+    float m0[kDecodeTiles], m1[kDecodeTiles];
+#pragma unroll
+    for (int i = 0; i < kDecodeTiles; ++i) {
+        const size_t e0 = (first + i) * kTile + wave * kRow;   // this wave's row of tile i
+        w[i] = 0;
+        m0[i] = m1[i] = 0.0f;
+        if (e0 >= n) continue;
+        const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+        const size_t c = e0 / chunk;                            // a row never straddles chunks
+        if (CODEC == 0) {
+            m0[i] = meta[2 * c];
+            m1[i] = meta[2 * c + 1];
+            w[i] = load_codes_row(static_cast<const uint8_t*>(codes) + e0, lane, remain);
+        } else {
+            m0[i] = meta[c];
+            if (static_cast<long>(lane >> 3) * 32 < remain) w[i] = static_cast<const uint32_t*>(codes)[(e0 >> 5) + (lane >> 3)];
+        }
+    }
+    // 2. the table: almost every tile lies inside one tensor, whose base pointer is then uniform
+    float* tile_dst[kDecodeTiles];
+    uint32_t lo0[kDecodeTiles], hi0[kDecodeTiles];
+#pragma unroll
+    for (int i = 0; i < kDecodeTiles; ++i) {
+        const size_t tile = first + i;
+        tile_dst[i] = nullptr;
+        lo0[i] = hi0[i] = T;
+        if (tile >= ntiles) continue;
+        lo0[i] = tile_first[tile];
+        hi0[i] = tile_first[tile + 1];
+        const size_t tile0 = tile * kTile;
+        if (lo0[i] < T && tile0 + kTile <= n) {
+            const TensorDesc d = desc[lo0[i]];
+            if (d.dst <= tile0 && tile0 + kTile <= d.dst + d.numel) tile_dst[i] = const_cast<float*>(d.src) + (tile0 - d.dst);
+        }
+    }
+    // 3. decode and scatter
+#pragma unroll
+    for (int i = 0; i < kDecodeTiles; ++i) {
+        const size_t tile0 = (first + i) * kTile;
+        const size_t e0 = tile0 + wave * kRow;
+        if (e0 >= n) continue;
+        f4 v;
+        if (CODEC == 0) {
+            const float mn = m0[i], step = minmax_step(mn, m1[i]);
+            v.x = mn + byte_to_float(w[i], 0) * step;
+            v.y = mn + byte_to_float(w[i], 1) * step;
+            v.z = mn + byte_to_float(w[i], 2) * step;
+            v.w = mn + byte_to_float(w[i], 3) * step;
+        } else {
+            const float sc = m0[i], neg = -sc;
+            const uint32_t nib = w[i] >> (4 * (lane & 7));
+            v.x = (nib & 1u) ? sc : neg;
+            v.y = (nib & 2u) ? sc : neg;
+            v.z = (nib & 4u) ? sc : neg;
+            v.w = (nib & 8u) ? sc : neg;
+        }
+        const size_t e = e0 + lane * 4;
+        if (tile_dst[i]) {
+            __builtin_nontemporal_store(f4_a4{v.x, v.y, v.z, v.w}, reinterpret_cast<f4_a4*>(tile_dst[i] + (e - tile0)));
+            continue;
+        }
+        if (e >= n) continue;
+        // first tensor whose end lies beyond e, searched in [lo0, hi0]
+        uint32_t lo = lo0[i], hi = hi0[i];
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (desc[mid].dst + desc[mid].numel <= e) lo = mid + 1;
+            else hi = mid;
+        }
+        uint32_t t = lo;
+        if (t < T && e + 4 <= n) {
+            const TensorDesc d = desc[t];
+            if (d.dst <= e && e + 4 <= d.dst + d.numel) {
+                float* s = const_cast<float*>(d.src) + (e - d.dst);
+                __builtin_nontemporal_store(f4_a4{v.x, v.y, v.z, v.w}, reinterpret_cast<f4_a4*>(s));
+                continue;
+            }
+        }
+        const float q[4] = {v.x, v.y, v.z, v.w};
+        for (int r = 0; r < 4; ++r) {
+            const size_t eq = e + r;
+            if (eq >= n) break;
+            while (t < T && desc[t].dst + desc[t].numel <= eq) ++t;
+            if (t < T && desc[t].dst <= eq) const_cast<float*>(desc[t].src)[eq - desc[t].dst] = q[r];
+        }
+    }
+}
+
 }  // namespace bagua
 
 using namespace bagua;
@@ -265,6 +371,25 @@ extern "C" int bagua_bucket_flatten_batched_run(const void* const* plans, const 
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (batch_upload(table.data(), table.size(), static_cast<uint64_t*>(workspace), s) != BAGUA_OK) return BAGUA_ERR_LAUNCH;
     hipLaunchKernelGGL(k_flatten_batched, dim3(static_cast<unsigned>(total)), dim3(256), 0, s, batch_view(workspace, B, ew));
+    return launch_status();
+}
+
+extern "C" int bagua_decompress_unflatten(int codec, const void* codes, const float* meta, size_t n, size_t chunk,
+                                          const void* workspace, size_t T, void* stream)
+{
+    if (codec != BAGUA_CODEC_MINMAX_U8 && codec != BAGUA_CODEC_SIGN1) return BAGUA_ERR_INVALID_ARG;
+    if (!codes || !meta || !workspace || n == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
+    if (T > 0xfffffff0u || num_tiles(n) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (!aligned16(codes) || !aligned4(meta) || !aligned16(workspace)) return BAGUA_ERR_ALIGNMENT;
+    const FlattenPlanView pv = plan_view(workspace, T);
+    dim3 grid(static_cast<unsigned>((num_tiles(n) + kDecodeTiles - 1) / kDecodeTiles)), block(256);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (codec == BAGUA_CODEC_MINMAX_U8)
+        hipLaunchKernelGGL((k_decompress_unflatten<0>), grid, block, 0, s, pv.desc, pv.tile_first, static_cast<uint32_t>(T),
+                           codes, meta, n, static_cast<uint32_t>(chunk));
+    else
+        hipLaunchKernelGGL((k_decompress_unflatten<1>), grid, block, 0, s, pv.desc, pv.tile_first, static_cast<uint32_t>(T),
+                           codes, meta, n, static_cast<uint32_t>(chunk));
     return launch_status();
 }
 

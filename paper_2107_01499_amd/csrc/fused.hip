@@ -5,6 +5,7 @@
 #include "flatten_device.hpp"
 #include "launchers.hpp"
 #include "minmax_device.hpp"
+#include "sign_device.hpp"
 
 #pragma clang fp contract(off)
 
@@ -55,6 +56,53 @@ k_flatten_compress_minmax(const TensorDesc* __restrict__ desc, const uint32_t* _
     }
     minmax_encode_chunk<RPW, EF, false>(v, len, wave, lane, nwaves, EF ? residual + base : nullptr,
                                         codes + base, minmax + 2 * c, nullptr, s_red);
+}
+
+// The same gather in front of the 1-bit sign codec: bagua_bucket_flatten followed by bagua_sign_compress_ef.
+template <int RPW, bool EF, bool WB>
+__global__ void __launch_bounds__(wg_threads_max(RPW))
+k_flatten_sign_compress(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile_first, uint32_t T,
+                        float* __restrict__ residual, size_t n, uint32_t chunk, uint32_t* __restrict__ bits,
+                        float* __restrict__ scale, float* __restrict__ bucket_out)
+{
+    extern __shared__ float s_q[];
+    const size_t c = blockIdx.x;
+    const size_t base = c * static_cast<size_t>(chunk);
+    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+
+    f4 d[RPW];
+    if (EF) {
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const long off = static_cast<long>(wave * RPW + i) * kRow;
+            const long remain = len - off;
+            d[i] = f4{0.f, 0.f, 0.f, 0.f};
+            if (remain > 0) d[i] = load_row(residual + base + off, lane, remain, 0.0f);
+        }
+    }
+    f4 v[RPW];
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        const long off = static_cast<long>(wave * RPW + i) * kRow;
+        const long remain = len - off;
+        v[i] = f4{0.f, 0.f, 0.f, 0.f};
+        if (remain > 0) {
+            v[i] = gather_row(desc, tile_first, T, base + off, lane, remain);
+            if (WB) store_row(bucket_out + base + off, lane, remain, v[i]);
+        }
+    }
+    if (EF) {
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            v[i].x = v[i].x + d[i].x;
+            v[i].y = v[i].y + d[i].y;
+            v[i].z = v[i].z + d[i].z;
+            v[i].w = v[i].w + d[i].w;
+        }
+    }
+    sign_encode_chunk<RPW, EF, false>(v, len, chunk, wave, lane, nwaves, EF ? residual + base : nullptr,
+                                      bits + (base >> 5), scale + c, nullptr, s_q);
 }
 
 // Intra-node stage of hierarchical C_LP_S (Section 3.5): the k_local workers' uncompressed buckets are
@@ -149,6 +197,40 @@ extern "C" int bagua_flatten_compress_minmax_u8(const void* workspace, size_t T,
     else if (bucket_out) { BAGUA_FC(false, true) }
     else { BAGUA_FC(false, false) }
 #undef BAGUA_FC
+    return launch_status();
+}
+
+extern "C" int bagua_flatten_sign_compress_ef(const void* workspace, size_t T, float* residual, size_t bucket_numel,
+                                              size_t chunk, uint32_t* bits, float* scale, float* bucket_out,
+                                              void* stream)
+{
+    if (!workspace || !bits || !scale || bucket_numel == 0 || !chunk_ok(chunk)) return BAGUA_ERR_INVALID_ARG;
+    RangeCheck rc;
+    rc.writes(residual, bucket_numel * sizeof(float));
+    rc.writes(bits, ((bucket_numel + 31) / 32) * sizeof(uint32_t));
+    rc.writes(scale, num_chunks(bucket_numel, chunk) * sizeof(float));
+    rc.writes(bucket_out, bucket_numel * sizeof(float));
+    if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    if (T > 0xfffffff0u || num_chunks(bucket_numel, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (!aligned16(workspace) || !aligned16(residual) || !aligned16(bits) || !aligned4(scale) || !aligned16(bucket_out))
+        return BAGUA_ERR_ALIGNMENT;
+    const FlattenPlanView pv = plan_view(workspace, T);
+    const int rows = static_cast<int>(chunk / kRow);
+    const int rpw = pick_rpw(rows, BAGUA_RPW_SIGN);
+    const int waves = (rows + rpw - 1) / rpw;
+    dim3 grid(static_cast<unsigned>(num_chunks(bucket_numel, chunk))), block(64 * waves);
+    const size_t lds = waves > 1 ? static_cast<size_t>(rows) * kWave * sizeof(float) : 0;
+    const uint32_t ch = static_cast<uint32_t>(chunk), t32 = static_cast<uint32_t>(T);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define BAGUA_FS(EFv, WBv)                                                                                       \
+    BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_flatten_sign_compress<RPW, EFv, WBv>), grid, block, lds, s,    \
+                                               pv.desc, pv.tile_first, t32, residual, bucket_numel, ch, bits,   \
+                                               scale, bucket_out))
+    if (residual && bucket_out) { BAGUA_FS(true, true) }
+    else if (residual) { BAGUA_FS(true, false) }
+    else if (bucket_out) { BAGUA_FS(false, true) }
+    else { BAGUA_FS(false, false) }
+#undef BAGUA_FS
     return launch_status();
 }
 
