@@ -236,6 +236,14 @@ int bagua_reduce_compress_minmax_u8(const float* const* x, int k_local, float* r
                                     uint8_t* codes, float* minmax, void* stream);
 
 /*
+ * The same intra-node stage with the 1-bit sign codec (Section 3.5 "Hierarchical Communications" with the Q of
+ * Section 4.1's 1-bit Adam): a = ((x_0 + x_1) + ...) * fl(1/k_local), then exactly bagua_sign_compress_ef on a with the
+ * leader's error state.  bits u32[ceil(n/32)], scale fp32[nc]; other arguments as above.
+ */
+int bagua_reduce_compress_sign_ef(const float* const* x, int k_local, float* residual, size_t n, size_t chunk,
+                                  uint32_t* bits, float* scale, void* stream);
+
+/*
  * Decentralised full-precision averaging with the "random" peer strategy of Section 3.4 (each worker exchanges
  * with one peer chosen for the round; the D_FP_S equation of Section 3.2 with N(i) = {i, peer[i]}, weight 1/2):
  *   x_out[i] = (x_in[i] + x_in[peer[i]]) * 0.5f        from the old values.

@@ -211,6 +211,14 @@ def reduce_compress_minmax_u8(xs, residual, chunk):
     return codes, minmax
 
 
+def reduce_compress_sign(xs, residual, chunk):
+    """Intra-node stage of hierarchical C_LP_S with the 1-bit sign codec (Section 3.5 "Hierarchical Communications";
+    Q of Section 4.1's 1-bit Adam): the k_local uncompressed buckets are averaged as in reduce_compress_minmax_u8
+    (ascending order, one multiply by fl(1/k_local)), then the leader sign-compresses the average with its error
+    state.  Written as that composition: centralized_avg_fp, then sign_compress_ef.  Returns (bits, scale)."""
+    return sign_compress_ef(centralized_avg_fp(xs), residual, chunk)
+
+
 def bucket_unflatten(bucket, dsts, src_offset):
     """Inverse of bucket_flatten: writes every tensor's range of the bucket into the given arrays (in place)."""
     T = len(dsts)

@@ -30,7 +30,7 @@ EXPORTS = (
     "bagua_decompress_adam_step", "bagua_momentum_sign_compress_ef", "bagua_lp_encode", "bagua_lp_apply_mix", "bagua_bucket_flatten_static",
     "bagua_batch_workspace_bytes", "bagua_compress_minmax_u8_batched", "bagua_sign_compress_ef_batched",
     "bagua_decompress_reduce_recompress_batched", "bagua_bucket_flatten_batched_run", "bagua_probe_read",
-    "bagua_probe_streams", "bagua_flatten_sign_compress_ef", "bagua_decompress_unflatten",
+    "bagua_probe_streams", "bagua_flatten_sign_compress_ef", "bagua_decompress_unflatten", "bagua_reduce_compress_sign_ef",
 )
 
 
@@ -77,6 +77,7 @@ def _load():
     lib.bagua_lp_apply_mix.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, sz, vp, vp]
     lib.bagua_flatten_sign_compress_ef.argtypes = [vp, sz, vp, sz, sz, vp, vp, vp, vp]
     lib.bagua_decompress_unflatten.argtypes = [i32, vp, vp, sz, sz, vp, sz, vp]
+    lib.bagua_reduce_compress_sign_ef.argtypes = [vp, i32, vp, sz, sz, vp, vp, vp]
     lib.bagua_probe_read.argtypes = [vp, sz, vp, vp]
     lib.bagua_probe_streams.argtypes = [vp, vp, vp, i32, i32, i32, i32, sz, vp]
     lib.bagua_batch_workspace_bytes.argtypes = [sz, i32]
@@ -274,6 +275,14 @@ def bagua_reduce_compress_minmax_u8(xs, residual, chunk, codes, minmax, stream=N
     _check("bagua_reduce_compress_minmax_u8", _lib.bagua_reduce_compress_minmax_u8(
         _ptr_array(xs, torch.float32, 4 * n), len(xs), _ptr(residual, torch.float32, 4 * n), n, chunk,
         _ptr(codes, torch.uint8, n), _ptr(minmax, torch.float32, 8 * num_chunks(n, chunk)), _stream(stream)))
+
+
+def bagua_reduce_compress_sign_ef(xs, residual, chunk, bits, scale, stream=None):
+    n = xs[0].numel()
+    _check("bagua_reduce_compress_sign_ef", _lib.bagua_reduce_compress_sign_ef(
+        _ptr_array(xs, torch.float32, 4 * n), len(xs), _ptr(residual, torch.float32, 4 * n), n, chunk,
+        _ptr(bits, torch.int32, _code_bytes(CODEC_SIGN1, n)), _ptr(scale, torch.float32, _meta_bytes(CODEC_SIGN1, n, chunk)),
+        _stream(stream)))
 
 
 def bagua_centralized_avg_fp(xs, out, stream=None):

@@ -163,6 +163,62 @@ k_reduce_compress_minmax(PtrTable xs, int k_local, float inv_k, float* __restric
                                         codes + base, minmax + 2 * c, nullptr, s_red);
 }
 
+// The same intra-node stage in front of the 1-bit sign codec.
+template <int RPW, bool EF>
+__global__ void __launch_bounds__(wg_threads_max(RPW))
+k_reduce_compress_sign(PtrTable xs, int k_local, float inv_k, float* __restrict__ residual, size_t n, uint32_t chunk,
+                       uint32_t* __restrict__ bits, float* __restrict__ scale)
+{
+    extern __shared__ float s_q[];
+    const size_t c = blockIdx.x;
+    const size_t base = c * static_cast<size_t>(chunk);
+    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+
+    f4 v[RPW];
+    for (int j = 0; j < k_local; ++j) {
+        const float* xj = static_cast<const float*>(xs.p[j]) + base;
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const long off = static_cast<long>(wave * RPW + i) * kRow;
+            const long remain = len - off;
+            f4 d = f4{0.f, 0.f, 0.f, 0.f};
+            if (remain > 0) d = load_row(xj + off, lane, remain, 0.0f);
+            if (j == 0) {
+                v[i] = d;
+            } else {
+                v[i].x = v[i].x + d.x;
+                v[i].y = v[i].y + d.y;
+                v[i].z = v[i].z + d.z;
+                v[i].w = v[i].w + d.w;
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        v[i].x = v[i].x * inv_k;
+        v[i].y = v[i].y * inv_k;
+        v[i].z = v[i].z * inv_k;
+        v[i].w = v[i].w * inv_k;
+    }
+    if (EF) {
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const long off = static_cast<long>(wave * RPW + i) * kRow;
+            const long remain = len - off;
+            if (remain > 0) {
+                const f4 d = load_row(residual + base + off, lane, remain, 0.0f);
+                v[i].x = v[i].x + d.x;
+                v[i].y = v[i].y + d.y;
+                v[i].z = v[i].z + d.z;
+                v[i].w = v[i].w + d.w;
+            }
+        }
+    }
+    sign_encode_chunk<RPW, EF, false>(v, len, chunk, wave, lane, nwaves, EF ? residual + base : nullptr,
+                                      bits + (base >> 5), scale + c, nullptr, s_q);
+}
+
 }  // namespace bagua
 
 using namespace bagua;
@@ -266,6 +322,44 @@ extern "C" int bagua_reduce_compress_minmax_u8(const float* const* x, int k_loca
     } else {
         BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_reduce_compress_minmax<RPW, false>), grid, block, 0, s, xt, k_local,
                                                    inv_k, residual, n, ch, codes, minmax))
+    }
+    return launch_status();
+}
+
+extern "C" int bagua_reduce_compress_sign_ef(const float* const* x, int k_local, float* residual, size_t n, size_t chunk,
+                                             uint32_t* bits, float* scale, void* stream)
+{
+    if (!x || k_local < 1 || k_local > BAGUA_MAX_WORKERS || !bits || !scale || n == 0 || !chunk_ok(chunk))
+        return BAGUA_ERR_INVALID_ARG;
+    RangeCheck rc;
+    for (int j = 0; j < k_local; ++j) {
+        if (!x[j]) return BAGUA_ERR_INVALID_ARG;
+        rc.reads(x[j], n * sizeof(float));
+    }
+    rc.writes(residual, n * sizeof(float));
+    rc.writes(bits, ((n + 31) / 32) * sizeof(uint32_t));
+    rc.writes(scale, num_chunks(n, chunk) * sizeof(float));
+    if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    if (num_chunks(n, chunk) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    for (int j = 0; j < k_local; ++j)
+        if (!aligned16(x[j])) return BAGUA_ERR_ALIGNMENT;
+    if (!aligned16(residual) || !aligned16(bits) || !aligned4(scale)) return BAGUA_ERR_ALIGNMENT;
+    PtrTable xt{};
+    for (int j = 0; j < k_local; ++j) xt.p[j] = x[j];
+    const int rows = static_cast<int>(chunk / kRow);
+    const int rpw = pick_rpw(rows, BAGUA_RPW_SIGN);
+    const int waves = (rows + rpw - 1) / rpw;
+    dim3 grid(static_cast<unsigned>(num_chunks(n, chunk))), block(64 * waves);
+    const size_t lds = waves > 1 ? static_cast<size_t>(rows) * kWave * sizeof(float) : 0;
+    const float inv_k = 1.0f / static_cast<float>(k_local);
+    const uint32_t ch = static_cast<uint32_t>(chunk);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (residual) {
+        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_reduce_compress_sign<RPW, true>), grid, block, lds, s, xt, k_local,
+                                                   inv_k, residual, n, ch, bits, scale))
+    } else {
+        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_reduce_compress_sign<RPW, false>), grid, block, lds, s, xt, k_local,
+                                                   inv_k, residual, n, ch, bits, scale))
     }
     return launch_status();
 }

@@ -41,6 +41,27 @@ def test_reduce_compress(bg, oracle, k, n, C, ef):
         assert np.array_equal(rg.cpu().numpy().view(np.uint32), res_o.view(np.uint32))
 
 
+@pytest.mark.parametrize("k", [1, 2, 4, 32])
+@pytest.mark.parametrize("n,C", [(1, 256), (257, 256), (3 * 2048 + 77, 2048), (70001, 8192), (40000, 16384)])
+@pytest.mark.parametrize("ef", [False, True])
+def test_reduce_compress_sign(bg, oracle, k, n, C, ef):
+    print("reduce_compress_sign k=%d n=%d C=%d ef=%s" % (k, n, C, ef), flush=True)
+    xs = [vals(n, 37 * k + j) for j in range(k)]
+    xs[0][::17] = 0.0
+    res = vals(n, 8) * np.float32(0.05) if ef else None
+    res_o = None if res is None else res.copy()
+    bo, so = oracle.reduce_compress_sign(xs, res_o, C)
+    rg = None if res is None else dev(res)
+    bits = torch.full(((n + 31) // 32,), -1, dtype=torch.int32, device="cuda")
+    scale = torch.full((bg.num_chunks(n, C),), float("nan"), device="cuda")
+    bg.bagua_reduce_compress_sign_ef([dev(x) for x in xs], rg, C, bits, scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits.cpu().numpy().view(np.uint32), bo)
+    assert np.array_equal(scale.cpu().numpy().view(np.uint32), so.view(np.uint32))
+    if ef:
+        assert np.array_equal(rg.cpu().numpy().view(np.uint32), res_o.view(np.uint32))
+
+
 def test_two_level_pipeline(bg, oracle):
     """4 nodes x 2 local workers, two iterations with all error states carried: intra-node reduce+compress at the
     leaders, inter-node server step, decode on every worker."""

@@ -94,3 +94,44 @@ def test_centralized_full_precision_average(oracle, k):
     assert np.all(np.abs(outq - avg) <= rng_ / 255 / 2 * (1 + 1e-4) + 1e-9)
     for c in range(2):
         assert mm[2 * c] == avg[c * C:(c + 1) * C].min() and mm[2 * c + 1] == avg[c * C:(c + 1) * C].max()
+
+
+# ----------------------------------------------------------------------------- intra-node stage, sign codec
+@pytest.mark.parametrize("n,C", [(1, 256), (300, 256), (2 * 2048 + 9, 2048)])
+def test_sign_single_local_worker_is_plain_sign_compression(oracle, n, C):
+    x = vals(n, n + 5)
+    d1 = vals(n, 2) * np.float32(0.1)
+    d2 = d1.copy()
+    b1, s1 = oracle.reduce_compress_sign([x], d1, C)
+    b2, s2 = oracle.sign_compress_ef(x, d2, C)
+    assert np.array_equal(b1, b2) and np.array_equal(s1, s2) and np.array_equal(d1, d2)
+
+
+@pytest.mark.parametrize("k", [2, 3, 8])
+def test_sign_aggregate_is_left_to_right_average_then_sign(oracle, k):
+    """Bits are the signs of (ascending-order fp32 average + error state), the scale is the chunk mean of its
+    magnitude (fp64 check), the new error state closes the identity v = decode + delta', and the summation order is
+    visible through 2^24 + 1 + 1 - 2^24."""
+    n, C = 3 * 256 + 40, 256
+    xs = [vals(n, 20 * k + j) for j in range(k)]
+    s = xs[0].copy()
+    for j in range(1, k):
+        s = (s + xs[j]).astype(np.float32)
+    a = (s * (np.float32(1.0) / np.float32(k))).astype(np.float32)
+    d0 = vals(n, 98) * np.float32(0.05)
+    d = d0.copy()
+    bits, scale = oracle.reduce_compress_sign(xs, d, C)
+    v = (a + d0).astype(np.float32)
+    want_bits = np.packbits((v >= 0).astype(np.uint8), bitorder="little")
+    got_bits = bits.view(np.uint8)[:want_bits.size]
+    assert np.array_equal(got_bits, want_bits)
+    for c, lo in enumerate(range(0, n, C)):
+        hi = min(n, lo + C)
+        assert abs(float(scale[c]) - np.mean(np.abs(v[lo:hi].astype(np.float64)))) <= 1e-6 * float(scale[c]) + 1e-12
+    deq = oracle.decompress_sign(bits, scale, n, C)
+    assert np.array_equal(d, (v - deq).astype(np.float32))
+    if k == 3:
+        big = np.float32(2.0 ** 24)
+        ys = [np.full(256, t, np.float32) for t in (big, 1.0, -big)]
+        b, sc = oracle.reduce_compress_sign(ys, None, 256)
+        assert sc.tolist() == [0.0] and not np.any(b != 0xFFFFFFFF)   # (2^24 + 1) - 2^24 = 0 in fp32: +0 everywhere
