@@ -806,10 +806,10 @@ def run_block(torch, bg, args, name, layout, only, extras):
              "per_primitive": per_prim, "roofline": roof}
     if name == "single_bucket_x32":
         block["single_instance_latency_us"] = single_instance_latency(torch, bg, wl)
-    if "flatten" in prims and layout == "flat" and only is None:
-        block["flatten_misaligned"] = misaligned_flatten(torch, bg, wl)
     if not args.no_cpu_baseline and layout == "flat" and only is None and not args.fused_flatten and not extras:
         block["cpu_baseline"], block["parity"] = cpu_baseline(wl, torch)
+    if "flatten" in prims and layout == "flat" and only is None:      # last: it overwrites the resident buckets
+        block["flatten_misaligned"] = misaligned_flatten(torch, bg, wl)
     del wl
     import gc
     gc.collect()
