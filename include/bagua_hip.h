@@ -189,6 +189,9 @@ int bagua_decompress_reduce_recompress(int codec, const void* const* codes_in, c
  *   xhat    host[k] of device fp32[n], LP only: public copies of the replicas, updated in place
  *   codes   host[k] of device u8[n], LP only, written;  minmax host[k] of device fp32[2*nc], LP only, written
  *   chunk   used by LP only (ignored for FP)
+  * Placement: this call streams 2k (FP) or 5k (LP) buffers at once.  On MI355X it runs 15-20 % faster when those
+ * buffers are scattered over more than ~48 GiB of the GPU's address space than when they lie back to back (any
+ * placement gives the same results).
  */
 int bagua_decentralized_avg(int mode, const float* const* x_in, float* const* x_out, float* const* xhat,
                             uint8_t* const* codes, float* const* minmax, int k, size_t n, size_t chunk,
