@@ -803,6 +803,18 @@ def read_traffic(workload, kernel):
     return None
 
 
+def source_hash():
+    """sha256 (16 hex digits) over the library's sources: which code the loaded .so was checked against by ensure_built."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    files = sorted(glob.glob(os.path.join(ROOT, "paper_2107_01499_amd", "csrc", "*")) + glob.glob(os.path.join(ROOT, "include", "*.h")))
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
 def run_block(torch, bg, args, name, layout, only, extras):
     """Build one workload, time --warmup + --steps steps of it, then (flat layout) the oracle sample and parity."""
     wl = Workload(torch, bg, name, layout=layout, only=only, fused=args.fused_flatten, extras=extras,
@@ -1119,6 +1131,7 @@ def main():
         "copy_kernel_GBps": ceil["copy_kernel_GBps"],
         "read_kernel_GBps": ceil["read_kernel_GBps"],
         "blocks": blocks,
+        "library": {"path": os.path.relpath(bg.binding.LIB_PATH, ROOT), "source_sha16": source_hash()},
     }
     base = [(k_, b["cpu_baseline"]) for k_, b in blocks.items() if "cpu_baseline" in b]
     if base:
