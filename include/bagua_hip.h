@@ -331,6 +331,16 @@ int bagua_decompress_sgd_step(int codec, const void* codes, const float* meta, s
                               void* stream);
 
 /*
+ * The same step after a round with the per-chunk top-K codec (Section 3.2 names top-K as the aggressive compression;
+ * Section 3.5: the optimizer works on the flattened bucket): g = the decoded sparse entries, +0 at every other element,
+ * then the update above on EVERY element.  idx / val / keep as bagua_decompress_topk.  Without momentum and weight
+ * decay (and with a finite lr >= +0) only the kept entries are touched, which gives the same bits.
+ */
+int bagua_decompress_sgd_step_topk(const uint16_t* idx, const float* val, size_t n, size_t chunk, size_t keep,
+                                   float* param, float* momentum_buf, float lr, float momentum, float weight_decay,
+                                   void* stream);
+
+/*
  * Decode fused into an Adam-type update of the flattened bucket (Section 3.5: the optimizer runs on the bucket;
  * Section 4.1: QSGD and 1-bit Adam are C_LP_S followed by the optimizer; the steps of 1-bit Adam are those of the
  * published algorithm the paper cites).  Adam without bias correction, one rounding per operation:

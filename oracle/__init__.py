@@ -185,6 +185,16 @@ def decompress_sgd_step(codec, codes, meta, n, chunk, param, momentum_buf, lr, m
           None if momentum_buf is None else _chk(momentum_buf, np.float32), lr, momentum, weight_decay), "decompress_sgd_step")
 
 
+def decompress_sgd_step_topk(idx, val, n, chunk, keep, param, momentum_buf, lr, momentum=0.0, weight_decay=0.0):
+    """Decode of a top-K bucket fused with the SGD step on the flat bucket; param / momentum_buf updated in place."""
+    f = lib().oracle_decompress_sgd_step_topk
+    f.restype = ctypes.c_int
+    f.argtypes = [_c_p, _c_p, _c_sz, _c_sz, _c_sz, _c_p, _c_p, ctypes.c_float, ctypes.c_float, ctypes.c_float]
+    _ok(f(_chk(idx, np.uint16), _chk(val, np.float32), n, chunk, keep, _chk(param, np.float32),
+          None if momentum_buf is None else _chk(momentum_buf, np.float32), lr, momentum, weight_decay),
+        "decompress_sgd_step_topk")
+
+
 def peer_avg_fp(x_in, peer):
     """D_FP_S with one chosen peer per worker: x_i' = (x_i + x_peer[i]) / 2. Returns the list of new replicas."""
     k = len(x_in)

@@ -495,15 +495,10 @@ int oracle_bucket_flatten(const float* const* src, const size_t* numel, const si
  *     p = p - lr * u
  * A zero-initialised momentum buffer reproduces the usual "first step: m = g".
  */
-int oracle_decompress_sgd_step(int codec, const void* codes, const float* meta, size_t n, size_t chunk,
-                               float* param, float* momentum_buf, float lr, float momentum, float weight_decay)
+/* The update above for a decoded gradient g (shared by every codec's step). */
+static void sgd_update(const float* g, size_t n, float* param, float* momentum_buf, float lr, float momentum,
+                       float weight_decay)
 {
-    if ((codec != 0 && codec != 1) || !codes || !meta || !param || n == 0 || !chunk_ok(chunk)) return 1;
-    float* g = (float*)malloc(n * sizeof(float));
-    if (!g) return 1;
-    int rc = codec == 0 ? oracle_decompress_minmax_u8((const uint8_t*)codes, meta, n, chunk, g)
-                        : oracle_decompress_sign((const uint32_t*)codes, meta, n, chunk, g);
-    if (rc) { free(g); return rc; }
     for (size_t i = 0; i < n; ++i) {
         float gi = g[i];
         if (weight_decay != 0.0f) {
@@ -520,8 +515,36 @@ int oracle_decompress_sgd_step(int codec, const void* codes, const float* meta, 
         float s = lr * u;
         param[i] = param[i] - s;
     }
+}
+
+int oracle_decompress_sgd_step(int codec, const void* codes, const float* meta, size_t n, size_t chunk,
+                               float* param, float* momentum_buf, float lr, float momentum, float weight_decay)
+{
+    if ((codec != 0 && codec != 1) || !codes || !meta || !param || n == 0 || !chunk_ok(chunk)) return 1;
+    float* g = (float*)malloc(n * sizeof(float));
+    if (!g) return 1;
+    int rc = codec == 0 ? oracle_decompress_minmax_u8((const uint8_t*)codes, meta, n, chunk, g)
+                        : oracle_decompress_sign((const uint32_t*)codes, meta, n, chunk, g);
+    if (rc) { free(g); return rc; }
+    sgd_update(g, n, param, momentum_buf, lr, momentum, weight_decay);
     free(g);
     return 0;
+}
+
+int oracle_decompress_topk(const uint16_t* idx, const float* val, size_t n, size_t chunk, size_t keep, float* out);
+
+/* The same step after a top-K round (Section 3.2 names top-K as the aggressive Q): g = decode of the sparse entries,
+ * +0 everywhere else, then the identical update on EVERY element (so weight decay and momentum act on all of them). */
+int oracle_decompress_sgd_step_topk(const uint16_t* idx, const float* val, size_t n, size_t chunk, size_t keep,
+                                    float* param, float* momentum_buf, float lr, float momentum, float weight_decay)
+{
+    if (!idx || !val || !param || n == 0 || !chunk_ok(chunk) || keep < 1 || keep > chunk) return 1;
+    float* g = (float*)malloc(n * sizeof(float));
+    if (!g) return 1;
+    int rc = oracle_decompress_topk(idx, val, n, chunk, keep, g);
+    if (!rc) sgd_update(g, n, param, momentum_buf, lr, momentum, weight_decay);
+    free(g);
+    return rc;
 }
 
 /* ------------------------------------------------ decentralised averaging, "random" peer strategy */

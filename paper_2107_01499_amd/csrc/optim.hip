@@ -2,6 +2,8 @@
 // (decode the tensor the server sent back) and the update of the flattened bucket (Section 3.5 of
 // the paper) in one pass.  The decoded tensor is never written to memory.  SGD: 1 (or 1/8) + 8
 // (+ 8 with momentum) bytes per element; Adam: 1 + 24 (full), 1/8 + 16 (frozen variance).
+#include <cmath>
+
 #include "launchers.hpp"
 
 #pragma clang fp contract(off)
@@ -125,6 +127,84 @@ k_decompress_adam(const void* __restrict__ codes, const float* __restrict__ meta
     store_row(param + e0, lane, remain, p);
 }
 
+// ------------------------------------------------------------------------------------------ top-K codec
+// Without momentum and weight decay (and lr >= +0, finite) only the kept entries change: p - fl(lr * +0) = p bit for
+// bit.  One thread per (chunk, slot) entry.
+__global__ void __launch_bounds__(256)
+k_sgd_topk_sparse(const uint16_t* __restrict__ idx, const float* __restrict__ val, size_t entries, uint32_t chunk,
+                  uint32_t keep, size_t n, float* __restrict__ param, float lr)
+{
+    const size_t e = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (e >= entries) return;
+    const uint32_t q = idx[e];
+    if (q == 0xFFFFu) return;
+    const size_t i = (e / keep) * chunk + q;
+    if (i < n) param[i] = param[i] - lr * val[e];
+}
+
+// General case: the chunk's decoded gradient is built in LDS (+0 everywhere, then the kept entries), and every
+// element is updated as in k_decompress_sgd.  One workgroup per chunk, RPW rows per wave.
+template <int RPW, bool MOM, bool WD>
+__global__ void __launch_bounds__(wg_threads_max(RPW))
+k_decompress_sgd_topk(const uint16_t* __restrict__ idx, const float* __restrict__ val, size_t n, uint32_t chunk,
+                      uint32_t keep, float* __restrict__ param, float* __restrict__ mbuf, float lr, float mu, float wd)
+{
+    extern __shared__ float s_g[];   // chunk floats
+    const size_t c = blockIdx.x;
+    const size_t base = c * static_cast<size_t>(chunk);
+    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+
+    // parameters (and momentum) do not depend on the decode: request them first
+    f4 p[RPW], m[RPW];
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        const long off = static_cast<long>(wave * RPW + i) * kRow;
+        const long remain = len - off;
+        p[i] = f4{0.f, 0.f, 0.f, 0.f};
+        m[i] = p[i];
+        if (remain > 0) {
+            p[i] = load_row(param + base + off, lane, remain, 0.0f);
+            if (MOM) m[i] = load_row(mbuf + base + off, lane, remain, 0.0f);
+        }
+    }
+    for (uint32_t e = threadIdx.x * 4; e < chunk; e += blockDim.x * 4)
+        *reinterpret_cast<f4*>(s_g + e) = f4{0.f, 0.f, 0.f, 0.f};
+    __syncthreads();
+    for (uint32_t s = threadIdx.x; s < keep; s += blockDim.x) {
+        const uint32_t q = idx[c * keep + s];
+        if (q != 0xFFFFu && q < chunk) s_g[q] = val[c * keep + s];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        const long off = static_cast<long>(wave * RPW + i) * kRow;
+        const long remain = len - off;
+        if (remain <= 0) continue;
+        f4 g = *reinterpret_cast<const f4*>(s_g + off + lane * 4);
+        if (WD) {
+            g.x = g.x + wd * p[i].x;
+            g.y = g.y + wd * p[i].y;
+            g.z = g.z + wd * p[i].z;
+            g.w = g.w + wd * p[i].w;
+        }
+        f4 u = g;
+        if (MOM) {
+            m[i].x = mu * m[i].x + g.x;
+            m[i].y = mu * m[i].y + g.y;
+            m[i].z = mu * m[i].z + g.z;
+            m[i].w = mu * m[i].w + g.w;
+            store_row(mbuf + base + off, lane, remain, m[i]);
+            u = m[i];
+        }
+        p[i].x = p[i].x - lr * u.x;
+        p[i].y = p[i].y - lr * u.y;
+        p[i].z = p[i].z - lr * u.z;
+        p[i].w = p[i].w - lr * u.w;
+        store_row(param + base + off, lane, remain, p[i]);
+    }
+}
+
 }  // namespace bagua
 
 using namespace bagua;
@@ -203,5 +283,46 @@ extern "C" int bagua_decompress_adam_step(int codec, const void* codes, const fl
     else { BAGUA_ADAM_CODEC(BAGUA_CODEC_SIGN1) }
 #undef BAGUA_ADAM_CODEC
 #undef BAGUA_ADAM
+    return launch_status();
+}
+
+extern "C" int bagua_decompress_sgd_step_topk(const uint16_t* idx, const float* val, size_t n, size_t chunk, size_t keep,
+                                              float* param, float* momentum_buf, float lr, float momentum,
+                                              float weight_decay, void* stream)
+{
+    if (!idx || !val || !param || n == 0 || !chunk_ok(chunk) || keep < 1 || keep > chunk) return BAGUA_ERR_INVALID_ARG;
+    const size_t nc = num_chunks(n, chunk);
+    {
+        RangeCheck rc;
+        rc.reads(idx, nc * keep * sizeof(uint16_t));
+        rc.reads(val, nc * keep * sizeof(float));
+        rc.writes(param, n * sizeof(float));
+        rc.writes(momentum_buf, n * sizeof(float));
+        if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    }
+    if (nc > kMaxGrid || (nc * keep + 255) / 256 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (!aligned2(idx) || !aligned4(val) || !aligned16(param) || !aligned16(momentum_buf)) return BAGUA_ERR_ALIGNMENT;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint32_t ch = static_cast<uint32_t>(chunk), kp = static_cast<uint32_t>(keep);
+    const bool mom = momentum_buf != nullptr, wd = weight_decay != 0.0f;
+    // lr * (+0) must be +0 for the sparse form to equal the dense update: lr finite with a clear sign bit
+    if (!mom && !wd && std::isfinite(lr) && !std::signbit(lr)) {
+        const size_t entries = nc * keep;
+        hipLaunchKernelGGL(k_sgd_topk_sparse, dim3(static_cast<unsigned>((entries + 255) / 256)), dim3(256), 0, s, idx, val,
+                           entries, ch, kp, n, param, lr);
+        return launch_status();
+    }
+    const int rows = static_cast<int>(chunk / kRow);
+    const int rpw = pick_rpw(rows, 2);
+    dim3 grid(static_cast<unsigned>(nc)), block(64 * ((rows + rpw - 1) / rpw));
+    const size_t lds = chunk * sizeof(float);
+#define BAGUA_TS(MOMv, WDv)                                                                                      \
+    BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_decompress_sgd_topk<RPW, MOMv, WDv>), grid, block, lds, s, idx, \
+                                               val, n, ch, kp, param, momentum_buf, lr, momentum, weight_decay))
+    if (mom && wd) { BAGUA_TS(true, true) }
+    else if (mom) { BAGUA_TS(true, false) }
+    else if (wd) { BAGUA_TS(false, true) }
+    else { BAGUA_TS(false, false) }
+#undef BAGUA_TS
     return launch_status();
 }

@@ -48,3 +48,24 @@ def test_decompress_sgd_step(bg, oracle, codec, n, C, mom, wd):
     bit_equal(p_g, p_o, "param")
     if mom:
         bit_equal(m_g, m_o, "momentum")
+
+
+@pytest.mark.parametrize("n,C,keep", [(1, 256, 1), (257, 256, 8), (3 * 4096 + 77, 4096, 128), (70001, 2048, 2048), (40000, 16384, 7)])
+@pytest.mark.parametrize("mom,wd,lr", [(False, 0.0, 0.1), (False, 0.0, -0.1), (True, 0.0, 0.1), (False, 1e-2, 0.1), (True, 1e-2, 0.05)])
+def test_decompress_sgd_step_topk(bg, oracle, n, C, keep, mom, wd, lr):
+    """Two steps with state carried; lr < 0 without momentum / weight decay takes the dense form (-0 parameters)."""
+    print("sgd topk n=%d C=%d keep=%d mom=%s wd=%g lr=%g" % (n, C, keep, mom, wd, lr), flush=True)
+    r = np.random.default_rng(n + C + keep)
+    p_o = r.standard_normal(n).astype(np.float32)
+    p_o[::13] = -0.0
+    m_o = (r.standard_normal(n) * 0.1).astype(np.float32) if mom else None
+    pg, mg = dev(p_o), (dev(m_o) if mom else None)
+    for step in range(2):
+        x = (r.standard_t(3, n) * 1e-3).astype(np.float32)
+        idx, val = oracle.compress_topk(x, None, C, keep)
+        oracle.decompress_sgd_step_topk(idx, val, n, C, keep, p_o, m_o, lr, 0.9, wd)
+        bg.bagua_decompress_sgd_step_topk(dev(idx.view(np.int16)), dev(val), n, C, keep, pg, mg, lr, 0.9, wd)
+        torch.cuda.synchronize()
+        bit_equal(pg, p_o, "param step %d" % step)
+        if mom:
+            bit_equal(mg, m_o, "momentum step %d" % step)

@@ -87,3 +87,68 @@ def test_sign_codec_decode_feeds_the_step(oracle):
     want = np.where(x >= 0, 1.0, -1.0) * np.repeat(scale.astype(np.float64), C)[:n]
     assert np.max(np.abs(step - want)) <= 1e-7          # |p0| ~ 1: the subtraction rounds at 6e-8
     assert np.all(np.sign(step) == np.where(x >= 0, 1.0, -1.0))
+
+
+# ----------------------------------------------------------------------------- the step after a top-K round
+def _topk_inputs(n, C, keep, seed):
+    r = np.random.default_rng(seed)
+    x = (r.standard_normal(n) * 1e-2).astype(np.float32)
+    return x
+
+
+def test_topk_plain_sgd_moves_only_the_kept_entries(oracle):
+    """Without momentum and weight decay the kept entries move by fl(lr * value) and every other parameter keeps its
+    bits (g = +0 there): checked against the sparse entries themselves, not against a dense decode."""
+    n, C, keep = 3 * 256 + 40, 256, 8
+    x = _topk_inputs(n, C, keep, 1)
+    idx, val = oracle.compress_topk(x, None, C, keep)
+    p0 = (np.random.default_rng(2).standard_normal(n)).astype(np.float32)
+    p0[5] = -0.0
+    p = p0.copy()
+    lr = np.float32(0.1)
+    oracle.decompress_sgd_step_topk(idx, val, n, C, keep, p, None, float(lr))
+    want = p0.copy()
+    for c in range((n + C - 1) // C):
+        for s_ in range(keep):
+            q = int(idx[c * keep + s_])
+            if q != 0xFFFF:
+                want[c * C + q] = p0[c * C + q] - lr * val[c * keep + s_]
+    assert p.tobytes() == want.tobytes()
+    assert np.count_nonzero(p != p0) <= ((n + C - 1) // C) * keep
+
+
+def test_topk_sgd_with_everything_kept_is_the_dense_step(oracle):
+    """keep = C makes the codec lossless: the step must equal the fp64 formula of SGD with weight decay and momentum on
+    the exact gradient, over three steps (state carried)."""
+    n, C = 2 * 256, 256
+    p = (np.random.default_rng(3).standard_normal(n)).astype(np.float32)
+    m = np.zeros(n, np.float32)
+    p64, m64 = p.astype(np.float64), m.astype(np.float64)
+    lr, mu, wd = 0.05, 0.9, 1e-2
+    for step in range(3):
+        g = _topk_inputs(n, C, C, 10 + step)
+        idx, val = oracle.compress_topk(g, None, C, C)
+        oracle.decompress_sgd_step_topk(idx, val, n, C, C, p, m, lr, mu, wd)
+        g64 = g.astype(np.float64) + wd * p64
+        m64 = mu * m64 + g64
+        p64 = p64 - lr * m64
+    assert np.max(np.abs(p - p64)) <= 1e-5 * np.max(np.abs(p64))
+    assert np.max(np.abs(m - m64)) <= 1e-5 * np.max(np.abs(m64)) + 1e-9
+
+
+def test_topk_sgd_momentum_decays_where_nothing_is_kept(oracle):
+    """Entries that are never selected see g = 0: their momentum decays geometrically and the parameter follows the
+    closed form p_T = p_0 - lr * m_0 * (mu + mu^2 + ... + mu^T)."""
+    n, C, keep = 256, 256, 4
+    g = np.zeros(n, np.float32)
+    g[:4] = [5.0, -6.0, 7.0, -8.0]                       # always the four kept entries
+    idx, val = oracle.compress_topk(g, None, C, keep)
+    p = np.ones(n, np.float32)
+    m = np.full(n, 0.5, np.float32)
+    lr, mu, T = 0.1, 0.5, 6
+    for _ in range(T):
+        oracle.decompress_sgd_step_topk(idx, val, n, C, keep, p, m, lr, mu, 0.0)
+    geo = sum(mu ** t for t in range(1, T + 1))
+    assert np.allclose(p[4:], 1.0 - lr * 0.5 * geo, rtol=1e-6)
+    assert np.allclose(m[4:], 0.5 * mu ** T, rtol=1e-6)
+    assert np.all(p[:4] != p[4])                          # the kept entries did move differently
