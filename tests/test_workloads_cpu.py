@@ -48,3 +48,25 @@ def test_generators_are_seeded_and_shaped():
     sig = layer_sigmas(161, seed_for(1, 0, 99))
     assert len(sig) == 161 and min(sig) >= 1e-5 and max(sig) <= 1e-2
     assert seed_for(2, 1, 7) == 2107014990000 + 20000 + 100 + 7
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is the single-GPU share of the path: --gpus N with N > 1 exits with a message that says so (checked
+    before anything touches a GPU, so this runs anywhere)."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode == 2
+    assert "single-GPU" in res.stderr and "--gpus 1" in res.stderr
+
+
+def test_bench_default_plan_names_the_largest_configurations():
+    import bench
+    primary = [name for name, layout, counts in bench.DEFAULT_PLAN if counts]
+    assert primary == ["bert_large", "bert_base_ring", "onebit"]
+    prims = [p for name in primary for p in bench.WORKLOADS[name]["prims"]]
+    assert sorted(prims) == sorted(bench.ALL_PRIMS)          # every primitive exactly once in the headline
+    assert bench.WORKLOADS["bert_large"]["k"] == 16 and bench.WORKLOADS["bert_large"]["chunk"] == 8192
+    assert bench.WORKLOADS["onebit"]["sign_chunk"] == 2048 and bench.ONEBIT_N == 1500000000
