@@ -45,13 +45,14 @@ WORKLOADS = {
     "resnet50": dict(cfg=1, k=8, chunk=4096, sign_chunk=2048, dist="normal_layer", sets=3, prims=ALL_PRIMS,
                      placement="spread", mean_gap_gib=1.0,
                      label="configs[1]: ResNet-50-shaped gradients, 25,557,032 fp32 per worker"),
-    "bert_large": dict(cfg=2, k=16, chunk=8192, sign_chunk=2048, dist="student_t3", sets=1,
+    "bert_large": dict(cfg=2, k=16, chunk=8192, sign_chunk=2048, dist="student_t3", sets=1, mean_gap_gib=1.3,
                        prims=["flatten", "compress_minmax", "drr_minmax"],
                        label="configs[2]: BERT-large-shaped gradients, 335,141,888 fp32 per worker, Student-t(3)"),
     "bert_base_ring": dict(cfg=3, k=8, chunk=4096, sign_chunk=2048, dist="normal", sets=1, prims=["ring_fp", "ring_lp"],
                            placement="spread", mean_gap_gib=3.0,
                            label="configs[3]: 8 peers x BERT-base-shaped replicas (109,482,240 fp32), base + drift"),
     "onebit": dict(cfg=4, k=8, chunk=4096, sign_chunk=2048, dist="laplace", sets=1, prims=["sign_compress", "drr_sign"],
+                   mean_gap_gib=2.0,
                    label="configs[4]: 1.5e9 fp32 per worker, Laplace(0,1e-3), 1-bit sign codec"),
     "single_bucket_x32": dict(cfg=0, k=4, chunk=4096, sign_chunk=2048, dist="normal", sets=3,
                               placement="spread", mean_gap_gib=4.0,
@@ -135,7 +136,12 @@ class Workload:
         self.placement = placement or WORKLOADS[name].get("placement", "packed")
         self._placer = None
         if self.placement == "spread":
-            self._placer = Placer(torch, SPREAD_GIB, WORKLOADS[name]["cfg"], WORKLOADS[name].get("mean_gap_gib", 1.0))
+            try:
+                self._placer = Placer(torch, SPREAD_GIB, WORKLOADS[name]["cfg"], WORKLOADS[name].get("mean_gap_gib", 1.0))
+            except RuntimeError as e:       # not enough free HBM for the reservation: say so and run packed
+                print("bench: %d GiB reservation failed (%s); placement packed" % (SPREAD_GIB, str(e).splitlines()[0]),
+                      file=sys.stderr, flush=True)
+                self.placement = "packed (the %d GiB reservation of the spread placement could not be allocated)" % SPREAD_GIB
         per_bucket = layout in ("per_bucket", "buckets")
         self.batched = layout == "buckets"
         w = WORKLOADS[name]
