@@ -730,7 +730,7 @@ def cpu_baseline(wl, torch):
     torch.cuda.synchronize()
     grad_bytes = 4.0 * elems * k * nprims
     base = {"value": round(grad_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "seconds": round(dt, 2), "gradient_bytes": grad_bytes,
+            "seconds": round(dt, 4), "gradient_bytes": grad_bytes,
             "sample": "%s (%d elements x %d workers, %.2f GiB of fp32 input), %d primitives, %.1f s on %d threads" %
                       (what, elems, k, 4.0 * elems * k / GIB, nprims, dt, threads)}
     par = dict(cnt.c)
