@@ -170,3 +170,53 @@ def test_binding_refuses_per_worker_lists_of_unequal_length(bg):
     i16 = [torch.zeros(8, dtype=torch.int16) for _ in range(3)]
     with pytest.raises(ValueError, match="val_in names 2"):
         bg.bagua_decompress_reduce_recompress_topk(i16, t[:2], 8, None, 256, 256, i16[0], t[0])
+
+
+def test_validation_of_the_batched_and_fused_entry_points_without_gpu(bg):
+    """Host-side checks of the entry points added after the first set: every call returns before anything is enqueued."""
+    lib = bg.binding.raw()
+    INVALID, ALIGN, UNSUPPORTED = 1, 2, 4
+    A, B, Cc, D, W = 0x100000, 0x200000, 0x300000, 0x400000, 0x500000
+    one = lambda v: (ctypes.c_void_p * 1)(v)
+    n1, n0 = (ctypes.c_size_t * 1)(64), (ctypes.c_size_t * 1)(0)
+    wsb = bg.bagua_batch_workspace_bytes(1, 0)
+    assert wsb > 0 and bg.bagua_batch_workspace_bytes(3, 8) > bg.bagua_batch_workspace_bytes(3, 0)
+    assert bg.bagua_batch_workspace_bytes(1, 33) == 0                                  # k out of range
+    f = lib.bagua_compress_minmax_u8_batched
+    assert f(one(A), None, n1, 1, 256, one(B), one(Cc), W, wsb - 1, None) == INVALID       # workspace too small
+    assert f(one(A), None, n1, 0, 256, one(B), one(Cc), W, wsb, None) == INVALID           # no buckets
+    assert f(one(A), None, n0, 1, 256, one(B), one(Cc), W, wsb, None) == INVALID           # empty bucket
+    assert f(one(A), None, n1, 1, 100, one(B), one(Cc), W, wsb, None) == INVALID           # bad chunk
+    assert f(one(A + 4), None, n1, 1, 256, one(B), one(Cc), W, wsb, None) == ALIGN
+    assert f(one(A), None, n1, 1, 256, one(A), one(Cc), W, wsb, None) == INVALID           # codes alias x
+    assert f(one(A), None, n1, 1, 256, one(B), one(Cc), A, wsb, None) == INVALID           # table over x
+    g = lib.bagua_sign_compress_ef_batched
+    assert g(one(A), one(None), n1, 1, 256, one(B), one(Cc), W, wsb, None) == INVALID      # residual array with a NULL entry
+    assert g(one(A), None, n1, 1, 256, one(B + 2), one(Cc), W, wsb, None) == ALIGN
+    h = lib.bagua_decompress_reduce_recompress_batched
+    wk = bg.bagua_batch_workspace_bytes(1, 1)
+    assert h(7, one(A), one(B), 1, None, n1, 1, 256, one(Cc), one(D), None, W, wk, None) == INVALID    # codec
+    assert h(0, one(A), one(B), 0, None, n1, 1, 256, one(Cc), one(D), None, W, wk, None) == INVALID    # k
+    assert h(0, one(A), one(B), 1, None, n1, 1, 256, one(A), one(D), None, W, wk, None) == INVALID     # output over input
+    assert lib.bagua_bucket_flatten_batched_run(one(A), n1, one(B), n0, 1, W, wsb, None) == INVALID     # empty bucket
+    # no-allocation flatten: limits
+    assert lib.bagua_bucket_flatten_static(None, None, None, 0, A, 67108864 + 1, None) == UNSUPPORTED
+    T = 4097
+    arr, num, off = (ctypes.c_void_p * T)(), (ctypes.c_size_t * T)(), (ctypes.c_size_t * T)()
+    assert lib.bagua_bucket_flatten_static(arr, num, off, T, A, 1 << 20, None) == UNSUPPORTED
+    assert lib.bagua_bucket_flatten_static(None, None, None, 0, A + 4, 1024, None) == ALIGN
+    # fused forms
+    assert lib.bagua_flatten_sign_compress_ef(W, 1, None, 0, 256, B, Cc, None, None) == INVALID
+    assert lib.bagua_flatten_sign_compress_ef(W, 1, None, 64, 256, B + 4, Cc, None, None) == ALIGN
+    assert lib.bagua_decompress_unflatten(5, A, B, 64, 256, W, 1, None) == INVALID
+    assert lib.bagua_decompress_unflatten(0, A, B, 64, 256, W + 8, 1, None) == ALIGN
+    assert lib.bagua_reduce_compress_sign_ef(one(A), 0, None, 64, 256, B, Cc, None) == INVALID
+    assert lib.bagua_reduce_compress_sign_ef(one(A), 1, None, 64, 256, A, Cc, None) == INVALID         # bits alias x
+    assert lib.bagua_decompress_sgd_step_topk(A, B, 64, 256, 0, Cc, None, 0.1, 0.0, 0.0, None) == INVALID   # keep = 0
+    assert lib.bagua_decompress_sgd_step_topk(A, B, 64, 256, 300, Cc, None, 0.1, 0.0, 0.0, None) == INVALID  # keep > chunk
+    assert lib.bagua_decompress_sgd_step_topk(A, B, 64, 256, 8, Cc + 4, None, 0.1, 0.0, 0.0, None) == ALIGN
+    # probes
+    assert lib.bagua_probe_read(None, 10, B, None) == INVALID
+    assert lib.bagua_probe_streams(one(A), one(B), None, 1, 1, 0, 1, 100, None) == INVALID             # n not a multiple of 256
+    three = (ctypes.c_void_p * 3)(A, Cc, D)
+    assert lib.bagua_probe_streams(three, one(B), None, 3, 1, 0, 1, 256, None) == UNSUPPORTED            # combination not offered
