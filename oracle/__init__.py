@@ -21,8 +21,12 @@ def lib():
     """Load (building if necessary) the oracle shared library."""
     global _lib
     if _lib is None:
-        path = _build.LIB
+        # BAGUA_ORACLE_LIB: a test may point this module at another build of the oracle's source
+        # (tests/test_oracle_mutants.py checks that the pins reject deliberately wrong builds).
+        path = os.environ.get("BAGUA_ORACLE_LIB") or _build.LIB
         if not os.path.exists(path):
+            if path != _build.LIB:
+                raise FileNotFoundError(path)
             _build.build()
         _lib = ctypes.CDLL(path)
         for name in ("oracle_compress_minmax_u8", "oracle_decompress_minmax_u8", "oracle_drr_minmax_u8",
