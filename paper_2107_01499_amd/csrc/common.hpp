@@ -103,6 +103,14 @@ struct MutPtrTable {
     void* p[BAGUA_MAX_WORKERS];
 };
 
+// Index of this wavefront in its workgroup, as a scalar.  The compiler cannot tell that threadIdx.x >> 6 is the same
+// in all 64 lanes and would carry every row offset and tail test derived from it through 64-bit vector arithmetic
+// and exec-mask branches; read from the first lane it lives in scalar registers.
+__device__ __forceinline__ int wave_index()
+{
+    return __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+}
+
 // ---------------------------------------------------------------- wave-level reductions
 __device__ __forceinline__ float wave_min(float v)
 {

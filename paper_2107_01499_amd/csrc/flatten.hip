@@ -179,7 +179,7 @@ k_decompress_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __re
                        const void* __restrict__ codes, const float* __restrict__ meta, size_t n, uint32_t chunk)
 {
     static_assert(kTile == 1024, "one 256-element row per wave and tile");
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = wave_index(), lane = threadIdx.x & 63;
     const size_t ntiles = (n + kTile - 1) / kTile;
     const size_t first = static_cast<size_t>(blockIdx.x) * kDecodeTiles;
 

@@ -21,7 +21,7 @@ k_flatten_compress_minmax(const TensorDesc* __restrict__ desc, const uint32_t* _
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     // the error state does not depend on the table lookups: get its loads going first
     f4 d[RPW];
@@ -69,7 +69,7 @@ k_flatten_sign_compress(const TensorDesc* __restrict__ desc, const uint32_t* __r
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     f4 d[RPW];
     if (EF) {
@@ -117,7 +117,7 @@ k_reduce_compress_minmax(PtrTable xs, int k_local, float inv_k, float* __restric
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     f4 v[RPW];
     for (int j = 0; j < k_local; ++j) {
@@ -173,7 +173,7 @@ k_reduce_compress_sign(PtrTable xs, int k_local, float inv_k, float* __restrict_
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     f4 v[RPW];
     for (int j = 0; j < k_local; ++j) {

@@ -21,7 +21,7 @@ __device__ __forceinline__ void compress_minmax_chunk(const float* __restrict__ 
 {
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     f4 v[RPW];
 #pragma unroll
@@ -95,7 +95,7 @@ __device__ __forceinline__ void drr_minmax_chunk(const SRC& src, int k, float in
 {
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     // per-worker (min, step) of this chunk: one lane per worker, so the k divisions run side by side
     if (static_cast<int>(threadIdx.x) < k) {
@@ -208,7 +208,7 @@ __global__ void __launch_bounds__(256)
 k_decompress_minmax(const uint8_t* __restrict__ codes, const float* __restrict__ minmax, size_t n,
                     uint32_t chunk, float* __restrict__ out)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;

@@ -43,7 +43,7 @@ __global__ void __launch_bounds__(256)
 k_decompress_sgd(const void* __restrict__ codes, const float* __restrict__ meta, size_t n, uint32_t chunk,
                  float* __restrict__ param, float* __restrict__ mbuf, float lr, float mu, float wd)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -85,7 +85,7 @@ k_decompress_adam(const void* __restrict__ codes, const float* __restrict__ meta
                   float* __restrict__ param, float* __restrict__ mbuf, float* __restrict__ vbuf, float lr, float beta1,
                   float omb1, float beta2, float omb2, float eps, float wd)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -153,7 +153,7 @@ k_decompress_sgd_topk(const uint16_t* __restrict__ idx, const float* __restrict_
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = wave_index(), lane = threadIdx.x & 63;
 
     // parameters (and momentum) do not depend on the decode: request them first
     f4 p[RPW], m[RPW];

@@ -12,7 +12,7 @@ __global__ void __launch_bounds__(256)
 k_probe_read(const float* __restrict__ x, size_t n, float* __restrict__ tile_sums)
 {
     __shared__ float s_part[4];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = wave_index(), lane = threadIdx.x & 63;
     const size_t e0 = (static_cast<size_t>(blockIdx.x) * 4 + wave) * kProbeRows * kRow;
     f4 v[kProbeRows];
 #pragma unroll
@@ -36,7 +36,7 @@ template <int NR, int NW, int NB>
 __global__ void __launch_bounds__(256)
 k_probe_streams(PtrTable in, MutPtrTable out, MutPtrTable bout, int seq, size_t n)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;

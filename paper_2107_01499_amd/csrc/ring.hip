@@ -24,7 +24,7 @@ template <int K>
 __global__ void __launch_bounds__(64 * kFpWaves)
 k_ring_avg_fp(PtrTable xin, MutPtrTable xout, size_t n, float third)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * kFpWaves + (threadIdx.x >> 6);
+    const size_t row = static_cast<size_t>(blockIdx.x) * kFpWaves + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -43,7 +43,7 @@ k_ring_avg_fp(PtrTable xin, MutPtrTable xout, size_t n, float third)
 __global__ void __launch_bounds__(256)
 k_ring_avg_fp_any(PtrTable xin, MutPtrTable xout, int k, size_t n, float third)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -73,7 +73,7 @@ k_ring_avg_lp(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, MutPtrTable code
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     f4 h[K][RPW];    // new public copy xhat' of every peer
     f4 own[K][RPW];  // x - xhat' of every peer
@@ -147,7 +147,7 @@ k_lp_encode(const float* __restrict__ x, float* __restrict__ xhat, size_t n, uin
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
     f4 h[RPW], d[RPW];
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
@@ -174,7 +174,7 @@ k_lp_encode(const float* __restrict__ x, float* __restrict__ xhat, size_t n, uin
 __global__ void __launch_bounds__(256)
 k_lp_mix(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, int k, size_t n, float third)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -329,7 +329,7 @@ __global__ void __launch_bounds__(256)
 k_peer_avg_fp(PeerJobs jobs, size_t n)
 {
     const int job = blockIdx.y;
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -386,7 +386,7 @@ namespace bagua {
 __global__ void __launch_bounds__(256)
 k_centralized_avg_fp(PtrTable xs, int k, float inv_k, size_t n, float* __restrict__ out)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -455,7 +455,7 @@ k_peer_avg_lp(PeerLpJobs jobs, size_t n, uint32_t chunk)
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     f4 h[2][RPW], own[2][RPW];
 #pragma unroll
@@ -513,7 +513,7 @@ __global__ void __launch_bounds__(256)
 k_peer_mix_lp(PeerMixJobs jobs, size_t n)
 {
     const int i = blockIdx.y;
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -614,7 +614,7 @@ k_lp_apply_mix(const float* __restrict__ x, const float* __restrict__ h_own, flo
                const uint8_t* __restrict__ c_right, const float* __restrict__ m_right, size_t n, uint32_t chunk,
                float third, float* __restrict__ x_out)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;

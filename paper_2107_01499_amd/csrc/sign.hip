@@ -24,7 +24,7 @@ __device__ __forceinline__ void sign_compress_chunk(const float* __restrict__ x,
 {
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     f4 v[RPW];
 #pragma unroll
@@ -112,7 +112,7 @@ __device__ __forceinline__ void drr_sign_chunk(const SRC& src, int k, float inv_
 {
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
     const int sh = 4 * (lane & 7);
 
     // Scales of this chunk: lane j fetches worker j's (one memory round trip for all workers instead of a chain
@@ -121,74 +121,143 @@ __device__ __forceinline__ void drr_sign_chunk(const SRC& src, int k, float inv_
     if (lane < k) lane_scale = src.meta(lane)[c];
 
     f4 v[RPW];
-    // Workers are summed in ascending order; the sign words of NJ workers are fetched together.
-    constexpr int NJ = BAGUA_DRR_SIGN_NJ;
-    auto accumulate = [&](int j, uint32_t (&w)[RPW]) {
-        const float sc = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(lane_scale), j));
-        const float neg = -sc;
+    constexpr int NJ = BAGUA_DRR_SIGN_NJ;   // workers whose sign words are fetched together
+    // Workers are summed in ascending order; worker 0 starts the sum (s = d_0, not 0 + d_0).
+    if (static_cast<long>(wave * RPW + RPW) * kRow <= len) {
+        // ---- every row of this wave is complete (wave-uniform; all waves of all chunks but the bucket's last):
+        // no tail tests, uniform row addresses, one shift + one bit-field insert + one add per element and worker.
+        f4 e[RPW];
+        if (EF) {
+#pragma unroll
+            for (int i = 0; i < RPW; ++i)
+                e[i] = ld_stream(reinterpret_cast<const f4*>(eps + base + static_cast<size_t>(wave * RPW + i) * kRow) + lane);
+        }
+        const uint32_t word = static_cast<uint32_t>(lane >> 3);
+        const uint32_t s0 = 31u - sh, s1 = 30u - sh, s2 = 29u - sh, s3 = 28u - sh;   // element's bit -> bit 31
+        const size_t first_word = (base >> 5) + static_cast<size_t>(wave * RPW) * (kRow / 32);
+        auto fetch = [&](int j, uint32_t (&w)[RPW]) {
+            const uint32_t* bj = static_cast<const uint32_t*>(src.code(j)) + first_word;
+#pragma unroll
+            for (int i = 0; i < RPW; ++i) w[i] = bj[i * (kRow / 32) + word];
+        };
+        auto decode = [&](int j, const uint32_t (&w)[RPW], bool first) {
+            const uint32_t sc = __builtin_amdgcn_readlane(__float_as_uint(lane_scale), j);
+            const uint32_t neg = sc ^ 0x80000000u;
+#pragma unroll
+            for (int i = 0; i < RPW; ++i) {
+                f4 d;
+                d.x = sign_select(w[i] << s0, sc, neg);
+                d.y = sign_select(w[i] << s1, sc, neg);
+                d.z = sign_select(w[i] << s2, sc, neg);
+                d.w = sign_select(w[i] << s3, sc, neg);
+                if (first) {
+                    v[i] = d;
+                } else {
+                    v[i].x = v[i].x + d.x;
+                    v[i].y = v[i].y + d.y;
+                    v[i].z = v[i].z + d.z;
+                    v[i].w = v[i].w + d.w;
+                }
+            }
+        };
+        int j = 0;
+        if (k >= NJ) {
+            uint32_t w[NJ][RPW];
+#pragma unroll
+            for (int u = 0; u < NJ; ++u) fetch(u, w[u]);
+            decode(0, w[0], true);
+#pragma unroll
+            for (int u = 1; u < NJ; ++u) decode(u, w[u], false);
+            j = NJ;
+        } else {
+            uint32_t w[RPW];
+            fetch(0, w);
+            decode(0, w, true);
+            j = 1;
+        }
+        for (; j + NJ <= k; j += NJ) {
+            uint32_t w[NJ][RPW];
+#pragma unroll
+            for (int u = 0; u < NJ; ++u) fetch(j + u, w[u]);
+#pragma unroll
+            for (int u = 0; u < NJ; ++u) decode(j + u, w[u], false);
+        }
+        for (; j < k; ++j) {
+            uint32_t w[RPW];
+            fetch(j, w);
+            decode(j, w, false);
+        }
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
-            const uint32_t nib = w[i] >> sh;
-            f4 d;
-            d.x = (nib & 1u) ? sc : neg;
-            d.y = (nib & 2u) ? sc : neg;
-            d.z = (nib & 4u) ? sc : neg;
-            d.w = (nib & 8u) ? sc : neg;
-            if (j == 0) {
-                v[i] = d;
-            } else {
-                v[i].x = v[i].x + d.x;
-                v[i].y = v[i].y + d.y;
-                v[i].z = v[i].z + d.z;
-                v[i].w = v[i].w + d.w;
+            v[i].x = v[i].x * inv_k;
+            v[i].y = v[i].y * inv_k;
+            v[i].z = v[i].z * inv_k;
+            v[i].w = v[i].w * inv_k;
+            if (EF) {
+                v[i].x = v[i].x + e[i].x;
+                v[i].y = v[i].y + e[i].y;
+                v[i].z = v[i].z + e[i].z;
+                v[i].w = v[i].w + e[i].w;
             }
         }
-    };
-    auto fetch = [&](int j, uint32_t (&w)[RPW]) {
-        const uint32_t* bj = static_cast<const uint32_t*>(src.code(j)) + (base >> 5);
+    } else {
+        // ---- a wave with a ragged or absent row (only in the last chunk of a bucket)
+        auto accumulate = [&](int j, uint32_t (&w)[RPW]) {
+            const float sc = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(lane_scale), j));
+            const float neg = -sc;
 #pragma unroll
-        for (int i = 0; i < RPW; ++i) {
-            const long off = static_cast<long>(wave * RPW + i) * kRow;
-            const long remain = len - off;
-            w[i] = 0;
-            if (static_cast<long>(lane >> 3) * 32 < remain) w[i] = bj[(off >> 5) + (lane >> 3)];
+            for (int i = 0; i < RPW; ++i) {
+                const uint32_t nib = w[i] >> sh;
+                f4 d;
+                d.x = (nib & 1u) ? sc : neg;
+                d.y = (nib & 2u) ? sc : neg;
+                d.z = (nib & 4u) ? sc : neg;
+                d.w = (nib & 8u) ? sc : neg;
+                if (j == 0) {
+                    v[i] = d;
+                } else {
+                    v[i].x = v[i].x + d.x;
+                    v[i].y = v[i].y + d.y;
+                    v[i].z = v[i].z + d.z;
+                    v[i].w = v[i].w + d.w;
+                }
+            }
+        };
+        for (int j = 0; j < k; ++j) {
+            const uint32_t* bj = static_cast<const uint32_t*>(src.code(j)) + (base >> 5);
+            uint32_t w[RPW];
+#pragma unroll
+            for (int i = 0; i < RPW; ++i) {
+                const long off = static_cast<long>(wave * RPW + i) * kRow;
+                const long remain = len - off;
+                w[i] = 0;
+                if (static_cast<long>(lane >> 3) * 32 < remain) w[i] = bj[(off >> 5) + (lane >> 3)];
+            }
+            accumulate(j, w);
         }
-    };
-    int j = 0;
-    for (; j + NJ <= k; j += NJ) {
-        uint32_t w[NJ][RPW];
-#pragma unroll
-        for (int u = 0; u < NJ; ++u) fetch(j + u, w[u]);
-#pragma unroll
-        for (int u = 0; u < NJ; ++u) accumulate(j + u, w[u]);
-    }
-    for (; j < k; ++j) {
-        uint32_t w[RPW];
-        fetch(j, w);
-        accumulate(j, w);
-    }
-#pragma unroll
-    for (int i = 0; i < RPW; ++i) {
-        const long off = static_cast<long>(wave * RPW + i) * kRow;
-        const long remain = len - off;
-        const int e = lane * 4;
-        // elements beyond the chunk must enter the |v| sum as +0.0f
-        v[i].x = (e + 0 < remain) ? v[i].x * inv_k : 0.0f;
-        v[i].y = (e + 1 < remain) ? v[i].y * inv_k : 0.0f;
-        v[i].z = (e + 2 < remain) ? v[i].z * inv_k : 0.0f;
-        v[i].w = (e + 3 < remain) ? v[i].w * inv_k : 0.0f;
-    }
-    if (EF) {
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
             const long off = static_cast<long>(wave * RPW + i) * kRow;
             const long remain = len - off;
-            if (remain > 0) {
-                const f4 d = load_row(eps + base + off, lane, remain, 0.0f);
-                v[i].x = v[i].x + d.x;
-                v[i].y = v[i].y + d.y;
-                v[i].z = v[i].z + d.z;
-                v[i].w = v[i].w + d.w;
+            const int e = lane * 4;
+            // elements beyond the chunk must enter the |v| sum as +0.0f
+            v[i].x = (e + 0 < remain) ? v[i].x * inv_k : 0.0f;
+            v[i].y = (e + 1 < remain) ? v[i].y * inv_k : 0.0f;
+            v[i].z = (e + 2 < remain) ? v[i].z * inv_k : 0.0f;
+            v[i].w = (e + 3 < remain) ? v[i].w * inv_k : 0.0f;
+        }
+        if (EF) {
+#pragma unroll
+            for (int i = 0; i < RPW; ++i) {
+                const long off = static_cast<long>(wave * RPW + i) * kRow;
+                const long remain = len - off;
+                if (remain > 0) {
+                    const f4 d = load_row(eps + base + off, lane, remain, 0.0f);
+                    v[i].x = v[i].x + d.x;
+                    v[i].y = v[i].y + d.y;
+                    v[i].z = v[i].z + d.z;
+                    v[i].w = v[i].w + d.w;
+                }
             }
         }
     }
@@ -223,7 +292,7 @@ __global__ void __launch_bounds__(256)
 k_decompress_sign(const uint32_t* __restrict__ bits, const float* __restrict__ scale, size_t n, uint32_t chunk,
                   float* __restrict__ out)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;

@@ -50,6 +50,14 @@ __device__ __forceinline__ uint32_t gather_word(uint32_t nib, int lane)
     return w;
 }
 
+// bit ? sc : -sc for a sign bit that has been shifted to bit 31 of t; the bits of t below bit 31 are arbitrary.
+// sc and -sc differ in the sign bit only, so selecting sc's bits where t is set and (-sc)'s elsewhere gives exactly
+// the two-way choice (one bit-field insert instead of test + compare + select).
+__device__ __forceinline__ float sign_select(uint32_t t, uint32_t sc_bits, uint32_t neg_bits)
+{
+    return __uint_as_float((t & sc_bits) | (~t & neg_bits));
+}
+
 // Encode the chunk held in v (absent elements must be +0.0f).  `bits` points at the word of the
 // chunk's first element; residual/out point at the chunk's first element.
 template <int RPW, bool EF, bool OUT>
@@ -66,19 +74,24 @@ __device__ __forceinline__ void sign_encode_chunk(f4 (&v)[RPW], long len, uint32
     else scale = sum / static_cast<float>(len);
     if (threadIdx.x == 0) *scale_c = scale;
     const float neg = -scale;
+    // every row of this wave complete (wave-uniform): no per-element tail tests
+    const bool full = static_cast<long>(wave * RPW + RPW) * kRow <= len;
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
         const long off = static_cast<long>(wave * RPW + i) * kRow;
         const long remain = len - off;
         if (remain <= 0) continue;
-        const int e = lane * 4;
-        const bool b0 = (v[i].x >= 0.0f) && (e + 0 < remain);
-        const bool b1 = (v[i].y >= 0.0f) && (e + 1 < remain);
-        const bool b2 = (v[i].z >= 0.0f) && (e + 2 < remain);
-        const bool b3 = (v[i].w >= 0.0f) && (e + 3 < remain);
+        bool b0 = v[i].x >= 0.0f, b1 = v[i].y >= 0.0f, b2 = v[i].z >= 0.0f, b3 = v[i].w >= 0.0f;
+        if (!full) {
+            const int e = lane * 4;
+            b0 = b0 && (e + 0 < remain);
+            b1 = b1 && (e + 1 < remain);
+            b2 = b2 && (e + 2 < remain);
+            b3 = b3 && (e + 3 < remain);
+        }
         const uint32_t nib = (b0 ? 1u : 0u) | (b1 ? 2u : 0u) | (b2 ? 4u : 0u) | (b3 ? 8u : 0u);
         const uint32_t w = gather_word(nib, lane);
-        if ((lane & 7) == 0 && static_cast<long>(lane >> 3) * 32 < remain) bits[(off >> 5) + (lane >> 3)] = w;
+        if ((lane & 7) == 0 && (full || static_cast<long>(lane >> 3) * 32 < remain)) bits[(off >> 5) + (lane >> 3)] = w;
         if (EF || OUT) {
             f4 deq;
             deq.x = b0 ? scale : neg;
@@ -91,9 +104,9 @@ __device__ __forceinline__ void sign_encode_chunk(f4 (&v)[RPW], long len, uint32
                 r.y = v[i].y - deq.y;
                 r.z = v[i].z - deq.z;
                 r.w = v[i].w - deq.w;
-                store_row(residual + off, lane, remain, r);
+                store_row(residual + off, lane, full ? kRow : remain, r);
             }
-            if (OUT) store_row(out + off, lane, remain, deq);
+            if (OUT) store_row(out + off, lane, full ? kRow : remain, deq);
         }
     }
 }

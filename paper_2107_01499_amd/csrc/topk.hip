@@ -226,7 +226,7 @@ k_compress_topk(const float* __restrict__ x, float* __restrict__ residual, size_
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
     f4 v[RPW], d[RPW];
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
@@ -267,7 +267,7 @@ k_drr_topk(PtrTable idx_in, PtrTable val_in, int k, float inv_k, uint32_t keep, 
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
     const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     // The error state of this wave's rows is requested first: it is not needed before the sparse sums are done.
     f4 e[RPW];
@@ -362,7 +362,7 @@ k_decompress_topk(const uint16_t* __restrict__ idx, const float* __restrict__ va
         if (static_cast<long>(p) < len) dense[p] = val[c * keep + t];
     }
     __syncthreads();
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = wave_index(), lane = threadIdx.x & 63;
     for (long off = static_cast<long>(wave) * kRow; off < len; off += 4 * kRow)
         store_row(out + base + off, lane, len - off, *reinterpret_cast<const f4*>(dense + off + lane * 4));
 }
