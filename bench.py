@@ -45,14 +45,15 @@ WORKLOADS = {
     "resnet50": dict(cfg=1, k=8, chunk=4096, sign_chunk=2048, dist="normal_layer", sets=3, prims=ALL_PRIMS,
                      placement="spread", mean_gap_gib=1.0,
                      label="configs[1]: ResNet-50-shaped gradients, 25,557,032 fp32 per worker"),
-    "bert_large": dict(cfg=2, k=16, chunk=8192, sign_chunk=2048, dist="student_t3", sets=1, mean_gap_gib=1.3,
+    "bert_large": dict(cfg=2, k=16, chunk=8192, sign_chunk=2048, dist="student_t3", sets=1,
+                       placement="spread", mean_gap_gib=1.3,
                        prims=["flatten", "compress_minmax", "drr_minmax"],
                        label="configs[2]: BERT-large-shaped gradients, 335,141,888 fp32 per worker, Student-t(3)"),
     "bert_base_ring": dict(cfg=3, k=8, chunk=4096, sign_chunk=2048, dist="normal", sets=1, prims=["ring_fp", "ring_lp"],
                            placement="spread", mean_gap_gib=3.0,
                            label="configs[3]: 8 peers x BERT-base-shaped replicas (109,482,240 fp32), base + drift"),
     "onebit": dict(cfg=4, k=8, chunk=4096, sign_chunk=2048, dist="laplace", sets=1, prims=["sign_compress", "drr_sign"],
-                   mean_gap_gib=2.0,
+                   placement="spread", mean_gap_gib=2.0,
                    label="configs[4]: 1.5e9 fp32 per worker, Laplace(0,1e-3), 1-bit sign codec"),
     "single_bucket_x32": dict(cfg=0, k=4, chunk=4096, sign_chunk=2048, dist="normal", sets=3,
                               placement="spread", mean_gap_gib=4.0,
@@ -109,12 +110,14 @@ class Placer:
         self.rng = random.Random(seed)
         self.mean_gap = int(mean_gap_gib * (1 << 30))
         self.bump = 0
+        self.overflow = 0       # tensors that no longer fitted into the reservation
 
     def place(self, t):
         nbytes = t.numel() * t.element_size()
         start = (self.bump + (1 << 21) - 1) >> 21 << 21
-        if start + nbytes > self.arena.numel():
-            raise RuntimeError("spread placement: the reservation of %d GiB is exhausted" % (self.arena.numel() >> 30))
+        if start + nbytes > self.arena.numel():      # reservation exhausted: this tensor stays where the allocator put it
+            self.overflow += 1
+            return t
         out = self.arena[start:start + nbytes].view(t.dtype)
         out.copy_(t)
         self.bump = start + nbytes + self.rng.randrange(0, 2 * self.mean_gap)
@@ -132,8 +135,10 @@ class Workload:
         # Where the resident buffers lie in HBM.  "spread": every buffer is placed in one large reservation with a seeded
         # pseudo-random gap after it, so the workload's buffers are scattered over SPREAD_GIB of HBM, as they are in a
         # training process whose HBM is mostly in use; "packed": plain allocations, back to back in a fresh process.
-        # The two big workloads fill 75-110 GB by themselves and are left to the allocator.
-        self.placement = placement or WORKLOADS[name].get("placement", "packed")
+        # Every flat block of the default run is spread (also the two big ones: the buffers one server-step launch
+        # streams, k code arrays + error state + output, lie within 14 GB of each other when packed); the layout of
+        # separately allocated buckets is what the allocator makes of it.
+        self.placement = placement or ("packed" if layout == "buckets" else WORKLOADS[name].get("placement", "packed"))
         self._placer = None
         if self.placement == "spread":
             try:
@@ -377,17 +382,30 @@ class Workload:
                "compress_topk": U * k, "drr_topk": U, "decompress_unflatten": U * k, "flatten_sign_compress": U * k}
         return {p: per[p] for p in self.prims}
 
+    @staticmethod
+    def _rpw_worker(chunk):
+        """Rows per wave the library picks for an unbatched worker-side launch (pick_rpw_worker in csrc/common.hpp)."""
+        rows = chunk // 256
+        rpw = 1 if 6 <= rows <= 8 else 2
+        while rpw < 8 and (rows + rpw - 1) // rpw > 16:
+            rpw *= 2
+        return rpw
+
+    def placement_note(self):
+        over = self._placer.overflow if self._placer is not None else 0
+        return self.placement + (" (%d tensors did not fit into the reservation and lie where the allocator put them)" % over if over else "")
+
     def kernel_name(self, p):
         if self.batched and p in ("flatten", "compress_minmax", "drr_minmax", "sign_compress", "drr_sign"):
             return {"flatten": "k_flatten_batched", "compress_minmax": "k_compress_minmax_batched<2,true>",
                     "drr_minmax": "k_drr_minmax_batched<4,true,true>", "sign_compress": "k_sign_compress_batched<2,true>",
                     "drr_sign": "k_drr_sign_batched<2,true,true>"}[p]
         return {"flatten": "k_flatten", "flatten_compress": "k_flatten_compress_minmax<2,true,%s>" %
-                ("true" if "sign_compress" in self.prims else "false"), "compress_minmax": "k_compress_minmax<2,true>",
+                ("true" if "sign_compress" in self.prims else "false"), "compress_minmax": "k_compress_minmax<%d,true>" % self._rpw_worker(self.C),
                 "drr_minmax": "k_drr_minmax<4,true,true>", "ring_fp": "k_ring_avg_fp<%d>" % self.k,
-                "ring_lp": "k_ring_avg_lp<%d,2>" % self.k, "sign_compress": "k_sign_compress<2,true,false>",
+                "ring_lp": "k_ring_avg_lp<%d,2>" % self.k, "sign_compress": "k_sign_compress<%d,true,false>" % self._rpw_worker(self.SC),
                 "drr_sign": "k_drr_sign<2,true,true>", "sgd_step": "k_decompress_sgd<0,true,false>",
-                "adam_step": "k_decompress_adam<0,false,false>", "momentum_sign": "k_sign_compress<2,true,true>",
+                "adam_step": "k_decompress_adam<0,false,false>", "momentum_sign": "k_sign_compress<%d,true,true>" % self._rpw_worker(self.SC),
                 "adam_frozen_step": "k_decompress_adam<1,true,false>",
                 "peer_fp": "k_peer_avg_fp", "peer_lp": "k_peer_avg_lp<2>", "lp_encode": "k_lp_encode<2>", "lp_apply_mix": "k_lp_apply_mix<true,true,false>", "reduce_compress": "k_reduce_compress_minmax<2,true>",
                 "compress_topk": "k_compress_topk<4,true>", "drr_topk": "k_drr_topk<4,true,true>",
@@ -871,7 +889,7 @@ def run_block(torch, bg, args, name, layout, only, extras):
     block = {"workload": "%s; %d buckets, %d padded elements per worker, %d simulated workers, chunk %d (sign codec %d); "
                          "primitives per step: %s" % (wl.w["label"], len(wl.units) if layout != "flat" else max(1, len(wl.buckets)),
                                                       wl.n_elems, wl.k, wl.C, wl.SC, ", ".join(prims)),
-             "launch": launch, "placement": wl.placement, "ms_per_step": round(wall * 1e3 / args.steps, 4), "gpu_ms_per_step": round(gpu_ms / args.steps, 4),
+             "launch": launch, "placement": wl.placement_note(), "ms_per_step": round(wall * 1e3 / args.steps, 4), "gpu_ms_per_step": round(gpu_ms / args.steps, 4),
              "per_primitive": per_prim, "roofline": roof}
     if name == "single_bucket_x32":
         block["single_instance_latency_us"] = single_instance_latency(torch, bg, wl)

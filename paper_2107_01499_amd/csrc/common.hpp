@@ -244,9 +244,28 @@ inline int pick_rpw(int rows, int preferred)
     return rpw;
 }
 
+// Worker-side kernels (compress with error feedback, both codecs), one launch over one contiguous buffer: two rows
+// per wave stream fastest, except for chunks of 6 to 8 rows (1536..2048 elements), where that gives a workgroup of
+// three or four waves -- measured slowest at every chunk size -- and one row per wave (six to eight waves) is
+// 1-4 % faster.  Not used by the batched launches: there every wave first looks up its bucket, and with half the
+// bytes per wave that latency is no longer hidden (11 % slower).
+inline int pick_rpw_worker(int rows, int preferred)
+{
+    return pick_rpw(rows, (preferred == 2 && rows >= 6 && rows <= 8) ? 1 : preferred);
+}
+
 // Expands `stmt` with a constexpr RPW equal to the runtime value rpw (2, 4 or 8).
 #define BAGUA_DISPATCH_RPW(rpw, stmt)                    \
     switch (rpw) {                                        \
+        case 2: { constexpr int RPW = 2; stmt; } break;  \
+        case 4: { constexpr int RPW = 4; stmt; } break;  \
+        default: { constexpr int RPW = 8; stmt; } break; \
+    }
+
+// The same for the worker-side kernels, which also come with one row per wave.
+#define BAGUA_DISPATCH_RPW_WORKER(rpw, stmt)             \
+    switch (rpw) {                                        \
+        case 1: { constexpr int RPW = 1; stmt; } break;  \
         case 2: { constexpr int RPW = 2; stmt; } break;  \
         case 4: { constexpr int RPW = 4; stmt; } break;  \
         default: { constexpr int RPW = 8; stmt; } break; \

@@ -229,15 +229,15 @@ int launch_compress_minmax(const float* x, float* residual, size_t n, size_t chu
                            float* minmax, hipStream_t stream)
 {
     const int rows = static_cast<int>(chunk / kRow);
-    const int rpw = pick_rpw(rows, BAGUA_RPW_COMPRESS);
+    const int rpw = pick_rpw_worker(rows, BAGUA_RPW_COMPRESS);
     dim3 grid(static_cast<unsigned>(num_chunks(n, chunk))), block(64 * ((rows + rpw - 1) / rpw));
     const uint32_t ch = static_cast<uint32_t>(chunk);
     if (residual) {
-        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_compress_minmax<RPW, true>), grid, block, 0, stream, x,
-                                                   residual, n, ch, codes, minmax))
+        BAGUA_DISPATCH_RPW_WORKER(rpw, hipLaunchKernelGGL((k_compress_minmax<RPW, true>), grid, block, 0, stream, x,
+                                                          residual, n, ch, codes, minmax))
     } else {
-        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_compress_minmax<RPW, false>), grid, block, 0, stream, x,
-                                                   residual, n, ch, codes, minmax))
+        BAGUA_DISPATCH_RPW_WORKER(rpw, hipLaunchKernelGGL((k_compress_minmax<RPW, false>), grid, block, 0, stream, x,
+                                                          residual, n, ch, codes, minmax))
     }
     return launch_status();
 }

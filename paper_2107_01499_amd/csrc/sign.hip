@@ -123,22 +123,29 @@ __device__ __forceinline__ void drr_sign_chunk(const SRC& src, int k, float inv_
     f4 v[RPW];
     constexpr int NJ = BAGUA_DRR_SIGN_NJ;   // workers whose sign words are fetched together
     // Workers are summed in ascending order; worker 0 starts the sum (s = d_0, not 0 + d_0).
-    if (static_cast<long>(wave * RPW + RPW) * kRow <= len) {
-        // ---- every row of this wave is complete (wave-uniform; all waves of all chunks but the bucket's last):
-        // no tail tests, uniform row addresses, one shift + one bit-field insert + one add per element and worker.
+    // The one row of a bucket's last chunk that is cut short (if any) is the only one that needs per-element tail
+    // tests; a wave that does not own it sees complete rows and, past the chunk's end, absent ones.
+    const int rows = static_cast<int>(len / kRow);   // complete rows of this chunk
+    const int ragged_row = (len % kRow) ? rows : -1;
+    if (rows > 0 && (ragged_row < wave * RPW || ragged_row >= wave * RPW + RPW)) {
+        // ---- complete (or absent) rows only, wave-uniform: no tail tests, uniform row addresses, one shift + one
+        // three-input bit operation + one add per element and worker.  An absent row re-reads row 0 of the chunk
+        // (complete, since rows > 0) and is cleared afterwards.
+        int row_of[RPW];
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) row_of[i] = (wave * RPW + i < rows) ? wave * RPW + i : 0;
         f4 e[RPW];
         if (EF) {
 #pragma unroll
             for (int i = 0; i < RPW; ++i)
-                e[i] = ld_stream(reinterpret_cast<const f4*>(eps + base + static_cast<size_t>(wave * RPW + i) * kRow) + lane);
+                e[i] = ld_stream(reinterpret_cast<const f4*>(eps + base + static_cast<size_t>(row_of[i]) * kRow) + lane);
         }
         const uint32_t word = static_cast<uint32_t>(lane >> 3);
         const uint32_t s0 = 31u - sh, s1 = 30u - sh, s2 = 29u - sh, s3 = 28u - sh;   // element's bit -> bit 31
-        const size_t first_word = (base >> 5) + static_cast<size_t>(wave * RPW) * (kRow / 32);
         auto fetch = [&](int j, uint32_t (&w)[RPW]) {
-            const uint32_t* bj = static_cast<const uint32_t*>(src.code(j)) + first_word;
+            const uint32_t* bj = static_cast<const uint32_t*>(src.code(j)) + (base >> 5);
 #pragma unroll
-            for (int i = 0; i < RPW; ++i) w[i] = bj[i * (kRow / 32) + word];
+            for (int i = 0; i < RPW; ++i) w[i] = bj[row_of[i] * (kRow / 32) + word];
         };
         auto decode = [&](int j, const uint32_t (&w)[RPW], bool first) {
             const uint32_t sc = __builtin_amdgcn_readlane(__float_as_uint(lane_scale), j);
@@ -199,9 +206,10 @@ __device__ __forceinline__ void drr_sign_chunk(const SRC& src, int k, float inv_
                 v[i].z = v[i].z + e[i].z;
                 v[i].w = v[i].w + e[i].w;
             }
+            if (wave * RPW + i >= rows) v[i] = f4{0.f, 0.f, 0.f, 0.f};   // absent row: +0 in the |v| sum, nothing stored
         }
     } else {
-        // ---- a wave with a ragged or absent row (only in the last chunk of a bucket)
+        // ---- the wave that owns the ragged row of a bucket's last chunk
         auto accumulate = [&](int j, uint32_t (&w)[RPW]) {
             const float sc = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(lane_scale), j));
             const float neg = -sc;
@@ -316,11 +324,11 @@ struct SignGeometry {
     size_t lds;
     int rpw;
 };
-static SignGeometry sign_geometry(size_t n, size_t chunk, int preferred)
+static SignGeometry sign_geometry(size_t n, size_t chunk, int preferred, bool worker_side)
 {
     SignGeometry g;
     const int rows = static_cast<int>(chunk / kRow);
-    g.rpw = pick_rpw(rows, preferred);
+    g.rpw = worker_side ? pick_rpw_worker(rows, preferred) : pick_rpw(rows, preferred);
     const int waves = (rows + g.rpw - 1) / g.rpw;
     g.grid = dim3(static_cast<unsigned>(num_chunks(n, chunk)));
     g.block = dim3(64 * waves);
@@ -331,13 +339,13 @@ static SignGeometry sign_geometry(size_t n, size_t chunk, int preferred)
 int launch_sign_compress(const float* x, float* residual, size_t n, size_t chunk, uint32_t* bits, float* scale,
                          hipStream_t stream)
 {
-    const SignGeometry g = sign_geometry(n, chunk, BAGUA_RPW_SIGN);
+    const SignGeometry g = sign_geometry(n, chunk, BAGUA_RPW_SIGN, true);
     const uint32_t ch = static_cast<uint32_t>(chunk);
     if (residual) {
-        BAGUA_DISPATCH_RPW(g.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, true>), g.grid, g.block, g.lds, stream, x,
+        BAGUA_DISPATCH_RPW_WORKER(g.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, true>), g.grid, g.block, g.lds, stream, x,
                                                      residual, n, ch, bits, scale, nullptr, 0.0f, 0.0f))
     } else {
-        BAGUA_DISPATCH_RPW(g.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, false>), g.grid, g.block, g.lds, stream, x,
+        BAGUA_DISPATCH_RPW_WORKER(g.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, false>), g.grid, g.block, g.lds, stream, x,
                                                      residual, n, ch, bits, scale, nullptr, 0.0f, 0.0f))
     }
     return launch_status();
@@ -351,7 +359,7 @@ int launch_drr_sign(const void* const* bits_in, const float* const* scale_in, in
         bt.p[j] = bits_in[j];
         st.p[j] = scale_in[j];
     }
-    const SignGeometry g = sign_geometry(n, chunk, BAGUA_RPW_DRR_SIGN);
+    const SignGeometry g = sign_geometry(n, chunk, BAGUA_RPW_DRR_SIGN, false);
     const float inv_k = 1.0f / static_cast<float>(k);
     const uint32_t ch = static_cast<uint32_t>(chunk);
 #define BAGUA_DRR(EFv, OUTv)                                                                                      \
@@ -369,7 +377,7 @@ int launch_drr_sign_batched(const void* workspace, size_t B, int k, size_t total
                             bool with_out, hipStream_t stream)
 {
     const BatchView bv = batch_view(workspace, B, 5 + 2 * static_cast<size_t>(k));
-    SignGeometry g = sign_geometry(chunk, chunk, BAGUA_RPW_DRR_SIGN);
+    SignGeometry g = sign_geometry(chunk, chunk, BAGUA_RPW_DRR_SIGN, false);
     g.grid = dim3(static_cast<unsigned>(total_chunks));
     const float inv_k = 1.0f / static_cast<float>(k);
     const uint32_t ch = static_cast<uint32_t>(chunk);
@@ -427,14 +435,14 @@ extern "C" int bagua_momentum_sign_compress_ef(const float* g, const float* m, f
     if (!aligned16(g) || !aligned16(m) || !aligned16(residual) || !aligned16(bits) || !aligned4(scale))
         return BAGUA_ERR_ALIGNMENT;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const SignGeometry geo = sign_geometry(n, chunk, BAGUA_RPW_SIGN);
+    const SignGeometry geo = sign_geometry(n, chunk, BAGUA_RPW_SIGN, true);
     const uint32_t ch = static_cast<uint32_t>(chunk);
     const float omb1 = 1.0f - beta1;
     if (residual) {
-        BAGUA_DISPATCH_RPW(geo.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, true, true>), geo.grid, geo.block, geo.lds,
+        BAGUA_DISPATCH_RPW_WORKER(geo.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, true, true>), geo.grid, geo.block, geo.lds,
                                                        s, g, residual, n, ch, bits, scale, m, beta1, omb1))
     } else {
-        BAGUA_DISPATCH_RPW(geo.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, false, true>), geo.grid, geo.block, geo.lds,
+        BAGUA_DISPATCH_RPW_WORKER(geo.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, false, true>), geo.grid, geo.block, geo.lds,
                                                        s, g, residual, n, ch, bits, scale, m, beta1, omb1))
     }
     return launch_status();
@@ -479,7 +487,7 @@ extern "C" int bagua_sign_compress_ef_batched(const float* const* x, float* cons
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (batch_upload(table.data(), table.size(), static_cast<uint64_t*>(workspace), s) != BAGUA_OK) return BAGUA_ERR_LAUNCH;
     const BatchView bv = batch_view(workspace, B, ew);
-    SignGeometry g = sign_geometry(chunk, chunk, BAGUA_RPW_SIGN);
+    SignGeometry g = sign_geometry(chunk, chunk, BAGUA_RPW_SIGN, false);
     g.grid = dim3(static_cast<unsigned>(total));
     const uint32_t ch = static_cast<uint32_t>(chunk);
     if (ef) {

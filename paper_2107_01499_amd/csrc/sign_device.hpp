@@ -74,13 +74,12 @@ __device__ __forceinline__ void sign_encode_chunk(f4 (&v)[RPW], long len, uint32
     else scale = sum / static_cast<float>(len);
     if (threadIdx.x == 0) *scale_c = scale;
     const float neg = -scale;
-    // every row of this wave complete (wave-uniform): no per-element tail tests
-    const bool full = static_cast<long>(wave * RPW + RPW) * kRow <= len;
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
         const long off = static_cast<long>(wave * RPW + i) * kRow;
         const long remain = len - off;
         if (remain <= 0) continue;
+        const bool full = remain >= kRow;   // wave-uniform: a complete row needs no per-element tail tests
         bool b0 = v[i].x >= 0.0f, b1 = v[i].y >= 0.0f, b2 = v[i].z >= 0.0f, b3 = v[i].w >= 0.0f;
         if (!full) {
             const int e = lane * 4;
