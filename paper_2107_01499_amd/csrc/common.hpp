@@ -135,7 +135,7 @@ __device__ __forceinline__ float wave_butterfly_sum(float v)
 // ---------------------------------------------------------------- row accessors with ragged tails
 // `remain` = number of valid elements counted from the start of the row (wave-uniform, may be <= 0
 // for an absent row or >= 256 for a full one).  Absent elements read as `fill`.
-__device__ __forceinline__ f4 load_row(const float* __restrict__ row, int lane, long remain, float fill)
+__device__ __forceinline__ f4 load_row(const float* __restrict__ row, int lane, int remain, float fill)
 {
     f4 r;
     if (remain >= kRow) {
@@ -149,7 +149,7 @@ __device__ __forceinline__ f4 load_row(const float* __restrict__ row, int lane, 
     }
     return r;
 }
-__device__ __forceinline__ void store_row(float* __restrict__ row, int lane, long remain, f4 v)
+__device__ __forceinline__ void store_row(float* __restrict__ row, int lane, int remain, f4 v)
 {
     if (remain >= kRow) {
         st_stream(reinterpret_cast<f4*>(row) + lane, v);
@@ -162,7 +162,7 @@ __device__ __forceinline__ void store_row(float* __restrict__ row, int lane, lon
     }
 }
 // Four u8 codes per lane, little-endian in one dword.
-__device__ __forceinline__ uint32_t load_codes_row(const uint8_t* __restrict__ row, int lane, long remain)
+__device__ __forceinline__ uint32_t load_codes_row(const uint8_t* __restrict__ row, int lane, int remain)
 {
     if (remain >= kRow) return ld_stream(reinterpret_cast<const uint32_t*>(row) + lane);
     uint32_t w = 0;
@@ -172,7 +172,7 @@ __device__ __forceinline__ uint32_t load_codes_row(const uint8_t* __restrict__ r
         if (e + t < remain) w |= static_cast<uint32_t>(row[e + t]) << (8 * t);
     return w;
 }
-__device__ __forceinline__ void store_codes_row(uint8_t* __restrict__ row, int lane, long remain, uint32_t w)
+__device__ __forceinline__ void store_codes_row(uint8_t* __restrict__ row, int lane, int remain, uint32_t w)
 {
     if (remain >= kRow) {
         st_stream(reinterpret_cast<uint32_t*>(row) + lane, w);

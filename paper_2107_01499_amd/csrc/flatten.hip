@@ -192,7 +192,7 @@ k_decompress_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __re
         w[i] = 0;
         m0[i] = m1[i] = 0.0f;
         if (e0 >= n) continue;
-        const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+        const int remain = static_cast<int>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
         const size_t c = e0 / chunk;                            // a row never straddles chunks
         if (CODEC == 0) {
             m0[i] = meta[2 * c];
@@ -200,7 +200,7 @@ k_decompress_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __re
             w[i] = load_codes_row(static_cast<const uint8_t*>(codes) + e0, lane, remain);
         } else {
             m0[i] = meta[c];
-            if (static_cast<long>(lane >> 3) * 32 < remain) w[i] = static_cast<const uint32_t*>(codes)[(e0 >> 5) + (lane >> 3)];
+            if (static_cast<int>(lane >> 3) * 32 < remain) w[i] = static_cast<const uint32_t*>(codes)[(e0 >> 5) + (lane >> 3)];
         }
     }
     // 2. the table: almost every tile lies inside one tensor, whose base pointer is then uniform

@@ -54,7 +54,7 @@ inline FlattenPlanView plan_view(const void* workspace, size_t T)
 // straight from the layer tensors: lane l receives elements e0+4l .. e0+4l+3; elements beyond
 // `remain` or not covered by a tensor read as +0.0f.
 __device__ __forceinline__ f4 gather_row(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile_first,
-                                         uint32_t T, size_t e0, int lane, long remain)
+                                         uint32_t T, size_t e0, int lane, int remain)
 {
     const size_t tile = e0 / kTile;
     uint32_t lo = tile_first[tile];

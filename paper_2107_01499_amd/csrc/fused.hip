@@ -20,7 +20,7 @@ k_flatten_compress_minmax(const TensorDesc* __restrict__ desc, const uint32_t* _
     __shared__ float s_red[2 * kMaxWaves];
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
-    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
     const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     // the error state does not depend on the table lookups: get its loads going first
@@ -28,8 +28,8 @@ k_flatten_compress_minmax(const TensorDesc* __restrict__ desc, const uint32_t* _
     if (EF) {
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
-            const long off = static_cast<long>(wave * RPW + i) * kRow;
-            const long remain = len - off;
+            const int off = static_cast<int>(wave * RPW + i) * kRow;
+            const int remain = len - off;
             d[i] = f4{0.f, 0.f, 0.f, 0.f};
             if (remain > 0) d[i] = load_row(residual + base + off, lane, remain, 0.0f);
         }
@@ -37,8 +37,8 @@ k_flatten_compress_minmax(const TensorDesc* __restrict__ desc, const uint32_t* _
     f4 v[RPW];
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
-        const long off = static_cast<long>(wave * RPW + i) * kRow;
-        const long remain = len - off;
+        const int off = static_cast<int>(wave * RPW + i) * kRow;
+        const int remain = len - off;
         v[i] = f4{0.f, 0.f, 0.f, 0.f};
         if (remain > 0) {
             v[i] = gather_row(desc, tile_first, T, base + off, lane, remain);
@@ -68,15 +68,15 @@ k_flatten_sign_compress(const TensorDesc* __restrict__ desc, const uint32_t* __r
     extern __shared__ float s_q[];
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
-    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
     const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     f4 d[RPW];
     if (EF) {
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
-            const long off = static_cast<long>(wave * RPW + i) * kRow;
-            const long remain = len - off;
+            const int off = static_cast<int>(wave * RPW + i) * kRow;
+            const int remain = len - off;
             d[i] = f4{0.f, 0.f, 0.f, 0.f};
             if (remain > 0) d[i] = load_row(residual + base + off, lane, remain, 0.0f);
         }
@@ -84,8 +84,8 @@ k_flatten_sign_compress(const TensorDesc* __restrict__ desc, const uint32_t* __r
     f4 v[RPW];
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
-        const long off = static_cast<long>(wave * RPW + i) * kRow;
-        const long remain = len - off;
+        const int off = static_cast<int>(wave * RPW + i) * kRow;
+        const int remain = len - off;
         v[i] = f4{0.f, 0.f, 0.f, 0.f};
         if (remain > 0) {
             v[i] = gather_row(desc, tile_first, T, base + off, lane, remain);
@@ -116,7 +116,7 @@ k_reduce_compress_minmax(PtrTable xs, int k_local, float inv_k, float* __restric
     __shared__ float s_red[2 * kMaxWaves];
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
-    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
     const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     f4 v[RPW];
@@ -124,8 +124,8 @@ k_reduce_compress_minmax(PtrTable xs, int k_local, float inv_k, float* __restric
         const float* xj = static_cast<const float*>(xs.p[j]) + base;
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
-            const long off = static_cast<long>(wave * RPW + i) * kRow;
-            const long remain = len - off;
+            const int off = static_cast<int>(wave * RPW + i) * kRow;
+            const int remain = len - off;
             f4 d = f4{0.f, 0.f, 0.f, 0.f};
             if (remain > 0) d = load_row(xj + off, lane, remain, 0.0f);
             if (j == 0) {
@@ -148,8 +148,8 @@ k_reduce_compress_minmax(PtrTable xs, int k_local, float inv_k, float* __restric
     if (EF) {
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
-            const long off = static_cast<long>(wave * RPW + i) * kRow;
-            const long remain = len - off;
+            const int off = static_cast<int>(wave * RPW + i) * kRow;
+            const int remain = len - off;
             if (remain > 0) {
                 const f4 d = load_row(residual + base + off, lane, remain, 0.0f);
                 v[i].x = v[i].x + d.x;
@@ -172,7 +172,7 @@ k_reduce_compress_sign(PtrTable xs, int k_local, float inv_k, float* __restrict_
     extern __shared__ float s_q[];
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
-    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
     const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     f4 v[RPW];
@@ -180,8 +180,8 @@ k_reduce_compress_sign(PtrTable xs, int k_local, float inv_k, float* __restrict_
         const float* xj = static_cast<const float*>(xs.p[j]) + base;
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
-            const long off = static_cast<long>(wave * RPW + i) * kRow;
-            const long remain = len - off;
+            const int off = static_cast<int>(wave * RPW + i) * kRow;
+            const int remain = len - off;
             f4 d = f4{0.f, 0.f, 0.f, 0.f};
             if (remain > 0) d = load_row(xj + off, lane, remain, 0.0f);
             if (j == 0) {
@@ -204,8 +204,8 @@ k_reduce_compress_sign(PtrTable xs, int k_local, float inv_k, float* __restrict_
     if (EF) {
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
-            const long off = static_cast<long>(wave * RPW + i) * kRow;
-            const long remain = len - off;
+            const int off = static_cast<int>(wave * RPW + i) * kRow;
+            const int remain = len - off;
             if (remain > 0) {
                 const f4 d = load_row(residual + base + off, lane, remain, 0.0f);
                 v[i].x = v[i].x + d.x;

@@ -20,22 +20,22 @@ __device__ __forceinline__ void compress_minmax_chunk(const float* __restrict__ 
                                                       float* __restrict__ minmax, size_t c, float* s_red)
 {
     const size_t base = c * static_cast<size_t>(chunk);
-    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
     const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     f4 v[RPW];
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
-        const long off = static_cast<long>(wave * RPW + i) * kRow;
-        const long remain = len - off;
+        const int off = static_cast<int>(wave * RPW + i) * kRow;
+        const int remain = len - off;
         v[i] = f4{0.f, 0.f, 0.f, 0.f};
         if (remain > 0) v[i] = load_row(x + base + off, lane, remain, 0.0f);
     }
     if (EF) {
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
-            const long off = static_cast<long>(wave * RPW + i) * kRow;
-            const long remain = len - off;
+            const int off = static_cast<int>(wave * RPW + i) * kRow;
+            const int remain = len - off;
             if (remain > 0) {
                 const f4 d = load_row(residual + base + off, lane, remain, 0.0f);
                 v[i].x = v[i].x + d.x;
@@ -94,7 +94,7 @@ __device__ __forceinline__ void drr_minmax_chunk(const SRC& src, int k, float in
                                                  float* s_red, float* s_mn, float* s_step)
 {
     const size_t base = c * static_cast<size_t>(chunk);
-    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
     const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     // per-worker (min, step) of this chunk: one lane per worker, so the k divisions run side by side
@@ -133,8 +133,8 @@ __device__ __forceinline__ void drr_minmax_chunk(const SRC& src, int k, float in
         const uint8_t* cj = static_cast<const uint8_t*>(src.code(j)) + base;
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
-            const long off = static_cast<long>(wave * RPW + i) * kRow;
-            const long remain = len - off;
+            const int off = static_cast<int>(wave * RPW + i) * kRow;
+            const int remain = len - off;
             w[i] = 0;
             if (remain > 0) w[i] = load_codes_row(cj + off, lane, remain);
         }
@@ -162,8 +162,8 @@ __device__ __forceinline__ void drr_minmax_chunk(const SRC& src, int k, float in
     if (EF) {
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
-            const long off = static_cast<long>(wave * RPW + i) * kRow;
-            const long remain = len - off;
+            const int off = static_cast<int>(wave * RPW + i) * kRow;
+            const int remain = len - off;
             if (remain > 0) {
                 const f4 d = load_row(eps + base + off, lane, remain, 0.0f);
                 v[i].x = v[i].x + d.x;
@@ -214,7 +214,7 @@ k_decompress_minmax(const uint8_t* __restrict__ codes, const float* __restrict__
     if (e0 >= n) return;
     const size_t c = e0 / chunk;
     const float mn = minmax[2 * c], step = minmax_step(mn, minmax[2 * c + 1]);
-    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const int remain = static_cast<int>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
     const uint32_t w = load_codes_row(codes + e0, lane, remain);
     f4 d;
     d.x = mn + byte_to_float(w, 0) * step;

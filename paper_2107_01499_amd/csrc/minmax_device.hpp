@@ -11,13 +11,13 @@ namespace bagua {
 // Phase 1: this wave's (min, max) over its valid elements (`len` = valid elements of the chunk; rows
 // beyond it are ignored); with several waves the pair is also parked in s_red (2*kMaxWaves floats).
 template <int RPW>
-__device__ __forceinline__ void chunk_minmax_partial(const f4 (&v)[RPW], long len, int wave, int lane, int nwaves,
+__device__ __forceinline__ void chunk_minmax_partial(const f4 (&v)[RPW], int len, int wave, int lane, int nwaves,
                                                      float* s_red, float& mn_out, float& mx_out)
 {
     float mn = INFINITY, mx = -INFINITY;
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
-        const long remain = len - static_cast<long>(wave * RPW + i) * kRow;
+        const int remain = len - static_cast<int>(wave * RPW + i) * kRow;
         if (remain >= kRow) {
             mn = fminf(fminf(mn, v[i].x), fminf(v[i].y, fminf(v[i].z, v[i].w)));
             mx = fmaxf(fmaxf(mx, v[i].x), fmaxf(v[i].y, fmaxf(v[i].z, v[i].w)));
@@ -51,7 +51,7 @@ __device__ __forceinline__ void chunk_minmax_finish(int nwaves, const float* s_r
     mx = mx + 0.0f;
 }
 template <int RPW>
-__device__ __forceinline__ void chunk_minmax(const f4 (&v)[RPW], long len, int wave, int lane, int nwaves,
+__device__ __forceinline__ void chunk_minmax(const f4 (&v)[RPW], int len, int wave, int lane, int nwaves,
                                              float* s_red, float& mn_out, float& mx_out)
 {
     chunk_minmax_partial<RPW>(v, len, wave, lane, nwaves, s_red, mn_out, mx_out);
@@ -82,7 +82,7 @@ __device__ __forceinline__ uint32_t pack_codes(float q0, float q1, float q2, flo
 }
 
 template <int RPW, bool EF, bool OUT, bool DEQ_BACK>
-__device__ __forceinline__ void minmax_quantise_chunk(f4 (&v)[RPW], float mn, float mx, long len, int wave, int lane,
+__device__ __forceinline__ void minmax_quantise_chunk(f4 (&v)[RPW], float mn, float mx, int len, int wave, int lane,
                                                       float* __restrict__ residual, uint8_t* __restrict__ codes,
                                                       float* __restrict__ minmax_c, float* __restrict__ out);
 
@@ -90,7 +90,7 @@ __device__ __forceinline__ void minmax_quantise_chunk(f4 (&v)[RPW], float mn, fl
 // (v - decode) and the decoded values.  Pointers are already offset to the start of the chunk.
 // If DEQ_BACK, v is overwritten with the decoded values (used by the decentralised LP kernel).
 template <int RPW, bool EF, bool OUT, bool DEQ_BACK = false>
-__device__ __forceinline__ void minmax_encode_chunk(f4 (&v)[RPW], long len, int wave, int lane, int nwaves,
+__device__ __forceinline__ void minmax_encode_chunk(f4 (&v)[RPW], int len, int wave, int lane, int nwaves,
                                                     float* __restrict__ residual, uint8_t* __restrict__ codes,
                                                     float* __restrict__ minmax_c, float* __restrict__ out,
                                                     float* s_red)
@@ -103,7 +103,7 @@ __device__ __forceinline__ void minmax_encode_chunk(f4 (&v)[RPW], long len, int 
 // Quantise the chunk held in v given its canonical (min, max): writes codes, (min,max), and optionally the
 // updated residual (v - decode) and the decoded values; if DEQ_BACK, v is overwritten with the decoded values.
 template <int RPW, bool EF, bool OUT, bool DEQ_BACK>
-__device__ __forceinline__ void minmax_quantise_chunk(f4 (&v)[RPW], float mn, float mx, long len, int wave, int lane,
+__device__ __forceinline__ void minmax_quantise_chunk(f4 (&v)[RPW], float mn, float mx, int len, int wave, int lane,
                                                       float* __restrict__ residual, uint8_t* __restrict__ codes,
                                                       float* __restrict__ minmax_c, float* __restrict__ out)
 {
@@ -116,8 +116,8 @@ __device__ __forceinline__ void minmax_quantise_chunk(f4 (&v)[RPW], float mn, fl
     }
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
-        const long off = static_cast<long>(wave * RPW + i) * kRow;
-        const long remain = len - off;
+        const int off = static_cast<int>(wave * RPW + i) * kRow;
+        const int remain = len - off;
         if (remain <= 0) continue;
         const float q0 = quantise(v[i].x, mn, inv), q1 = quantise(v[i].y, mn, inv);
         const float q2 = quantise(v[i].z, mn, inv), q3 = quantise(v[i].w, mn, inv);

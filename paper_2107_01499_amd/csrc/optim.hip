@@ -13,7 +13,7 @@ namespace bagua {
 // Decoded values of the row starting at element e0 (chunk c): four per lane.
 template <int CODEC>
 __device__ __forceinline__ f4 decode_row(const void* __restrict__ codes, const float* __restrict__ meta, size_t e0,
-                                         size_t c, int lane, long remain)
+                                         size_t c, int lane, int remain)
 {
     f4 g;
     if (CODEC == BAGUA_CODEC_MINMAX_U8) {
@@ -27,7 +27,7 @@ __device__ __forceinline__ f4 decode_row(const void* __restrict__ codes, const f
         const float sc = meta[c];
         const float neg = -sc;
         uint32_t w = 0;
-        if (static_cast<long>(lane >> 3) * 32 < remain) w = static_cast<const uint32_t*>(codes)[(e0 >> 5) + (lane >> 3)];
+        if (static_cast<int>(lane >> 3) * 32 < remain) w = static_cast<const uint32_t*>(codes)[(e0 >> 5) + (lane >> 3)];
         const uint32_t nib = w >> (4 * (lane & 7));
         g.x = (nib & 1u) ? sc : neg;
         g.y = (nib & 2u) ? sc : neg;
@@ -48,7 +48,7 @@ k_decompress_sgd(const void* __restrict__ codes, const float* __restrict__ meta,
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
     const size_t c = e0 / chunk;
-    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const int remain = static_cast<int>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
 
     f4 p = load_row(param + e0, lane, remain, 0.0f);
     f4 m = f4{0.f, 0.f, 0.f, 0.f};
@@ -90,7 +90,7 @@ k_decompress_adam(const void* __restrict__ codes, const float* __restrict__ meta
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
     const size_t c = e0 / chunk;
-    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const int remain = static_cast<int>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
 
     f4 p = load_row(param + e0, lane, remain, 0.0f);
     f4 v = load_row(vbuf + e0, lane, remain, 1.0f);
@@ -152,15 +152,15 @@ k_decompress_sgd_topk(const uint16_t* __restrict__ idx, const float* __restrict_
     extern __shared__ float s_g[];   // chunk floats
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
-    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
     const int wave = wave_index(), lane = threadIdx.x & 63;
 
     // parameters (and momentum) do not depend on the decode: request them first
     f4 p[RPW], m[RPW];
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
-        const long off = static_cast<long>(wave * RPW + i) * kRow;
-        const long remain = len - off;
+        const int off = static_cast<int>(wave * RPW + i) * kRow;
+        const int remain = len - off;
         p[i] = f4{0.f, 0.f, 0.f, 0.f};
         m[i] = p[i];
         if (remain > 0) {
@@ -178,8 +178,8 @@ k_decompress_sgd_topk(const uint16_t* __restrict__ idx, const float* __restrict_
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
-        const long off = static_cast<long>(wave * RPW + i) * kRow;
-        const long remain = len - off;
+        const int off = static_cast<int>(wave * RPW + i) * kRow;
+        const int remain = len - off;
         if (remain <= 0) continue;
         f4 g = *reinterpret_cast<const f4*>(s_g + off + lane * 4);
         if (WD) {

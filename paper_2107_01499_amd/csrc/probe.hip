@@ -19,7 +19,7 @@ k_probe_read(const float* __restrict__ x, size_t n, float* __restrict__ tile_sum
     for (int r = 0; r < kProbeRows; ++r) {
         const size_t e = e0 + static_cast<size_t>(r) * kRow;
         v[r] = f4{0.f, 0.f, 0.f, 0.f};
-        if (e < n) v[r] = load_row(x + e, lane, static_cast<long>((n - e < static_cast<size_t>(kRow)) ? (n - e) : kRow), 0.0f);
+        if (e < n) v[r] = load_row(x + e, lane, static_cast<int>((n - e < static_cast<size_t>(kRow)) ? (n - e) : kRow), 0.0f);
     }
     float s = 0.0f;
 #pragma unroll

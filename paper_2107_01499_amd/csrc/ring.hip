@@ -28,7 +28,7 @@ k_ring_avg_fp(PtrTable xin, MutPtrTable xout, size_t n, float third)
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
-    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const int remain = static_cast<int>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
     f4 x[K];
 #pragma unroll
     for (int i = 0; i < K; ++i) x[i] = load_row(static_cast<const float*>(xin.p[i]) + e0, lane, remain, 0.0f);
@@ -47,7 +47,7 @@ k_ring_avg_fp_any(PtrTable xin, MutPtrTable xout, int k, size_t n, float third)
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
-    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const int remain = static_cast<int>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
     const f4 first = load_row(static_cast<const float*>(xin.p[0]) + e0, lane, remain, 0.0f);
     f4 prev = load_row(static_cast<const float*>(xin.p[k - 1]) + e0, lane, remain, 0.0f);
     f4 cur = first;
@@ -72,7 +72,7 @@ k_ring_avg_lp(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, MutPtrTable code
     __shared__ float s_red[K][2 * kMaxWaves];
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
-    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
     const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     f4 h[K][RPW];    // new public copy xhat' of every peer
@@ -80,8 +80,8 @@ k_ring_avg_lp(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, MutPtrTable code
     auto finalize = [&](int p) {
 #pragma unroll
         for (int r = 0; r < RPW; ++r) {
-            const long off = static_cast<long>(wave * RPW + r) * kRow;
-            const long remain = len - off;
+            const int off = static_cast<int>(wave * RPW + r) * kRow;
+            const int remain = len - off;
             const f4 s = add4(add4(h[(p + K - 1) % K][r], h[p][r]), h[(p + 1) % K][r]);
             const f4 o = add4(mul4(s, third), own[p][r]);
             if (remain > 0) store_row(static_cast<float*>(xout.p[p]) + base + off, lane, remain, o);
@@ -99,8 +99,8 @@ k_ring_avg_lp(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, MutPtrTable code
             if (i >= K) continue;
 #pragma unroll
             for (int r = 0; r < RPW; ++r) {
-                const long off = static_cast<long>(wave * RPW + r) * kRow;
-                const long remain = len - off;
+                const int off = static_cast<int>(wave * RPW + r) * kRow;
+                const int remain = len - off;
                 x[gi][r] = f4{0.f, 0.f, 0.f, 0.f};
                 h[i][r] = f4{0.f, 0.f, 0.f, 0.f};
                 if (remain > 0) {
@@ -123,8 +123,8 @@ k_ring_avg_lp(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, MutPtrTable code
                                                            static_cast<float*>(minmax.p[i]) + 2 * c, nullptr);
 #pragma unroll
             for (int r = 0; r < RPW; ++r) {
-                const long off = static_cast<long>(wave * RPW + r) * kRow;
-                const long remain = len - off;
+                const int off = static_cast<int>(wave * RPW + r) * kRow;
+                const int remain = len - off;
                 h[i][r] = add4(h[i][r], d[gi][r]);
                 own[i][r] = sub4(x[gi][r], h[i][r]);
                 if (remain > 0) store_row(static_cast<float*>(xhat.p[i]) + base + off, lane, remain, h[i][r]);
@@ -146,13 +146,13 @@ k_lp_encode(const float* __restrict__ x, float* __restrict__ xhat, size_t n, uin
     __shared__ float s_red[2 * kMaxWaves];
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
-    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
     const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
     f4 h[RPW], d[RPW];
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
-        const long off = static_cast<long>(wave * RPW + r) * kRow;
-        const long remain = len - off;
+        const int off = static_cast<int>(wave * RPW + r) * kRow;
+        const int remain = len - off;
         h[r] = f4{0.f, 0.f, 0.f, 0.f};
         d[r] = h[r];
         if (remain > 0) {
@@ -164,8 +164,8 @@ k_lp_encode(const float* __restrict__ x, float* __restrict__ xhat, size_t n, uin
                                                  minmax + 2 * c, nullptr, s_red);
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
-        const long off = static_cast<long>(wave * RPW + r) * kRow;
-        const long remain = len - off;
+        const int off = static_cast<int>(wave * RPW + r) * kRow;
+        const int remain = len - off;
         if (remain > 0) store_row(xhat + base + off, lane, remain, add4(h[r], d[r]));
     }
 }
@@ -178,7 +178,7 @@ k_lp_mix(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, int k, size_t n, floa
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
-    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const int remain = static_cast<int>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
     const f4 first = load_row(static_cast<const float*>(xhat.p[0]) + e0, lane, remain, 0.0f);
     f4 prev = load_row(static_cast<const float*>(xhat.p[k - 1]) + e0, lane, remain, 0.0f);
     f4 cur = first;
@@ -333,7 +333,7 @@ k_peer_avg_fp(PeerJobs jobs, size_t n)
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
-    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const int remain = static_cast<int>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
     const f4 xa = load_row(jobs.a[job] + e0, lane, remain, 0.0f);
     const f4 xb = load_row(jobs.b[job] + e0, lane, remain, 0.0f);
     const f4 o = mul4(add4(xa, xb), 0.5f);
@@ -390,7 +390,7 @@ k_centralized_avg_fp(PtrTable xs, int k, float inv_k, size_t n, float* __restric
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
-    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const int remain = static_cast<int>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
     f4 s = load_row(static_cast<const float*>(xs.p[0]) + e0, lane, remain, 0.0f);
     int j = 1;
     for (; j + 4 <= k; j += 4) {
@@ -454,7 +454,7 @@ k_peer_avg_lp(PeerLpJobs jobs, size_t n, uint32_t chunk)
     const int job = blockIdx.y;
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
-    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
     const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     f4 h[2][RPW], own[2][RPW];
@@ -466,8 +466,8 @@ k_peer_avg_lp(PeerLpJobs jobs, size_t n, uint32_t chunk)
         float mn, mx;
 #pragma unroll
         for (int r = 0; r < RPW; ++r) {
-            const long off = static_cast<long>(wave * RPW + r) * kRow;
-            const long remain = len - off;
+            const int off = static_cast<int>(wave * RPW + r) * kRow;
+            const int remain = len - off;
             x[r] = f4{0.f, 0.f, 0.f, 0.f};
             h[sd][r] = x[r];
             if (remain > 0) {
@@ -483,8 +483,8 @@ k_peer_avg_lp(PeerLpJobs jobs, size_t n, uint32_t chunk)
                                                        jobs.minmax[sd][job] + 2 * c, nullptr);
 #pragma unroll
         for (int r = 0; r < RPW; ++r) {
-            const long off = static_cast<long>(wave * RPW + r) * kRow;
-            const long remain = len - off;
+            const int off = static_cast<int>(wave * RPW + r) * kRow;
+            const int remain = len - off;
             h[sd][r] = add4(h[sd][r], d[r]);
             own[sd][r] = sub4(x[r], h[sd][r]);
             if (remain > 0) store_row(hp + base + off, lane, remain, h[sd][r]);
@@ -492,8 +492,8 @@ k_peer_avg_lp(PeerLpJobs jobs, size_t n, uint32_t chunk)
     }
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
-        const long off = static_cast<long>(wave * RPW + r) * kRow;
-        const long remain = len - off;
+        const int off = static_cast<int>(wave * RPW + r) * kRow;
+        const int remain = len - off;
         if (remain <= 0) continue;
         const f4 avg = mul4(add4(h[0][r], h[1][r]), 0.5f);
         store_row(jobs.out[0][job] + base + off, lane, remain, add4(avg, own[0][r]));
@@ -517,7 +517,7 @@ k_peer_mix_lp(PeerMixJobs jobs, size_t n)
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
-    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const int remain = static_cast<int>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
     const f4 a = load_row(jobs.hat_own[i] + e0, lane, remain, 0.0f);
     const f4 b = load_row(jobs.hat_peer[i] + e0, lane, remain, 0.0f);
     const f4 xi = load_row(jobs.x[i] + e0, lane, remain, 0.0f);
@@ -619,7 +619,7 @@ k_lp_apply_mix(const float* __restrict__ x, const float* __restrict__ h_own, flo
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
     const size_t c = e0 / chunk;
-    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const int remain = static_cast<int>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
     const f4 xi = load_row(x + e0, lane, remain, 0.0f);
     const f4 ho = load_row(h_own + e0, lane, remain, 0.0f);
     auto advanced = [&](float* h, const uint8_t* codes, const float* mm, bool apply) {

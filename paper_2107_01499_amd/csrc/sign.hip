@@ -23,22 +23,22 @@ __device__ __forceinline__ void sign_compress_chunk(const float* __restrict__ x,
                                                     float beta1, float omb1, size_t c, float* s_q)
 {
     const size_t base = c * static_cast<size_t>(chunk);
-    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
     const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     f4 v[RPW];
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
-        const long off = static_cast<long>(wave * RPW + i) * kRow;
-        const long remain = len - off;
+        const int off = static_cast<int>(wave * RPW + i) * kRow;
+        const int remain = len - off;
         v[i] = f4{0.f, 0.f, 0.f, 0.f};
         if (remain > 0) v[i] = load_row(x + base + off, lane, remain, 0.0f);
     }
     if (MOM) {
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
-            const long off = static_cast<long>(wave * RPW + i) * kRow;
-            const long remain = len - off;
+            const int off = static_cast<int>(wave * RPW + i) * kRow;
+            const int remain = len - off;
             if (remain > 0) {
                 const f4 m = load_row(mom + base + off, lane, remain, 0.0f);
                 v[i].x = beta1 * m.x + omb1 * v[i].x;
@@ -51,8 +51,8 @@ __device__ __forceinline__ void sign_compress_chunk(const float* __restrict__ x,
     if (EF) {
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
-            const long off = static_cast<long>(wave * RPW + i) * kRow;
-            const long remain = len - off;
+            const int off = static_cast<int>(wave * RPW + i) * kRow;
+            const int remain = len - off;
             if (remain > 0) {
                 const f4 d = load_row(residual + base + off, lane, remain, 0.0f);
                 v[i].x = v[i].x + d.x;
@@ -111,7 +111,7 @@ __device__ __forceinline__ void drr_sign_chunk(const SRC& src, int k, float inv_
                                                float* s_q)
 {
     const size_t base = c * static_cast<size_t>(chunk);
-    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
     const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
     const int sh = 4 * (lane & 7);
 
@@ -236,17 +236,17 @@ __device__ __forceinline__ void drr_sign_chunk(const SRC& src, int k, float inv_
             uint32_t w[RPW];
 #pragma unroll
             for (int i = 0; i < RPW; ++i) {
-                const long off = static_cast<long>(wave * RPW + i) * kRow;
-                const long remain = len - off;
+                const int off = static_cast<int>(wave * RPW + i) * kRow;
+                const int remain = len - off;
                 w[i] = 0;
-                if (static_cast<long>(lane >> 3) * 32 < remain) w[i] = bj[(off >> 5) + (lane >> 3)];
+                if (static_cast<int>(lane >> 3) * 32 < remain) w[i] = bj[(off >> 5) + (lane >> 3)];
             }
             accumulate(j, w);
         }
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
-            const long off = static_cast<long>(wave * RPW + i) * kRow;
-            const long remain = len - off;
+            const int off = static_cast<int>(wave * RPW + i) * kRow;
+            const int remain = len - off;
             const int e = lane * 4;
             // elements beyond the chunk must enter the |v| sum as +0.0f
             v[i].x = (e + 0 < remain) ? v[i].x * inv_k : 0.0f;
@@ -257,8 +257,8 @@ __device__ __forceinline__ void drr_sign_chunk(const SRC& src, int k, float inv_
         if (EF) {
 #pragma unroll
             for (int i = 0; i < RPW; ++i) {
-                const long off = static_cast<long>(wave * RPW + i) * kRow;
-                const long remain = len - off;
+                const int off = static_cast<int>(wave * RPW + i) * kRow;
+                const int remain = len - off;
                 if (remain > 0) {
                     const f4 d = load_row(eps + base + off, lane, remain, 0.0f);
                     v[i].x = v[i].x + d.x;
@@ -306,9 +306,9 @@ k_decompress_sign(const uint32_t* __restrict__ bits, const float* __restrict__ s
     if (e0 >= n) return;
     const float sc = scale[e0 / chunk];
     const float neg = -sc;
-    const long remain = static_cast<long>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
+    const int remain = static_cast<int>((n - e0 < static_cast<size_t>(kRow)) ? (n - e0) : kRow);
     uint32_t w = 0;
-    if (static_cast<long>(lane >> 3) * 32 < remain) w = bits[(e0 >> 5) + (lane >> 3)];
+    if (static_cast<int>(lane >> 3) * 32 < remain) w = bits[(e0 >> 5) + (lane >> 3)];
     const uint32_t nib = w >> (4 * (lane & 7));
     f4 d;
     d.x = (nib & 1u) ? sc : neg;

@@ -61,7 +61,7 @@ __device__ __forceinline__ float sign_select(uint32_t t, uint32_t sc_bits, uint3
 // Encode the chunk held in v (absent elements must be +0.0f).  `bits` points at the word of the
 // chunk's first element; residual/out point at the chunk's first element.
 template <int RPW, bool EF, bool OUT>
-__device__ __forceinline__ void sign_encode_chunk(f4 (&v)[RPW], long len, uint32_t chunk, int wave, int lane,
+__device__ __forceinline__ void sign_encode_chunk(f4 (&v)[RPW], int len, uint32_t chunk, int wave, int lane,
                                                   int nwaves, float* __restrict__ residual,
                                                   uint32_t* __restrict__ bits, float* __restrict__ scale_c,
                                                   float* __restrict__ out, float* s_q)
@@ -70,14 +70,14 @@ __device__ __forceinline__ void sign_encode_chunk(f4 (&v)[RPW], long len, uint32
     const float sum = chunk_abs_sum<RPW>(v, rows, wave, lane, nwaves, s_q);
     const bool pow2 = (chunk & (chunk - 1)) == 0;
     float scale;
-    if (len == static_cast<long>(chunk) && pow2) scale = sum * (1.0f / static_cast<float>(chunk));
+    if (len == static_cast<int>(chunk) && pow2) scale = sum * (1.0f / static_cast<float>(chunk));
     else scale = sum / static_cast<float>(len);
     if (threadIdx.x == 0) *scale_c = scale;
     const float neg = -scale;
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
-        const long off = static_cast<long>(wave * RPW + i) * kRow;
-        const long remain = len - off;
+        const int off = static_cast<int>(wave * RPW + i) * kRow;
+        const int remain = len - off;
         if (remain <= 0) continue;
         const bool full = remain >= kRow;   // wave-uniform: a complete row needs no per-element tail tests
         bool b0 = v[i].x >= 0.0f, b1 = v[i].y >= 0.0f, b2 = v[i].z >= 0.0f, b3 = v[i].w >= 0.0f;
@@ -90,7 +90,7 @@ __device__ __forceinline__ void sign_encode_chunk(f4 (&v)[RPW], long len, uint32
         }
         const uint32_t nib = (b0 ? 1u : 0u) | (b1 ? 2u : 0u) | (b2 ? 4u : 0u) | (b3 ? 8u : 0u);
         const uint32_t w = gather_word(nib, lane);
-        if ((lane & 7) == 0 && (full || static_cast<long>(lane >> 3) * 32 < remain)) bits[(off >> 5) + (lane >> 3)] = w;
+        if ((lane & 7) == 0 && (full || static_cast<int>(lane >> 3) * 32 < remain)) bits[(off >> 5) + (lane >> 3)] = w;
         if (EF || OUT) {
             f4 deq;
             deq.x = b0 ? scale : neg;

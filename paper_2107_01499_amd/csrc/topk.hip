@@ -87,7 +87,7 @@ __device__ __forceinline__ void topk_clear_lds(uint32_t* smem)
 // output slots, residual/out at the chunk's first element (nullptr = not wanted).
 // smem: kTopkLdsWords words of LDS, cleared by topk_clear_lds (all waves must have passed its barrier).
 template <int RPW>
-__device__ __forceinline__ void topk_encode_chunk(const f4 (&v)[RPW], long len, uint32_t keep, int wave, int lane,
+__device__ __forceinline__ void topk_encode_chunk(const f4 (&v)[RPW], int len, uint32_t keep, int wave, int lane,
                                                   int nwaves, float* __restrict__ residual,
                                                   uint16_t* __restrict__ idx_c, float* __restrict__ val_c,
                                                   float* __restrict__ out, uint32_t* smem)
@@ -95,13 +95,13 @@ __device__ __forceinline__ void topk_encode_chunk(const f4 (&v)[RPW], long len, 
     uint32_t* copies = smem;                  // [256][kCopies], first pass only
     uint32_t* hist = smem + 256 * kCopies;    // [4][256]
     uint32_t* tot = hist + 4 * 256;
-    const uint32_t keff = (static_cast<long>(keep) < len) ? keep : static_cast<uint32_t>(len);
+    const uint32_t keff = (static_cast<int>(keep) < len) ? keep : static_cast<uint32_t>(len);
 
     uint32_t key[RPW][4];
     bool valid[RPW][4];
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
-        const long e0 = static_cast<long>(wave * RPW + i) * kRow + lane * 4;
+        const int e0 = static_cast<int>(wave * RPW + i) * kRow + lane * 4;
         const float el[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -185,10 +185,10 @@ __device__ __forceinline__ void topk_encode_chunk(const f4 (&v)[RPW], long len, 
     // ---- emit
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
-        const long off = static_cast<long>(wave * RPW + i) * kRow;
-        const long remain = len - off;
+        const int off = static_cast<int>(wave * RPW + i) * kRow;
+        const int remain = len - off;
         if (remain <= 0) continue;
-        const long e0 = off + lane * 4;
+        const int e0 = off + lane * 4;
         const float el[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
         float res[4], dec[4];
         uint32_t before = before_wave + lane_excl[i];
@@ -225,13 +225,13 @@ k_compress_topk(const float* __restrict__ x, float* __restrict__ residual, size_
     extern __shared__ uint32_t smem[];
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
-    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
     const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
     f4 v[RPW], d[RPW];
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
-        const long off = static_cast<long>(wave * RPW + i) * kRow;
-        const long remain = len - off;
+        const int off = static_cast<int>(wave * RPW + i) * kRow;
+        const int remain = len - off;
         v[i] = f4{0.f, 0.f, 0.f, 0.f};
         d[i] = v[i];
         if (remain > 0) {
@@ -266,7 +266,7 @@ k_drr_topk(PtrTable idx_in, PtrTable val_in, int k, float inv_k, uint32_t keep, 
     float* dense = reinterpret_cast<float*>(smem);
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
-    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
     const int wave = wave_index(), lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
 
     // The error state of this wave's rows is requested first: it is not needed before the sparse sums are done.
@@ -274,8 +274,8 @@ k_drr_topk(PtrTable idx_in, PtrTable val_in, int k, float inv_k, uint32_t keep, 
     if (EF) {
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
-            const long off = static_cast<long>(wave * RPW + i) * kRow;
-            const long remain = len - off;
+            const int off = static_cast<int>(wave * RPW + i) * kRow;
+            const int remain = len - off;
             e[i] = f4{0.f, 0.f, 0.f, 0.f};
             if (remain > 0) e[i] = load_row(eps + base + off, lane, remain, 0.0f);
         }
@@ -302,7 +302,7 @@ k_drr_topk(PtrTable idx_in, PtrTable val_in, int k, float inv_k, uint32_t keep, 
             for (int g = 0; g < G; ++g) {
                 if (j0 + g >= k) break;
                 __syncthreads();  // the previous worker's sums (or the clear) are complete
-                if (static_cast<long>(p[g]) < len) dense[p[g]] = dense[p[g]] + a[g];
+                if (static_cast<int>(p[g]) < len) dense[p[g]] = dense[p[g]] + a[g];
             }
         }
         __syncthreads();
@@ -313,7 +313,7 @@ k_drr_topk(PtrTable idx_in, PtrTable val_in, int k, float inv_k, uint32_t keep, 
             const float* vj = static_cast<const float*>(val_in.p[j]) + c * keep;
             for (uint32_t t = threadIdx.x; t < keep; t += blockDim.x) {
                 const uint32_t p = ij[t];
-                if (static_cast<long>(p) < len) dense[p] = dense[p] + vj[t];
+                if (static_cast<int>(p) < len) dense[p] = dense[p] + vj[t];
             }
             __syncthreads();
         }
@@ -321,8 +321,8 @@ k_drr_topk(PtrTable idx_in, PtrTable val_in, int k, float inv_k, uint32_t keep, 
     f4 v[RPW];
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
-        const long off = static_cast<long>(wave * RPW + i) * kRow;
-        const long remain = len - off;
+        const int off = static_cast<int>(wave * RPW + i) * kRow;
+        const int remain = len - off;
         v[i] = f4{0.f, 0.f, 0.f, 0.f};
         if (remain > 0) {
             const f4 a = *reinterpret_cast<const f4*>(dense + off + lane * 4);
@@ -354,16 +354,16 @@ k_decompress_topk(const uint16_t* __restrict__ idx, const float* __restrict__ va
     float* dense = reinterpret_cast<float*>(smem);
     const size_t c = blockIdx.x;
     const size_t base = c * static_cast<size_t>(chunk);
-    const long len = static_cast<long>((n - base < chunk) ? (n - base) : chunk);
+    const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
     for (uint32_t t = threadIdx.x; t < chunk; t += blockDim.x) dense[t] = 0.0f;
     __syncthreads();
     for (uint32_t t = threadIdx.x; t < keep; t += blockDim.x) {
         const uint32_t p = idx[c * keep + t];
-        if (static_cast<long>(p) < len) dense[p] = val[c * keep + t];
+        if (static_cast<int>(p) < len) dense[p] = val[c * keep + t];
     }
     __syncthreads();
     const int wave = wave_index(), lane = threadIdx.x & 63;
-    for (long off = static_cast<long>(wave) * kRow; off < len; off += 4 * kRow)
+    for (int off = static_cast<int>(wave) * kRow; off < len; off += 4 * kRow)
         store_row(out + base + off, lane, len - off, *reinterpret_cast<const f4*>(dense + off + lane * 4));
 }
 
