@@ -787,7 +787,12 @@ def ceilings(torch, bg):
     sums = torch.empty(n // 4096, device="cuda")
     t = time_fn(torch, lambda i: bg.bagua_probe_read(bufs[i % 2][i % 2], sums), 20)
     out["read_kernel_GBps"] = round(4.0 * n / t / 1e9, 1)
-    del bufs, plans
+    # the worker-side kernels' traffic without their arithmetic or their barrier: x and the error state read, the error
+    # state written in place, one byte stream written (13 B per element; the sign codec writes 1/8 B instead of 1)
+    codes = torch.empty(n, dtype=torch.uint8, device="cuda")
+    t = time_fn(torch, lambda i: bg.bagua_probe_streams([bufs[i % 2][0], bufs[i % 2][1]], [bufs[i % 2][1]], [codes], 2, 1, 1, 1, n), 20)
+    out["mix_2R1W1B_in_place_GBps"] = round(13.0 * n / t / 1e9, 1)
+    del bufs, plans, codes
     m = 32 * 1024 * 1024          # 8 peers x (x, xhat, out fp32 + codes u8) = 3.6 GB per launch
     for tag in ("packed", "spread"):
         pl = Placer(torch, SPREAD_GIB, 7, 3.0) if tag == "spread" else None
