@@ -86,8 +86,10 @@ __device__ __forceinline__ void topk_clear_lds(uint32_t* smem)
 // Encode the chunk held in v (absent elements are ignored).  idx_c/val_c point at the chunk's `keep`
 // output slots, residual/out at the chunk's first element (nullptr = not wanted).
 // smem: kTopkLdsWords words of LDS, cleared by topk_clear_lds (all waves must have passed its barrier).
-template <int RPW>
-__device__ __forceinline__ void topk_encode_chunk(const f4 (&v)[RPW], int len, uint32_t keep, int wave, int lane,
+// FULL: every row of every wave of the workgroup is complete (len == RPW * 256 * nwaves), so no element needs a validity
+// test.
+template <int RPW, bool FULL>
+__device__ __forceinline__ void topk_encode_rows(const f4 (&v)[RPW], int len, uint32_t keep, int wave, int lane,
                                                   int nwaves, float* __restrict__ residual,
                                                   uint16_t* __restrict__ idx_c, float* __restrict__ val_c,
                                                   float* __restrict__ out, uint32_t* smem)
@@ -106,7 +108,7 @@ __device__ __forceinline__ void topk_encode_chunk(const f4 (&v)[RPW], int len, u
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             key[i][e] = mag_key(el[e]);
-            valid[i][e] = e0 + e < len;
+            valid[i][e] = FULL || e0 + e < len;
         }
     }
 
@@ -214,6 +216,17 @@ __device__ __forceinline__ void topk_encode_chunk(const f4 (&v)[RPW], int len, u
         idx_c[t] = 0xFFFFu;
         val_c[t] = 0.0f;
     }
+}
+
+template <int RPW>
+__device__ __forceinline__ void topk_encode_chunk(const f4 (&v)[RPW], int len, uint32_t keep, int wave, int lane,
+                                                  int nwaves, float* __restrict__ residual,
+                                                  uint16_t* __restrict__ idx_c, float* __restrict__ val_c,
+                                                  float* __restrict__ out, uint32_t* smem)
+{
+    // the same branch for every wave of the workgroup (the barriers inside are reached by all of them either way)
+    if (len == RPW * kRow * nwaves) topk_encode_rows<RPW, true>(v, len, keep, wave, lane, nwaves, residual, idx_c, val_c, out, smem);
+    else topk_encode_rows<RPW, false>(v, len, keep, wave, lane, nwaves, residual, idx_c, val_c, out, smem);
 }
 
 // ------------------------------------------------------------------------------------------ worker side
