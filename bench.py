@@ -897,7 +897,7 @@ def run_block(torch, bg, args, name, layout, only, extras):
              "launch": launch, "placement": wl.placement_note(), "ms_per_step": round(wall * 1e3 / args.steps, 4), "gpu_ms_per_step": round(gpu_ms / args.steps, 4),
              "per_primitive": per_prim, "roofline": roof}
     if name == "single_bucket_x32":
-        block["single_instance_latency_us"] = single_instance_latency(torch, bg, wl)
+        block["single_instance_latency_us"] = single_instance_latency(torch, bg, wl)      # three ways of launching it
     if not args.no_cpu_baseline and layout == "flat" and only is None and not args.fused_flatten and not extras:
         block["cpu_baseline"], block["parity"] = cpu_baseline(wl, torch)
     if "flatten" in prims and layout == "flat" and only is None:      # last: it overwrites the resident buckets
@@ -942,7 +942,8 @@ def misaligned_flatten(torch, bg, wl, reps=5):
 
 def single_instance_latency(torch, bg, wl):
     """configs[0] as it stands (one 1,048,576-element bucket, 4 workers): 4 compress launches + the server step, data
-    resident in the caches; microseconds per pass, launch gaps included."""
+    resident in the caches; microseconds per pass, launch gaps included: launched call by call, with the compressions
+    batched into one launch, and as a HIP graph."""
     n, k, C = 1048576, wl.k, wl.C
     nc = n // C
     xs = [wl.bucket[j][0][:n] for j in range(k)]
@@ -956,7 +957,29 @@ def single_instance_latency(torch, bg, wl):
         for j in range(k):
             bg.bagua_compress_minmax_u8(xs[j], delta[j], C, codes[j], mm[j])
         bg.bagua_decompress_reduce_recompress(bg.CODEC_MINMAX_U8, codes, mm, eps, n, C, c2, m2, out)
-    return round(time_fn(torch, once, 50) * 1e6, 2)
+    res = {"launch_per_worker": round(time_fn(torch, once, 50) * 1e6, 2)}
+
+    # the k workers' compressions as ONE batched launch (plus the launch that writes its bucket table)
+    ws = torch.empty(bg.bagua_batch_workspace_bytes(k, 0), dtype=torch.uint8, device="cuda")
+
+    def once_batched(i):
+        bg.bagua_compress_minmax_u8_batched(xs, delta, C, codes, mm, ws)
+        bg.bagua_decompress_reduce_recompress(bg.CODEC_MINMAX_U8, codes, mm, eps, n, C, c2, m2, out)
+    res["batched_compress"] = round(time_fn(torch, once_batched, 50) * 1e6, 2)
+
+    # the per-worker launches recorded into a HIP graph: one graph launch per pass
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        once(0)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        once(0)
+    res["hip_graph_of_the_per_worker_launches"] = round(time_fn(torch, lambda i: g.replay(), 50) * 1e6, 2)
+    del g
+    return res
 
 
 def _verify_setup():
