@@ -15,9 +15,16 @@
 
 namespace bagua {
 
-// One tile (kTile elements) of one bucket; `tile` = index of the tile in its bucket.
+// Workgroups are single wavefronts: a plain copy streams 3-4 % faster that way than with four waves per workgroup
+// (a wave's slot is free again as soon as its own stores are out).  kTileWaves of them share one tile of the table.
+constexpr int kTileWaves = kTile / kRow;
+static_assert(kTile == 1024 && kTileWaves == 4, "the tile body below moves 16 bytes per lane of 256 lanes");
+
+// One tile (kTile elements) of one bucket; `tile` = index of the tile in its bucket, `tid` = 0..255 = this lane's
+// place among the tile's 256 lanes.
 __device__ __forceinline__ void flatten_tile(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile_first,
-                                             uint32_t T, float* __restrict__ bucket, size_t bucket_numel, size_t tile)
+                                             uint32_t T, float* __restrict__ bucket, size_t bucket_numel, size_t tile,
+                                             uint32_t tid)
 {
     const size_t tile0 = tile * kTile;
     const uint32_t lo0 = tile_first[tile], hi0 = tile_first[tile + 1];
@@ -33,23 +40,23 @@ __device__ __forceinline__ void flatten_tile(const TensorDesc* __restrict__ desc
                 f4* b4 = reinterpret_cast<f4*>(bucket + tile0);
                 f4 v[kTile / 1024];
 #pragma unroll
-                for (int g = 0; g < kTile / 1024; ++g) v[g] = ld_stream(s4 + g * 256 + threadIdx.x);
+                for (int g = 0; g < kTile / 1024; ++g) v[g] = ld_stream(s4 + g * 256 + tid);
 #pragma unroll
-                for (int g = 0; g < kTile / 1024; ++g) st_stream(b4 + g * 256 + threadIdx.x, v[g]);
+                for (int g = 0; g < kTile / 1024; ++g) st_stream(b4 + g * 256 + tid, v[g]);
                 return;
             }
             // same, source only 4-byte aligned: 128-bit loads with 4-byte declared alignment, aligned 128-bit stores
             f4* b4 = reinterpret_cast<f4*>(bucket + tile0);
 #pragma unroll
             for (int g = 0; g < kTile / 1024; ++g)
-                st_stream(b4 + g * 256 + threadIdx.x, load_row_shifted(s + g * 1024, threadIdx.x));
+                st_stream(b4 + g * 256 + tid, load_row_shifted(s + g * 1024, tid));
             return;
         }
     }
 
 #pragma unroll
     for (int g = 0; g < kTile / 1024; ++g) {
-        const size_t e = tile0 + static_cast<size_t>(g) * 1024 + threadIdx.x * 4;
+        const size_t e = tile0 + static_cast<size_t>(g) * 1024 + tid * 4;
         if (e >= bucket_numel) continue;
         // first tensor whose end lies beyond e, searched in [lo0, hi0]
         uint32_t lo = lo0, hi = hi0;
@@ -86,24 +93,27 @@ __device__ __forceinline__ void flatten_tile(const TensorDesc* __restrict__ desc
     }
 }
 
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kWave)
 k_flatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile_first, uint32_t T,
           float* __restrict__ bucket, size_t bucket_numel)
 {
-    flatten_tile(desc, tile_first, T, bucket, bucket_numel, blockIdx.x);
+    flatten_tile(desc, tile_first, T, bucket, bucket_numel, blockIdx.x / kTileWaves,
+                 (blockIdx.x % kTileWaves) * kWave + threadIdx.x);
 }
 
 // Batched: entry = [planned workspace, T, bucket, bucket_numel]; unit = tile.
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kWave)
 k_flatten_batched(BatchView bv)
 {
-    const uint32_t b = batch_find(bv, blockIdx.x);
+    const uint32_t unit = blockIdx.x / kTileWaves;
+    const uint32_t b = batch_find(bv, unit);
     const uint64_t* e = bv.entries + static_cast<size_t>(b) * bv.entry_words;
     const size_t T = e[1];
     const unsigned char* ws = reinterpret_cast<const unsigned char*>(e[0]);
     const size_t desc_bytes = ((T ? T : 1) * sizeof(TensorDesc) + 15) & ~static_cast<size_t>(15);
     flatten_tile(reinterpret_cast<const TensorDesc*>(ws), reinterpret_cast<const uint32_t*>(ws + desc_bytes),
-                 static_cast<uint32_t>(T), reinterpret_cast<float*>(e[2]), e[3], blockIdx.x - bv.first_unit[b]);
+                 static_cast<uint32_t>(T), reinterpret_cast<float*>(e[2]), e[3], unit - bv.first_unit[b],
+                 (blockIdx.x % kTileWaves) * kWave + threadIdx.x);
 }
 
 // Inverse scatter: copy every tensor's range of the bucket back into the tensor (same table as the
@@ -286,7 +296,7 @@ extern "C" int bagua_flatten_plan(const void* const* src, const size_t* numel, c
                                   size_t bucket_numel, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (bucket_numel == 0 || !workspace || (T && (!src || !numel || !dst_offset))) return BAGUA_ERR_INVALID_ARG;
-    if (T > 0xfffffff0u || num_tiles(bucket_numel) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (T > 0xfffffff0u || num_tiles(bucket_numel) > kMaxGrid / kTileWaves) return BAGUA_ERR_UNSUPPORTED;
     if (workspace_bytes < bagua_flatten_workspace_bytes(T, bucket_numel)) return BAGUA_ERR_INVALID_ARG;
     if (!aligned16(workspace)) return BAGUA_ERR_ALIGNMENT;
     size_t prev_end = 0;
@@ -319,10 +329,10 @@ extern "C" int bagua_flatten_plan(const void* const* src, const size_t* numel, c
 extern "C" int bagua_bucket_flatten_run(const void* workspace, size_t T, float* bucket, size_t bucket_numel, void* stream)
 {
     if (!workspace || !bucket || bucket_numel == 0) return BAGUA_ERR_INVALID_ARG;
-    if (T > 0xfffffff0u || num_tiles(bucket_numel) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (T > 0xfffffff0u || num_tiles(bucket_numel) > kMaxGrid / kTileWaves) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(workspace) || !aligned16(bucket)) return BAGUA_ERR_ALIGNMENT;
     const FlattenPlanView pv = plan_view(workspace, T);
-    hipLaunchKernelGGL(k_flatten, dim3(static_cast<unsigned>(num_tiles(bucket_numel))), dim3(256), 0,
+    hipLaunchKernelGGL(k_flatten, dim3(static_cast<unsigned>(num_tiles(bucket_numel) * kTileWaves)), dim3(kWave), 0,
                        static_cast<hipStream_t>(stream), pv.desc, pv.tile_first, static_cast<uint32_t>(T), bucket, bucket_numel);
     return launch_status();
 }
@@ -367,10 +377,11 @@ extern "C" int bagua_bucket_flatten_batched_run(const void* const* plans, const 
     table[B] = total;
     rl.writes(workspace, table.size() * sizeof(uint64_t));
     if (!rl.disjoint()) return BAGUA_ERR_INVALID_ARG;
-    if (total > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (total > kMaxGrid / kTileWaves) return BAGUA_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (batch_upload(table.data(), table.size(), static_cast<uint64_t*>(workspace), s) != BAGUA_OK) return BAGUA_ERR_LAUNCH;
-    hipLaunchKernelGGL(k_flatten_batched, dim3(static_cast<unsigned>(total)), dim3(256), 0, s, batch_view(workspace, B, ew));
+    hipLaunchKernelGGL(k_flatten_batched, dim3(static_cast<unsigned>(total * kTileWaves)), dim3(kWave), 0, s,
+                       batch_view(workspace, B, ew));
     return launch_status();
 }
 
@@ -494,7 +505,7 @@ extern "C" int bagua_bucket_flatten_static(const void* const* src, const size_t*
     const size_t tiles = num_tiles(bucket_numel);
     hipLaunchKernelGGL(k_table_tiles, dim3(static_cast<unsigned>((tiles + 1 + 255) / 256)), dim3(256), 0, s, desc,
                        static_cast<uint32_t>(T), tile_first, tiles);
-    hipLaunchKernelGGL(k_flatten, dim3(static_cast<unsigned>(tiles)), dim3(256), 0, s, desc, tile_first,
+    hipLaunchKernelGGL(k_flatten, dim3(static_cast<unsigned>(tiles * kTileWaves)), dim3(kWave), 0, s, desc, tile_first,
                        static_cast<uint32_t>(T), bucket, bucket_numel);
     return launch_status();
 }
