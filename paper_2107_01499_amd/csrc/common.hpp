@@ -87,6 +87,12 @@ __device__ __forceinline__ void st_stream(T* p, T v)
 constexpr int kWave = 64;
 constexpr int kRow = 256;      // elements per wave-wide 128-bit access
 constexpr int kMaxWaves = 16;  // waves per workgroup (1024 threads)
+// Rows (one wavefront each) per workgroup of the kernels that stream row by row without a chunk statistic (decode,
+// optimizer steps, peer averaging, the probes).  Measured: two waves per workgroup are 0.5-3 % faster than four and than one.
+#ifndef BAGUA_ROW_WAVES
+#define BAGUA_ROW_WAVES 2
+#endif
+constexpr int kRowWaves = BAGUA_ROW_WAVES;
 
 // Upper bound on the workgroup size of a chunked kernel that keeps RPW rows per wave: chunks have at most
 // 64 rows, and pick_rpw never asks for more than kMaxWaves waves.

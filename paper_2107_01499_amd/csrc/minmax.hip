@@ -204,11 +204,11 @@ k_drr_minmax_batched(BatchView bv, int k, float inv_k, uint32_t chunk)
 
 // ------------------------------------------------------------------------------------------
 // Decode: out = mn + code * step.  One wave per row, 4 rows per workgroup.
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kWave * kRowWaves)
 k_decompress_minmax(const uint8_t* __restrict__ codes, const float* __restrict__ minmax, size_t n,
                     uint32_t chunk, float* __restrict__ out)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
+    const size_t row = static_cast<size_t>(blockIdx.x) * kRowWaves + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -290,7 +290,7 @@ int launch_decompress_minmax(const uint8_t* codes, const float* minmax, size_t n
                              hipStream_t stream)
 {
     const size_t rows = (n + kRow - 1) / kRow;
-    dim3 grid(static_cast<unsigned>((rows + 3) / 4)), block(256);
+    dim3 grid(static_cast<unsigned>((rows + kRowWaves - 1) / kRowWaves)), block(kWave * kRowWaves);
     hipLaunchKernelGGL(k_decompress_minmax, grid, block, 0, stream, codes, minmax, n,
                        static_cast<uint32_t>(chunk), out);
     return launch_status();

@@ -39,11 +39,11 @@ __device__ __forceinline__ f4 decode_row(const void* __restrict__ codes, const f
 
 // One wave per 256-element row, four rows per workgroup.
 template <int CODEC, bool MOM, bool WD>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kWave * kRowWaves)
 k_decompress_sgd(const void* __restrict__ codes, const float* __restrict__ meta, size_t n, uint32_t chunk,
                  float* __restrict__ param, float* __restrict__ mbuf, float lr, float mu, float wd)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
+    const size_t row = static_cast<size_t>(blockIdx.x) * kRowWaves + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -80,12 +80,12 @@ k_decompress_sgd(const void* __restrict__ codes, const float* __restrict__ meta,
 // Adam-type update (no bias correction).  FROZEN: the decoded tensor is the averaged momentum of the
 // compression stage of 1-bit Adam: it replaces m, and v is only read.
 template <int CODEC, bool FROZEN, bool WD>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kWave * kRowWaves)
 k_decompress_adam(const void* __restrict__ codes, const float* __restrict__ meta, size_t n, uint32_t chunk,
                   float* __restrict__ param, float* __restrict__ mbuf, float* __restrict__ vbuf, float lr, float beta1,
                   float omb1, float beta2, float omb2, float eps, float wd)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
+    const size_t row = static_cast<size_t>(blockIdx.x) * kRowWaves + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -225,9 +225,9 @@ extern "C" int bagua_decompress_sgd_step(int codec, const void* codes, const flo
         if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     }
     const size_t rows = (n + kRow - 1) / kRow;
-    if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if ((rows + kRowWaves - 1) / kRowWaves > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(codes) || !aligned4(meta) || !aligned16(param) || !aligned16(momentum_buf)) return BAGUA_ERR_ALIGNMENT;
-    dim3 grid(static_cast<unsigned>((rows + 3) / 4)), block(256);
+    dim3 grid(static_cast<unsigned>((rows + kRowWaves - 1) / kRowWaves)), block(kWave * kRowWaves);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint32_t ch = static_cast<uint32_t>(chunk);
     const bool mom = momentum_buf != nullptr, wd = weight_decay != 0.0f;
@@ -263,10 +263,10 @@ extern "C" int bagua_decompress_adam_step(int codec, const void* codes, const fl
         if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     }
     const size_t rows = (n + kRow - 1) / kRow;
-    if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if ((rows + kRowWaves - 1) / kRowWaves > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(codes) || !aligned4(meta) || !aligned16(param) || !aligned16(m) || !aligned16(v))
         return BAGUA_ERR_ALIGNMENT;
-    dim3 grid(static_cast<unsigned>((rows + 3) / 4)), block(256);
+    dim3 grid(static_cast<unsigned>((rows + kRowWaves - 1) / kRowWaves)), block(kWave * kRowWaves);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint32_t ch = static_cast<uint32_t>(chunk);
     const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;

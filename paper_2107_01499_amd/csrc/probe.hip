@@ -33,10 +33,10 @@ k_probe_read(const float* __restrict__ x, size_t n, float* __restrict__ tile_sum
 // Stream mix: a wave owns one row and visits `seq` groups of streams one after another; in each group it reads
 // the row from NR fp32 streams, then writes it to NW fp32 streams and NB byte streams (one dword per lane).
 template <int NR, int NW, int NB>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kWave * kRowWaves)
 k_probe_streams(PtrTable in, MutPtrTable out, MutPtrTable bout, int seq, size_t n)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
+    const size_t row = static_cast<size_t>(blockIdx.x) * kRowWaves + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -100,8 +100,8 @@ extern "C" int bagua_probe_streams(const float* const* in, float* const* out, ui
         bt.p[i] = bout[i];
     }
     const size_t rows = n / kRow;
-    if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
-    dim3 grid(static_cast<unsigned>((rows + 3) / 4)), block(256);
+    if ((rows + kRowWaves - 1) / kRowWaves > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    dim3 grid(static_cast<unsigned>((rows + kRowWaves - 1) / kRowWaves)), block(kWave * kRowWaves);
     hipStream_t s = static_cast<hipStream_t>(stream);
 #define BAGUA_PROBE(NR, NW, NB)                                                                          \
     if (nr == NR && nw == NW && nb == NB) {                                                              \

@@ -19,7 +19,10 @@ __device__ __forceinline__ f4 mul4(f4 a, float s) { return f4{a.x * s, a.y * s, 
 // ------------------------------------------------------------------------------------------ FP
 // One wave per 256-element row; K replicas held in registers.  kFpWaves rows per workgroup: measured at 8 peers x
 // 110 M elements, 1 and 8 waves per workgroup stream 3-5 % faster than 2, 4 or 16.
-constexpr int kFpWaves = 8;
+#ifndef BAGUA_FP_WAVES
+#define BAGUA_FP_WAVES 8
+#endif
+constexpr int kFpWaves = BAGUA_FP_WAVES;
 template <int K>
 __global__ void __launch_bounds__(64 * kFpWaves)
 k_ring_avg_fp(PtrTable xin, MutPtrTable xout, size_t n, float third)
@@ -40,10 +43,10 @@ k_ring_avg_fp(PtrTable xin, MutPtrTable xout, size_t n, float third)
 }
 
 // Any k: rolling window over the peers (fewer loads in flight; used above the templated range).
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kWave * kRowWaves)
 k_ring_avg_fp_any(PtrTable xin, MutPtrTable xout, int k, size_t n, float third)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
+    const size_t row = static_cast<size_t>(blockIdx.x) * kRowWaves + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -171,10 +174,10 @@ k_lp_encode(const float* __restrict__ x, float* __restrict__ xhat, size_t n, uin
 }
 
 // Pass 2: x_out[i] = ((xhat[i-1] + xhat[i]) + xhat[i+1]) * third + (x[i] - xhat[i]), rolling over peers.
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kWave * kRowWaves)
 k_lp_mix(PtrTable xin, MutPtrTable xout, MutPtrTable xhat, int k, size_t n, float third)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
+    const size_t row = static_cast<size_t>(blockIdx.x) * kRowWaves + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -210,7 +213,7 @@ static int launch_ring_fp(const float* const* x_in, float* const* x_out, int k, 
         out.p[i] = x_out[i];
     }
     const size_t rows = (n + kRow - 1) / kRow;
-    dim3 grid(static_cast<unsigned>((rows + 3) / 4));
+    dim3 grid(static_cast<unsigned>((rows + kRowWaves - 1) / kRowWaves));
     const float third = 1.0f / 3.0f;
     switch (k) {
 #define BAGUA_FP_CASE(K) case K: launch_fp_k<K>(in, out, n, third, grid, stream); break;
@@ -219,7 +222,7 @@ static int launch_ring_fp(const float* const* x_in, float* const* x_out, int k, 
         BAGUA_FP_CASE(13) BAGUA_FP_CASE(14) BAGUA_FP_CASE(15) BAGUA_FP_CASE(16)
 #undef BAGUA_FP_CASE
         default:
-            hipLaunchKernelGGL(k_ring_avg_fp_any, grid, dim3(256), 0, stream, in, out, k, n, third);
+            hipLaunchKernelGGL(k_ring_avg_fp_any, grid, dim3(kWave * kRowWaves), 0, stream, in, out, k, n, third);
     }
     return launch_status();
 }
@@ -266,7 +269,7 @@ static int launch_ring_lp(const float* const* x_in, float* const* x_out, float* 
                                                    static_cast<uint32_t>(chunk), codes[i], minmax[i]))
     }
     const size_t nrows = (n + kRow - 1) / kRow;
-    hipLaunchKernelGGL(k_lp_mix, dim3(static_cast<unsigned>((nrows + 3) / 4)), dim3(256), 0, stream, in, out, hat, k, n,
+    hipLaunchKernelGGL(k_lp_mix, dim3(static_cast<unsigned>((nrows + kRowWaves - 1) / kRowWaves)), dim3(kWave * kRowWaves), 0, stream, in, out, hat, k, n,
                        third);
     return launch_status();
 }
@@ -306,7 +309,7 @@ extern "C" int bagua_decentralized_avg(int mode, const float* const* x_in, float
         if (lp && (!aligned16(xhat[i]) || !aligned16(codes[i]) || !aligned4(minmax[i]))) return BAGUA_ERR_ALIGNMENT;
     }
     const size_t rows = (n + kRow - 1) / kRow;
-    if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if ((rows + kRowWaves - 1) / kRowWaves > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!lp) return launch_ring_fp(x_in, x_out, k, n, s);
     return launch_ring_lp(x_in, x_out, xhat, codes, minmax, k, n, chunk, s);
@@ -325,11 +328,11 @@ struct PeerJobs {
     float* out_b[BAGUA_MAX_WORKERS];  // nullptr for a single-output job
 };
 
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kWave * kRowWaves)
 k_peer_avg_fp(PeerJobs jobs, size_t n)
 {
     const int job = blockIdx.y;
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
+    const size_t row = static_cast<size_t>(blockIdx.x) * kRowWaves + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -360,7 +363,7 @@ extern "C" int bagua_decentralized_avg_peers(const float* const* x_in, float* co
     for (int i = 0; i < k; ++i)
         if (!aligned16(x_in[i]) || !aligned16(x_out[i])) return BAGUA_ERR_ALIGNMENT;
     const size_t rows = (n + kRow - 1) / kRow;
-    if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if ((rows + kRowWaves - 1) / kRowWaves > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     PeerJobs jobs{};
     int nj = 0;
     for (int i = 0; i < k; ++i) {
@@ -373,7 +376,7 @@ extern "C" int bagua_decentralized_avg_peers(const float* const* x_in, float* co
         jobs.out_b[nj] = matched ? x_out[p] : nullptr;
         ++nj;
     }
-    hipLaunchKernelGGL(k_peer_avg_fp, dim3(static_cast<unsigned>((rows + 3) / 4), nj), dim3(256), 0,
+    hipLaunchKernelGGL(k_peer_avg_fp, dim3(static_cast<unsigned>((rows + kRowWaves - 1) / kRowWaves), nj), dim3(kWave * kRowWaves), 0,
                        static_cast<hipStream_t>(stream), jobs, n);
     return launch_status();
 }
@@ -383,10 +386,10 @@ extern "C" int bagua_decentralized_avg_peers(const float* const* x_in, float* co
 // One wave per row; the loads of four workers are in flight together.
 namespace bagua {
 
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kWave * kRowWaves)
 k_centralized_avg_fp(PtrTable xs, int k, float inv_k, size_t n, float* __restrict__ out)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
+    const size_t row = static_cast<size_t>(blockIdx.x) * kRowWaves + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -422,10 +425,10 @@ extern "C" int bagua_centralized_avg_fp(const float* const* x, int k, size_t n, 
         if (!aligned16(x[j])) return BAGUA_ERR_ALIGNMENT;
     if (!aligned16(out)) return BAGUA_ERR_ALIGNMENT;
     const size_t rows = (n + kRow - 1) / kRow;
-    if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if ((rows + kRowWaves - 1) / kRowWaves > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     PtrTable xt{};
     for (int j = 0; j < k; ++j) xt.p[j] = x[j];
-    hipLaunchKernelGGL(k_centralized_avg_fp, dim3(static_cast<unsigned>((rows + 3) / 4)), dim3(256), 0,
+    hipLaunchKernelGGL(k_centralized_avg_fp, dim3(static_cast<unsigned>((rows + kRowWaves - 1) / kRowWaves)), dim3(kWave * kRowWaves), 0,
                        static_cast<hipStream_t>(stream), xt, k, 1.0f / static_cast<float>(k), n, out);
     return launch_status();
 }
@@ -509,11 +512,11 @@ struct PeerMixJobs {
     float* out[BAGUA_MAX_WORKERS];
 };
 
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kWave * kRowWaves)
 k_peer_mix_lp(PeerMixJobs jobs, size_t n)
 {
     const int i = blockIdx.y;
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
+    const size_t row = static_cast<size_t>(blockIdx.x) * kRowWaves + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -594,7 +597,7 @@ extern "C" int bagua_decentralized_avg_peers_lp(const float* const* x_in, float*
         mix.hat_peer[i] = xhat[peer[i]];
         mix.out[i] = x_out[i];
     }
-    hipLaunchKernelGGL(k_peer_mix_lp, dim3(static_cast<unsigned>((nrows + 3) / 4), k), dim3(256), 0, s, mix, n);
+    hipLaunchKernelGGL(k_peer_mix_lp, dim3(static_cast<unsigned>((nrows + kRowWaves - 1) / kRowWaves), k), dim3(kWave * kRowWaves), 0, s, mix, n);
     return launch_status();
 }
 
@@ -608,13 +611,13 @@ namespace bagua {
 // APPLY_L / APPLY_R: that neighbour's codes are decoded into its copy (otherwise the copy is current).
 // SAME: both neighbours are one peer (ring of two): one copy, advanced once, counted twice.
 template <bool APPLY_L, bool APPLY_R, bool SAME>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kWave * kRowWaves)
 k_lp_apply_mix(const float* __restrict__ x, const float* __restrict__ h_own, float* h_left, float* h_right,
                const uint8_t* __restrict__ c_left, const float* __restrict__ m_left,
                const uint8_t* __restrict__ c_right, const float* __restrict__ m_right, size_t n, uint32_t chunk,
                float third, float* __restrict__ x_out)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
+    const size_t row = static_cast<size_t>(blockIdx.x) * kRowWaves + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -686,11 +689,11 @@ extern "C" int bagua_lp_apply_mix(const float* x, const float* xhat_own, float* 
     rc.reads(xhat_own, bytes);
     if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
     const size_t rows = (n + kRow - 1) / kRow;
-    if ((rows + 3) / 4 > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if ((rows + kRowWaves - 1) / kRowWaves > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(xhat_own) || !aligned16(xhat_left) || !aligned16(xhat_right) || !aligned16(codes_left) ||
         !aligned16(codes_right) || !aligned4(minmax_left) || !aligned4(minmax_right) || !aligned16(x_out))
         return BAGUA_ERR_ALIGNMENT;
-    dim3 grid(static_cast<unsigned>((rows + 3) / 4)), block(256);
+    dim3 grid(static_cast<unsigned>((rows + kRowWaves - 1) / kRowWaves)), block(kWave * kRowWaves);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint32_t ch = static_cast<uint32_t>(chunk);
     const float third = 1.0f / 3.0f;

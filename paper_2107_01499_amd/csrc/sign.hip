@@ -296,11 +296,11 @@ k_drr_sign_batched(BatchView bv, int k, float inv_k, uint32_t chunk)
                                  reinterpret_cast<float*>(e[3]), blockIdx.x - bv.first_unit[b], s_q);
 }
 
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kWave * kRowWaves)
 k_decompress_sign(const uint32_t* __restrict__ bits, const float* __restrict__ scale, size_t n, uint32_t chunk,
                   float* __restrict__ out)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * 4 + wave_index();
+    const size_t row = static_cast<size_t>(blockIdx.x) * kRowWaves + wave_index();
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -396,7 +396,7 @@ int launch_decompress_sign(const uint32_t* bits, const float* scale, size_t n, s
                            hipStream_t stream)
 {
     const size_t rows = (n + kRow - 1) / kRow;
-    dim3 grid(static_cast<unsigned>((rows + 3) / 4)), block(256);
+    dim3 grid(static_cast<unsigned>((rows + kRowWaves - 1) / kRowWaves)), block(kWave * kRowWaves);
     hipLaunchKernelGGL(k_decompress_sign, grid, block, 0, stream, bits, scale, n, static_cast<uint32_t>(chunk), out);
     return launch_status();
 }
