@@ -119,12 +119,14 @@ k_flatten_batched(BatchView bv)
 // Inverse scatter: copy every tensor's range of the bucket back into the tensor (same table as the
 // flatten; bucket elements no tensor covers are skipped).  The tensors' pointers in the table are
 // written through, so the table must have been planned with writable tensors.
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kWave)
 k_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ tile_first, uint32_t T,
             const float* __restrict__ bucket, size_t bucket_numel)
 {
-    const size_t tile0 = static_cast<size_t>(blockIdx.x) * kTile;
-    const uint32_t lo0 = tile_first[blockIdx.x], hi0 = tile_first[blockIdx.x + 1];
+    const size_t tile = blockIdx.x / kTileWaves;                                  // single-wave workgroups, as in k_flatten
+    const uint32_t tid = (blockIdx.x % kTileWaves) * kWave + threadIdx.x;
+    const size_t tile0 = tile * kTile;
+    const uint32_t lo0 = tile_first[tile], hi0 = tile_first[tile + 1];
     if (lo0 < T && tile0 + kTile <= bucket_numel) {
         const TensorDesc d = desc[lo0];
         if (d.dst <= tile0 && tile0 + kTile <= d.dst + d.numel) {
@@ -134,9 +136,9 @@ k_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ ti
                 const f4* b4 = reinterpret_cast<const f4*>(bucket + tile0);
                 f4 v[kTile / 1024];
 #pragma unroll
-                for (int g = 0; g < kTile / 1024; ++g) v[g] = ld_stream(b4 + g * 256 + threadIdx.x);
+                for (int g = 0; g < kTile / 1024; ++g) v[g] = ld_stream(b4 + g * 256 + tid);
 #pragma unroll
-                for (int g = 0; g < kTile / 1024; ++g) st_stream(s4 + g * 256 + threadIdx.x, v[g]);
+                for (int g = 0; g < kTile / 1024; ++g) st_stream(s4 + g * 256 + tid, v[g]);
                 return;
             }
             // same, tensor only 4-byte aligned: 128-bit stores with 4-byte declared alignment
@@ -144,15 +146,15 @@ k_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ ti
             f4_a4* s4 = reinterpret_cast<f4_a4*>(s);
 #pragma unroll
             for (int g = 0; g < kTile / 1024; ++g) {
-                const f4 v = ld_stream(b4 + g * 256 + threadIdx.x);
-                __builtin_nontemporal_store(f4_a4{v.x, v.y, v.z, v.w}, s4 + g * 256 + threadIdx.x);
+                const f4 v = ld_stream(b4 + g * 256 + tid);
+                __builtin_nontemporal_store(f4_a4{v.x, v.y, v.z, v.w}, s4 + g * 256 + tid);
             }
             return;
         }
     }
 #pragma unroll
     for (int g = 0; g < kTile / 1024; ++g) {
-        const size_t e = tile0 + static_cast<size_t>(g) * 1024 + threadIdx.x * 4;
+        const size_t e = tile0 + static_cast<size_t>(g) * 1024 + tid * 4;
         if (e >= bucket_numel) continue;
         uint32_t lo = lo0, hi = hi0;
         while (lo < hi) {
@@ -514,10 +516,10 @@ extern "C" int bagua_bucket_unflatten_run(const void* workspace, size_t T, const
                                           void* stream)
 {
     if (!workspace || !bucket || bucket_numel == 0) return BAGUA_ERR_INVALID_ARG;
-    if (T > 0xfffffff0u || num_tiles(bucket_numel) > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (T > 0xfffffff0u || num_tiles(bucket_numel) > kMaxGrid / kTileWaves) return BAGUA_ERR_UNSUPPORTED;
     if (!aligned16(workspace) || !aligned16(bucket)) return BAGUA_ERR_ALIGNMENT;
     const FlattenPlanView pv = plan_view(workspace, T);
-    hipLaunchKernelGGL(k_unflatten, dim3(static_cast<unsigned>(num_tiles(bucket_numel))), dim3(256), 0,
+    hipLaunchKernelGGL(k_unflatten, dim3(static_cast<unsigned>(num_tiles(bucket_numel) * kTileWaves)), dim3(kWave), 0,
                        static_cast<hipStream_t>(stream), pv.desc, pv.tile_first, static_cast<uint32_t>(T), bucket, bucket_numel);
     return launch_status();
 }
