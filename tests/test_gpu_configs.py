@@ -290,3 +290,90 @@ def test_more_than_2_to_32_elements(bg, oracle):
     for (lo, hi), (xh, _) in keep.items():
         b, s = oracle.sign_compress_ef(xh, None, C)
         exact(host(bits[lo // 32:(hi + 31) // 32]).view(np.uint32), b, "bits"); exact(host(sc[lo // C:(hi + C - 1) // C]), s, "scale")
+
+
+def test_more_than_2_to_32_elements_server_steps_flatten_ring(bg, oracle):
+    """The same oversize bucket through the remaining primitives: the server step of both codecs (k = 2), flatten and
+    its inverse (one tensor that ends just below 2^32 elements, two small ones behind it, gaps between them), and one
+    round of full-precision ring averaging; compared on the ranges at the start, across the 2^32 boundary and at the
+    ragged end."""
+    from bagua_workloads import draw, seed_for
+    print("oversize bucket: server steps, flatten, ring", flush=True)
+    C = 4096
+    n = (1 << 32) + 3 * C + 77
+    nc = (n + C - 1) // C
+    rs = [(0, 64 * C), ((1 << 32) - 32 * C, (1 << 32) + 2 * C), (n - 77 - 16 * C, n)]
+    mslice = lambda lo, hi: slice(2 * lo // C, 2 * ((hi + C - 1) // C))
+    sslice = lambda lo, hi: slice(lo // C, (hi + C - 1) // C)
+    x = draw("normal", n, seed_for(9, 1, 0), DEV, 1e-3)
+    # ---- server step, MinMax: worker 0 = x, worker 1 = 0.5 x
+    c0 = torch.empty(n, dtype=torch.uint8, device=DEV); m0 = torch.empty(2 * nc, device=DEV)
+    c1 = torch.empty(n, dtype=torch.uint8, device=DEV); m1 = torch.empty(2 * nc, device=DEV)
+    b0 = torch.empty((n + 31) // 32, dtype=torch.int32, device=DEV); s0 = torch.empty(nc, device=DEV)
+    b1 = torch.empty((n + 31) // 32, dtype=torch.int32, device=DEV); s1 = torch.empty(nc, device=DEV)
+    bg.bagua_compress_minmax_u8(x, None, C, c0, m0)
+    bg.bagua_sign_compress_ef(x, None, C, b0, s0)
+    xs = {r: x[r[0]:r[1]].cpu().numpy() for r in rs}
+    x.mul_(0.5)
+    bg.bagua_compress_minmax_u8(x, None, C, c1, m1)
+    bg.bagua_sign_compress_ef(x, None, C, b1, s1)
+    eps = x                                         # reuse: the halved gradient serves as the error state
+    eps_h = {r: eps[r[0]:r[1]].cpu().numpy().copy() for r in rs}
+    out = torch.empty(n, device=DEV)
+    co = torch.empty(n, dtype=torch.uint8, device=DEV); mo = torch.empty(2 * nc, device=DEV)
+    bg.bagua_decompress_reduce_recompress(bg.CODEC_MINMAX_U8, [c0, c1], [m0, m1], eps, n, C, co, mo, out)
+    for lo, hi in rs:
+        e = eps_h[(lo, hi)].copy()
+        cw, mw, ow = oracle.drr_minmax_u8([host(c0[lo:hi]), host(c1[lo:hi])], [host(m0[mslice(lo, hi)]), host(m1[mslice(lo, hi)])], e, C)
+        exact(host(co[lo:hi]), cw, "server codes"); exact(host(mo[mslice(lo, hi)]), mw, "server minmax")
+        exact(host(out[lo:hi]), ow, "server out"); exact(host(eps[lo:hi]), e, "server eps")
+    del c0, c1, co
+    # ---- server step, sign codec, error state = what the MinMax step left
+    eps_h = {r: eps[r[0]:r[1]].cpu().numpy().copy() for r in rs}
+    bo = torch.empty((n + 31) // 32, dtype=torch.int32, device=DEV); so = torch.empty(nc, device=DEV)
+    bg.bagua_decompress_reduce_recompress(bg.CODEC_SIGN1, [b0, b1], [s0, s1], eps, n, C, bo, so, out)
+    for lo, hi in rs:
+        e = eps_h[(lo, hi)].copy()
+        w = slice(lo // 32, (hi + 31) // 32)
+        bw, sw, ow = oracle.drr_sign([host(b0[w]).view(np.uint32), host(b1[w]).view(np.uint32)],
+                                     [host(s0[sslice(lo, hi)]), host(s1[sslice(lo, hi)])], e, hi - lo, C)
+        exact(host(bo[w]).view(np.uint32), bw, "sign server bits"); exact(host(so[sslice(lo, hi)]), sw, "sign server scale")
+        exact(host(out[lo:hi]), ow, "sign server out"); exact(host(eps[lo:hi]), e, "sign server eps")
+    del b0, b1, bo, eps
+    # ---- flatten and its inverse: tensors are views of `src` (one of them only 4-byte aligned), bucket = `out`
+    src = x
+    big = (1 << 32) - 5
+    sizes = [big, 7, n - big - 7 - 30]
+    starts_src = [0, big + 1, big + 1 + 7 + 2]                       # source positions (second and third misaligned)
+    offs = [3, big + 3 + 9, big + 3 + 9 + 7 + 4]                      # bucket offsets with gaps
+    assert offs[2] + sizes[2] <= n and starts_src[2] + sizes[2] <= n
+    tens = [src[a:a + s] for a, s in zip(starts_src, sizes)]
+    ws = torch.empty(bg.bagua_flatten_workspace_bytes(3, n), dtype=torch.uint8, device=DEV)
+    out.fill_(float("nan"))
+    bg.bagua_bucket_flatten(tens, offs, out, ws)
+    torch.cuda.synchronize()
+    for t, o, s in zip(tens, offs, sizes):
+        for lo, hi in ((0, min(s, 5000)), (max(0, s - 5000), s)):    # head and tail of every tensor
+            assert torch.equal(out[o + lo:o + hi].view(torch.int32), t[lo:hi].view(torch.int32))
+    for lo, hi in ((0, 3), (offs[0] + sizes[0], offs[1]), (offs[1] + sizes[1], offs[2]), (offs[2] + sizes[2], n)):
+        assert not out[lo:hi].view(torch.int32).any(), "gap %d..%d not zero" % (lo, hi)
+    mid = (1 << 31) + 12345                                           # somewhere inside the big tensor
+    assert torch.equal(out[3 + mid:3 + mid + 70000].view(torch.int32), tens[0][mid:mid + 70000].view(torch.int32))
+    # inverse: scatter a marked bucket back
+    out.mul_(2.0)
+    want_head = [out[o:o + min(s, 4096)].clone() for o, s in zip(offs, sizes)]
+    want_tail = [out[o + max(0, s - 4096):o + s].clone() for o, s in zip(offs, sizes)]
+    bg.bagua_bucket_unflatten_run(ws, 3, out)
+    torch.cuda.synchronize()
+    for t, s, wh, wt in zip(tens, sizes, want_head, want_tail):
+        assert torch.equal(t[:min(s, 4096)].view(torch.int32), wh.view(torch.int32))
+        assert torch.equal(t[max(0, s - 4096):].view(torch.int32), wt.view(torch.int32))
+    # ---- ring averaging, two peers (each peer's neighbours are the other one, twice)
+    y = out
+    x0 = {r: src[r[0]:r[1]].cpu().numpy() for r in rs}
+    y0 = {r: y[r[0]:r[1]].cpu().numpy() for r in rs}
+    ox, oy = torch.empty(n, device=DEV), torch.empty(n, device=DEV)
+    bg.bagua_decentralized_avg(bg.AVG_FP, [src, y], [ox, oy])
+    for r in rs:
+        wx, wy = oracle.ring_avg_fp([x0[r], y0[r]])
+        exact(host(ox[r[0]:r[1]]), wx, "ring x"); exact(host(oy[r[0]:r[1]]), wy, "ring y")
