@@ -240,12 +240,12 @@ extern "C" int bagua_flatten_compress_minmax_u8(const void* workspace, size_t T,
         return BAGUA_ERR_ALIGNMENT;
     const FlattenPlanView pv = plan_view(workspace, T);
     const int rows = static_cast<int>(chunk / kRow);
-    const int rpw = pick_rpw(rows, BAGUA_RPW_COMPRESS);
+    const int rpw = pick_rpw_worker(rows, BAGUA_RPW_COMPRESS);
     dim3 grid(static_cast<unsigned>(num_chunks(bucket_numel, chunk))), block(64 * ((rows + rpw - 1) / rpw));
     const uint32_t ch = static_cast<uint32_t>(chunk), t32 = static_cast<uint32_t>(T);
     hipStream_t s = static_cast<hipStream_t>(stream);
 #define BAGUA_FC(EFv, WBv)                                                                                       \
-    BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_flatten_compress_minmax<RPW, EFv, WBv>), grid, block, 0, s,    \
+    BAGUA_DISPATCH_RPW_WORKER(rpw, hipLaunchKernelGGL((k_flatten_compress_minmax<RPW, EFv, WBv>), grid, block, 0, s,    \
                                                pv.desc, pv.tile_first, t32, residual, bucket_numel, ch, codes,  \
                                                minmax, bucket_out))
     if (residual && bucket_out) { BAGUA_FC(true, true) }
@@ -272,14 +272,14 @@ extern "C" int bagua_flatten_sign_compress_ef(const void* workspace, size_t T, f
         return BAGUA_ERR_ALIGNMENT;
     const FlattenPlanView pv = plan_view(workspace, T);
     const int rows = static_cast<int>(chunk / kRow);
-    const int rpw = pick_rpw(rows, BAGUA_RPW_SIGN);
+    const int rpw = pick_rpw_worker(rows, BAGUA_RPW_SIGN);
     const int waves = (rows + rpw - 1) / rpw;
     dim3 grid(static_cast<unsigned>(num_chunks(bucket_numel, chunk))), block(64 * waves);
     const size_t lds = waves > 1 ? static_cast<size_t>(rows) * kWave * sizeof(float) : 0;
     const uint32_t ch = static_cast<uint32_t>(chunk), t32 = static_cast<uint32_t>(T);
     hipStream_t s = static_cast<hipStream_t>(stream);
 #define BAGUA_FS(EFv, WBv)                                                                                       \
-    BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_flatten_sign_compress<RPW, EFv, WBv>), grid, block, lds, s,    \
+    BAGUA_DISPATCH_RPW_WORKER(rpw, hipLaunchKernelGGL((k_flatten_sign_compress<RPW, EFv, WBv>), grid, block, lds, s,    \
                                                pv.desc, pv.tile_first, t32, residual, bucket_numel, ch, bits,   \
                                                scale, bucket_out))
     if (residual && bucket_out) { BAGUA_FS(true, true) }
@@ -311,16 +311,16 @@ extern "C" int bagua_reduce_compress_minmax_u8(const float* const* x, int k_loca
     PtrTable xt{};
     for (int j = 0; j < k_local; ++j) xt.p[j] = x[j];
     const int rows = static_cast<int>(chunk / kRow);
-    const int rpw = pick_rpw(rows, BAGUA_RPW_COMPRESS);
+    const int rpw = pick_rpw_worker(rows, BAGUA_RPW_COMPRESS);
     dim3 grid(static_cast<unsigned>(num_chunks(n, chunk))), block(64 * ((rows + rpw - 1) / rpw));
     const float inv_k = 1.0f / static_cast<float>(k_local);
     const uint32_t ch = static_cast<uint32_t>(chunk);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (residual) {
-        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_reduce_compress_minmax<RPW, true>), grid, block, 0, s, xt, k_local,
+        BAGUA_DISPATCH_RPW_WORKER(rpw, hipLaunchKernelGGL((k_reduce_compress_minmax<RPW, true>), grid, block, 0, s, xt, k_local,
                                                    inv_k, residual, n, ch, codes, minmax))
     } else {
-        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_reduce_compress_minmax<RPW, false>), grid, block, 0, s, xt, k_local,
+        BAGUA_DISPATCH_RPW_WORKER(rpw, hipLaunchKernelGGL((k_reduce_compress_minmax<RPW, false>), grid, block, 0, s, xt, k_local,
                                                    inv_k, residual, n, ch, codes, minmax))
     }
     return launch_status();
@@ -347,7 +347,7 @@ extern "C" int bagua_reduce_compress_sign_ef(const float* const* x, int k_local,
     PtrTable xt{};
     for (int j = 0; j < k_local; ++j) xt.p[j] = x[j];
     const int rows = static_cast<int>(chunk / kRow);
-    const int rpw = pick_rpw(rows, BAGUA_RPW_SIGN);
+    const int rpw = pick_rpw_worker(rows, BAGUA_RPW_SIGN);
     const int waves = (rows + rpw - 1) / rpw;
     dim3 grid(static_cast<unsigned>(num_chunks(n, chunk))), block(64 * waves);
     const size_t lds = waves > 1 ? static_cast<size_t>(rows) * kWave * sizeof(float) : 0;
@@ -355,10 +355,10 @@ extern "C" int bagua_reduce_compress_sign_ef(const float* const* x, int k_local,
     const uint32_t ch = static_cast<uint32_t>(chunk);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (residual) {
-        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_reduce_compress_sign<RPW, true>), grid, block, lds, s, xt, k_local,
+        BAGUA_DISPATCH_RPW_WORKER(rpw, hipLaunchKernelGGL((k_reduce_compress_sign<RPW, true>), grid, block, lds, s, xt, k_local,
                                                    inv_k, residual, n, ch, bits, scale))
     } else {
-        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_reduce_compress_sign<RPW, false>), grid, block, lds, s, xt, k_local,
+        BAGUA_DISPATCH_RPW_WORKER(rpw, hipLaunchKernelGGL((k_reduce_compress_sign<RPW, false>), grid, block, lds, s, xt, k_local,
                                                    inv_k, residual, n, ch, bits, scale))
     }
     return launch_status();
