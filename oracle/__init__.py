@@ -325,6 +325,17 @@ def decompress_adam_step(codec, codes, meta, n, chunk, param, m, v, lr, beta1=0.
           _chk(v, np.float32), lr, beta1, beta2, eps, weight_decay, int(bool(variance_frozen))), "decompress_adam_step")
 
 
+def decompress_adam_step_topk(idx, val, n, chunk, keep, param, m, v, lr, beta1=0.9, beta2=0.999, eps=1e-8,
+                              weight_decay=0.0, variance_frozen=False):
+    """Decode of a top-K bucket fused with the Adam-type update, in place on param, m (and v unless frozen)."""
+    f = lib().oracle_decompress_adam_step_topk
+    f.restype = ctypes.c_int
+    cf = ctypes.c_float
+    f.argtypes = [_c_p, _c_p, _c_sz, _c_sz, _c_sz, _c_p, _c_p, _c_p, cf, cf, cf, cf, cf, ctypes.c_int]
+    _ok(f(_chk(idx, np.uint16), _chk(val, np.float32), n, chunk, keep, _chk(param, np.float32), _chk(m, np.float32),
+          _chk(v, np.float32), lr, beta1, beta2, eps, weight_decay, int(bool(variance_frozen))), "decompress_adam_step_topk")
+
+
 def momentum_sign_compress_ef(g, m, beta1, residual, chunk):
     """Sign-compress beta1*m + (1-beta1)*g with error feedback (residual updated in place). Returns (bits, scale)."""
     n = g.size

@@ -815,16 +815,10 @@ int oracle_peer_avg_lp(const float* const* x_in, float* const* x_out, float* con
  *       m = d ;  v unchanged
  *   u = m / (sqrtf(v) + eps) ;  if weight_decay != 0:  u = u + weight_decay*p ;  p = p - lr*u
  */
-int oracle_decompress_adam_step(int codec, const void* codes, const float* meta, size_t n, size_t chunk,
-                                float* param, float* m, float* v, float lr, float beta1, float beta2, float eps,
-                                float weight_decay, int variance_frozen)
+/* The update above for a decoded tensor d (shared by every codec's step). */
+static void adam_update(const float* d, size_t n, float* param, float* m, float* v, float lr, float beta1, float beta2,
+                        float eps, float weight_decay, int variance_frozen)
 {
-    if ((codec != 0 && codec != 1) || !codes || !meta || !param || !m || !v || n == 0 || !chunk_ok(chunk)) return 1;
-    float* d = (float*)malloc(n * sizeof(float));
-    if (!d) return 1;
-    int rc = codec == 0 ? oracle_decompress_minmax_u8((const uint8_t*)codes, meta, n, chunk, d)
-                        : oracle_decompress_sign((const uint32_t*)codes, meta, n, chunk, d);
-    if (rc) { free(d); return rc; }
     const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
     for (size_t i = 0; i < n; ++i) {
         float mi, vi = v[i];
@@ -851,8 +845,37 @@ int oracle_decompress_adam_step(int codec, const void* codes, const float* meta,
         float step = lr * u;
         param[i] = param[i] - step;
     }
+}
+
+int oracle_decompress_adam_step(int codec, const void* codes, const float* meta, size_t n, size_t chunk,
+                                float* param, float* m, float* v, float lr, float beta1, float beta2, float eps,
+                                float weight_decay, int variance_frozen)
+{
+    if ((codec != 0 && codec != 1) || !codes || !meta || !param || !m || !v || n == 0 || !chunk_ok(chunk)) return 1;
+    float* d = (float*)malloc(n * sizeof(float));
+    if (!d) return 1;
+    int rc = codec == 0 ? oracle_decompress_minmax_u8((const uint8_t*)codes, meta, n, chunk, d)
+                        : oracle_decompress_sign((const uint32_t*)codes, meta, n, chunk, d);
+    if (rc) { free(d); return rc; }
+    adam_update(d, n, param, m, v, lr, beta1, beta2, eps, weight_decay, variance_frozen);
     free(d);
     return 0;
+}
+
+/* The same step after a top-K round: d = decode of the sparse entries, +0 everywhere else, then the identical update
+ * on EVERY element (where nothing was kept the momentum decays by beta1, the variance by beta2, and the parameter
+ * still moves by the decayed momentum). */
+int oracle_decompress_adam_step_topk(const uint16_t* idx, const float* val, size_t n, size_t chunk, size_t keep,
+                                     float* param, float* m, float* v, float lr, float beta1, float beta2, float eps,
+                                     float weight_decay, int variance_frozen)
+{
+    if (!idx || !val || !param || !m || !v || n == 0 || !chunk_ok(chunk) || keep < 1 || keep > chunk) return 1;
+    float* d = (float*)malloc(n * sizeof(float));
+    if (!d) return 1;
+    int rc = oracle_decompress_topk(idx, val, n, chunk, keep, d);
+    if (!rc) adam_update(d, n, param, m, v, lr, beta1, beta2, eps, weight_decay, variance_frozen);
+    free(d);
+    return rc;
 }
 
 /*

@@ -160,3 +160,84 @@ def test_one_bit_adam_compression_stage_tracks_uncompressed_momentum(oracle):
     # (a few times the typical magnitude), while both sums grow linearly with T
     assert np.max(resid) <= 12 * mean_abs
     assert np.max(np.abs(acc_exact)) >= 0.5 * T * 5e-3 * (1 - beta)
+
+
+def test_adam_after_topk_keep_everything_is_torch_adam(oracle):
+    """keep = C makes the top-K round lossless, so three steps must follow torch.optim.Adam's state and the fp64
+    parameter formula exactly as the dense step does."""
+    rng = np.random.default_rng(20)
+    n, C = 3 * 256 + 100, 256
+    p0 = rng.standard_normal(n).astype(np.float32)
+    p, m, v = p0.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32)
+    tp = torch.nn.Parameter(torch.from_numpy(p0.copy()).double())
+    opt = torch.optim.Adam([tp], lr=1e-3, betas=(float(np.float32(0.9)), float(np.float32(0.999))), eps=1e-8)
+    p64 = p0.astype(np.float64)
+    for it in range(3):
+        g = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+        idx, val = oracle.compress_topk(g, None, C, C)
+        oracle.decompress_adam_step_topk(idx, val, n, C, C, p, m, v, 1e-3, 0.9, 0.999, 1e-8)
+        tp.grad = torch.from_numpy(g).double()
+        opt.step()
+        st = opt.state[tp]
+        em, ev = st["exp_avg"].numpy(), st["exp_avg_sq"].numpy()
+        assert np.max(np.abs(m - em)) <= 4e-7 * np.max(np.abs(em))
+        assert np.max(np.abs(v - ev)) <= 4e-7 * np.max(np.abs(ev))
+        p64 = p64 - 1e-3 * em / (np.sqrt(ev) + 1e-8)
+        assert np.max(np.abs(p - p64)) <= 1e-6 * (it + 1)
+
+
+def test_adam_after_topk_where_nothing_is_kept(oracle):
+    """Dropped positions see a zero gradient: m decays by beta1 and v by beta2 exactly (one multiplication each), the
+    parameter moves by the decayed momentum; kept positions follow the dense recurrences; with the variance frozen the
+    momentum is REPLACED by the decoded tensor (0 where nothing was kept) and v stays."""
+    rng = np.random.default_rng(21)
+    n, C, keep = 4 * 256, 256, 8
+    g = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+    idx, val = oracle.compress_topk(g, None, C, keep)
+    kept = np.zeros(n, bool)
+    for c in range(n // C):
+        kept[c * C + idx[c * keep:(c + 1) * keep].astype(np.int64)] = True
+    assert kept.sum() == keep * (n // C)
+    p0 = rng.standard_normal(n).astype(np.float32)
+    m0 = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+    v0 = (np.abs(rng.standard_normal(n)) * 1e-4 + 1e-6).astype(np.float32)
+    b1, b2, lr, eps = np.float32(0.9), np.float32(0.999), np.float32(1e-2), np.float32(1e-8)
+    p, m, v = p0.copy(), m0.copy(), v0.copy()
+    oracle.decompress_adam_step_topk(idx, val, n, C, keep, p, m, v, float(lr), float(b1), float(b2), float(eps))
+    d = ~kept
+    assert np.array_equal(m[d], b1 * m0[d]) and np.array_equal(v[d], b2 * v0[d])
+    want = p0[d].astype(np.float64) - float(lr) * m[d].astype(np.float64) / (np.sqrt(v[d].astype(np.float64)) + float(eps))
+    assert np.max(np.abs(p[d] - want)) <= 1e-6
+    mk = float(b1) * m0[kept].astype(np.float64) + (1 - float(b1)) * g[kept].astype(np.float64)
+    vk = float(b2) * v0[kept].astype(np.float64) + (1 - float(b2)) * g[kept].astype(np.float64) ** 2
+    assert np.max(np.abs(m[kept] - mk)) <= 1e-7 and np.max(np.abs(v[kept] - vk)) <= 1e-9
+    # frozen variance
+    p, m, v = p0.copy(), m0.copy(), v0.copy()
+    oracle.decompress_adam_step_topk(idx, val, n, C, keep, p, m, v, float(lr), float(b1), float(b2), float(eps), 0.0, True)
+    assert np.array_equal(v, v0)
+    assert not m[d].any() and np.array_equal(m[kept], g[kept])
+    assert np.array_equal(p[d], p0[d])                      # a zero momentum moves nothing
+    want = p0[kept].astype(np.float64) - float(lr) * g[kept].astype(np.float64) / (np.sqrt(v0[kept].astype(np.float64)) + float(eps))
+    assert np.max(np.abs(p[kept] - want)) <= 1e-6
+
+
+def test_adam_after_topk_equals_the_dense_step_on_the_decoded_tensor(oracle):
+    """The composition itself: the same bits as the pinned dense step fed with a lossless MinMax coding of the decoded
+    top-K tensor (values on a 255-step grid so that the MinMax round trip is exact)."""
+    rng = np.random.default_rng(22)
+    n, C, keep = 2 * 256, 256, 16
+    g = grid_values(rng, n, C)
+    idx, val = oracle.compress_topk(g, None, C, keep)
+    dec = oracle.decompress_topk(idx, val, n, C, keep)
+    dec[0::C], dec[1::C] = np.float32(-128 * 2.0 ** -10), np.float32(127 * 2.0 ** -10)   # span the grid in every chunk
+    idx2, val2 = oracle.compress_topk(dec, None, C, C)                                   # lossless top-K of it
+    codes, mm = lossless_codes(oracle, dec, C)
+    for frozen in (False, True):
+        for wd in (0.0, 0.01):
+            a = [rng.standard_normal(n).astype(np.float32), (rng.standard_normal(n) * 1e-2).astype(np.float32),
+                 (np.abs(rng.standard_normal(n)) * 1e-4).astype(np.float32)]
+            b = [t.copy() for t in a]
+            oracle.decompress_adam_step_topk(idx2, val2, n, C, C, a[0], a[1], a[2], 1e-3, 0.9, 0.999, 1e-8, wd, frozen)
+            oracle.decompress_adam_step(0, codes, mm, n, C, b[0], b[1], b[2], 1e-3, 0.9, 0.999, 1e-8, wd, frozen)
+            for x, y in zip(a, b):
+                assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
