@@ -355,6 +355,16 @@ int bagua_decompress_adam_step(int codec, const void* codes, const float* meta, 
                                int variance_frozen, void* stream);
 
 /*
+ * The same step after a round with the per-chunk top-K codec (Section 3.2 top-K; Section 3.5 optimizer on the flattened
+ * bucket): d = the decoded sparse entries, +0 at every other element, then the update above on EVERY element (where
+ * nothing was kept m decays by beta1, v by beta2, and p still moves by the decayed momentum).  idx / val / keep as
+ * bagua_decompress_topk; param, m, v as above.
+ */
+int bagua_decompress_adam_step_topk(const uint16_t* idx, const float* val, size_t n, size_t chunk, size_t keep,
+                                    float* param, float* m, float* v, float lr, float beta1, float beta2, float eps,
+                                    float weight_decay, int variance_frozen, void* stream);
+
+/*
  * Worker side of the compression stage of 1-bit Adam (Section 4.1: 1-bit Adam = C_LP_S with error compensation,
  * applied to the momentum): compresses the local momentum u = beta1*m + (1-beta1)*g exactly as
  * bagua_sign_compress_ef compresses x (same codec, error state, layouts and limits).

@@ -30,7 +30,7 @@ EXPORTS = (
     "bagua_decompress_adam_step", "bagua_momentum_sign_compress_ef", "bagua_lp_encode", "bagua_lp_apply_mix", "bagua_bucket_flatten_static",
     "bagua_batch_workspace_bytes", "bagua_compress_minmax_u8_batched", "bagua_sign_compress_ef_batched",
     "bagua_decompress_reduce_recompress_batched", "bagua_bucket_flatten_batched_run", "bagua_probe_read",
-    "bagua_probe_streams", "bagua_flatten_sign_compress_ef", "bagua_decompress_unflatten", "bagua_reduce_compress_sign_ef", "bagua_decompress_sgd_step_topk",
+    "bagua_probe_streams", "bagua_flatten_sign_compress_ef", "bagua_decompress_unflatten", "bagua_reduce_compress_sign_ef", "bagua_decompress_sgd_step_topk", "bagua_decompress_adam_step_topk",
 )
 
 
@@ -80,6 +80,7 @@ def _load():
     lib.bagua_reduce_compress_sign_ef.argtypes = [vp, i32, vp, sz, sz, vp, vp, vp]
     lib.bagua_decompress_sgd_step_topk.argtypes = [vp, vp, sz, sz, sz, vp, vp, ctypes.c_float, ctypes.c_float,
                                                    ctypes.c_float, vp]
+    lib.bagua_decompress_adam_step_topk.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, cf, cf, cf, cf, cf, i32, vp]
     lib.bagua_probe_read.argtypes = [vp, sz, vp, vp]
     lib.bagua_probe_streams.argtypes = [vp, vp, vp, i32, i32, i32, i32, sz, vp]
     lib.bagua_batch_workspace_bytes.argtypes = [sz, i32]
@@ -356,6 +357,14 @@ def bagua_decompress_sgd_step_topk(idx, val, n, chunk, keep, param, momentum_buf
         _ptr(idx, torch.int16, 2 * keep * num_chunks(n, chunk)), _ptr(val, torch.float32, 4 * keep * num_chunks(n, chunk)),
         n, chunk, keep, _ptr(param, torch.float32, 4 * n), _ptr(momentum_buf, torch.float32, 4 * n), lr, momentum,
         weight_decay, _stream(stream)))
+
+
+def bagua_decompress_adam_step_topk(idx, val, n, chunk, keep, param, m, v, lr, beta1=0.9, beta2=0.999, eps=1e-8,
+                                    weight_decay=0.0, variance_frozen=False, stream=None):
+    _check("bagua_decompress_adam_step_topk", _lib.bagua_decompress_adam_step_topk(
+        _ptr(idx, torch.int16, 2 * keep * num_chunks(n, chunk)), _ptr(val, torch.float32, 4 * keep * num_chunks(n, chunk)),
+        n, chunk, keep, _ptr(param, torch.float32, 4 * n), _ptr(m, torch.float32, 4 * n), _ptr(v, torch.float32, 4 * n),
+        lr, beta1, beta2, eps, weight_decay, int(bool(variance_frozen)), _stream(stream)))
 
 
 def bagua_compress_topk_ef(x, residual, chunk, keep, idx, val, stream=None):

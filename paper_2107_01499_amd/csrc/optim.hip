@@ -205,6 +205,81 @@ k_decompress_sgd_topk(const uint16_t* __restrict__ idx, const float* __restrict_
     }
 }
 
+// Adam-type update after a top-K round: the chunk's decoded tensor is built in LDS as above, then every element is
+// updated as in k_decompress_adam.
+template <int RPW, bool FROZEN, bool WD>
+__global__ void __launch_bounds__(wg_threads_max(RPW))
+k_decompress_adam_topk(const uint16_t* __restrict__ idx, const float* __restrict__ val, size_t n, uint32_t chunk,
+                       uint32_t keep, float* __restrict__ param, float* __restrict__ mbuf, float* __restrict__ vbuf,
+                       float lr, float beta1, float omb1, float beta2, float omb2, float eps, float wd)
+{
+    extern __shared__ float s_g[];   // chunk floats
+    const size_t c = blockIdx.x;
+    const size_t base = c * static_cast<size_t>(chunk);
+    const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
+    const int wave = wave_index(), lane = threadIdx.x & 63;
+
+    // parameters and optimizer state do not depend on the decode: request them first
+    f4 p[RPW], m[RPW], v[RPW];
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        const int off = static_cast<int>(wave * RPW + i) * kRow;
+        const int remain = len - off;
+        p[i] = f4{0.f, 0.f, 0.f, 0.f};
+        m[i] = p[i];
+        v[i] = f4{1.f, 1.f, 1.f, 1.f};
+        if (remain > 0) {
+            p[i] = load_row(param + base + off, lane, remain, 0.0f);
+            v[i] = load_row(vbuf + base + off, lane, remain, 1.0f);
+            if (!FROZEN) m[i] = load_row(mbuf + base + off, lane, remain, 0.0f);
+        }
+    }
+    for (uint32_t e = threadIdx.x * 4; e < chunk; e += blockDim.x * 4)
+        *reinterpret_cast<f4*>(s_g + e) = f4{0.f, 0.f, 0.f, 0.f};
+    __syncthreads();
+    for (uint32_t s = threadIdx.x; s < keep; s += blockDim.x) {
+        const uint32_t q = idx[c * keep + s];
+        if (q != 0xFFFFu && q < chunk) s_g[q] = val[c * keep + s];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        const int off = static_cast<int>(wave * RPW + i) * kRow;
+        const int remain = len - off;
+        if (remain <= 0) continue;
+        const f4 d = *reinterpret_cast<const f4*>(s_g + off + lane * 4);
+        f4 mi = d;
+        if (!FROZEN) {
+            mi.x = beta1 * m[i].x + omb1 * d.x;
+            mi.y = beta1 * m[i].y + omb1 * d.y;
+            mi.z = beta1 * m[i].z + omb1 * d.z;
+            mi.w = beta1 * m[i].w + omb1 * d.w;
+            v[i].x = beta2 * v[i].x + omb2 * (d.x * d.x);
+            v[i].y = beta2 * v[i].y + omb2 * (d.y * d.y);
+            v[i].z = beta2 * v[i].z + omb2 * (d.z * d.z);
+            v[i].w = beta2 * v[i].w + omb2 * (d.w * d.w);
+            store_row(vbuf + base + off, lane, remain, v[i]);
+        }
+        store_row(mbuf + base + off, lane, remain, mi);
+        f4 u;
+        u.x = mi.x / (sqrtf(v[i].x) + eps);
+        u.y = mi.y / (sqrtf(v[i].y) + eps);
+        u.z = mi.z / (sqrtf(v[i].z) + eps);
+        u.w = mi.w / (sqrtf(v[i].w) + eps);
+        if (WD) {
+            u.x = u.x + wd * p[i].x;
+            u.y = u.y + wd * p[i].y;
+            u.z = u.z + wd * p[i].z;
+            u.w = u.w + wd * p[i].w;
+        }
+        p[i].x = p[i].x - lr * u.x;
+        p[i].y = p[i].y - lr * u.y;
+        p[i].z = p[i].z - lr * u.z;
+        p[i].w = p[i].w - lr * u.w;
+        store_row(param + base + off, lane, remain, p[i]);
+    }
+}
+
 }  // namespace bagua
 
 using namespace bagua;
@@ -324,5 +399,43 @@ extern "C" int bagua_decompress_sgd_step_topk(const uint16_t* idx, const float* 
     else if (wd) { BAGUA_TS(false, true) }
     else { BAGUA_TS(false, false) }
 #undef BAGUA_TS
+    return launch_status();
+}
+
+extern "C" int bagua_decompress_adam_step_topk(const uint16_t* idx, const float* val, size_t n, size_t chunk, size_t keep,
+                                               float* param, float* m, float* v, float lr, float beta1, float beta2,
+                                               float eps, float weight_decay, int variance_frozen, void* stream)
+{
+    if (!idx || !val || !param || !m || !v || n == 0 || !chunk_ok(chunk) || keep < 1 || keep > chunk)
+        return BAGUA_ERR_INVALID_ARG;
+    const size_t nc = num_chunks(n, chunk);
+    {
+        RangeCheck rc;
+        rc.reads(idx, nc * keep * sizeof(uint16_t));
+        rc.reads(val, nc * keep * sizeof(float));
+        rc.writes(param, n * sizeof(float));
+        rc.writes(m, n * sizeof(float));
+        rc.writes(v, n * sizeof(float));
+        if (!rc.disjoint()) return BAGUA_ERR_INVALID_ARG;
+    }
+    if (nc > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    if (!aligned2(idx) || !aligned4(val) || !aligned16(param) || !aligned16(m) || !aligned16(v)) return BAGUA_ERR_ALIGNMENT;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint32_t ch = static_cast<uint32_t>(chunk), kp = static_cast<uint32_t>(keep);
+    const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
+    const bool frozen = variance_frozen != 0, wd = weight_decay != 0.0f;
+    const int rows = static_cast<int>(chunk / kRow);
+    const int rpw = pick_rpw(rows, 2);
+    dim3 grid(static_cast<unsigned>(nc)), block(64 * ((rows + rpw - 1) / rpw));
+    const size_t lds = chunk * sizeof(float);
+#define BAGUA_TA(FRv, WDv)                                                                                         \
+    BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_decompress_adam_topk<RPW, FRv, WDv>), grid, block, lds, s, idx,  \
+                                               val, n, ch, kp, param, m, v, lr, beta1, omb1, beta2, omb2, eps,     \
+                                               weight_decay))
+    if (frozen && wd) { BAGUA_TA(true, true) }
+    else if (frozen) { BAGUA_TA(true, false) }
+    else if (wd) { BAGUA_TA(false, true) }
+    else { BAGUA_TA(false, false) }
+#undef BAGUA_TA
     return launch_status();
 }

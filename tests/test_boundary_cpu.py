@@ -215,6 +215,11 @@ def test_validation_of_the_batched_and_fused_entry_points_without_gpu(bg):
     assert lib.bagua_decompress_sgd_step_topk(A, B, 64, 256, 0, Cc, None, 0.1, 0.0, 0.0, None) == INVALID   # keep = 0
     assert lib.bagua_decompress_sgd_step_topk(A, B, 64, 256, 300, Cc, None, 0.1, 0.0, 0.0, None) == INVALID  # keep > chunk
     assert lib.bagua_decompress_sgd_step_topk(A, B, 64, 256, 8, Cc + 4, None, 0.1, 0.0, 0.0, None) == ALIGN
+    at = lib.bagua_decompress_adam_step_topk
+    assert at(A, B, 64, 256, 0, Cc, D, W, 0.1, 0.9, 0.999, 1e-8, 0.0, 0, None) == INVALID          # keep = 0
+    assert at(A, B, 64, 256, 8, Cc, None, W, 0.1, 0.9, 0.999, 1e-8, 0.0, 0, None) == INVALID       # no momentum buffer
+    assert at(A, B, 64, 256, 8, Cc, D, D, 0.1, 0.9, 0.999, 1e-8, 0.0, 0, None) == INVALID          # m aliases v
+    assert at(A, B, 64, 256, 8, Cc, D + 4, W, 0.1, 0.9, 0.999, 1e-8, 0.0, 0, None) == ALIGN
     # probes
     assert lib.bagua_probe_read(None, 10, B, None) == INVALID
     assert lib.bagua_probe_streams(one(A), one(B), None, 1, 1, 0, 1, 100, None) == INVALID             # n not a multiple of 256

@@ -117,3 +117,27 @@ def test_one_bit_adam_iteration_end_to_end(bg, oracle):
         bit_equal(delta_g[j], delta[j], "delta worker %d" % j)
     bit_equal(eps_g, eps, "eps")
     bit_equal(v_g, v, "v untouched")
+
+
+@pytest.mark.parametrize("n,C,keep", [(1, 256, 1), (257, 256, 7), (3 * 4096 + 77, 4096, 128), (70001, 2048, 2048),
+                                      (40000, 16384, 500), (5 * 768 + 3, 768, 1)])
+@pytest.mark.parametrize("frozen,wd", [(False, 0.0), (True, 0.0), (False, 1e-2), (True, 1e-2)])
+def test_decompress_adam_step_topk(bg, oracle, n, C, keep, frozen, wd):
+    """Decode of a top-K round fused with the Adam-type step: three steps with the state carried along on both sides."""
+    print("adam topk n=%d C=%d keep=%d frozen=%s wd=%g" % (n, C, keep, frozen, wd), flush=True)
+    r = np.random.default_rng(n + C + keep)
+    p_o = r.standard_normal(n).astype(np.float32)
+    m_o = (r.standard_normal(n) * 1e-3).astype(np.float32)
+    v_o = (r.random(n) * 1e-5).astype(np.float32)
+    v_o[::7] = 0.0
+    p_g, m_g, v_g = dev(p_o), dev(m_o), dev(v_o)
+    for it in range(3):
+        x = (r.standard_t(3, n) * 1e-3).astype(np.float32)
+        x[r.integers(0, n, max(1, n // 40))] = 0.0
+        idx, val = oracle.compress_topk(x, None, C, keep)
+        oracle.decompress_adam_step_topk(idx, val, n, C, keep, p_o, m_o, v_o, 1e-3, 0.9, 0.999, 1e-8, wd, frozen)
+        bg.bagua_decompress_adam_step_topk(dev(idx.view(np.int16)), dev(val), n, C, keep, p_g, m_g, v_g, 1e-3, 0.9, 0.999,
+                                           1e-8, wd, frozen)
+        bit_equal(p_g, p_o, "p step %d" % it)
+        bit_equal(m_g, m_o, "m step %d" % it)
+        bit_equal(v_g, v_o, "v step %d" % it)

@@ -407,3 +407,11 @@ def test_random_batched_and_intra_node(bg, oracle, seed):
     same(p_g, p_o, "topk sgd p")
     if use_mom:
         same(mo_g, mo_o, "topk sgd m")
+    # Adam-type step fed by the same top-K round
+    v_o = np.abs(values(r, n)).astype(np.float32) * np.float32(1e-3)
+    a_o = [p_o.copy(), m_o.copy(), v_o]
+    a_g = [dev(t) for t in a_o]
+    frozen = bool(r.integers(0, 2))
+    oracle.decompress_adam_step_topk(io, vo, n, C, keep, a_o[0], a_o[1], a_o[2], 1e-3, 0.9, 0.999, 1e-8, wd, frozen)
+    bg.bagua_decompress_adam_step_topk(dev(io), dev(vo), n, C, keep, a_g[0], a_g[1], a_g[2], 1e-3, 0.9, 0.999, 1e-8, wd, frozen)
+    same(a_g[0], a_o[0], "topk adam p"); same(a_g[1], a_o[1], "topk adam m"); same(a_g[2], a_o[2], "topk adam v")
