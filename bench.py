@@ -142,7 +142,9 @@ class Workload:
         self._placer = None
         if self.placement == "spread":
             try:
-                self._placer = Placer(torch, SPREAD_GIB, WORKLOADS[name]["cfg"], WORKLOADS[name].get("mean_gap_gib", 1.0))
+                # separately allocated buckets are thousands of small buffers: a small gap after each
+                gap = 0.008 if layout == "buckets" else WORKLOADS[name].get("mean_gap_gib", 1.0)
+                self._placer = Placer(torch, SPREAD_GIB, WORKLOADS[name]["cfg"], gap)
             except RuntimeError as e:       # not enough free HBM for the reservation: say so and run packed
                 print("bench: %d GiB reservation failed (%s); placement packed" % (SPREAD_GIB, str(e).splitlines()[0]),
                       file=sys.stderr, flush=True)
@@ -226,9 +228,15 @@ class Workload:
         def views(t, div=1, mul=1):
             """Per-unit views of a flat tensor whose index is element_index * mul / div; in the "buckets" layout every
             unit gets an allocation of its own instead (the flat tensor is dropped by the caller)."""
+            if self.batched:        # every unit an allocation (or, spread, a place in the reservation) of its own
+                vs = [t[lo * mul // div:-(-(lo + ln) * mul // div)] for lo, ln, _, _ in self.units]
+                out = []
+                for v in vs:
+                    pv = place(v)
+                    out.append(v.clone() if pv is v else pv)      # packed, or the reservation is exhausted
+                return out
             t = place(t)
-            vs = [t[lo * mul // div:-(-(lo + ln) * mul // div)] for lo, ln, _, _ in self.units]
-            return [v.clone() for v in vs] if self.batched else vs
+            return [t[lo * mul // div:-(-(lo + ln) * mul // div)] for lo, ln, _, _ in self.units]
 
         # ---- gradients: layer tensors (when flatten runs) or ready-made flat buckets
         self.sets = w["sets"]
