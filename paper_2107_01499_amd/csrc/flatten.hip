@@ -34,7 +34,7 @@ __device__ __forceinline__ void flatten_tile(const TensorDesc* __restrict__ desc
     if (lo0 < T && tile0 + kTile <= bucket_numel) {
         const TensorDesc d = desc[lo0];   // uniform: scalar loads
         if (d.dst <= tile0 && tile0 + kTile <= d.dst + d.numel) {
-            const float* s = d.src + (tile0 - d.dst);
+            const float* s = tensor_ptr(d) + (tile0 - d.dst);
             if ((reinterpret_cast<uintptr_t>(s) & 15u) == 0) {
                 const f4* s4 = reinterpret_cast<const f4*>(s);
                 f4* b4 = reinterpret_cast<f4*>(bucket + tile0);
@@ -71,7 +71,7 @@ __device__ __forceinline__ void flatten_tile(const TensorDesc* __restrict__ desc
         if (t < T) {
             const TensorDesc d = desc[t];
             if (d.dst <= e && e + 4 <= d.dst + d.numel) {
-                const float* s = d.src + (e - d.dst);
+                const float* s = tensor_ptr(d) + (e - d.dst);
                 const f4_a4 u = __builtin_nontemporal_load(reinterpret_cast<const f4_a4*>(s));   // any 4-byte alignment
                 v = f4{u.x, u.y, u.z, u.w};
                 done = true;
@@ -109,10 +109,10 @@ k_flatten_batched(BatchView bv)
     const uint32_t b = batch_find(bv, unit);
     const uint64_t* e = bv.entries + static_cast<size_t>(b) * bv.entry_words;
     const size_t T = e[1];
-    const unsigned char* ws = reinterpret_cast<const unsigned char*>(e[0]);
+    const unsigned char* ws = table_ptr<const unsigned char>(e[0]);
     const size_t desc_bytes = ((T ? T : 1) * sizeof(TensorDesc) + 15) & ~static_cast<size_t>(15);
     flatten_tile(reinterpret_cast<const TensorDesc*>(ws), reinterpret_cast<const uint32_t*>(ws + desc_bytes),
-                 static_cast<uint32_t>(T), reinterpret_cast<float*>(e[2]), e[3], unit - bv.first_unit[b],
+                 static_cast<uint32_t>(T), table_ptr<float>(e[2]), e[3], unit - bv.first_unit[b],
                  (blockIdx.x % kTileWaves) * kWave + threadIdx.x);
 }
 
@@ -130,7 +130,7 @@ k_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ ti
     if (lo0 < T && tile0 + kTile <= bucket_numel) {
         const TensorDesc d = desc[lo0];
         if (d.dst <= tile0 && tile0 + kTile <= d.dst + d.numel) {
-            float* s = const_cast<float*>(d.src) + (tile0 - d.dst);
+            float* s = const_cast<float*>(tensor_ptr(d)) + (tile0 - d.dst);
             if ((reinterpret_cast<uintptr_t>(s) & 15u) == 0) {
                 f4* s4 = reinterpret_cast<f4*>(s);
                 const f4* b4 = reinterpret_cast<const f4*>(bucket + tile0);
@@ -166,7 +166,7 @@ k_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ ti
         if (t < T && e + 4 <= bucket_numel) {
             const TensorDesc d = desc[t];
             if (d.dst <= e && e + 4 <= d.dst + d.numel) {
-                float* s = const_cast<float*>(d.src) + (e - d.dst);
+                float* s = const_cast<float*>(tensor_ptr(d)) + (e - d.dst);
                 const f4 v = ld_stream(reinterpret_cast<const f4*>(bucket + e));
                 __builtin_nontemporal_store(f4_a4{v.x, v.y, v.z, v.w}, reinterpret_cast<f4_a4*>(s));   // any 4-byte alignment
                 continue;
@@ -176,7 +176,7 @@ k_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ ti
             const size_t eq = e + q;
             if (eq >= bucket_numel) break;
             while (t < T && desc[t].dst + desc[t].numel <= eq) ++t;
-            if (t < T && desc[t].dst <= eq) const_cast<float*>(desc[t].src)[eq - desc[t].dst] = bucket[eq];
+            if (t < T && desc[t].dst <= eq) const_cast<float*>(tensor_ptr(desc[t]))[eq - desc[t].dst] = bucket[eq];
         }
     }
 }
@@ -229,7 +229,7 @@ k_decompress_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __re
         const size_t tile0 = tile * kTile;
         if (lo0[i] < T && tile0 + kTile <= n) {
             const TensorDesc d = desc[lo0[i]];
-            if (d.dst <= tile0 && tile0 + kTile <= d.dst + d.numel) tile_dst[i] = const_cast<float*>(d.src) + (tile0 - d.dst);
+            if (d.dst <= tile0 && tile0 + kTile <= d.dst + d.numel) tile_dst[i] = const_cast<float*>(tensor_ptr(d)) + (tile0 - d.dst);
         }
     }
     // 3. decode and scatter
@@ -255,7 +255,9 @@ k_decompress_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __re
         }
         const size_t e = e0 + lane * 4;
         if (tile_dst[i]) {
-            __builtin_nontemporal_store(f4_a4{v.x, v.y, v.z, v.w}, reinterpret_cast<f4_a4*>(tile_dst[i] + (e - tile0)));
+            typedef __attribute__((address_space(1))) float* global_ptr;     // tile_dst[i] came from the tensor table
+            float* gd = (float*)reinterpret_cast<global_ptr>(reinterpret_cast<uintptr_t>(tile_dst[i]));
+            __builtin_nontemporal_store(f4_a4{v.x, v.y, v.z, v.w}, reinterpret_cast<f4_a4*>(gd + (e - tile0)));
             continue;
         }
         if (e >= n) continue;
@@ -270,7 +272,7 @@ k_decompress_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __re
         if (t < T && e + 4 <= n) {
             const TensorDesc d = desc[t];
             if (d.dst <= e && e + 4 <= d.dst + d.numel) {
-                float* s = const_cast<float*>(d.src) + (e - d.dst);
+                float* s = const_cast<float*>(tensor_ptr(d)) + (e - d.dst);
                 __builtin_nontemporal_store(f4_a4{v.x, v.y, v.z, v.w}, reinterpret_cast<f4_a4*>(s));
                 continue;
             }
@@ -280,7 +282,7 @@ k_decompress_unflatten(const TensorDesc* __restrict__ desc, const uint32_t* __re
             const size_t eq = e + r;
             if (eq >= n) break;
             while (t < T && desc[t].dst + desc[t].numel <= eq) ++t;
-            if (t < T && desc[t].dst <= eq) const_cast<float*>(desc[t].src)[eq - desc[t].dst] = q[r];
+            if (t < T && desc[t].dst <= eq) const_cast<float*>(tensor_ptr(desc[t]))[eq - desc[t].dst] = q[r];
         }
     }
 }

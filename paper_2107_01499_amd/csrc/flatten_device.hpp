@@ -10,6 +10,15 @@ struct TensorDesc {
     size_t dst;  // element offset in the bucket
 };
 
+// The tensor's pointer as read from the table on the device.  Cast through the global address space: a pointer loaded
+// from memory is otherwise a generic one, and every access through it a "flat" instruction that counts against both
+// wait counters and cannot stay in flight past LDS or scalar-memory waits.
+__device__ __forceinline__ const float* tensor_ptr(const TensorDesc& d)
+{
+    typedef __attribute__((address_space(1))) const float* global_ptr;
+    return (const float*)reinterpret_cast<global_ptr>(reinterpret_cast<uintptr_t>(d.src));
+}
+
 #ifndef BAGUA_FLATTEN_TILE
 #define BAGUA_FLATTEN_TILE 1024
 #endif
@@ -23,7 +32,7 @@ inline size_t num_tiles(size_t bucket_numel) { return (bucket_numel + kTile - 1)
 __device__ __forceinline__ float element_at(const TensorDesc* __restrict__ desc, uint32_t& t, uint32_t T, size_t e)
 {
     while (t < T && desc[t].dst + desc[t].numel <= e) ++t;
-    if (t < T && desc[t].dst <= e) return desc[t].src[e - desc[t].dst];
+    if (t < T && desc[t].dst <= e) return tensor_ptr(desc[t])[e - desc[t].dst];
     return 0.0f;
 }
 
@@ -64,7 +73,7 @@ __device__ __forceinline__ f4 gather_row(const TensorDesc* __restrict__ desc, co
     if (lo < T && remain >= kRow) {
         const TensorDesc d = desc[lo];
         if (d.dst <= e0 && e0 + kRow <= d.dst + d.numel) {
-            const float* s = d.src + (e0 - d.dst);
+            const float* s = tensor_ptr(d) + (e0 - d.dst);
             if ((reinterpret_cast<uintptr_t>(s) & 15u) == 0) return ld_stream(reinterpret_cast<const f4*>(s) + lane);
             return load_row_shifted(s, lane);
         }

@@ -66,8 +66,8 @@ k_compress_minmax_batched(BatchView bv, uint32_t chunk)
     __shared__ float s_red[2 * kMaxWaves];
     const uint32_t b = batch_find(bv, blockIdx.x);
     const uint64_t* e = bv.entries + static_cast<size_t>(b) * bv.entry_words;
-    compress_minmax_chunk<RPW, EF>(reinterpret_cast<const float*>(e[0]), reinterpret_cast<float*>(e[1]), e[4], chunk,
-                                   reinterpret_cast<uint8_t*>(e[2]), reinterpret_cast<float*>(e[3]),
+    compress_minmax_chunk<RPW, EF>(table_ptr<const float>(e[0]), table_ptr<float>(e[1]), e[4], chunk,
+                                   table_ptr<uint8_t>(e[2]), table_ptr<float>(e[3]),
                                    blockIdx.x - bv.first_unit[b], s_red);
 }
 
@@ -83,8 +83,8 @@ struct DrrTableSrc {   // pointers in the kernel arguments
 struct DrrEntrySrc {   // pointers in a batch entry: [eps, codes_out, meta_out, out, n, code[0..k), meta[0..k)]
     const uint64_t* e;
     int k;
-    __device__ __forceinline__ const void* code(int j) const { return reinterpret_cast<const void*>(e[5 + j]); }
-    __device__ __forceinline__ const float* meta(int j) const { return reinterpret_cast<const float*>(e[5 + k + j]); }
+    __device__ __forceinline__ const void* code(int j) const { return table_ptr<const void>(e[5 + j]); }
+    __device__ __forceinline__ const float* meta(int j) const { return table_ptr<const float>(e[5 + k + j]); }
 };
 
 template <int RPW, bool EF, bool OUT, typename SRC>
@@ -197,9 +197,9 @@ k_drr_minmax_batched(BatchView bv, int k, float inv_k, uint32_t chunk)
     __shared__ float s_mn[BAGUA_MAX_WORKERS], s_step[BAGUA_MAX_WORKERS];
     const uint32_t b = batch_find(bv, blockIdx.x);
     const uint64_t* e = bv.entries + static_cast<size_t>(b) * bv.entry_words;
-    drr_minmax_chunk<RPW, EF, OUT>(DrrEntrySrc{e, k}, k, inv_k, reinterpret_cast<float*>(e[0]), e[4], chunk,
-                                   reinterpret_cast<uint8_t*>(e[1]), reinterpret_cast<float*>(e[2]),
-                                   reinterpret_cast<float*>(e[3]), blockIdx.x - bv.first_unit[b], s_red, s_mn, s_step);
+    drr_minmax_chunk<RPW, EF, OUT>(DrrEntrySrc{e, k}, k, inv_k, table_ptr<float>(e[0]), e[4], chunk,
+                                   table_ptr<uint8_t>(e[1]), table_ptr<float>(e[2]),
+                                   table_ptr<float>(e[3]), blockIdx.x - bv.first_unit[b], s_red, s_mn, s_step);
 }
 
 // ------------------------------------------------------------------------------------------

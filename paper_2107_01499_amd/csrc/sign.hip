@@ -84,8 +84,8 @@ k_sign_compress_batched(BatchView bv, uint32_t chunk)
     extern __shared__ float s_q[];
     const uint32_t b = batch_find(bv, blockIdx.x);
     const uint64_t* e = bv.entries + static_cast<size_t>(b) * bv.entry_words;
-    sign_compress_chunk<RPW, EF, false>(reinterpret_cast<const float*>(e[0]), reinterpret_cast<float*>(e[1]), e[4], chunk,
-                                        reinterpret_cast<uint32_t*>(e[2]), reinterpret_cast<float*>(e[3]), nullptr, 0.0f,
+    sign_compress_chunk<RPW, EF, false>(table_ptr<const float>(e[0]), table_ptr<float>(e[1]), e[4], chunk,
+                                        table_ptr<uint32_t>(e[2]), table_ptr<float>(e[3]), nullptr, 0.0f,
                                         0.0f, blockIdx.x - bv.first_unit[b], s_q);
 }
 
@@ -100,8 +100,8 @@ struct SignTableSrc {   // pointers in the kernel arguments
 struct SignEntrySrc {   // pointers in a batch entry: [eps, bits_out, scale_out, out, n, bits[0..k), scale[0..k)]
     const uint64_t* e;
     int k;
-    __device__ __forceinline__ const void* code(int j) const { return reinterpret_cast<const void*>(e[5 + j]); }
-    __device__ __forceinline__ const float* meta(int j) const { return reinterpret_cast<const float*>(e[5 + k + j]); }
+    __device__ __forceinline__ const void* code(int j) const { return table_ptr<const void>(e[5 + j]); }
+    __device__ __forceinline__ const float* meta(int j) const { return table_ptr<const float>(e[5 + k + j]); }
 };
 
 template <int RPW, bool EF, bool OUT, typename SRC>
@@ -291,9 +291,9 @@ k_drr_sign_batched(BatchView bv, int k, float inv_k, uint32_t chunk)
     extern __shared__ float s_q[];
     const uint32_t b = batch_find(bv, blockIdx.x);
     const uint64_t* e = bv.entries + static_cast<size_t>(b) * bv.entry_words;
-    drr_sign_chunk<RPW, EF, OUT>(SignEntrySrc{e, k}, k, inv_k, reinterpret_cast<float*>(e[0]), e[4], chunk,
-                                 reinterpret_cast<uint32_t*>(e[1]), reinterpret_cast<float*>(e[2]),
-                                 reinterpret_cast<float*>(e[3]), blockIdx.x - bv.first_unit[b], s_q);
+    drr_sign_chunk<RPW, EF, OUT>(SignEntrySrc{e, k}, k, inv_k, table_ptr<float>(e[0]), e[4], chunk,
+                                 table_ptr<uint32_t>(e[1]), table_ptr<float>(e[2]),
+                                 table_ptr<float>(e[3]), blockIdx.x - bv.first_unit[b], s_q);
 }
 
 __global__ void __launch_bounds__(kWave * kRowWaves)
