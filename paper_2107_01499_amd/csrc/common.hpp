@@ -109,6 +109,14 @@ struct MutPtrTable {
     void* p[BAGUA_MAX_WORKERS];
 };
 
+// Pacing of a wave's streaming loads in the worker-side kernels.  In a very large launch the memory system is
+// saturated and latency is mostly queueing: a wave that waits for each row before it requests the next keeps the
+// queues shorter, which the DRAM scheduler rewards (+3 % for the batched sign compression over 229 buckets of
+// 1.5 G elements, +0.5-1 % for the unbatched launches in an A/B on the same buffers); in a small launch the longer
+// chain of dependent requests costs 3 %.  The launchers pace from 2^28 elements per launch on.
+__device__ __forceinline__ void pace_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+inline int pace_for(size_t elements_per_launch) { return elements_per_launch >= (static_cast<size_t>(1) << 28) ? 1 : 0; }
+
 // Index of this wavefront in its workgroup, as a scalar.  The compiler cannot tell that threadIdx.x >> 6 is the same
 // in all 64 lanes and would carry every row offset and tail test derived from it through 64-bit vector arithmetic
 // and exec-mask branches; read from the first lane it lives in scalar registers.

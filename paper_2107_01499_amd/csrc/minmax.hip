@@ -17,7 +17,7 @@ namespace bagua {
 template <int RPW, bool EF>
 __device__ __forceinline__ void compress_minmax_chunk(const float* __restrict__ x, float* __restrict__ residual, size_t n,
                                                       uint32_t chunk, uint8_t* __restrict__ codes,
-                                                      float* __restrict__ minmax, size_t c, float* s_red)
+                                                      float* __restrict__ minmax, size_t c, float* s_red, int pace)
 {
     const size_t base = c * static_cast<size_t>(chunk);
     const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
@@ -30,6 +30,7 @@ __device__ __forceinline__ void compress_minmax_chunk(const float* __restrict__ 
         const int remain = len - off;
         v[i] = f4{0.f, 0.f, 0.f, 0.f};
         if (remain > 0) v[i] = load_row(x + base + off, lane, remain, 0.0f);
+        if (pace) pace_loads();
     }
     if (EF) {
 #pragma unroll
@@ -38,6 +39,7 @@ __device__ __forceinline__ void compress_minmax_chunk(const float* __restrict__ 
             const int remain = len - off;
             if (remain > 0) {
                 const f4 d = load_row(residual + base + off, lane, remain, 0.0f);
+                if (pace) pace_loads();
                 v[i].x = v[i].x + d.x;
                 v[i].y = v[i].y + d.y;
                 v[i].z = v[i].z + d.z;
@@ -52,23 +54,23 @@ __device__ __forceinline__ void compress_minmax_chunk(const float* __restrict__ 
 template <int RPW, bool EF>
 __global__ void __launch_bounds__(wg_threads_max(RPW))
 k_compress_minmax(const float* __restrict__ x, float* __restrict__ residual, size_t n, uint32_t chunk,
-                  uint8_t* __restrict__ codes, float* __restrict__ minmax)
+                  uint8_t* __restrict__ codes, float* __restrict__ minmax, int pace)
 {
     __shared__ float s_red[2 * kMaxWaves];
-    compress_minmax_chunk<RPW, EF>(x, residual, n, chunk, codes, minmax, blockIdx.x, s_red);
+    compress_minmax_chunk<RPW, EF>(x, residual, n, chunk, codes, minmax, blockIdx.x, s_red, pace);
 }
 
 // Batched: entry = [x, residual, codes, minmax, n]; unit = chunk.
 template <int RPW, bool EF>
 __global__ void __launch_bounds__(wg_threads_max(RPW))
-k_compress_minmax_batched(BatchView bv, uint32_t chunk)
+k_compress_minmax_batched(BatchView bv, uint32_t chunk, int pace)
 {
     __shared__ float s_red[2 * kMaxWaves];
     const uint32_t b = batch_find(bv, blockIdx.x);
     const uint64_t* e = bv.entries + static_cast<size_t>(b) * bv.entry_words;
     compress_minmax_chunk<RPW, EF>(table_ptr<const float>(e[0]), table_ptr<float>(e[1]), e[4], chunk,
                                    table_ptr<uint8_t>(e[2]), table_ptr<float>(e[3]),
-                                   blockIdx.x - bv.first_unit[b], s_red);
+                                   blockIdx.x - bv.first_unit[b], s_red, pace);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -234,10 +236,10 @@ int launch_compress_minmax(const float* x, float* residual, size_t n, size_t chu
     const uint32_t ch = static_cast<uint32_t>(chunk);
     if (residual) {
         BAGUA_DISPATCH_RPW_WORKER(rpw, hipLaunchKernelGGL((k_compress_minmax<RPW, true>), grid, block, 0, stream, x,
-                                                          residual, n, ch, codes, minmax))
+                                                          residual, n, ch, codes, minmax, pace_for(n)))
     } else {
         BAGUA_DISPATCH_RPW_WORKER(rpw, hipLaunchKernelGGL((k_compress_minmax<RPW, false>), grid, block, 0, stream, x,
-                                                          residual, n, ch, codes, minmax))
+                                                          residual, n, ch, codes, minmax, pace_for(n)))
     }
     return launch_status();
 }
@@ -359,9 +361,9 @@ extern "C" int bagua_compress_minmax_u8_batched(const float* const* x, float* co
     dim3 grid(static_cast<unsigned>(total)), block(64 * ((rows + rpw - 1) / rpw));
     const uint32_t ch = static_cast<uint32_t>(chunk);
     if (ef) {
-        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_compress_minmax_batched<RPW, true>), grid, block, 0, s, bv, ch))
+        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_compress_minmax_batched<RPW, true>), grid, block, 0, s, bv, ch, pace_for(total * chunk)))
     } else {
-        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_compress_minmax_batched<RPW, false>), grid, block, 0, s, bv, ch))
+        BAGUA_DISPATCH_RPW(rpw, hipLaunchKernelGGL((k_compress_minmax_batched<RPW, false>), grid, block, 0, s, bv, ch, pace_for(total * chunk)))
     }
     return launch_status();
 }

@@ -20,7 +20,7 @@ template <int RPW, bool EF, bool MOM>
 __device__ __forceinline__ void sign_compress_chunk(const float* __restrict__ x, float* __restrict__ residual, size_t n,
                                                     uint32_t chunk, uint32_t* __restrict__ bits,
                                                     float* __restrict__ scale, const float* __restrict__ mom,
-                                                    float beta1, float omb1, size_t c, float* s_q)
+                                                    float beta1, float omb1, size_t c, float* s_q, int pace)
 {
     const size_t base = c * static_cast<size_t>(chunk);
     const int len = static_cast<int>((n - base < chunk) ? (n - base) : chunk);
@@ -33,6 +33,7 @@ __device__ __forceinline__ void sign_compress_chunk(const float* __restrict__ x,
         const int remain = len - off;
         v[i] = f4{0.f, 0.f, 0.f, 0.f};
         if (remain > 0) v[i] = load_row(x + base + off, lane, remain, 0.0f);
+        if (pace) pace_loads();
     }
     if (MOM) {
 #pragma unroll
@@ -55,6 +56,7 @@ __device__ __forceinline__ void sign_compress_chunk(const float* __restrict__ x,
             const int remain = len - off;
             if (remain > 0) {
                 const f4 d = load_row(residual + base + off, lane, remain, 0.0f);
+                if (pace) pace_loads();
                 v[i].x = v[i].x + d.x;
                 v[i].y = v[i].y + d.y;
                 v[i].z = v[i].z + d.z;
@@ -70,23 +72,23 @@ template <int RPW, bool EF, bool MOM = false>
 __global__ void __launch_bounds__(wg_threads_max(RPW))
 k_sign_compress(const float* __restrict__ x, float* __restrict__ residual, size_t n, uint32_t chunk,
                 uint32_t* __restrict__ bits, float* __restrict__ scale, const float* __restrict__ mom, float beta1,
-                float omb1)
+                float omb1, int pace)
 {
     extern __shared__ float s_q[];
-    sign_compress_chunk<RPW, EF, MOM>(x, residual, n, chunk, bits, scale, mom, beta1, omb1, blockIdx.x, s_q);
+    sign_compress_chunk<RPW, EF, MOM>(x, residual, n, chunk, bits, scale, mom, beta1, omb1, blockIdx.x, s_q, pace);
 }
 
 // Batched: entry = [x, residual, bits, scale, n]; unit = chunk.
 template <int RPW, bool EF>
 __global__ void __launch_bounds__(wg_threads_max(RPW))
-k_sign_compress_batched(BatchView bv, uint32_t chunk)
+k_sign_compress_batched(BatchView bv, uint32_t chunk, int pace)
 {
     extern __shared__ float s_q[];
     const uint32_t b = batch_find(bv, blockIdx.x);
     const uint64_t* e = bv.entries + static_cast<size_t>(b) * bv.entry_words;
     sign_compress_chunk<RPW, EF, false>(table_ptr<const float>(e[0]), table_ptr<float>(e[1]), e[4], chunk,
                                         table_ptr<uint32_t>(e[2]), table_ptr<float>(e[3]), nullptr, 0.0f,
-                                        0.0f, blockIdx.x - bv.first_unit[b], s_q);
+                                        0.0f, blockIdx.x - bv.first_unit[b], s_q, pace);
 }
 
 // Server side with the sign codec: a = (sum_j +-scale_j) * inv_k in ascending j; w = a (+ eps).
@@ -343,10 +345,10 @@ int launch_sign_compress(const float* x, float* residual, size_t n, size_t chunk
     const uint32_t ch = static_cast<uint32_t>(chunk);
     if (residual) {
         BAGUA_DISPATCH_RPW_WORKER(g.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, true>), g.grid, g.block, g.lds, stream, x,
-                                                     residual, n, ch, bits, scale, nullptr, 0.0f, 0.0f))
+                                                     residual, n, ch, bits, scale, nullptr, 0.0f, 0.0f, pace_for(n)))
     } else {
         BAGUA_DISPATCH_RPW_WORKER(g.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, false>), g.grid, g.block, g.lds, stream, x,
-                                                     residual, n, ch, bits, scale, nullptr, 0.0f, 0.0f))
+                                                     residual, n, ch, bits, scale, nullptr, 0.0f, 0.0f, pace_for(n)))
     }
     return launch_status();
 }
@@ -440,10 +442,10 @@ extern "C" int bagua_momentum_sign_compress_ef(const float* g, const float* m, f
     const float omb1 = 1.0f - beta1;
     if (residual) {
         BAGUA_DISPATCH_RPW_WORKER(geo.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, true, true>), geo.grid, geo.block, geo.lds,
-                                                       s, g, residual, n, ch, bits, scale, m, beta1, omb1))
+                                                       s, g, residual, n, ch, bits, scale, m, beta1, omb1, pace_for(n)))
     } else {
         BAGUA_DISPATCH_RPW_WORKER(geo.rpw, hipLaunchKernelGGL((k_sign_compress<RPW, false, true>), geo.grid, geo.block, geo.lds,
-                                                       s, g, residual, n, ch, bits, scale, m, beta1, omb1))
+                                                       s, g, residual, n, ch, bits, scale, m, beta1, omb1, pace_for(n)))
     }
     return launch_status();
 }
@@ -491,9 +493,9 @@ extern "C" int bagua_sign_compress_ef_batched(const float* const* x, float* cons
     g.grid = dim3(static_cast<unsigned>(total));
     const uint32_t ch = static_cast<uint32_t>(chunk);
     if (ef) {
-        BAGUA_DISPATCH_RPW(g.rpw, hipLaunchKernelGGL((k_sign_compress_batched<RPW, true>), g.grid, g.block, g.lds, s, bv, ch))
+        BAGUA_DISPATCH_RPW(g.rpw, hipLaunchKernelGGL((k_sign_compress_batched<RPW, true>), g.grid, g.block, g.lds, s, bv, ch, pace_for(total * chunk)))
     } else {
-        BAGUA_DISPATCH_RPW(g.rpw, hipLaunchKernelGGL((k_sign_compress_batched<RPW, false>), g.grid, g.block, g.lds, s, bv, ch))
+        BAGUA_DISPATCH_RPW(g.rpw, hipLaunchKernelGGL((k_sign_compress_batched<RPW, false>), g.grid, g.block, g.lds, s, bv, ch, pace_for(total * chunk)))
     }
     return launch_status();
 }
