@@ -404,8 +404,29 @@ def _ws(workspace):
     return _ptr(workspace), workspace.numel() * workspace.element_size()
 
 
-def bagua_compress_minmax_u8_batched(xs, residuals, chunk, codes, minmaxs, workspace, stream=None):
-    """B buckets in one launch; xs/codes/minmaxs are lists of B tensors, residuals a list of B tensors or None."""
+class PreparedCall:
+    """A batched call with its pointer arrays already marshalled.  Marshalling thousands of tensors costs Python more
+    time than the launch takes on the GPU; a caller whose buffers stay where they are prepares once (prepare=True) and
+    then calls the object every step: that is only the C call (table build, upload launches, kernel launch)."""
+
+    def __init__(self, name, fn, args, keep):
+        self.name, self.fn, self.args, self.keep = name, fn, args, keep      # keep: the tensors behind the pointers
+
+    def __call__(self, stream=None):
+        _check(self.name, self.fn(*self.args, _stream(stream)))
+
+
+def _run(prepare, name, fn, args, keep, stream):
+    call = PreparedCall(name, fn, args, keep)
+    if prepare:
+        return call
+    call(stream)
+    return None
+
+
+def bagua_compress_minmax_u8_batched(xs, residuals, chunk, codes, minmaxs, workspace, stream=None, prepare=False):
+    """B buckets in one launch; xs/codes/minmaxs are lists of B tensors, residuals a list of B tensors or None.
+    prepare=True returns a PreparedCall instead of launching (so do the other batched calls)."""
     B = len(xs)
     _same_len(B, residuals=residuals, codes=codes, minmaxs=minmaxs)
     ns = [x.numel() for x in xs]
@@ -415,11 +436,11 @@ def bagua_compress_minmax_u8_batched(xs, residuals, chunk, codes, minmaxs, works
     ra = None if residuals is None else (ctypes.c_void_p * B)(*[_ptr(r, torch.float32, 4 * n).value for r, n in zip(residuals, ns)])
     ca = (ctypes.c_void_p * B)(*[_ptr(c, torch.uint8, n).value for c, n in zip(codes, ns)])
     ma = (ctypes.c_void_p * B)(*[_ptr(m, torch.float32, 8 * num_chunks(n, chunk)).value for m, n in zip(minmaxs, ns)])
-    _check("bagua_compress_minmax_u8_batched", _lib.bagua_compress_minmax_u8_batched(
-        xa, ra, _sizes(ns), B, chunk, ca, ma, wp, wb, _stream(stream)))
+    return _run(prepare, "bagua_compress_minmax_u8_batched", _lib.bagua_compress_minmax_u8_batched,
+                (xa, ra, _sizes(ns), B, chunk, ca, ma, wp, wb), (xs, residuals, codes, minmaxs, workspace), stream)
 
 
-def bagua_sign_compress_ef_batched(xs, residuals, chunk, bits, scales, workspace, stream=None):
+def bagua_sign_compress_ef_batched(xs, residuals, chunk, bits, scales, workspace, stream=None, prepare=False):
     B = len(xs)
     _same_len(B, residuals=residuals, bits=bits, scales=scales)
     ns = [x.numel() for x in xs]
@@ -428,12 +449,12 @@ def bagua_sign_compress_ef_batched(xs, residuals, chunk, bits, scales, workspace
     ra = None if residuals is None else (ctypes.c_void_p * B)(*[_ptr(r, torch.float32, 4 * n).value for r, n in zip(residuals, ns)])
     ba = (ctypes.c_void_p * B)(*[_ptr(b, torch.int32, _code_bytes(CODEC_SIGN1, n)).value for b, n in zip(bits, ns)])
     sa = (ctypes.c_void_p * B)(*[_ptr(s, torch.float32, _meta_bytes(CODEC_SIGN1, n, chunk)).value for s, n in zip(scales, ns)])
-    _check("bagua_sign_compress_ef_batched", _lib.bagua_sign_compress_ef_batched(
-        xa, ra, _sizes(ns), B, chunk, ba, sa, wp, wb, _stream(stream)))
+    return _run(prepare, "bagua_sign_compress_ef_batched", _lib.bagua_sign_compress_ef_batched,
+                (xa, ra, _sizes(ns), B, chunk, ba, sa, wp, wb), (xs, residuals, bits, scales, workspace), stream)
 
 
 def bagua_decompress_reduce_recompress_batched(codec, codes_in, meta_in, server_residuals, ns, chunk, codes_out, meta_out,
-                                               outs, workspace, stream=None):
+                                               outs, workspace, stream=None, prepare=False):
     """codes_in / meta_in: list over buckets of lists over the k workers."""
     B = len(ns)
     _same_len(B, codes_in=codes_in, meta_in=meta_in, server_residuals=server_residuals, codes_out=codes_out,
@@ -450,18 +471,19 @@ def bagua_decompress_reduce_recompress_batched(codec, codes_in, meta_in, server_
     co = (ctypes.c_void_p * B)(*[_ptr(c, None, _code_bytes(codec, n)).value for c, n in zip(codes_out, ns)])
     mo = (ctypes.c_void_p * B)(*[_ptr(m, torch.float32, _meta_bytes(codec, n, chunk)).value for m, n in zip(meta_out, ns)])
     oa = None if outs is None else (ctypes.c_void_p * B)(*[_ptr(o, torch.float32, 4 * n).value for o, n in zip(outs, ns)])
-    _check("bagua_decompress_reduce_recompress_batched", _lib.bagua_decompress_reduce_recompress_batched(
-        codec, ci, mi, k, ea, _sizes(ns), B, chunk, co, mo, oa, wp, wb, _stream(stream)))
+    return _run(prepare, "bagua_decompress_reduce_recompress_batched", _lib.bagua_decompress_reduce_recompress_batched,
+                (codec, ci, mi, k, ea, _sizes(ns), B, chunk, co, mo, oa, wp, wb),
+                (codes_in, meta_in, server_residuals, codes_out, meta_out, outs, workspace), stream)
 
 
-def bagua_bucket_flatten_batched_run(plans, Ts, buckets, workspace, stream=None):
+def bagua_bucket_flatten_batched_run(plans, Ts, buckets, workspace, stream=None, prepare=False):
     B = len(plans)
     _same_len(B, Ts=Ts, buckets=buckets)
     wp, wb = _ws(workspace)
     pa = (ctypes.c_void_p * B)(*[_ptr(p).value for p in plans])
     ba = (ctypes.c_void_p * B)(*[_ptr(b, torch.float32).value for b in buckets])
-    _check("bagua_bucket_flatten_batched_run", _lib.bagua_bucket_flatten_batched_run(
-        pa, _sizes(Ts), ba, _sizes([b.numel() for b in buckets]), B, wp, wb, _stream(stream)))
+    return _run(prepare, "bagua_bucket_flatten_batched_run", _lib.bagua_bucket_flatten_batched_run,
+                (pa, _sizes(Ts), ba, _sizes([b.numel() for b in buckets]), B, wp, wb), (plans, buckets, workspace), stream)
 
 
 # ---------------------------------------------------------------------------------------------- probes

@@ -106,6 +106,7 @@ extern "C" int bagua_decompress_reduce_recompress_batched(int codec, const void*
         total += nc;
     }
     table[B] = total;
+    batch_fill_lut(table.data(), B, ew);
     rl.writes(workspace, table.size() * sizeof(uint64_t));
     if (!rl.disjoint()) return BAGUA_ERR_INVALID_ARG;
     if (total > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;

@@ -2,13 +2,14 @@
 // (Section 3.1 "Bucketing": a training run hands over its buckets one by one, each too small to fill the chip).
 //
 // A batched entry point writes a table into the caller's workspace and launches the ordinary chunk kernel over the
-// concatenation of all buckets' chunks; a workgroup finds its bucket by a binary search over the buckets' first
-// unit indices (B + 1 uniform 8-byte loads at most log2(B) deep, served by the scalar cache).  The table travels to
+// concatenation of all buckets' chunks; a workgroup finds its bucket from the buckets' first unit indices through a
+// small lookup table (two or three dependent uniform loads, served by the scalar cache).  The table travels to
 // the device as kernel arguments of small upload launches: no host-to-device copy, no synchronisation, and the host
 // arrays may be reused as soon as the call returns.
 //
 // Table layout (8-byte words):  first_unit[0..B]  (first_unit[B] = units in the launch), padded to 16 bytes, then B
-// entries of `entry_words` words each (layout per entry point, see the kernels).
+// entries of `entry_words` words each (layout per entry point, see the kernels), then a unit -> bucket lookup table of
+// 16..1024 32-bit entries (see batch_find).
 #pragma once
 #include <vector>
 
@@ -19,19 +20,56 @@ namespace bagua {
 struct BatchView {
     const uint64_t* first_unit;  // [B + 1]
     const uint64_t* entries;     // [B][entry_words]
+    const uint32_t* lut;         // [lut entries]: lut[i] = bucket that owns unit i << shift
     uint32_t B;
     uint32_t entry_words;
+    uint32_t shift;
 };
 
 inline size_t batch_first_words(size_t B) { return (B + 1 + 1) & ~static_cast<size_t>(1); }  // 16-byte multiple
-inline size_t batch_table_words(size_t B, size_t entry_words) { return batch_first_words(B) + B * entry_words; }
+// Entries of the unit -> bucket lookup table: a power of two, about four per bucket, 16..1024.
+inline size_t batch_lut_entries(size_t B)
+{
+    size_t L = 16;
+    while (L < 4 * B && L < 1024) L *= 2;
+    return L;
+}
+inline size_t batch_lut_words(size_t B) { return batch_lut_entries(B) / 2; }   // 32-bit entries in 64-bit words
+inline size_t batch_table_words(size_t B, size_t entry_words)
+{
+    return batch_first_words(B) + B * entry_words + batch_lut_words(B);
+}
 // Words per entry that bagua_batch_workspace_bytes(B, k) provides for.
 inline size_t batch_entry_words_for(int k) { return 6 + 2 * static_cast<size_t>(k > 0 ? k : 0); }
+// Smallest shift with (total_units - 1) >> shift < lut entries.
+inline uint32_t batch_lut_shift(size_t B, size_t total_units)
+{
+    const size_t L = batch_lut_entries(B);
+    uint32_t s = 0;
+    while (total_units > 0 && ((total_units - 1) >> s) >= L) ++s;
+    return s;
+}
 
-inline BatchView batch_view(const void* workspace, size_t B, size_t entry_words)
+inline BatchView batch_view(const void* workspace, size_t B, size_t entry_words, size_t total_units)
 {
     const uint64_t* w = static_cast<const uint64_t*>(workspace);
-    return BatchView{w, w + batch_first_words(B), static_cast<uint32_t>(B), static_cast<uint32_t>(entry_words)};
+    const uint64_t* entries = w + batch_first_words(B);
+    return BatchView{w, entries, reinterpret_cast<const uint32_t*>(entries + B * entry_words), static_cast<uint32_t>(B),
+                     static_cast<uint32_t>(entry_words), batch_lut_shift(B, total_units)};
+}
+
+// Host side: fills the lookup table at the end of `table` (whose first_unit[0..B] are already set).
+inline void batch_fill_lut(uint64_t* table, size_t B, size_t entry_words)
+{
+    const size_t total = table[B];
+    const uint32_t shift = batch_lut_shift(B, total);
+    uint32_t* lut = reinterpret_cast<uint32_t*>(table + batch_first_words(B) + B * entry_words);
+    size_t b = 0;
+    for (size_t i = 0; i < batch_lut_entries(B); ++i) {
+        const uint64_t u = static_cast<uint64_t>(i) << shift;
+        while (b + 1 < B && table[b + 1] <= u) ++b;       // the largest b with first_unit[b] <= u (buckets are non-empty)
+        lut[i] = static_cast<uint32_t>(b);
+    }
 }
 
 // A device pointer read from the table.  The table holds integers; the cast goes through the global address space so
@@ -46,16 +84,15 @@ __device__ __forceinline__ T* table_ptr(uint64_t v)
     return (T*)reinterpret_cast<global_ptr>(v);
 }
 
-// Bucket that owns unit g: the largest b with first_unit[b] <= g.  Wave-uniform.
+// Bucket that owns unit g: the largest b with first_unit[b] <= g.  Wave-uniform.  The lookup table gives the bucket of
+// the unit at the start of g's stride; a few steps forward (none when buckets are longer than the stride) reach g's
+// own: two or three dependent scalar loads instead of log2(B) + 1, which matters for the kernels whose workgroups are
+// small (a 2048-element chunk of the sign codec).
 __device__ __forceinline__ uint32_t batch_find(const BatchView& bv, uint64_t g)
 {
-    uint32_t lo = 0, hi = bv.B;
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (bv.first_unit[mid] <= g) lo = mid;
-        else hi = mid;
-    }
-    return lo;
+    uint32_t b = bv.lut[g >> bv.shift];
+    while (bv.first_unit[b + 1] <= g) ++b;     // first_unit[B] = all units > g: stops at b <= B - 1
+    return b;
 }
 
 // ---------------------------------------------------------------- table upload through kernel arguments

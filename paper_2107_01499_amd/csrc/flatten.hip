@@ -379,13 +379,14 @@ extern "C" int bagua_bucket_flatten_batched_run(const void* const* plans, const 
         total += num_tiles(bucket_numel[b]);
     }
     table[B] = total;
+    batch_fill_lut(table.data(), B, ew);
     rl.writes(workspace, table.size() * sizeof(uint64_t));
     if (!rl.disjoint()) return BAGUA_ERR_INVALID_ARG;
     if (total > kMaxGrid / kTileWaves) return BAGUA_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (batch_upload(table.data(), table.size(), static_cast<uint64_t*>(workspace), s) != BAGUA_OK) return BAGUA_ERR_LAUNCH;
     hipLaunchKernelGGL(k_flatten_batched, dim3(static_cast<unsigned>(total * kTileWaves)), dim3(kWave), 0, s,
-                       batch_view(workspace, B, ew));
+                       batch_view(workspace, B, ew, total));
     return launch_status();
 }
 

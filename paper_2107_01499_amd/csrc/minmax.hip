@@ -271,7 +271,7 @@ int launch_drr_minmax(const void* const* codes_in, const float* const* meta_in, 
 int launch_drr_minmax_batched(const void* workspace, size_t B, int k, size_t total_chunks, size_t chunk, bool ef,
                               bool with_out, hipStream_t stream)
 {
-    const BatchView bv = batch_view(workspace, B, 5 + 2 * static_cast<size_t>(k));
+    const BatchView bv = batch_view(workspace, B, 5 + 2 * static_cast<size_t>(k), total_chunks);
     const int rows = static_cast<int>(chunk / kRow);
     const int rpw = pick_rpw(rows, BAGUA_RPW_DRR);
     dim3 grid(static_cast<unsigned>(total_chunks)), block(64 * ((rows + rpw - 1) / rpw));
@@ -350,12 +350,13 @@ extern "C" int bagua_compress_minmax_u8_batched(const float* const* x, float* co
         total += nc;
     }
     table[B] = total;
+    batch_fill_lut(table.data(), B, ew);
     rl.writes(workspace, table.size() * sizeof(uint64_t));
     if (!rl.disjoint()) return BAGUA_ERR_INVALID_ARG;
     if (total > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (batch_upload(table.data(), table.size(), static_cast<uint64_t*>(workspace), s) != BAGUA_OK) return BAGUA_ERR_LAUNCH;
-    const BatchView bv = batch_view(workspace, B, ew);
+    const BatchView bv = batch_view(workspace, B, ew, total);
     const int rows = static_cast<int>(chunk / kRow);
     const int rpw = pick_rpw(rows, BAGUA_RPW_COMPRESS);
     dim3 grid(static_cast<unsigned>(total)), block(64 * ((rows + rpw - 1) / rpw));

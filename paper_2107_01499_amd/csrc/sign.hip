@@ -378,7 +378,7 @@ int launch_drr_sign(const void* const* bits_in, const float* const* scale_in, in
 int launch_drr_sign_batched(const void* workspace, size_t B, int k, size_t total_chunks, size_t chunk, bool ef,
                             bool with_out, hipStream_t stream)
 {
-    const BatchView bv = batch_view(workspace, B, 5 + 2 * static_cast<size_t>(k));
+    const BatchView bv = batch_view(workspace, B, 5 + 2 * static_cast<size_t>(k), total_chunks);
     SignGeometry g = sign_geometry(chunk, chunk, BAGUA_RPW_DRR_SIGN, false);
     g.grid = dim3(static_cast<unsigned>(total_chunks));
     const float inv_k = 1.0f / static_cast<float>(k);
@@ -483,12 +483,13 @@ extern "C" int bagua_sign_compress_ef_batched(const float* const* x, float* cons
         total += nc;
     }
     table[B] = total;
+    batch_fill_lut(table.data(), B, ew);
     rl.writes(workspace, table.size() * sizeof(uint64_t));
     if (!rl.disjoint()) return BAGUA_ERR_INVALID_ARG;
     if (total > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (batch_upload(table.data(), table.size(), static_cast<uint64_t*>(workspace), s) != BAGUA_OK) return BAGUA_ERR_LAUNCH;
-    const BatchView bv = batch_view(workspace, B, ew);
+    const BatchView bv = batch_view(workspace, B, ew, total);
     SignGeometry g = sign_geometry(chunk, chunk, BAGUA_RPW_SIGN, false);
     g.grid = dim3(static_cast<unsigned>(total));
     const uint32_t ch = static_cast<uint32_t>(chunk);
