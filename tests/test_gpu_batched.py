@@ -184,6 +184,49 @@ def test_batched_many_buckets_and_reuse(bg, oracle):
             same(host(mms[b]), mo, "minmax %d" % b)
 
 
+def test_prepared_calls(bg, oracle):
+    """prepare=True marshals once and launches nothing; every later call of the object is the whole batched step on the
+    buffers as they are then (error feedback carries over from call to call)."""
+    print("prepared batched calls", flush=True)
+    C, B, k = 256, len(NS), 3
+    xs = [vals(n, 300 + b) for b, n in enumerate(NS)]
+    res = [np.zeros(n, np.float32) for n in NS]
+    xg, rg = [dev(x) for x in xs], [dev(r) for r in res]
+    bits = [torch.zeros((n + 31) // 32, dtype=torch.int32, device="cuda") for n in NS]
+    sc = [torch.full((bg.num_chunks(n, C),), float("nan"), device="cuda") for n in NS]
+    ws = ws_for(bg, B, k)
+    call = bg.bagua_sign_compress_ef_batched(xg, rg, C, bits, sc, ws, prepare=True)
+    torch.cuda.synchronize()
+    assert all(torch.isnan(s).all() for s in sc) and all(int(r.count_nonzero()) == 0 for r in rg)   # nothing ran yet
+    for rep in range(2):
+        call()
+        torch.cuda.synchronize()
+        for b in range(B):
+            bo, so = oracle.sign_compress_ef(xs[b], res[b], C)            # updates res[b] in place
+            same(host(bits[b]).view(np.uint32), bo, "bits %d rep %d" % (b, rep))
+            same(host(sc[b]), so, "scale %d rep %d" % (b, rep))
+            same(host(rg[b]), res[b], "residual %d rep %d" % (b, rep))
+    # the server step over what k workers sent (the same bits k times), prepared, after the inputs changed once more
+    eps = [np.zeros(n, np.float32) for n in NS]
+    eg = [dev(e) for e in eps]
+    bo_g = [torch.zeros_like(b_) for b_ in bits]
+    so_g = [torch.zeros_like(s_) for s_ in sc]
+    out = [torch.empty(n, device="cuda") for n in NS]
+    drr = bg.bagua_decompress_reduce_recompress_batched(bg.CODEC_SIGN1, [[bits[b]] * k for b in range(B)],
+                                                        [[sc[b]] * k for b in range(B)], eg, NS, C, bo_g, so_g, out, ws,
+                                                        prepare=True)
+    call()                                                                # third compression: new bits, new scales
+    drr()
+    torch.cuda.synchronize()
+    for b in range(B):
+        bo, so = oracle.sign_compress_ef(xs[b], res[b], C)
+        b2, s2, o2 = oracle.drr_sign([bo] * k, [so] * k, eps[b], NS[b], C)
+        same(host(bo_g[b]).view(np.uint32), b2, "server bits %d" % b)
+        same(host(so_g[b]), s2, "server scale %d" % b)
+        same(host(out[b]), o2, "server out %d" % b)
+        same(host(eg[b]), eps[b], "server residual %d" % b)
+
+
 def test_batched_validation(bg):
     lib = bg.binding.raw()
     import ctypes
