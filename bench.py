@@ -918,11 +918,57 @@ def run_block(torch, bg, args, name, layout, only, extras):
         block["cpu_baseline"], block["parity"] = cpu_baseline(wl, torch)
     if "flatten" in prims and layout == "flat" and only is None:      # last: it overwrites the resident buckets
         block["flatten_misaligned"] = misaligned_flatten(torch, bg, wl)
+    if layout == "flat" and only is None and not extras and not args.fused_flatten:      # very last: overwrites error states
+        probe = same_traffic_probe(torch, bg, wl, dom)
+        if probe is not None:
+            probe["kernel_vs_probe"] = round(achieved / probe["GBps"], 4)
+            roof["same_traffic_probe"] = probe
     del wl
     import gc
     gc.collect()
     torch.cuda.empty_cache()
     return block, wall / args.steps
+
+
+def same_traffic_probe(torch, bg, wl, dom, reps=3):
+    """What the memory system delivers for the dominant kernel's traffic shape on the block's OWN resident buffers, at
+    their full size: bagua_probe_streams (one row per wave, loads then stores, no arithmetic, no barrier) over the same
+    arrays the kernel streams.  Run last: it overwrites them.  None for shapes the probe does not have."""
+    k, U = wl.k, len(wl.units)
+    ns = [wl.units[u][1] for u in range(U)]
+    if any(m % 256 for m in ns):
+        return None
+    if dom == "compress_minmax":
+        def once(i):
+            for j in range(k):
+                for u in range(U):
+                    bg.bagua_probe_streams([wl.bucket[j][u], wl.delta[j][u]], [wl.delta[j][u]], [wl.codes[j][u]], 2, 1, 1, 1, ns[u])
+        bpe, what = 13.0, "x and the error state read, the error state written in place, one byte per element written"
+    elif dom == "sign_compress":
+        def once(i):
+            for j in range(k):
+                for u in range(U):
+                    bg.bagua_probe_streams([wl.bucket[j][u], wl.sdelta[j][u]], [wl.sdelta[j][u]], [], 2, 1, 0, 1, ns[u])
+        bpe, what = 12.0, "x and the error state read, the error state written in place (the kernel's 1/8 B of sign bits left out)"
+    elif dom == "ring_lp" and k == 8:
+        def once(i):
+            for u in range(U):
+                ins = [t for p_ in range(k) for t in (wl.rep_lp[0][p_][u], wl.xhat[p_][u])]
+                outs = [t for p_ in range(k) for t in (wl.xhat[p_][u], wl.rep_lp[1][p_][u])]
+                bg.bagua_probe_streams(ins, outs, [wl.lp_codes[p_][u] for p_ in range(k)], 2, 2, 1, k, ns[u])
+        bpe, what = 17.0, "per peer x and the public replica read, the public replica and the new x written, one byte per element written; the 8 peers one after another in every wave"
+    elif dom == "ring_fp" and k == 8:
+        def once(i):
+            for u in range(U):
+                bg.bagua_probe_streams([wl.rep_fp[0][p_][u] for p_ in range(k)], [wl.rep_fp[1][p_][u] for p_ in range(k)], [], 8, 8, 0, 1, ns[u])
+        bpe, what = 8.0, "8 replicas read, 8 written"
+    else:
+        return None
+    t = time_fn(torch, once, reps)
+    rate = bpe * wl.n_elems * k / t / 1e9
+    return {"GBps": round(rate, 1), "frac_of_peak": round(rate / HBM_PEAK_GBS, 4), "bytes_per_element": bpe, "streams": what,
+            "note": "bagua_probe_streams on this block's own buffers at full size, same launches per step as the kernel; "
+                    "the `ceilings` block measures the same probes on 0.1-0.5 GiB buffers"}
 
 
 def misaligned_flatten(torch, bg, wl, reps=5):

@@ -414,7 +414,7 @@ int bagua_bucket_flatten_batched_run(const void* const* plans, const size_t* T, 
  * bagua_probe_streams: every wavefront owns one 256-element row and visits `seq` groups of streams one after
  * another; in a group it reads the row from nr fp32 streams, then writes it to nw fp32 streams and to nb byte
  * streams.  in: host[seq*nr], out: host[seq*nw], bout: host[seq*nb] of device pointers (16-byte aligned, n
- * elements each, n a multiple of 256); (nr, nw, nb) in {(1,1,0), (2,1,1), (2,2,1), (4,4,0), (8,8,0), (1,8,0),
+ * elements each, n a multiple of 256); (nr, nw, nb) in {(1,1,0), (2,1,0), (2,1,1), (2,2,1), (4,4,0), (8,8,0), (1,8,0),
  * (8,1,0)}, BAGUA_ERR_UNSUPPORTED otherwise; seq*max(nr,nw,nb) <= BAGUA_MAX_WORKERS.
  */
 int bagua_probe_read(const float* x, size_t n, float* tile_sums, void* stream);

@@ -108,7 +108,7 @@ extern "C" int bagua_probe_streams(const float* const* in, float* const* out, ui
         hipLaunchKernelGGL((k_probe_streams<NR, NW, NB>), grid, block, 0, s, it, ot, bt, seq, n);        \
         return launch_status();                                                                          \
     }
-    BAGUA_PROBE(1, 1, 0) BAGUA_PROBE(2, 1, 1) BAGUA_PROBE(2, 2, 1) BAGUA_PROBE(4, 4, 0) BAGUA_PROBE(8, 8, 0)
+    BAGUA_PROBE(1, 1, 0) BAGUA_PROBE(2, 1, 0) BAGUA_PROBE(2, 1, 1) BAGUA_PROBE(2, 2, 1) BAGUA_PROBE(4, 4, 0) BAGUA_PROBE(8, 8, 0)
     BAGUA_PROBE(1, 8, 0) BAGUA_PROBE(8, 1, 0)
 #undef BAGUA_PROBE
     return BAGUA_ERR_UNSUPPORTED;

@@ -31,5 +31,9 @@ def test_probe_streams_copies_rows(bg):
     bg.bagua_probe_streams([a, b], out, byt, 2, 2, 1, 1, n)
     torch.cuda.synchronize()
     assert torch.equal(out[0], a + b) and torch.equal(out[1], a + b)
+    acc = b.clone()
+    bg.bagua_probe_streams([a, acc], [acc], [], 2, 1, 0, 1, n)                  # in place, no byte stream
+    torch.cuda.synchronize()
+    assert torch.equal(acc, a + b)
     with pytest.raises(bg.binding.BaguaError):
         bg.bagua_probe_streams([a, b, a], [out[0]], [], 3, 1, 0, 1, n)       # combination outside the menu
