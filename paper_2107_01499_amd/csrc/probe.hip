@@ -32,11 +32,15 @@ k_probe_read(const float* __restrict__ x, size_t n, float* __restrict__ tile_sum
 
 // Stream mix: a wave owns one row and visits `seq` groups of streams one after another; in each group it reads
 // the row from NR fp32 streams, then writes it to NW fp32 streams and NB byte streams (one dword per lane).
-template <int NR, int NW, int NB>
-__global__ void __launch_bounds__(kWave * kRowWaves)
-k_probe_streams(PtrTable in, MutPtrTable out, MutPtrTable bout, int seq, size_t n)
+// PW waves per workgroup: one for a single group (the copy-like shapes: measured at 1.5 G elements per launch,
+// 1R+1W 0.84 of peak with one wave per workgroup, 0.78 with two, 0.82 with four; 2R+1W in place 0.78-0.80 / 0.73-0.75 /
+// 0.78), two when a wave visits several groups (the ring kernels' shape, where two measured fastest).  `pace` as in
+// the worker-side kernels: wait for each load before the next is requested.
+template <int NR, int NW, int NB, int PW>
+__global__ void __launch_bounds__(kWave * PW)
+k_probe_streams(PtrTable in, MutPtrTable out, MutPtrTable bout, int seq, size_t n, int pace)
 {
-    const size_t row = static_cast<size_t>(blockIdx.x) * kRowWaves + wave_index();
+    const size_t row = static_cast<size_t>(blockIdx.x) * PW + (PW > 1 ? wave_index() : 0);
     const int lane = threadIdx.x & 63;
     const size_t e0 = row * kRow;
     if (e0 >= n) return;
@@ -44,8 +48,10 @@ k_probe_streams(PtrTable in, MutPtrTable out, MutPtrTable bout, int seq, size_t 
     for (int s = 0; s < seq; ++s) {
         f4 v[NR];
 #pragma unroll
-        for (int i = 0; i < NR; ++i)
+        for (int i = 0; i < NR; ++i) {
             v[i] = ld_stream(reinterpret_cast<const f4*>(static_cast<const float*>(in.p[s * NR + i]) + e0) + lane);
+            if (pace) pace_loads();
+        }
         f4 acc = carry;
 #pragma unroll
         for (int i = 0; i < NR; ++i) acc = acc + v[i];
@@ -100,13 +106,17 @@ extern "C" int bagua_probe_streams(const float* const* in, float* const* out, ui
         bt.p[i] = bout[i];
     }
     const size_t rows = n / kRow;
-    if ((rows + kRowWaves - 1) / kRowWaves > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
-    dim3 grid(static_cast<unsigned>((rows + kRowWaves - 1) / kRowWaves)), block(kWave * kRowWaves);
+    const int pw = seq == 1 ? 1 : kRowWaves;
+    const size_t groups = (rows + pw - 1) / pw;
+    if (groups > kMaxGrid) return BAGUA_ERR_UNSUPPORTED;
+    dim3 grid(static_cast<unsigned>(groups)), block(kWave * pw);
     hipStream_t s = static_cast<hipStream_t>(stream);
-#define BAGUA_PROBE(NR, NW, NB)                                                                          \
-    if (nr == NR && nw == NW && nb == NB) {                                                              \
-        hipLaunchKernelGGL((k_probe_streams<NR, NW, NB>), grid, block, 0, s, it, ot, bt, seq, n);        \
-        return launch_status();                                                                          \
+    const int pace = pace_for(n);
+#define BAGUA_PROBE(NR, NW, NB)                                                                                    \
+    if (nr == NR && nw == NW && nb == NB) {                                                                        \
+        if (pw == 1) hipLaunchKernelGGL((k_probe_streams<NR, NW, NB, 1>), grid, block, 0, s, it, ot, bt, seq, n, pace); \
+        else hipLaunchKernelGGL((k_probe_streams<NR, NW, NB, kRowWaves>), grid, block, 0, s, it, ot, bt, seq, n, pace); \
+        return launch_status();                                                                                    \
     }
     BAGUA_PROBE(1, 1, 0) BAGUA_PROBE(2, 1, 0) BAGUA_PROBE(2, 1, 1) BAGUA_PROBE(2, 2, 1) BAGUA_PROBE(4, 4, 0) BAGUA_PROBE(8, 8, 0)
     BAGUA_PROBE(1, 8, 0) BAGUA_PROBE(8, 1, 0)
