@@ -88,7 +88,7 @@ __device__ __forceinline__ T* table_ptr(uint64_t v)
 // the unit at the start of g's stride; a few steps forward (none when buckets are longer than the stride) reach g's
 // own: two or three dependent scalar loads instead of log2(B) + 1, which matters for the kernels whose workgroups are
 // small (a 2048-element chunk of the sign codec).
-__device__ __forceinline__ uint32_t batch_find(const BatchView& bv, uint64_t g)
+__host__ __device__ __forceinline__ uint32_t batch_find(const BatchView& bv, uint64_t g)
 {
     uint32_t b = bv.lut[g >> bv.shift];
     while (bv.first_unit[b + 1] <= g) ++b;     // first_unit[B] = all units > g: stops at b <= B - 1
