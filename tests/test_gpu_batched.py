@@ -163,6 +163,15 @@ def test_flatten_batched(bg, oracle):
     torch.cuda.synchronize()
     for b in range(len(layouts)):
         assert host(buckets[b]).tobytes() == wants[b].tobytes(), b
+    # the same as a prepared call, twice, after the buckets were overwritten
+    call = bg.bagua_bucket_flatten_batched_run(plans, Ts, buckets, ws_for(bg, len(layouts)), prepare=True)
+    for rep in range(2):
+        for bkt in buckets:
+            bkt.fill_(float("nan"))
+        call()
+        torch.cuda.synchronize()
+        for b in range(len(layouts)):
+            assert host(buckets[b]).tobytes() == wants[b].tobytes(), (rep, b)
 
 
 def test_batched_many_buckets_and_reuse(bg, oracle):
@@ -206,6 +215,20 @@ def test_prepared_calls(bg, oracle):
             same(host(bits[b]).view(np.uint32), bo, "bits %d rep %d" % (b, rep))
             same(host(sc[b]), so, "scale %d rep %d" % (b, rep))
             same(host(rg[b]), res[b], "residual %d rep %d" % (b, rep))
+    # MinMax compression, prepared, with error feedback carried over two calls
+    mres = [np.zeros(n, np.float32) for n in NS]
+    mrg = [dev(r) for r in mres]
+    codes = [torch.empty(n, dtype=torch.uint8, device="cuda") for n in NS]
+    mms = [torch.empty(2 * bg.num_chunks(n, C), device="cuda") for n in NS]
+    mcall = bg.bagua_compress_minmax_u8_batched(xg, mrg, C, codes, mms, ws_for(bg, B), prepare=True)
+    for rep in range(2):
+        mcall()
+        torch.cuda.synchronize()
+        for b in range(B):
+            co, mo = oracle.compress_minmax_u8(xs[b], mres[b], C)
+            same(host(codes[b]), co, "codes %d rep %d" % (b, rep))
+            same(host(mms[b]), mo, "minmax %d rep %d" % (b, rep))
+            same(host(mrg[b]), mres[b], "minmax residual %d rep %d" % (b, rep))
     # the server step over what k workers sent (the same bits k times), prepared, after the inputs changed once more
     eps = [np.zeros(n, np.float32) for n in NS]
     eg = [dev(e) for e in eps]
